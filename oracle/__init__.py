@@ -1,0 +1,176 @@
+"""CPU oracle for the Astra attention layer -- TEST INFRASTRUCTURE ONLY.
+
+A thin ctypes layer over ``astra_oracle.c`` (plain C, fp64 arithmetic).  Only
+tests, the smoke check and the benchmark's CPU-baseline leg may import this
+package; the product path never does, and this package never imports the
+product.  It holds no GPU code and shares nothing with the HIP library.
+
+Notation follows the paper: ``X`` token embeddings, ``G`` groups, ``K``
+codewords per group, ``Q = X W_q`` with ``W_q`` of shape ``[D, H_q*dh]``,
+Eq. 1 for the mixed-precision attention.  Parity status: every function here
+is pinned by tests/test_oracle_*.py (brute force, library routines, closed
+forms, invariants); the outputs of the authors' trained models are "parity
+unpinned" because the paper prints no worked numerical example.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "astra_oracle.c")
+_LIB = os.path.join(_HERE, "libastra_oracle.so")
+_lib = None
+
+
+def build(force: bool = True) -> str:
+    """Compile the C oracle with gcc (OpenMP over rows only)."""
+    if force or not os.path.exists(_LIB):
+        cmd = ["gcc", "-O3", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+               "-fno-fast-math", "-ffp-contract=off", _SRC, "-o", _LIB, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        lib = ctypes.CDLL(_LIB)
+        lib.oracle_num_threads.restype = ctypes.c_int
+        for name in ("oracle_vq_encode", "oracle_vq_decode", "oracle_linear",
+                     "oracle_mixed_attention", "oracle_layer_forward"):
+            getattr(lib, name).restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _f32(a):
+    return None if a is None else np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def vq_encode(x, codebook, return_gap: bool = False):
+    """codes[t, g] = argmin_k ||X[t, g-th slice] - C[g, k]||^2, lowest index on ties.
+
+    x [T, D] float, codebook [G, K, dg].  Returns int32 codes [T, G] (and the
+    relative best/second-best gap [T, G] when asked).
+    """
+    x = _f32(x)
+    codebook = _f32(codebook)
+    G, K, dg = codebook.shape
+    T, D = x.shape
+    assert D == G * dg, "D must equal G * dg"
+    codes = np.empty((T, G), dtype=np.int32)
+    gap = np.empty((T, G), dtype=np.float64) if return_gap else None
+    rc = _load().oracle_vq_encode(_p(x), ctypes.c_int64(T), D, G, K, _p(codebook), _p(codes), _p(gap))
+    if rc:
+        raise ValueError(f"oracle_vq_encode failed ({rc})")
+    return (codes, gap) if return_gap else codes
+
+
+def vq_decode(codes, codebook):
+    """X_hat[t, g-th slice] = C[g, codes[t, g]] (exact copy)."""
+    codebook = _f32(codebook)
+    codes = _i32(codes)
+    G, K, dg = codebook.shape
+    T = codes.shape[0]
+    assert codes.shape == (T, G)
+    out = np.empty((T, G * dg), dtype=np.float32)
+    rc = _load().oracle_vq_decode(_p(codes), ctypes.c_int64(T), G * dg, G, K, _p(codebook), _p(out))
+    if rc:
+        raise ValueError(f"oracle_vq_decode failed ({rc})")
+    return out
+
+
+def linear(x, w, bias=None):
+    """x [T, D_in] @ w [D_in, D_out] (+ bias), fp64."""
+    x = _f64(x)
+    w = _f32(w)
+    bias = _f32(bias)
+    T, d_in = x.shape
+    assert w.shape[0] == d_in
+    out = np.empty((T, w.shape[1]), dtype=np.float64)
+    rc = _load().oracle_linear(_p(x), ctypes.c_int64(T), d_in, w.shape[1], _p(w), _p(bias), _p(out))
+    if rc:
+        raise ValueError(f"oracle_linear failed ({rc})")
+    return out
+
+
+def mixed_attention(q, k_loc, v_loc, k_hat, v_hat, *, n_cls=0, causal=False, n_before=0,
+                    scale=0.0, return_lse=False, return_probs=False):
+    """Eq. 1 for one device.  q [T_q, H_q, dh]; k_loc/v_loc [T_q, H_kv, dh];
+    k_hat/v_hat [T_n, H_kv, dh].  Returns out [T_q, H_q, dh] fp64
+    (+ lse [H_q, T_q], + probs [H_q, T_q, T_q+T_n] when asked)."""
+    q, k_loc, v_loc, k_hat, v_hat = map(_f64, (q, k_loc, v_loc, k_hat, v_hat))
+    Tq, Hq, dh = q.shape
+    Hkv = k_loc.shape[1]
+    Tn = k_hat.shape[0]
+    assert k_loc.shape == (Tq, Hkv, dh) and v_loc.shape == (Tq, Hkv, dh)
+    assert k_hat.shape == (Tn, Hkv, dh) and v_hat.shape == (Tn, Hkv, dh)
+    out = np.empty((Tq, Hq, dh), dtype=np.float64)
+    lse = np.empty((Hq, Tq), dtype=np.float64) if return_lse else None
+    probs = np.empty((Hq, Tq, Tq + Tn), dtype=np.float64) if return_probs else None
+    rc = _load().oracle_mixed_attention(
+        _p(q), _p(k_loc), _p(v_loc), _p(k_hat), _p(v_hat), Hq, Hkv, dh,
+        int(n_cls), Tq - int(n_cls), Tn, int(bool(causal)), int(n_before),
+        ctypes.c_double(scale), _p(out), _p(lse), _p(probs))
+    if rc:
+        raise ValueError(f"oracle_mixed_attention failed ({rc})")
+    res = [out]
+    if return_lse:
+        res.append(lse)
+    if return_probs:
+        res.append(probs)
+    return res[0] if len(res) == 1 else tuple(res)
+
+
+def layer_forward(x_local, codes_nonlocal, codebook, wq, wk, wv, wo, *, n_q_heads, n_kv_heads,
+                  n_cls=0, causal=False, n_before=0, scale=0.0,
+                  bq=None, bk=None, bv=None, bo=None, return_gap=False):
+    """One device's layer (Sec. 3.1).  Weights in the paper's orientation
+    ``[D_in, D_out]``.  Returns (y [T_q, D] fp64, codes_local [T_l, G] int32
+    [, gap [T_l, G]])."""
+    x_local = _f32(x_local)
+    codebook = _f32(codebook)
+    codes_nonlocal = _i32(codes_nonlocal)
+    wq, wk, wv, wo = map(_f32, (wq, wk, wv, wo))
+    bq, bk, bv, bo = map(_f32, (bq, bk, bv, bo))
+    G, K, dg = codebook.shape
+    Tq, D = x_local.shape
+    Tn = codes_nonlocal.shape[0]
+    assert D == G * dg and codes_nonlocal.shape == (Tn, G)
+    dh = wq.shape[1] // n_q_heads
+    assert wq.shape == (D, n_q_heads * dh) and wk.shape == (D, n_kv_heads * dh)
+    assert wv.shape == (D, n_kv_heads * dh) and wo.shape == (n_q_heads * dh, D)
+    n_local = Tq - int(n_cls)
+    y = np.empty((Tq, D), dtype=np.float64)
+    codes_local = np.empty((n_local, G), dtype=np.int32)
+    gap = np.empty((n_local, G), dtype=np.float64) if return_gap else None
+    rc = _load().oracle_layer_forward(
+        _p(x_local), _p(codes_nonlocal), _p(codebook), D, G, K,
+        _p(wq), _p(wk), _p(wv), _p(wo), _p(bq), _p(bk), _p(bv), _p(bo),
+        n_q_heads, n_kv_heads, dh, int(n_cls), n_local, Tn,
+        int(bool(causal)), int(n_before), ctypes.c_double(scale),
+        _p(y), _p(codes_local), _p(gap))
+    if rc:
+        raise ValueError(f"oracle_layer_forward failed ({rc})")
+    return (y, codes_local, gap) if return_gap else (y, codes_local)

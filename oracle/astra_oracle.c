@@ -1,0 +1,246 @@
+/*
+ * CPU oracle for one device's share of an Astra attention layer.
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is the slow, plain, fp64
+ * statement of what the GPU path must compute, written from the paper's
+ * definitions.  Only tests, the smoke check and the benchmark's CPU-baseline
+ * leg may load it.  It shares no source, header, table or helper with the HIP
+ * library and never calls it.
+ *
+ * All arithmetic is IEEE double.  Inputs arrive as float arrays that hold the
+ * exact bits given to the GPU (for bf16 workloads they are bf16-representable
+ * values widened to float); nothing is rounded between steps.
+ *
+ * What each function follows:
+ *   oracle_vq_encode        Sec. 2 "Vanilla VQ" (i = argmin_i ||e_i - z||^2) and
+ *                           "Grouped VQ" (G equal sub-vectors, one codebook each)
+ *   oracle_vq_decode        Sec. 3.2 "Vector-Quantized Non-Local Tokens"
+ *                           (receiver rebuilds X-hat from the index alone)
+ *   oracle_linear           the linear projections named under Eq. 1
+ *   oracle_mixed_attention  Sec. 3.2 Eq. 1, sigma(Q [K | K-hat]^T / sqrt(d_k)) [V | V-hat]
+ *   oracle_layer_forward    Sec. 3.1 (per-block procedure on one device)
+ *
+ * Readings taken where the paper is silent (they are the library's too):
+ *   - groups are contiguous slices [g*dg, (g+1)*dg) of the D-vector;
+ *   - argmin ties go to the lowest index;
+ *   - the mask M of Eq. 1 excludes a (query, key) pair from the softmax, it
+ *     does not multiply a logit by zero; at inference it carries causality only;
+ *   - causality is on global positions with contiguous chunks, so non-local
+ *     rows [0, n_before) precede the local chunk (all visible) and rows
+ *     [n_before, T_n) follow it (all hidden);
+ *   - multi-head: Eq. 1 per head with d_k = head_dim; grouped-query attention
+ *     shares KV head h / (H_q / H_kv) among consecutive query heads;
+ *   - a class-token replica is an ordinary full-precision local row placed
+ *     first; it is not encoded.
+ *
+ * Parity pins live in tests/ (brute force, closed forms, library routines,
+ * invariants).  The numerical outputs of the authors' trained models are
+ * "parity unpinned": the paper prints no worked code or attention value.
+ */
+#include <float.h>
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* Grouped VQ encode.  x [T, D], codebook [G, K, D/G], codes [T, G].
+ * gap (nullable) [T, G] = (second-best - best) / best squared distance, the
+ * quantity the near-tie report is defined on.  Returns 0, or -1 on bad shape. */
+int oracle_vq_encode(const float* x, int64_t T, int D, int G, int K,
+                     const float* codebook, int32_t* codes, double* gap) {
+    if (T < 0 || D <= 0 || G <= 0 || K <= 0 || D % G != 0) return -1;
+    const int dg = D / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        for (int g = 0; g < G; ++g) {
+            const float* z = x + t * (int64_t)D + (int64_t)g * dg;
+            double best = INFINITY, second = INFINITY;
+            int arg = -1;
+            for (int k = 0; k < K; ++k) {
+                const float* e = codebook + ((int64_t)g * K + k) * dg;
+                double dist = 0.0;
+                for (int j = 0; j < dg; ++j) {
+                    const double diff = (double)e[j] - (double)z[j];
+                    dist += diff * diff;
+                }
+                if (dist < best) {          /* strict: equal distance keeps the lower index */
+                    second = best;
+                    best = dist;
+                    arg = k;
+                } else if (dist < second) {
+                    second = dist;
+                }
+            }
+            codes[t * (int64_t)G + g] = arg;
+            if (gap) {
+                const double den = best > DBL_MIN ? best : DBL_MIN;
+                gap[t * (int64_t)G + g] = (K > 1) ? (second - best) / den : INFINITY;
+            }
+        }
+    }
+    return 0;
+}
+
+/* Codebook lookup.  codes [T, G] -> x_hat [T, D]; values are copied, never
+ * recomputed.  Returns -2 if a code is outside [0, K). */
+int oracle_vq_decode(const int32_t* codes, int64_t T, int D, int G, int K,
+                     const float* codebook, float* x_hat) {
+    if (T < 0 || D <= 0 || G <= 0 || K <= 0 || D % G != 0) return -1;
+    const int dg = D / G;
+    for (int64_t i = 0; i < T * (int64_t)G; ++i)
+        if (codes[i] < 0 || codes[i] >= K) return -2;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t)
+        for (int g = 0; g < G; ++g) {
+            const float* e = codebook + ((int64_t)g * K + codes[t * (int64_t)G + g]) * dg;
+            memcpy(x_hat + t * (int64_t)D + (int64_t)g * dg, e, sizeof(float) * dg);
+        }
+    return 0;
+}
+
+/* out[t, o] = sum_i x[t, i] * w[i, o] + bias[o].  w is [D_in, D_out] as in
+ * Q = X W_q; bias nullable. */
+int oracle_linear(const double* x, int64_t T, int d_in, int d_out,
+                  const float* w, const float* bias, double* out) {
+    if (T < 0 || d_in <= 0 || d_out <= 0) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        double* o = out + t * (int64_t)d_out;
+        for (int c = 0; c < d_out; ++c) o[c] = 0.0;
+        for (int i = 0; i < d_in; ++i) {
+            const double xi = x[t * (int64_t)d_in + i];
+            const float* wr = w + (int64_t)i * d_out;
+            for (int c = 0; c < d_out; ++c) o[c] += xi * (double)wr[c];
+        }
+        if (bias)
+            for (int c = 0; c < d_out; ++c) o[c] += (double)bias[c];
+    }
+    return 0;
+}
+
+/* Eq. 1 for the T_q = n_cls + n_local local rows of one device.
+ *   q            [T_q, H_q, dh]
+ *   k_loc, v_loc [T_q, H_kv, dh]   full-precision local keys / values
+ *   k_hat, v_hat [T_n, H_kv, dh]   keys / values projected from decoded tokens
+ *   out          [T_q, H_q, dh]
+ *   lse (nullable)   [H_q, T_q]    log of the softmax denominator (natural log, incl. the max)
+ *   probs (nullable) [H_q, T_q, T_q + T_n]  the softmax row, local keys first as in [K | K-hat];
+ *                                            excluded pairs hold 0
+ * Allowed keys of local row i: not causal -> every local and non-local row;
+ * causal -> local rows j <= i and non-local rows t < n_before. */
+int oracle_mixed_attention(const double* q, const double* k_loc, const double* v_loc,
+                           const double* k_hat, const double* v_hat,
+                           int n_q_heads, int n_kv_heads, int head_dim,
+                           int n_cls, int n_local, int n_nonlocal,
+                           int causal, int n_before, double scale,
+                           double* out, double* lse, double* probs) {
+    if (n_q_heads <= 0 || n_kv_heads <= 0 || n_q_heads % n_kv_heads != 0 || head_dim <= 0) return -1;
+    if (n_cls < 0 || n_local < 0 || n_nonlocal < 0) return -1;
+    if (causal && (n_cls != 0 || n_before < 0 || n_before > n_nonlocal)) return -1;
+    const int Tq = n_cls + n_local, Tn = n_nonlocal, Tk = Tq + Tn;
+    const int rep = n_q_heads / n_kv_heads;
+    if (scale == 0.0) scale = 1.0 / sqrt((double)head_dim);
+    const int64_t rows = (int64_t)n_q_heads * Tq;
+#pragma omp parallel
+    {
+        double* s = (double*)malloc(sizeof(double) * (Tk > 0 ? Tk : 1));
+        char* allowed = (char*)malloc(Tk > 0 ? Tk : 1);
+#pragma omp for schedule(dynamic, 8)
+        for (int64_t r = 0; r < rows; ++r) {
+            const int h = (int)(r / Tq), i = (int)(r % Tq);
+            const int hk = h / rep;
+            const double* qi = q + ((int64_t)i * n_q_heads + h) * head_dim;
+            /* logits over the concatenation [K | K-hat] */
+            double smax = -INFINITY;
+            for (int j = 0; j < Tk; ++j) {
+                const int is_local = j < Tq;
+                const int jj = is_local ? j : j - Tq;
+                allowed[j] = !causal ? 1 : (is_local ? (jj <= i) : (jj < n_before));
+                if (!allowed[j]) continue;
+                const double* kj = (is_local ? k_loc : k_hat) + ((int64_t)jj * n_kv_heads + hk) * head_dim;
+                double dot = 0.0;
+                for (int d = 0; d < head_dim; ++d) dot += qi[d] * kj[d];
+                s[j] = dot * scale;
+                if (s[j] > smax) smax = s[j];
+            }
+            double denom = 0.0;
+            for (int j = 0; j < Tk; ++j)
+                if (allowed[j]) { s[j] = exp(s[j] - smax); denom += s[j]; }
+            double* o = out + ((int64_t)i * n_q_heads + h) * head_dim;
+            for (int d = 0; d < head_dim; ++d) o[d] = 0.0;
+            for (int j = 0; j < Tk; ++j) {
+                const double p = allowed[j] ? s[j] / denom : 0.0;
+                if (probs) probs[((int64_t)h * Tq + i) * Tk + j] = p;
+                if (!allowed[j]) continue;
+                const int is_local = j < Tq;
+                const int jj = is_local ? j : j - Tq;
+                const double* vj = (is_local ? v_loc : v_hat) + ((int64_t)jj * n_kv_heads + hk) * head_dim;
+                for (int d = 0; d < head_dim; ++d) o[d] += p * vj[d];
+            }
+            if (lse) lse[(int64_t)h * Tq + i] = smax + log(denom);
+        }
+        free(s);
+        free(allowed);
+    }
+    return 0;
+}
+
+/* One Astra attention layer on one device (Sec. 3.1):
+ *   codes_local = encode(content rows of x_local)        -> what this device transmits
+ *   X-hat       = decode(codes_nonlocal)                  -> what it rebuilds from its peers
+ *   Q, K, V     = x_local W_q, x_local W_k, x_local W_v   (full precision)
+ *   K-hat,V-hat = X-hat W_k, X-hat W_v                     (same weights)
+ *   Y           = Attn(Q, K, K-hat, V, V-hat) W_o
+ * x_local [T_q, D] with the class row (if any) first; weights [D_in, D_out];
+ * biases nullable.  y [T_q, D] double, codes_local [n_local, G], gap nullable. */
+int oracle_layer_forward(const float* x_local, const int32_t* codes_nonlocal,
+                         const float* codebook, int D, int G, int K,
+                         const float* wq, const float* wk, const float* wv, const float* wo,
+                         const float* bq, const float* bk, const float* bv, const float* bo,
+                         int n_q_heads, int n_kv_heads, int head_dim,
+                         int n_cls, int n_local, int n_nonlocal,
+                         int causal, int n_before, double scale,
+                         double* y, int32_t* codes_local, double* gap_local) {
+    const int Tq = n_cls + n_local, Tn = n_nonlocal;
+    const int dq = n_q_heads * head_dim, dkv = n_kv_heads * head_dim;
+    int rc = oracle_vq_encode(x_local + (int64_t)n_cls * D, n_local, D, G, K, codebook,
+                              codes_local, gap_local);
+    if (rc) return rc;
+
+    float* x_hat = (float*)malloc(sizeof(float) * ((int64_t)Tn * D + 1));
+    rc = oracle_vq_decode(codes_nonlocal, Tn, D, G, K, codebook, x_hat);
+    if (rc) { free(x_hat); return rc; }
+
+    double* xl = (double*)malloc(sizeof(double) * ((int64_t)Tq * D + 1));
+    double* xh = (double*)malloc(sizeof(double) * ((int64_t)Tn * D + 1));
+    for (int64_t i = 0; i < (int64_t)Tq * D; ++i) xl[i] = (double)x_local[i];
+    for (int64_t i = 0; i < (int64_t)Tn * D; ++i) xh[i] = (double)x_hat[i];
+    double* Q = (double*)malloc(sizeof(double) * ((int64_t)Tq * dq + 1));
+    double* Kl = (double*)malloc(sizeof(double) * ((int64_t)Tq * dkv + 1));
+    double* Vl = (double*)malloc(sizeof(double) * ((int64_t)Tq * dkv + 1));
+    double* Kh = (double*)malloc(sizeof(double) * ((int64_t)Tn * dkv + 1));
+    double* Vh = (double*)malloc(sizeof(double) * ((int64_t)Tn * dkv + 1));
+    double* O = (double*)malloc(sizeof(double) * ((int64_t)Tq * dq + 1));
+    oracle_linear(xl, Tq, D, dq, wq, bq, Q);
+    oracle_linear(xl, Tq, D, dkv, wk, bk, Kl);
+    oracle_linear(xl, Tq, D, dkv, wv, bv, Vl);
+    oracle_linear(xh, Tn, D, dkv, wk, bk, Kh);
+    oracle_linear(xh, Tn, D, dkv, wv, bv, Vh);
+    rc = oracle_mixed_attention(Q, Kl, Vl, Kh, Vh, n_q_heads, n_kv_heads, head_dim,
+                                n_cls, n_local, n_nonlocal, causal, n_before, scale,
+                                O, NULL, NULL);
+    if (!rc) oracle_linear(O, Tq, dq, D, wo, bo, y);
+    free(x_hat); free(xl); free(xh); free(Q); free(Kl); free(Vl); free(Kh); free(Vh); free(O);
+    return rc;
+}

@@ -1,0 +1,161 @@
+#!/usr/bin/env python3
+"""Benchmark of one device's Astra attention layer on one MI355X.
+
+A step is one astra_layer_forward call: grouped VQ encode of the local rows, K-hat/V-hat projection of
+the rows rebuilt from the peers' codes (decode fused into the operand load), Q/K/V projection of the
+local rows, mixed-precision attention (Eq. 1) and the output projection.  Inputs are seeded synthetic
+tensors already resident in HBM; the peers' codes are produced by the library's own encode.  Prints
+ONE JSON line: tokens/s per layer (local rows per second), the MFMA roofline of the dominant kernel
+(the grouped projection GEMM) from HIP-event stage timing, and the CPU oracle timed on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}       # MI355X dense MFMA peaks
+STAGES = ("vq_encode", "projections", "attention", "out_projection")
+
+
+def layer_flops(cfg, n_before):
+    """Algorithmic FLOPs of one call, per stage (masked-out causal work is not counted)."""
+    D, dq, dkv, dh = cfg.d_model, cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim, cfg.head_dim
+    tl, tq = cfg.n_local, cfg.n_local + cfg.n_cls
+    t_vis = n_before if cfg.causal else cfg.n_nonlocal
+    pairs = tl * t_vis + tl * (tl + 1) // 2 if cfg.causal else tq * (tq + t_vis)
+    return {
+        "vq_encode": 2.0 * tl * cfg.codebook_size * D,
+        "projections": 2.0 * D * (tq * (dq + 2 * dkv) + t_vis * 2 * dkv),
+        "attention": 4.0 * dh * cfg.n_q_heads * pairs,
+        "out_projection": 2.0 * tq * dq * D,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="llama3_8b_bf16")
+    ap.add_argument("--rank", type=int, default=-1, help="simulated device (default: last = critical path under causal masking)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one device's share on ONE GPU; the exchange of codes between devices is not "
+              "part of this build, so --gpus must be 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2505_19342_amd import binding as B
+    from paper_2505_19342_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("no GPU visible: the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+    B.load(build_if_missing=True)
+    dev = "cuda:0"
+    cfg = wl.CONFIGS[args.workload]
+    rank = args.rank if args.rank >= 0 else cfg.n_dev - 1
+    data = wl.generate(cfg)
+    view = wl.device_view(cfg, data, rank)
+    dt = cfg.dtype
+    G, K, D = cfg.n_groups, cfg.codebook_size, cfg.d_model
+
+    def to_dev(a):
+        a = np.ascontiguousarray(a, dtype=np.float32)
+        if dt == "bf16":
+            return torch.from_numpy(wl.bf16_bits(a).view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(a).to(dev)
+
+    code_t = torch.uint8 if K <= 256 else torch.int16
+    vq = B.vq_desc(dt, D, G, K)
+    codebook = to_dev(data["codebook"])
+    cnorm = torch.empty((G, K), dtype=torch.float32, device=dev)
+    B.astra_vq_prepare(vq, codebook, cnorm)
+    # the peers' codes: encode their rows with the library itself (what they would have transmitted)
+    x_nl = to_dev(view["x_nonlocal"])
+    tn = x_nl.shape[0]
+    codes_nl = torch.empty((tn, G), dtype=code_t, device=dev)
+    B.astra_vq_encode(vq, x_nl, tn, codebook, cnorm, codes_nl)
+    del x_nl
+    x_local = to_dev(view["x_local"])
+    tq = x_local.shape[0]
+    desc = B.LayerDesc(vq, B.attn_desc(dt, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n_cls, tq - cfg.n_cls, tn,
+                                       cfg.causal, view["n_before"]))
+    w = [to_dev(np.ascontiguousarray(data[n].T)) for n in ("wq", "wk", "wv", "wo")]
+    y = torch.empty((tq, D), dtype=torch.float32, device=dev)
+    codes_local = torch.empty((tq - cfg.n_cls, G), dtype=code_t, device=dev)
+    ws = torch.empty(max(B.astra_layer_workspace_bytes(desc), 256), dtype=torch.uint8, device=dev)
+    call_args = (desc, x_local, codes_nl, codebook, cnorm, *w, None, None, None, None, y, codes_local, ws)
+
+    for _ in range(args.warmup):
+        B.astra_layer_forward(*call_args)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly `steps` calls, stage boundaries marked with HIP events on the launch stream
+    events = [B.HipEvents(5) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        B.astra_layer_forward_profiled(*call_args, events[i].handles)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    stage_ms = {s: float(np.mean([ev.elapsed_ms(j, j + 1) for ev in events])) for j, s in enumerate(STAGES)}
+    gpu_ms = float(np.mean([ev.elapsed_ms(0, 4) for ev in events]))
+
+    flops = layer_flops(cfg, view["n_before"])
+    total_flops = sum(flops.values())
+    peak = PEAK_TFLOPS[dt]
+    dom = "projections"
+    achieved = flops[dom] / (stage_ms[dom] * 1e-3) / 1e12
+    result = {
+        "metric": "tokens/sec per layer (VQ encode + mixed attention) and % of MFMA roofline",
+        "value": tq / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": dt, "data": "synthetic",
+        "config": {"workload": cfg.name, "rank": rank, "n_dev": cfg.n_dev, "local_rows": tq, "nonlocal_rows": tn,
+                   "visible_nonlocal_rows": view["n_before"] if cfg.causal else tn, "d_model": D,
+                   "heads": [cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim], "vq": {"G": G, "K": K, "dg": cfg.group_dim},
+                   "causal": cfg.causal, "seed": cfg.seed},
+        "layer_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
+        "layer_mfma_frac": total_flops / (ms_per_step * 1e-3) / 1e12 / peak,
+        "gpu_ms_per_step_events": gpu_ms,
+        "stage_us": {s: stage_ms[s] * 1e3 for s in STAGES},
+        "stage_tflops": {s: flops[s] / (stage_ms[s] * 1e-3) / 1e12 for s in STAGES},
+        "roofline": {"kernel": "gemm_nt_bf16_kernel (grouped Q/K/V/K-hat/V-hat projections)" if dt == "bf16"
+                     else "gemm_nt_f32_kernel (grouped projections)",
+                     "bound": "mfma" if dt == "bf16" else "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                     "frac": achieved / peak, "traffic": None},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        codes_nl_host = codes_nl.cpu().numpy()
+        if K > 256:
+            codes_nl_host = codes_nl_host.view(np.uint16)
+        oracle.num_threads()            # load outside the timed part
+        c0 = time.perf_counter()
+        oracle.layer_forward(view["x_local"], codes_nl_host.astype(np.int32), data["codebook"], data["wq"], data["wk"],
+                             data["wv"], data["wo"], n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, n_cls=cfg.n_cls,
+                             causal=cfg.causal, n_before=view["n_before"])
+        c1 = time.perf_counter()
+        result["cpu_baseline"] = {"value": tq / (c1 - c0), "unit": "tokens/s", "cores": oracle.num_threads(),
+                                  "kind": "oracle", "sample": f"one whole layer call of the same workload ({tq} local rows), "
+                                  f"{c1 - c0:.2f} s, fp64 C/OpenMP oracle"}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,153 @@
+/*
+ * astra.h -- C ABI of the MI355X (gfx950) library for one device's share of an
+ * Astra attention layer (arXiv 2505.19342): grouped vector-quantisation encode of
+ * the device's local token embeddings, codebook-gather decode of its peers' codes,
+ * and mixed-precision attention of local queries over full-precision local K/V
+ * plus K/V projected from the decoded tokens.
+ *
+ * Conventions (all entry points)
+ *   - Every data pointer is a DEVICE pointer to a dense row-major array, 16-byte
+ *     aligned, owned by the caller.  The library allocates nothing, frees nothing
+ *     and keeps no pointer after a call returns; scratch comes from `workspace`.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     only enqueue work: they never synchronise, and the outputs are ready when the
+ *     stream reaches that point.  Calls on distinct streams may overlap.
+ *   - The return value is an astra_status.  Argument, shape and dtype errors are
+ *     found on the host before anything is launched and leave outputs untouched; a
+ *     failed launch returns ASTRA_ERR_HIP.  There is no CPU fallback.
+ *   - Element type (`dtype`): ASTRA_F32, or ASTRA_BF16 (bf16 storage, fp32
+ *     accumulation; products of two bf16 values are exact in fp32).
+ *   - Codes are unpacked unsigned integers, one per (token, group): uint8 when
+ *     K <= 256 (ASTRA_CODE_U8) or uint16 (ASTRA_CODE_U16, any K <= 65536).
+ *   - Linear weights are stored [out_features, in_features] (the storage order of a
+ *     framework linear layer): the paper's Q = X W_q is computed as x . wq^T with
+ *     wq of shape [H_q*dh, D].  Both matrix-core operands are then contiguous along
+ *     the contraction axis.
+ *   - Zero sizes (n_tokens == 0, n_nonlocal == 0) are valid and launch nothing for
+ *     the empty part.
+ */
+#ifndef ASTRA_H
+#define ASTRA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ASTRA_OK = 0,
+    ASTRA_ERR_NULL = -1,        /* a required pointer is NULL */
+    ASTRA_ERR_SHAPE = -2,       /* sizes inconsistent or out of the supported range */
+    ASTRA_ERR_DTYPE = -3,       /* unknown dtype / code type, or code type too narrow for K */
+    ASTRA_ERR_WORKSPACE = -4,   /* workspace NULL or smaller than astra_layer_workspace_bytes */
+    ASTRA_ERR_UNSUPPORTED = -5, /* valid request this build has no kernel for */
+    ASTRA_ERR_HIP = -6          /* the HIP runtime refused a launch */
+} astra_status;
+
+enum { ASTRA_F32 = 0, ASTRA_BF16 = 1 };
+enum { ASTRA_CODE_U8 = 0, ASTRA_CODE_U16 = 1 };
+
+/* Grouped VQ (Sec. 2, "Grouped VQ"): the D-vector is cut into G contiguous
+ * slices of dg = D / G values; slice g has its own codebook of K codewords. */
+typedef struct {
+    int32_t dtype;          /* element type of x, codebook, x_hat */
+    int32_t code_type;      /* ASTRA_CODE_U8 requires codebook_size <= 256 */
+    int32_t d_model;        /* D */
+    int32_t n_groups;       /* G, must divide D */
+    int32_t codebook_size;  /* K, 1 .. 65536 */
+} astra_vq_desc;
+
+/* Mixed-precision attention (Sec. 3.2, Eq. 1) for one device. */
+typedef struct {
+    int32_t dtype;
+    int32_t n_q_heads;          /* H_q */
+    int32_t n_kv_heads;         /* H_kv, divides H_q; query head h uses KV head h / (H_q / H_kv) */
+    int32_t head_dim;           /* dh: 64 or 128 for bf16; any multiple of 4 up to 256 for f32 */
+    int32_t n_cls;              /* 0 | 1 class-token replica, first row of the local block (Sec. 3.3);
+                                   must be 0 when causal */
+    int32_t n_local;            /* T_l content rows; local rows T_q = n_cls + n_local */
+    int32_t n_nonlocal;         /* T_n rows rebuilt from codes */
+    int32_t causal;             /* 0 | 1 */
+    int32_t n_nonlocal_before;  /* causal only: non-local rows [0, nb) precede the local chunk in the
+                                   sequence (all visible), rows [nb, T_n) follow it (all hidden) */
+    float scale;                /* logit scale; 0 means 1 / sqrt(head_dim) */
+} astra_attn_desc;
+
+typedef struct {
+    astra_vq_desc vq;
+    astra_attn_desc attn;       /* attn.dtype must equal vq.dtype; H_q*dh need not equal D */
+} astra_layer_desc;
+
+/* ||c||^2 of every codeword, the codeword-only term of the expanded distance
+ * ||x - c||^2 = ||x||^2 - 2 x.c + ||c||^2 (Sec. 2, "Vanilla VQ").  Run once per
+ * codebook.  codebook [G, K, dg] -> cnorm_out [G, K] fp32. */
+int astra_vq_prepare(const astra_vq_desc* desc, const void* codebook, float* cnorm_out, void* stream);
+
+/* Grouped VQ encode (Sec. 2): codes_out[t, g] = argmin_k || x[t, g*dg:(g+1)*dg] - codebook[g, k, :] ||^2,
+ * the lowest k among exact ties.  x [n_tokens, D]; cnorm [G, K] from astra_vq_prepare for the same
+ * codebook; codes_out [n_tokens, G] of desc->code_type.  The comparison is carried out in fp32 on
+ * x.c - ||c||^2 / 2, so a code can differ from exact arithmetic only where the best and second-best
+ * distances agree to fp32 rounding. */
+int astra_vq_encode(const astra_vq_desc* desc, const void* x, int64_t n_tokens, const void* codebook,
+                    const float* cnorm, void* codes_out, void* stream);
+
+/* VQ decode (Sec. 3.2, "Vector-Quantized Non-Local Tokens"): x_hat_out[t, g*dg:(g+1)*dg] =
+ * codebook[g, codes[t, g], :], a bit-exact copy.  A code >= K is a caller error; it is read as K-1
+ * so that no access leaves the codebook. */
+int astra_vq_decode(const astra_vq_desc* desc, const void* codes, int64_t n_tokens, const void* codebook,
+                    void* x_hat_out, void* stream);
+
+/* Mixed-precision attention (Eq. 1): out = softmax(q [k_local | k_hat]^T * scale) [v_local | v_hat]
+ * per query head over the keys a row may see (all of them, or under `causal` the local rows j <= i and
+ * the non-local rows before the chunk).  q, out [T_q, H_q, dh]; k_local, v_local [T_q, H_kv, dh];
+ * k_hat, v_hat [T_n, H_kv, dh] (may be NULL when T_n == 0); lse_out nullable [H_q, T_q] fp32, the
+ * natural-log softmax denominator (including the row maximum). */
+int astra_mixed_attention(const astra_attn_desc* desc, const void* q,
+                          const void* k_local, const void* v_local,
+                          const void* k_hat, const void* v_hat,
+                          void* out, float* lse_out, void* stream);
+
+/* Scratch bytes astra_layer_forward needs for this shape (0 on an invalid descriptor). */
+size_t astra_layer_workspace_bytes(const astra_layer_desc* desc);
+
+/* One Astra attention layer on one device (Sec. 3.1): encode the local content rows (the indices
+ * this device would transmit), rebuild the peers' tokens from their codes, project local rows to
+ * Q, K, V and rebuilt rows to K-hat, V-hat with the same weights, attend (Eq. 1), apply W_o.
+ *   x_local         [T_q, D], class row first when n_cls == 1 (it is not encoded)
+ *   codes_nonlocal  [T_n, G] in sequence order (rows before the local chunk first)
+ *   codebook, cnorm as for astra_vq_encode
+ *   wq [H_q*dh, D]; wk, wv [H_kv*dh, D]; wo [D, H_q*dh]; biases bq [H_q*dh], bk, bv [H_kv*dh],
+ *   bo [D], each nullable
+ *   y_out           [T_q, D] fp32 for BOTH element types: the output projection's fp32 accumulator is
+ *                   stored unrounded (a bf16 store alone would cost |y| * 2^-9 of accuracy)
+ *   codes_local_out [T_l, G]
+ *   workspace       at least astra_layer_workspace_bytes(desc) bytes, 256-byte aligned
+ * No residual, normalisation or positional encoding is applied. */
+int astra_layer_forward(const astra_layer_desc* desc, const void* x_local, const void* codes_nonlocal,
+                        const void* codebook, const float* cnorm,
+                        const void* wq, const void* wk, const void* wv, const void* wo,
+                        const void* bq, const void* bk, const void* bv, const void* bo,
+                        void* y_out, void* codes_local_out,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* astra_layer_forward with stage timing for benchmarks: identical work and results, and in addition
+ * stage_events[0..4] (five hipEvent_t created by the caller with timing enabled, passed as void*; a
+ * NULL entry is skipped) are recorded on `stream` before the encode and after the encode, the
+ * Q/K/V/K-hat/V-hat projections, the attention and the output projection (Sec. 3.1 order). */
+int astra_layer_forward_profiled(const astra_layer_desc* desc, const void* x_local, const void* codes_nonlocal,
+                                 const void* codebook, const float* cnorm,
+                                 const void* wq, const void* wk, const void* wv, const void* wo,
+                                 const void* bq, const void* bk, const void* bv, const void* bo,
+                                 void* y_out, void* codes_local_out,
+                                 void* workspace, size_t workspace_bytes, void* stream,
+                                 void* const* stage_events);
+
+const char* astra_status_string(int status);
+int astra_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ASTRA_H */

@@ -1,0 +1,179 @@
+"""ctypes binding of libastra_hip.so (include/astra.h).  Argument marshalling only: every step runs
+in the HIP kernels.  Tensors are torch CUDA(ROCm) tensors used purely as device memory; the current
+torch stream is handed to the library.  There is no CPU fallback: a missing library raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+ASTRA_F32, ASTRA_BF16 = 0, 1
+ASTRA_CODE_U8, ASTRA_CODE_U16 = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libastra_hip.so")
+_lib = None
+
+EXPORTS = ("astra_vq_prepare", "astra_vq_encode", "astra_vq_decode", "astra_mixed_attention",
+           "astra_layer_workspace_bytes", "astra_layer_forward", "astra_layer_forward_profiled",
+           "astra_status_string", "astra_version")
+
+
+class AstraError(RuntimeError):
+    pass
+
+
+class VqDesc(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("code_type", ctypes.c_int32), ("d_model", ctypes.c_int32),
+                ("n_groups", ctypes.c_int32), ("codebook_size", ctypes.c_int32)]
+
+
+class AttnDesc(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("n_cls", ctypes.c_int32), ("n_local", ctypes.c_int32),
+                ("n_nonlocal", ctypes.c_int32), ("causal", ctypes.c_int32), ("n_nonlocal_before", ctypes.c_int32),
+                ("scale", ctypes.c_float)]
+
+
+class LayerDesc(ctypes.Structure):
+    _fields_ = [("vq", VqDesc), ("attn", AttnDesc)]
+
+
+def load(build_if_missing: bool = True):
+    """Load the built library (building it first only if no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        if not build_if_missing:
+            raise AstraError(f"{LIB_PATH} is not built; run paper_2505_19342_amd/build.py")
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, f32p = ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p
+    lib.astra_vq_prepare.argtypes = [ctypes.POINTER(VqDesc), vp, f32p, vp]
+    lib.astra_vq_encode.argtypes = [ctypes.POINTER(VqDesc), vp, i64, vp, f32p, vp, vp]
+    lib.astra_vq_decode.argtypes = [ctypes.POINTER(VqDesc), vp, i64, vp, vp, vp]
+    lib.astra_mixed_attention.argtypes = [ctypes.POINTER(AttnDesc)] + [vp] * 8
+    lib.astra_layer_workspace_bytes.argtypes = [ctypes.POINTER(LayerDesc)]
+    lib.astra_layer_workspace_bytes.restype = ctypes.c_size_t
+    lib.astra_layer_forward.argtypes = [ctypes.POINTER(LayerDesc)] + [vp] * 15 + [ctypes.c_size_t, vp]
+    lib.astra_layer_forward_profiled.argtypes = [ctypes.POINTER(LayerDesc)] + [vp] * 15 + [ctypes.c_size_t, vp,
+                                                                                     ctypes.POINTER(ctypes.c_void_p)]
+    lib.astra_status_string.argtypes = [ctypes.c_int]
+    lib.astra_status_string.restype = ctypes.c_char_p
+    lib.astra_version.restype = ctypes.c_int
+    for name in EXPORTS[:4] + ("astra_layer_forward", "astra_layer_forward_profiled"):
+        getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise AstraError(f"{what}: {load().astra_status_string(rc).decode()} ({rc})")
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise AstraError("device tensor required")
+    if not t.is_contiguous():
+        raise AstraError("contiguous tensor required")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def astra_version() -> int:
+    return int(load().astra_version())
+
+
+def astra_vq_prepare(desc: VqDesc, codebook, cnorm_out):
+    _check(load().astra_vq_prepare(ctypes.byref(desc), _ptr(codebook), _ptr(cnorm_out), _stream()), "astra_vq_prepare")
+
+
+def astra_vq_encode(desc: VqDesc, x, n_tokens: int, codebook, cnorm, codes_out):
+    _check(load().astra_vq_encode(ctypes.byref(desc), _ptr(x), n_tokens, _ptr(codebook), _ptr(cnorm), _ptr(codes_out),
+                                  _stream()), "astra_vq_encode")
+
+
+def astra_vq_decode(desc: VqDesc, codes, n_tokens: int, codebook, x_hat_out):
+    _check(load().astra_vq_decode(ctypes.byref(desc), _ptr(codes), n_tokens, _ptr(codebook), _ptr(x_hat_out), _stream()),
+           "astra_vq_decode")
+
+
+def astra_mixed_attention(desc: AttnDesc, q, k_local, v_local, k_hat, v_hat, out, lse_out=None):
+    _check(load().astra_mixed_attention(ctypes.byref(desc), _ptr(q), _ptr(k_local), _ptr(v_local), _ptr(k_hat), _ptr(v_hat),
+                                        _ptr(out), _ptr(lse_out), _stream()), "astra_mixed_attention")
+
+
+def astra_layer_workspace_bytes(desc: LayerDesc) -> int:
+    return int(load().astra_layer_workspace_bytes(ctypes.byref(desc)))
+
+
+def astra_layer_forward(desc: LayerDesc, x_local, codes_nonlocal, codebook, cnorm, wq, wk, wv, wo,
+                        bq, bk, bv, bo, y_out, codes_local_out, workspace):
+    nbytes = workspace.numel() * workspace.element_size()
+    _check(load().astra_layer_forward(ctypes.byref(desc), _ptr(x_local), _ptr(codes_nonlocal), _ptr(codebook), _ptr(cnorm),
+                                      _ptr(wq), _ptr(wk), _ptr(wv), _ptr(wo), _ptr(bq), _ptr(bk), _ptr(bv), _ptr(bo),
+                                      _ptr(y_out), _ptr(codes_local_out), _ptr(workspace), nbytes, _stream()),
+           "astra_layer_forward")
+
+
+def astra_layer_forward_profiled(desc: LayerDesc, x_local, codes_nonlocal, codebook, cnorm, wq, wk, wv, wo,
+                                 bq, bk, bv, bo, y_out, codes_local_out, workspace, stage_events):
+    """stage_events: a ctypes array of 5 hipEvent_t handles (see HipEvents)."""
+    nbytes = workspace.numel() * workspace.element_size()
+    _check(load().astra_layer_forward_profiled(
+        ctypes.byref(desc), _ptr(x_local), _ptr(codes_nonlocal), _ptr(codebook), _ptr(cnorm),
+        _ptr(wq), _ptr(wk), _ptr(wv), _ptr(wo), _ptr(bq), _ptr(bk), _ptr(bv), _ptr(bo),
+        _ptr(y_out), _ptr(codes_local_out), _ptr(workspace), nbytes, _stream(), stage_events),
+        "astra_layer_forward_profiled")
+
+
+class HipEvents:
+    """n timing-enabled hipEvent_t created through the HIP runtime itself (no torch objects), for the
+    profiled entry point.  elapsed_ms(i, j) is valid after the stream has been synchronised."""
+
+    def __init__(self, n: int):
+        self._hip = ctypes.CDLL("libamdhip64.so")
+        self._hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self._hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self._hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.handles = (ctypes.c_void_p * n)()
+        for i in range(n):
+            ev = ctypes.c_void_p()
+            if self._hip.hipEventCreate(ctypes.byref(ev)) != 0:
+                raise AstraError("hipEventCreate failed")
+            self.handles[i] = ev
+
+    def elapsed_ms(self, i: int, j: int) -> float:
+        ms = ctypes.c_float()
+        if self._hip.hipEventElapsedTime(ctypes.byref(ms), self.handles[i], self.handles[j]) != 0:
+            raise AstraError("hipEventElapsedTime failed")
+        return float(ms.value)
+
+    def __del__(self):
+        try:
+            for h in self.handles:
+                if h:
+                    self._hip.hipEventDestroy(h)
+        except Exception:
+            pass
+
+
+# ---- descriptor helpers (pure bookkeeping) ------------------------------------------------------
+
+def vq_desc(dtype: str, d_model: int, n_groups: int, codebook_size: int) -> VqDesc:
+    return VqDesc(ASTRA_BF16 if dtype == "bf16" else ASTRA_F32,
+                  ASTRA_CODE_U8 if codebook_size <= 256 else ASTRA_CODE_U16, d_model, n_groups, codebook_size)
+
+
+def attn_desc(dtype: str, n_q_heads: int, n_kv_heads: int, head_dim: int, n_cls: int, n_local: int, n_nonlocal: int,
+              causal: bool, n_before: int = 0, scale: float = 0.0) -> AttnDesc:
+    return AttnDesc(ASTRA_BF16 if dtype == "bf16" else ASTRA_F32, n_q_heads, n_kv_heads, head_dim, n_cls, n_local,
+                    n_nonlocal, int(bool(causal)), n_before if causal else 0, scale)

@@ -1,0 +1,227 @@
+// C ABI of the library: argument checking and the per-layer orchestration (paper Sec. 3.1).
+#include "common.h"
+
+namespace astra {
+
+int check_vq_desc(const astra_vq_desc* d) {
+    if (!d) return ASTRA_ERR_NULL;
+    if (d->dtype != ASTRA_F32 && d->dtype != ASTRA_BF16) return ASTRA_ERR_DTYPE;
+    if (d->code_type != ASTRA_CODE_U8 && d->code_type != ASTRA_CODE_U16) return ASTRA_ERR_DTYPE;
+    if (d->d_model <= 0 || d->n_groups <= 0 || d->codebook_size <= 0) return ASTRA_ERR_SHAPE;
+    if (d->d_model % d->n_groups != 0) return ASTRA_ERR_SHAPE;
+    if (d->codebook_size > 65536) return ASTRA_ERR_SHAPE;
+    if (d->code_type == ASTRA_CODE_U8 && d->codebook_size > 256) return ASTRA_ERR_DTYPE;
+    return ASTRA_OK;
+}
+
+int check_attn_desc(const astra_attn_desc* d) {
+    if (!d) return ASTRA_ERR_NULL;
+    if (d->dtype != ASTRA_F32 && d->dtype != ASTRA_BF16) return ASTRA_ERR_DTYPE;
+    if (d->n_q_heads <= 0 || d->n_kv_heads <= 0 || d->head_dim <= 0) return ASTRA_ERR_SHAPE;
+    if (d->n_q_heads % d->n_kv_heads != 0 || d->n_q_heads > 65535) return ASTRA_ERR_SHAPE;
+    if (d->n_cls < 0 || d->n_cls > 1 || d->n_local < 0 || d->n_nonlocal < 0) return ASTRA_ERR_SHAPE;
+    if (d->causal != 0 && d->causal != 1) return ASTRA_ERR_SHAPE;
+    if (d->causal && (d->n_cls != 0 || d->n_nonlocal_before < 0 || d->n_nonlocal_before > d->n_nonlocal)) return ASTRA_ERR_SHAPE;
+    if (!(d->scale >= 0.f)) return ASTRA_ERR_SHAPE;
+    if ((int64_t)d->n_cls + d->n_local > (1 << 30) || d->n_nonlocal > (1 << 30)) return ASTRA_ERR_SHAPE;
+    if (d->dtype == ASTRA_BF16) {
+        if (d->head_dim != 64 && d->head_dim != 128) return ASTRA_ERR_UNSUPPORTED;
+    } else {
+        if (d->head_dim > 256) return ASTRA_ERR_UNSUPPORTED;
+    }
+    return ASTRA_OK;
+}
+
+struct LayerPlan {
+    int Tq, Tn, Tn_vis, D, dq, dkv;
+    bool need_xhat;
+    size_t off_q, off_k, off_v, off_kh, off_vh, off_o, off_xhat, total;
+};
+
+static int make_plan(const astra_layer_desc* desc, LayerPlan* pl) {
+    if (!desc) return ASTRA_ERR_NULL;
+    int rc = check_vq_desc(&desc->vq);
+    if (rc) return rc;
+    rc = check_attn_desc(&desc->attn);
+    if (rc) return rc;
+    if (desc->vq.dtype != desc->attn.dtype) return ASTRA_ERR_DTYPE;
+    const astra_attn_desc& a = desc->attn;
+    const int eb = elem_bytes(desc->vq.dtype);
+    pl->Tq = a.n_cls + a.n_local;
+    pl->Tn = a.n_nonlocal;
+    pl->Tn_vis = a.causal ? a.n_nonlocal_before : a.n_nonlocal;
+    pl->D = desc->vq.d_model;
+    pl->dq = a.n_q_heads * a.head_dim;
+    pl->dkv = a.n_kv_heads * a.head_dim;
+    const int dg = pl->D / desc->vq.n_groups;
+    if (desc->vq.dtype == ASTRA_BF16 && (pl->D % 8 != 0)) return ASTRA_ERR_UNSUPPORTED;
+    pl->need_xhat = desc->vq.dtype == ASTRA_BF16 && (dg % 8 != 0);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    pl->off_q = take((size_t)pl->Tq * pl->dq * eb);
+    pl->off_k = take((size_t)pl->Tq * pl->dkv * eb);
+    pl->off_v = take((size_t)pl->Tq * pl->dkv * eb);
+    pl->off_kh = take((size_t)pl->Tn_vis * pl->dkv * eb);
+    pl->off_vh = take((size_t)pl->Tn_vis * pl->dkv * eb);
+    pl->off_o = take((size_t)pl->Tq * pl->dq * eb);
+    pl->off_xhat = take(pl->need_xhat ? (size_t)pl->Tn_vis * pl->D * eb : 0);
+    pl->total = off > 0 ? off : 256;
+    return ASTRA_OK;
+}
+
+}  // namespace astra
+
+using namespace astra;
+
+extern "C" {
+
+int astra_version(void) { return 100; }
+
+const char* astra_status_string(int status) {
+    switch (status) {
+        case ASTRA_OK: return "ok";
+        case ASTRA_ERR_NULL: return "required pointer is NULL";
+        case ASTRA_ERR_SHAPE: return "inconsistent or out-of-range sizes";
+        case ASTRA_ERR_DTYPE: return "bad element or code type";
+        case ASTRA_ERR_WORKSPACE: return "workspace missing or too small";
+        case ASTRA_ERR_UNSUPPORTED: return "no kernel for this configuration";
+        case ASTRA_ERR_HIP: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+int astra_vq_prepare(const astra_vq_desc* desc, const void* codebook, float* cnorm_out, void* stream) {
+    int rc = check_vq_desc(desc);
+    if (rc) return rc;
+    if (!codebook || !cnorm_out) return ASTRA_ERR_NULL;
+    return launch_vq_prepare(*desc, codebook, cnorm_out, (hipStream_t)stream);
+}
+
+int astra_vq_encode(const astra_vq_desc* desc, const void* x, int64_t n_tokens, const void* codebook,
+                    const float* cnorm, void* codes_out, void* stream) {
+    int rc = check_vq_desc(desc);
+    if (rc) return rc;
+    if (n_tokens < 0) return ASTRA_ERR_SHAPE;
+    if (n_tokens == 0) return ASTRA_OK;
+    if (!x || !codebook || !cnorm || !codes_out) return ASTRA_ERR_NULL;
+    return launch_vq_encode(*desc, x, desc->d_model, n_tokens, codebook, cnorm, codes_out, (hipStream_t)stream);
+}
+
+int astra_vq_decode(const astra_vq_desc* desc, const void* codes, int64_t n_tokens, const void* codebook,
+                    void* x_hat_out, void* stream) {
+    int rc = check_vq_desc(desc);
+    if (rc) return rc;
+    if (n_tokens < 0) return ASTRA_ERR_SHAPE;
+    if (n_tokens == 0) return ASTRA_OK;
+    if (!codes || !codebook || !x_hat_out) return ASTRA_ERR_NULL;
+    return launch_vq_decode(*desc, codes, n_tokens, codebook, x_hat_out, (hipStream_t)stream);
+}
+
+int astra_mixed_attention(const astra_attn_desc* desc, const void* q, const void* k_local, const void* v_local,
+                          const void* k_hat, const void* v_hat, void* out, float* lse_out, void* stream) {
+    int rc = check_attn_desc(desc);
+    if (rc) return rc;
+    if (desc->n_cls + desc->n_local == 0) return ASTRA_OK;
+    if (!q || !k_local || !v_local || !out) return ASTRA_ERR_NULL;
+    const int vis = desc->causal ? desc->n_nonlocal_before : desc->n_nonlocal;
+    if (vis > 0 && (!k_hat || !v_hat)) return ASTRA_ERR_NULL;
+    return launch_attention(*desc, q, k_local, v_local, k_hat, v_hat, out, lse_out, (hipStream_t)stream);
+}
+
+size_t astra_layer_workspace_bytes(const astra_layer_desc* desc) {
+    LayerPlan pl;
+    if (make_plan(desc, &pl) != ASTRA_OK) return 0;
+    return pl.total;
+}
+
+static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local, const void* codes_nonlocal,
+                              const void* codebook, const float* cnorm,
+                              const void* wq, const void* wk, const void* wv, const void* wo,
+                              const void* bq, const void* bk, const void* bv, const void* bo,
+                              void* y_out, void* codes_local_out, void* workspace, size_t workspace_bytes, void* stream,
+                              void* const* ev) {
+    LayerPlan pl;
+    int rc = make_plan(desc, &pl);
+    if (rc) return rc;
+    const astra_vq_desc& vq = desc->vq;
+    const astra_attn_desc& at = desc->attn;
+    if (pl.Tq == 0) return ASTRA_OK;
+    if (!x_local || !codebook || !cnorm || !wq || !wk || !wv || !wo || !y_out) return ASTRA_ERR_NULL;
+    if (at.n_local > 0 && !codes_local_out) return ASTRA_ERR_NULL;
+    if (pl.Tn_vis > 0 && !codes_nonlocal) return ASTRA_ERR_NULL;
+    if (!workspace || workspace_bytes < pl.total) return ASTRA_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    auto mark = [&](int i) { if (ev && ev[i]) (void)hipEventRecord((hipEvent_t)ev[i], s); };
+    mark(0);
+    const int eb = elem_bytes(vq.dtype);
+    char* ws = (char*)workspace;
+    void *Q = ws + pl.off_q, *K = ws + pl.off_k, *V = ws + pl.off_v, *Kh = ws + pl.off_kh, *Vh = ws + pl.off_vh,
+         *O = ws + pl.off_o, *Xh = ws + pl.off_xhat;
+
+    // 1. indices this device transmits: encode the content rows (the class row is not encoded)
+    rc = launch_vq_encode(vq, (const char*)x_local + (size_t)at.n_cls * pl.D * eb, pl.D, at.n_local, codebook, cnorm,
+                          codes_local_out, s);
+    if (rc) return rc;
+    mark(1);
+
+    // 2. projections: Q, K, V of local rows; K-hat, V-hat of the rows rebuilt from the peers' codes
+    if (pl.need_xhat && pl.Tn_vis > 0) {
+        rc = launch_vq_decode(vq, codes_nonlocal, pl.Tn_vis, codebook, Xh, s);
+        if (rc) return rc;
+    }
+    GemmProblem pr[5] = {};
+    auto local = [&](GemmProblem& g, const void* w, const void* b, void* c, int n) {
+        g.a = x_local; g.b = w; g.bias = b; g.c = c; g.M = pl.Tq; g.N = n; g.K = pl.D; g.lda = pl.D; g.ldc = n;
+    };
+    auto nonlocal_ = [&](GemmProblem& g, const void* w, const void* b, void* c, int n) {
+        g.b = w; g.bias = b; g.c = c; g.M = pl.Tn_vis; g.N = n; g.K = pl.D; g.lda = pl.D; g.ldc = n;
+        if (pl.need_xhat) { g.a = Xh; }
+        else {
+            g.codes = codes_nonlocal; g.codebook = codebook; g.G = vq.n_groups; g.Kc = vq.codebook_size;
+            g.dg = pl.D / vq.n_groups; g.code_bytes = code_bytes(vq.code_type);
+        }
+    };
+    local(pr[0], wq, bq, Q, pl.dq);
+    local(pr[1], wk, bk, K, pl.dkv);
+    local(pr[2], wv, bv, V, pl.dkv);
+    nonlocal_(pr[3], wk, bk, Kh, pl.dkv);
+    nonlocal_(pr[4], wv, bv, Vh, pl.dkv);
+    rc = launch_gemm_batch(vq.dtype, pr, 5, s);
+    if (rc) return rc;
+    mark(2);
+
+    // 3. mixed-precision attention (Eq. 1)
+    rc = launch_attention(at, Q, K, V, Kh, Vh, O, nullptr, s);
+    if (rc) return rc;
+    mark(3);
+
+    // 4. output projection
+    GemmProblem po = {};
+    po.a = O; po.b = wo; po.bias = bo; po.c = y_out; po.M = pl.Tq; po.N = pl.D; po.K = pl.dq; po.lda = pl.dq; po.ldc = pl.D;
+    po.c_f32 = 1;      // y leaves the layer as the fp32 accumulator, for both element types
+    rc = launch_gemm_batch(vq.dtype, &po, 1, s);
+    mark(4);
+    return rc;
+}
+
+int astra_layer_forward(const astra_layer_desc* desc, const void* x_local, const void* codes_nonlocal,
+                        const void* codebook, const float* cnorm,
+                        const void* wq, const void* wk, const void* wv, const void* wo,
+                        const void* bq, const void* bk, const void* bv, const void* bo,
+                        void* y_out, void* codes_local_out, void* workspace, size_t workspace_bytes, void* stream) {
+    return layer_forward_impl(desc, x_local, codes_nonlocal, codebook, cnorm, wq, wk, wv, wo, bq, bk, bv, bo, y_out,
+                              codes_local_out, workspace, workspace_bytes, stream, nullptr);
+}
+
+int astra_layer_forward_profiled(const astra_layer_desc* desc, const void* x_local, const void* codes_nonlocal,
+                                 const void* codebook, const float* cnorm,
+                                 const void* wq, const void* wk, const void* wv, const void* wo,
+                                 const void* bq, const void* bk, const void* bv, const void* bo,
+                                 void* y_out, void* codes_local_out, void* workspace, size_t workspace_bytes, void* stream,
+                                 void* const* stage_events) {
+    if (!stage_events) return ASTRA_ERR_NULL;
+    return layer_forward_impl(desc, x_local, codes_nonlocal, codebook, cnorm, wq, wk, wv, wo, bq, bk, bv, bo, y_out,
+                              codes_local_out, workspace, workspace_bytes, stream, stage_events);
+}
+
+}  // extern "C"

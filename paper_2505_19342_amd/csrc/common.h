@@ -1,0 +1,87 @@
+// Internal definitions shared by the HIP sources of the library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/astra.h"
+
+namespace astra {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+
+// ---- bf16 helpers (storage is raw 16-bit patterns) -------------------------------------------
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {       // round to nearest even
+    __bf16 h = (__bf16)f;
+    return __builtin_bit_cast(uint16_t, h);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    bf16x2 v;
+    v[0] = (__bf16)lo;
+    v[1] = (__bf16)hi;
+    return __builtin_bit_cast(uint32_t, v);
+}
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// D = A(32x16) * B(16x32) + C on one wavefront.  Lane l supplies A[l%32][8*(l/32)+e] and
+// B[8*(l/32)+e][l%32], e = 0..7, and holds D[8*(v/4) + 4*(l/32) + v%4][l%32] in acc[v].
+__device__ __forceinline__ f32x16 mfma_32x32x16(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+// row of the 32x32 accumulator tile held in acc[v] by a lane of half-wave h = lane / 32
+__device__ __forceinline__ int acc_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }
+
+// 64-bit LDS transpose read: in every 16-lane group, lane s points at 4 consecutive 16-bit
+// values (row s/4, columns 4*(s%4)..+3 of a 4x16 block); lane L receives column L, rows 0..3.
+__device__ __forceinline__ s16x4 lds_read_tr16_b64(const void* lds_ptr) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(lds_ptr));
+}
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
+
+// ---- host side ---------------------------------------------------------------------------------
+inline int elem_bytes(int dtype) { return dtype == ASTRA_BF16 ? 2 : 4; }
+inline int code_bytes(int code_type) { return code_type == ASTRA_CODE_U16 ? 2 : 1; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? ASTRA_OK : ASTRA_ERR_HIP; }
+
+int check_vq_desc(const astra_vq_desc* d);
+int check_attn_desc(const astra_attn_desc* d);
+
+// ---- kernels' host launchers (each returns an astra_status) ---------------------------------
+int launch_vq_prepare(const astra_vq_desc& d, const void* codebook, float* cnorm, hipStream_t s);
+int launch_vq_encode(const astra_vq_desc& d, const void* x, int64_t ldx, int64_t n_tokens, const void* codebook,
+                     const float* cnorm, void* codes, hipStream_t s);
+int launch_vq_decode(const astra_vq_desc& d, const void* codes, int64_t n_tokens, const void* codebook,
+                     void* x_hat, hipStream_t s);
+
+// One C[M,N] = A[M,K] . B[N,K]^T (+ bias[N]) problem of a grouped launch.  When `codes` is set the
+// rows of A are not read from `a` but rebuilt on the fly: A[m, g*dg + j] = codebook[g, codes[m, g], j].
+struct GemmProblem {
+    const void* a;
+    const void* b;
+    const void* bias;
+    void* c;
+    const void* codes;
+    const void* codebook;
+    int32_t M, N, K;
+    int32_t lda, ldc;
+    int32_t G, Kc, dg, code_bytes;
+    int32_t c_f32;      // bf16 problems only: store C as fp32 (the unrounded accumulator) instead of bf16
+};
+constexpr int kMaxGemmProblems = 6;
+int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hipStream_t s);
+
+int launch_attention(const astra_attn_desc& d, const void* q, const void* k_local, const void* v_local,
+                     const void* k_hat, const void* v_hat, void* out, float* lse, hipStream_t s);
+
+}  // namespace astra

@@ -1,0 +1,124 @@
+"""Helpers for the GPU parity tests: move the seeded numpy inputs to device memory in the element
+type a workload uses, call the library through its binding, and bring results back as numpy."""
+import numpy as np
+import torch
+
+from paper_2505_19342_amd import binding as B
+from paper_2505_19342_amd import workloads as wl
+
+DEV = "cuda:0"
+
+
+def to_dev(a: np.ndarray, dtype: str):
+    """fp32 numpy (bf16-representable when dtype == 'bf16') -> device tensor of that element type."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if dtype == "bf16":
+        bits = wl.bf16_bits(a)
+        return torch.from_numpy(bits.view(np.int16)).to(DEV).view(torch.bfloat16)
+    return torch.from_numpy(a).to(DEV)
+
+
+def to_host(t) -> np.ndarray:
+    if t.dtype == torch.bfloat16:
+        return wl.bf16_bits_to_f32(t.view(torch.int16).cpu().numpy().view(np.uint16))
+    return t.cpu().numpy()
+
+
+def codes_to_dev(codes: np.ndarray, K: int):
+    if K <= 256:
+        return torch.from_numpy(np.ascontiguousarray(codes, dtype=np.uint8)).to(DEV)
+    return torch.from_numpy(np.ascontiguousarray(codes, dtype=np.uint16).view(np.int16)).to(DEV)
+
+
+def codes_to_host(t, K: int) -> np.ndarray:
+    a = t.cpu().numpy()
+    if K > 256:
+        a = a.view(np.uint16)
+    return a.astype(np.int32)
+
+
+def empty_codes(T: int, G: int, K: int):
+    return torch.empty((T, G), dtype=torch.uint8 if K <= 256 else torch.int16, device=DEV)
+
+
+def empty_like_dtype(shape, dtype: str):
+    return torch.empty(shape, dtype=torch.bfloat16 if dtype == "bf16" else torch.float32, device=DEV)
+
+
+def gpu_vq_encode(x: np.ndarray, codebook: np.ndarray, dtype: str) -> np.ndarray:
+    G, K, dg = codebook.shape
+    T = x.shape[0]
+    desc = B.vq_desc(dtype, G * dg, G, K)
+    cb = to_dev(codebook, dtype)
+    cnorm = torch.empty((G, K), dtype=torch.float32, device=DEV)
+    B.astra_vq_prepare(desc, cb, cnorm)
+    xd = to_dev(x, dtype) if T > 0 else None
+    codes = empty_codes(T, G, K)
+    B.astra_vq_encode(desc, xd, T, cb, cnorm, codes)
+    torch.cuda.synchronize()
+    return codes_to_host(codes, K)
+
+
+def gpu_vq_decode(codes: np.ndarray, codebook: np.ndarray, dtype: str) -> np.ndarray:
+    G, K, dg = codebook.shape
+    T = codes.shape[0]
+    desc = B.vq_desc(dtype, G * dg, G, K)
+    cb = to_dev(codebook, dtype)
+    out = empty_like_dtype((T, G * dg), dtype)
+    B.astra_vq_decode(desc, codes_to_dev(codes, K) if T > 0 else None, T, cb, out)
+    torch.cuda.synchronize()
+    return to_host(out)
+
+
+def gpu_mixed_attention(q, k_loc, v_loc, k_hat, v_hat, dtype, *, n_cls=0, causal=False, n_before=0, scale=0.0,
+                        want_lse=False):
+    Tq, Hq, dh = q.shape
+    Hkv = k_loc.shape[1]
+    Tn = k_hat.shape[0]
+    desc = B.attn_desc(dtype, Hq, Hkv, dh, n_cls, Tq - n_cls, Tn, causal, n_before, scale)
+    d = lambda a: to_dev(a, dtype) if a.shape[0] > 0 else None
+    out = empty_like_dtype((Tq, Hq, dh), dtype)
+    lse = torch.empty((Hq, Tq), dtype=torch.float32, device=DEV) if want_lse else None
+    B.astra_mixed_attention(desc, d(q), d(k_loc), d(v_loc), d(k_hat), d(v_hat), out, lse)
+    torch.cuda.synchronize()
+    return (to_host(out), lse.cpu().numpy()) if want_lse else to_host(out)
+
+
+class LayerOnGpu:
+    """Device-resident tensors of one layer call (weights stored [out, in] as the ABI asks)."""
+
+    def __init__(self, cfg, data, x_local, codes_nonlocal, n_before, biases=None):
+        dt = cfg.dtype
+        self.cfg, self.dtype = cfg, dt
+        G, K = cfg.n_groups, cfg.codebook_size
+        Tq, Tn = x_local.shape[0], codes_nonlocal.shape[0]
+        self.desc = B.LayerDesc(
+            B.vq_desc(dt, cfg.d_model, G, K),
+            B.attn_desc(dt, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n_cls, Tq - cfg.n_cls, Tn, cfg.causal, n_before))
+        self.x_local = to_dev(x_local, dt)
+        self.codes_nonlocal = codes_to_dev(codes_nonlocal, K) if Tn > 0 else None
+        self.codebook = to_dev(data["codebook"], dt)
+        self.cnorm = torch.empty((G, K), dtype=torch.float32, device=DEV)
+        B.astra_vq_prepare(self.desc.vq, self.codebook, self.cnorm)
+        self.w = [to_dev(np.ascontiguousarray(data[n].T), dt) for n in ("wq", "wk", "wv", "wo")]
+        self.b = [None] * 4 if biases is None else [to_dev(b, dt) for b in biases]
+        self.y = torch.empty((Tq, cfg.d_model), dtype=torch.float32, device=DEV)      # y is fp32 for both element types
+        self.codes_local = empty_codes(Tq - cfg.n_cls, G, K)
+        self.workspace = torch.empty(max(B.astra_layer_workspace_bytes(self.desc), 256), dtype=torch.uint8, device=DEV)
+
+    def run(self):
+        B.astra_layer_forward(self.desc, self.x_local, self.codes_nonlocal, self.codebook, self.cnorm, *self.w, *self.b,
+                              self.y, self.codes_local, self.workspace)
+
+    def results(self):
+        torch.cuda.synchronize()
+        return to_host(self.y), codes_to_host(self.codes_local, self.cfg.codebook_size)
+
+
+def compare_codes(gpu_codes, ref_codes, gap, tol=1e-5):
+    """Codes must be bit-exact except where the checker's best and second-best distances are within
+    `tol` relative (near-ties).  Returns the number of near-tie disagreements."""
+    diff = gpu_codes != ref_codes
+    bad = diff & ~(gap < tol)
+    assert not bad.any(), f"{int(bad.sum())} codes differ away from near-ties (of {diff.size}); first at {np.argwhere(bad)[0]}"
+    return int(diff.sum())

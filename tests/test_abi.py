@@ -1,0 +1,53 @@
+"""The C-ABI library loads and exports every function include/astra.h declares (no GPU needed), and
+the Python descriptors mirror the C structs."""
+import ctypes
+import os
+import re
+
+from paper_2505_19342_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "astra.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(astra_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load()
+    names = declared_functions()
+    assert set(B.EXPORTS) == set(names)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_status_strings_run_without_a_gpu():
+    lib = B.load()
+    assert lib.astra_version() >= 100
+    assert lib.astra_status_string(0) == b"ok"
+    assert b"workspace" in lib.astra_status_string(-4)
+
+
+def test_descriptor_layouts():
+    assert ctypes.sizeof(B.VqDesc) == 20
+    assert ctypes.sizeof(B.AttnDesc) == 40
+    assert ctypes.sizeof(B.LayerDesc) == 60
+    assert B.AttnDesc.scale.offset == 36
+
+
+def test_host_side_argument_checks_need_no_gpu():
+    lib = B.load()
+    bad = B.LayerDesc(B.VqDesc(B.ASTRA_BF16, B.ASTRA_CODE_U8, 768, 5, 256),        # 5 does not divide 768
+                      B.attn_desc("bf16", 12, 12, 64, 0, 256, 768, False))
+    assert lib.astra_layer_workspace_bytes(ctypes.byref(bad)) == 0
+    good = B.LayerDesc(B.vq_desc("bf16", 768, 16, 256), B.attn_desc("bf16", 12, 12, 64, 1, 256, 768, False))
+    need = lib.astra_layer_workspace_bytes(ctypes.byref(good))
+    # Q, O: 257 x 768; K, V: 257 x 768; K-hat, V-hat: 768 x 768, bf16, each rounded up to 256 bytes
+    assert need >= 2 * (4 * 257 * 768 + 2 * 768 * 768)
+    # NULL descriptor and NULL data pointers are reported, not dereferenced
+    assert lib.astra_vq_prepare(None, None, None, None) == -1
+    assert lib.astra_vq_encode(ctypes.byref(good.vq), None, 5, None, None, None, None) == -1
+    assert lib.astra_vq_encode(ctypes.byref(good.vq), None, 0, None, None, None, None) == 0
+    assert lib.astra_vq_encode(ctypes.byref(good.vq), None, -1, None, None, None, None) == -2

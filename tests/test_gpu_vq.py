@@ -1,0 +1,102 @@
+"""GPU parity: grouped VQ encode / decode through the C ABI against the CPU oracle on the same
+seeded inputs.  Codes are bit-exact except at near-ties (oracle best/second-best gap < 1e-5
+relative), which are counted; decode is bit-exact."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2505_19342_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+NEAR_TIE = 1e-5
+
+
+def make(seed, T, G, K, dg, dtype, dist="normal"):
+    rng = np.random.default_rng(seed)
+    x = wl._embeddings(rng, T, G * dg, dist) if T > 0 else np.zeros((0, G * dg), np.float32)
+    cb = rng.standard_normal((G, K, dg), dtype=np.float32)
+    if dtype == "bf16":
+        x, cb = wl.round_to_bf16(x), wl.round_to_bf16(cb)
+    return x, cb
+
+
+ENCODE_CASES = [
+    # (T, G, K, dg, dtype, dist)     spans several 128-token tiles and a ragged tail unless noted
+    (64, 4, 256, 48, "f32", "normal"),            # tiny ViT layer
+    (300, 4, 256, 48, "f32", "normal"),
+    (33, 3, 1000, 20, "f32", "normal"),           # uint16 codes, K not a multiple of the wave
+    (256, 16, 256, 48, "bf16", "normal_shift"),   # ViT-Base
+    (256, 32, 256, 24, "bf16", "student_t5"),     # GPT-2 small (dg padded to 32)
+    (1024, 64, 1024, 64, "bf16", "rms_normal"),   # Llama-3-8B shape, full size
+    (300, 16, 256, 48, "bf16", "normal"),         # ragged tail
+    (1, 2, 16, 8, "bf16", "normal"),              # single token, K below one MFMA tile
+    (130, 64, 16, 12, "bf16", "normal"),          # sweep corner: dg = 12 (unaligned slices), K = 16
+    (200, 4, 1024, 192, "bf16", "normal"),        # sweep: dg spans 3 LDS tiles
+    (140, 1, 1024, 768, "bf16", "normal"),        # vanilla VQ (G = 1), dg = 768
+    (257, 5, 100, 40, "bf16", "normal"),          # K not a multiple of 32, dg not a multiple of 16
+]
+
+
+@pytest.mark.parametrize("T,G,K,dg,dtype,dist", ENCODE_CASES)
+def test_encode_matches_oracle(T, G, K, dg, dtype, dist):
+    from gpu_util import compare_codes, gpu_vq_encode
+    x, cb = make(100 + T + G, T, G, K, dg, dtype, dist)
+    ref, gap = oracle.vq_encode(x, cb, return_gap=True)
+    got = gpu_vq_encode(x, cb, dtype)
+    n_tie = compare_codes(got, ref, gap, NEAR_TIE)
+    print(f"near-tie disagreements: {n_tie} of {ref.size}")
+    assert n_tie <= max(2, ref.size // 2000)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_encode_codewords_and_exact_ties(dtype):
+    from gpu_util import gpu_vq_decode, gpu_vq_encode
+    rng = np.random.default_rng(7)
+    G, K, dg = 3, 64, 16
+    cb = rng.standard_normal((G, K, dg), dtype=np.float32)
+    if dtype == "bf16":
+        cb = wl.round_to_bf16(cb)
+    cb[:, 40] = cb[:, 7]                       # duplicate codeword: 7 must win over 40
+    x = np.concatenate([cb[g] for g in range(G)], axis=1)
+    got = gpu_vq_encode(x, cb, dtype)
+    expect = np.repeat(np.arange(K)[:, None], G, axis=1)
+    expect[40] = 7
+    assert np.array_equal(got, expect)
+    assert np.array_equal(got, oracle.vq_encode(x, cb))
+    assert np.array_equal(gpu_vq_decode(got, cb, dtype), x)          # decode(encode(c)) == c
+
+
+DECODE_CASES = [(192, 4, 256, 48, "f32"), (768, 16, 256, 48, "bf16"), (777, 32, 256, 24, "bf16"),
+                (3072, 64, 1024, 64, "bf16"), (50, 64, 16, 12, "bf16"), (9, 3, 5, 7, "bf16"), (11, 2, 300, 5, "f32")]
+
+
+@pytest.mark.parametrize("T,G,K,dg,dtype", DECODE_CASES)
+def test_decode_is_bit_exact(T, G, K, dg, dtype):
+    from gpu_util import gpu_vq_decode
+    rng = np.random.default_rng(T)
+    cb = rng.standard_normal((G, K, dg), dtype=np.float32)
+    if dtype == "bf16":
+        cb = wl.round_to_bf16(cb)
+    codes = rng.integers(0, K, size=(T, G)).astype(np.int32)
+    codes[0, :] = K - 1
+    codes[-1, :] = 0
+    got = gpu_vq_decode(codes, cb, dtype)
+    assert np.array_equal(got.view(np.uint32), oracle.vq_decode(codes, cb).view(np.uint32))
+
+
+def test_empty_inputs_and_argument_errors():
+    import torch
+    from gpu_util import DEV, gpu_vq_decode, gpu_vq_encode, to_dev
+    from paper_2505_19342_amd import binding as B
+    cb = np.ones((2, 4, 8), dtype=np.float32)
+    assert gpu_vq_encode(np.zeros((0, 16), np.float32), cb, "bf16").shape == (0, 2)
+    assert gpu_vq_decode(np.zeros((0, 2), np.int32), cb, "bf16").shape == (0, 16)
+    cbd = to_dev(cb, "bf16")
+    cn = torch.empty((2, 4), dtype=torch.float32, device=DEV)
+    with pytest.raises(B.AstraError):      # G does not divide D
+        B.astra_vq_prepare(B.VqDesc(B.ASTRA_BF16, B.ASTRA_CODE_U8, 16, 3, 4), cbd, cn)
+    with pytest.raises(B.AstraError):      # uint8 codes cannot hold K = 1024
+        B.astra_vq_prepare(B.VqDesc(B.ASTRA_BF16, B.ASTRA_CODE_U8, 16, 2, 1024), cbd, cn)
+    with pytest.raises(B.AstraError):      # NULL output
+        B.astra_vq_prepare(B.vq_desc("bf16", 16, 2, 4), cbd, None)

@@ -172,9 +172,11 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     GemmProblem pr[5] = {};
     auto local = [&](GemmProblem& g, const void* w, const void* b, void* c, int n) {
         g.a = x_local; g.b = w; g.bias = b; g.c = c; g.M = pl.Tq; g.N = n; g.K = pl.D; g.lda = pl.D; g.ldc = n;
+        g.c_mode = vq.dtype == ASTRA_BF16 ? kCBf16 : kCF32;
     };
     auto nonlocal_ = [&](GemmProblem& g, const void* w, const void* b, void* c, int n) {
         g.b = w; g.bias = b; g.c = c; g.M = pl.Tn_vis; g.N = n; g.K = pl.D; g.lda = pl.D; g.ldc = n;
+        g.c_mode = vq.dtype == ASTRA_BF16 ? kCBf16 : kCF32;
         if (pl.need_xhat) { g.a = Xh; }
         else {
             g.codes = codes_nonlocal; g.codebook = codebook; g.G = vq.n_groups; g.Kc = vq.codebook_size;
@@ -198,7 +200,7 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     // 4. output projection
     GemmProblem po = {};
     po.a = O; po.b = wo; po.bias = bo; po.c = y_out; po.M = pl.Tq; po.N = pl.D; po.K = pl.dq; po.lda = pl.dq; po.ldc = pl.D;
-    po.c_f32 = 1;      // y leaves the layer as the fp32 accumulator, for both element types
+    po.c_mode = kCF32;      // y leaves the layer as the fp32 accumulator, for both element types
     rc = launch_gemm_batch(vq.dtype, &po, 1, s);
     mark(4);
     return rc;

@@ -13,6 +13,8 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // 16-byte register value (native vector, stays in registers)
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kWave = 64;
 
@@ -66,6 +68,10 @@ int launch_vq_decode(const astra_vq_desc& d, const void* codes, int64_t n_tokens
 
 // One C[M,N] = A[M,K] . B[N,K]^T (+ bias[N]) problem of a grouped launch.  When `codes` is set the
 // rows of A are not read from `a` but rebuilt on the fly: A[m, g*dg + j] = codebook[g, codes[m, g], j].
+enum { kCBf16 = 0,          // bf16, row-major [M, ldc]
+       kCF32 = 1,           // fp32 (the unrounded accumulator), row-major [M, ldc]
+       kCTransposedV = 2 }; // bf16, C^T as [N, ldc] with the M index permuted inside blocks of 16 (see vt_pos)
+
 struct GemmProblem {
     const void* a;
     const void* b;
@@ -76,10 +82,11 @@ struct GemmProblem {
     int32_t M, N, K;
     int32_t lda, ldc;
     int32_t G, Kc, dg, code_bytes;
-    int32_t c_f32;      // bf16 problems only: store C as fp32 (the unrounded accumulator) instead of bf16
+    int32_t c_mode;     // how C is stored (bf16 problems; fp32 problems always store fp32 row-major)
 };
 constexpr int kMaxGemmProblems = 6;
 int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hipStream_t s);
+extern int g_gemm_force_cfg;
 
 int launch_attention(const astra_attn_desc& d, const void* q, const void* k_local, const void* v_local,
                      const void* k_hat, const void* v_hat, void* out, float* lse, hipStream_t s);

@@ -9,17 +9,9 @@ namespace astra {
 struct GemmBatch {
     int32_t n;
     int32_t tile_begin[kMaxGemmProblems + 1];
-    int32_t tiles_n[kMaxGemmProblems];
+    int32_t tiles_m[kMaxGemmProblems];     // tiles along M of each problem (tile index = tn * tiles_m + tm)
     GemmProblem p[kMaxGemmProblems];
 };
-
-// ------------------------------------------------------------------------------------------------
-// bf16, matrix cores.  128x128 output tile per workgroup of 4 wavefronts (2x2, 64x64 each = 2x2
-// MFMA 32x32x16 tiles), contraction in steps of 64 staged through double-buffered LDS.  LDS tiles are
-// [rows][8 pieces of 8 bf16]; piece p of row r sits at p ^ (r & 7) so that the 16-byte fragment reads
-// of 8 consecutive rows cover all banks.
-// ------------------------------------------------------------------------------------------------
-constexpr int kBM = 128, kBN = 128, kBK = 64;
 
 __device__ __forceinline__ int find_problem(const GemmBatch& b, int tile) {
     int p = 0;
@@ -27,127 +19,234 @@ __device__ __forceinline__ int find_problem(const GemmBatch& b, int tile) {
     return p;
 }
 
-__global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmBatch batch) {
-    __shared__ uint4 lds_a[2][kBM * kBK / 8];   // 2 x 16 KiB
-    __shared__ uint4 lds_b[2][kBN * kBK / 8];   // 2 x 16 KiB
+// ------------------------------------------------------------------------------------------------
+// bf16, matrix cores.  A workgroup of WM x WN wavefronts owns a BM x BN output tile; each wavefront
+// owns a (BM/WM) x (BN/WN) sub-tile made of 32x32x16 MFMA tiles.  The contraction runs in steps of 64
+// through double-buffered LDS: while the matrix cores work on tile kt, the registers hold tile kt+1
+// (fetched one iteration earlier) on its way to the other LDS buffer, the loads of tile kt+2 are in
+// flight and, for gathered A rows, the codes of tile kt+3 are being fetched.  LDS tiles are
+// [rows][8 pieces of 8 bf16]; piece p of row r sits at p ^ ((r >> 1) & 7): rows are 128 bytes, the
+// LDS has 64 four-byte banks, so the 16-byte fragment reads of 16 consecutive rows touch every bank once.
+//
+// Workgroup -> tile mapping: hardware hands consecutive workgroup ids to the 8 XCDs round-robin, each
+// with its own L2.  Ids are remapped so that every XCD gets one contiguous range of tiles, walked with
+// the M index fastest: the tiles an XCD runs at the same time share their weight (B) panel and draw
+// their A panels from a few rows, so most operand traffic is served by that XCD's L2.
+// ------------------------------------------------------------------------------------------------
+constexpr int kBK = 64;
+constexpr int kXcds = 8;
 
-    const int pi = find_problem(batch, blockIdx.x);
+__device__ __forceinline__ int xcd_remap(int wg, int total) {
+    const int q = total / kXcds, r = total % kXcds;
+    const int xcd = wg % kXcds, slot = wg / kXcds;
+    return xcd < r ? xcd * (q + 1) + slot : r * (q + 1) + (xcd - r) * q + slot;
+}
+
+__device__ __forceinline__ int swz(int r) { return (r >> 1) & 7; }
+
+// position of token offset o (0..15) inside a 16-token block of the transposed-V layout: the 8 tokens
+// one half-wave holds of an MFMA accumulator column ({4h..4h+3} and {8+4h..8+4h+3}) become contiguous,
+// which is also the order the attention kernel's P^T operand keeps its 16 keys in.
+__device__ __forceinline__ int vt_pos(int o) { return 8 * ((o >> 2) & 1) + (o & 3) + 4 * (o >> 3); }
+
+template <int BM, int BN, int WM, int WN, bool CODE16>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_nt_bf16_kernel(const GemmBatch batch) {
+    constexpr int THREADS = 64 * WM * WN;
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;        // MFMA tiles per wavefront
+    constexpr int RPP = THREADS / 8;                           // rows staged per pass
+    constexpr int PA = BM / RPP, PB = BN / RPP;                // staging passes per thread
+    __shared__ u32x4 lds_a[2][BM * kBK / 8];
+    __shared__ u32x4 lds_b[2][BN * kBK / 8];
+
+    const int vt = xcd_remap(blockIdx.x, gridDim.x);
+    const int pi = find_problem(batch, vt);
     const GemmProblem& P = batch.p[pi];
-    const int tile = blockIdx.x - batch.tile_begin[pi];
-    const int tn = tile % batch.tiles_n[pi], tm = tile / batch.tiles_n[pi];
-    const int m0 = tm * kBM, n0 = tn * kBN;
+    const int tile = vt - batch.tile_begin[pi];
+    const int tiles_m = batch.tiles_m[pi];
+    const int tm = tile % tiles_m, tn = tile / tiles_m;
+    const int m0 = tm * BM, n0 = tn * BN;
     const int M = P.M, N = P.N, K = P.K;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int i32 = lane & 31, h = lane >> 5;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN, wn = wave % WN;
+    const int kc = tid & 7, r0 = tid >> 3;      // staging: 16-byte piece kc of rows r0 + RPP * it
 
-    // Global -> register staging: thread handles piece kc of rows r0 + 32*it, it = 0..3, for A and B.
-    const int kc = tid & 7, r0 = tid >> 3;
-    const uint16_t* __restrict__ A = (const uint16_t*)P.a;
-    const uint16_t* __restrict__ B = (const uint16_t*)P.b;
+    // One straight-line loader serves plain and gathered A rows.  For gathered rows the piece at
+    // contraction index k lies in group g = k / dg at offset j = k - g*dg of codeword codes[row, g];
+    // for plain rows the code load is a harmless read of the first bytes of A and the gathered offset is
+    // discarded by a select.  k / dg is a multiply-high by ceil(2^32 / dg), exact for k, dg < 2^16.
+    // Addresses are a wave-uniform base (scalar registers, advanced once per tile) plus a 32-bit byte
+    // offset per thread, which keeps the per-row state to one register.
     const bool gather = P.codes != nullptr;
-    const uint16_t* __restrict__ CB = (const uint16_t*)P.codebook;
-
-    int arow[4], brow[4];
+    const int dg = gather ? P.dg : 1, Kc = gather ? P.Kc : 1, G = gather ? P.G : 0;
+    const uint32_t magic = gather ? (uint32_t)(0x100000000ull / (uint32_t)dg) + 1u : 0u;
+    const char* __restrict__ a_base = (const char*)(gather ? P.codebook : P.a);   // plain A advances 128 bytes per tile
+    const int a_step = gather ? 0 : kBK * 2;
+    const uint32_t gmask = gather ? 0xffffffffu : 0u;                           // keeps the gathered offset, or zeroes it
+    const char* __restrict__ b_base = (const char*)P.b;
+    const char* __restrict__ c_base = (const char*)(gather ? P.codes : P.a);
+    uint32_t aoff[PA], coff[PA], boff[PB];
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        const int ra = m0 + r0 + 32 * it, rb = n0 + r0 + 32 * it;
-        arow[it] = ra < M ? ra : M - 1;
-        brow[it] = rb < N ? rb : N - 1;
+    for (int it = 0; it < PA; ++it) {
+        int ra = m0 + r0 + RPP * it;
+        ra = ra < M ? ra : M - 1;
+        aoff[it] = gather ? 0u : ((uint32_t)ra * (uint32_t)P.lda + kc * 8) * 2u;
+        coff[it] = (uint32_t)ra * (uint32_t)G * (CODE16 ? 2u : 1u);
     }
+#pragma unroll
+    for (int it = 0; it < PB; ++it) {
+        int rb = n0 + r0 + RPP * it;
+        rb = rb < N ? rb : N - 1;
+        boff[it] = ((uint32_t)rb * (uint32_t)K + kc * 8) * 2u;
+    }
+    int k_code = kc * 8;              // contraction index of this thread's piece in the tile whose codes are fetched next
+    int k_use = kc * 8;               // ... in the tile whose operand pieces are fetched next
+    int code[PA];
+    u32x4 ra[PA], rb[PB];
 
-    uint4 ra[4], rb[4];
-    auto load_tile = [&](int k0) {
-        const int k = k0 + kc * 8;
-        const bool kin = k < K;
-        if (!gather) {
+    auto load_codes = [&]() {
+        const uint32_t g_ = __umulhi((uint32_t)k_code, magic) * (CODE16 ? 2u : 1u);
 #pragma unroll
-            for (int it = 0; it < 4; ++it)
-                ra[it] = kin ? *reinterpret_cast<const uint4*>(A + (int64_t)arow[it] * P.lda + k) : make_uint4(0, 0, 0, 0);
-        } else {
-            const int kk = kin ? k : 0;
-            const int g = kk / P.dg, j = kk - g * P.dg;
+        for (int it = 0; it < PA; ++it) {
+            if (CODE16) code[it] = *reinterpret_cast<const uint16_t*>(c_base + (coff[it] + g_));
+            else code[it] = *reinterpret_cast<const uint8_t*>(c_base + (coff[it] + g_));
+        }
+        k_code += kBK;
+    };
+    auto load_tile = [&]() {
+        const uint32_t g_ = __umulhi((uint32_t)k_use, magic);
+        const uint32_t j_ = (uint32_t)k_use - g_ * (uint32_t)dg;
+        const uint32_t gbase_ = g_ * (uint32_t)Kc;
 #pragma unroll
-            for (int it = 0; it < 4; ++it) {
-                int code;
-                if (P.code_bytes == 1) code = ((const uint8_t*)P.codes)[(int64_t)arow[it] * P.G + g];
-                else code = ((const uint16_t*)P.codes)[(int64_t)arow[it] * P.G + g];
-                code = code < P.Kc ? code : P.Kc - 1;
-                ra[it] = kin ? *reinterpret_cast<const uint4*>(CB + ((int64_t)g * P.Kc + code) * P.dg + j) : make_uint4(0, 0, 0, 0);
-            }
+        for (int it = 0; it < PA; ++it) {
+            const uint32_t c_ = (uint32_t)(code[it] < Kc ? code[it] : Kc - 1);
+            const uint32_t goff_ = ((gbase_ + c_) * (uint32_t)dg + j_) * 2u;
+            ra[it] = *reinterpret_cast<const u32x4*>(a_base + ((goff_ & gmask) + aoff[it]));
         }
 #pragma unroll
-        for (int it = 0; it < 4; ++it)
-            rb[it] = kin ? *reinterpret_cast<const uint4*>(B + (int64_t)brow[it] * K + k) : make_uint4(0, 0, 0, 0);
+        for (int it = 0; it < PB; ++it) rb[it] = *reinterpret_cast<const u32x4*>(b_base + boff[it]);
+        a_base += a_step;
+        b_base += kBK * 2;
+        k_use += kBK;
     };
-    auto store_tile = [&](int buf) {
+    auto store_tile = [&](int buf_) {
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            const int r = r0 + 32 * it;
-            lds_a[buf][r * 8 + (kc ^ (r & 7))] = ra[it];
-            lds_b[buf][r * 8 + (kc ^ (r & 7))] = rb[it];
+        for (int it = 0; it < PA; ++it) {
+            const int r_ = r0 + RPP * it;
+            lds_a[buf_][r_ * 8 + (kc ^ swz(r_))] = ra[it];
+        }
+#pragma unroll
+        for (int it = 0; it < PB; ++it) {
+            const int r_ = r0 + RPP * it;
+            lds_b[buf_][r_ * 8 + (kc ^ swz(r_))] = rb[it];
         }
     };
 
-    f32x16 acc[2][2];
+    f32x16 acc[TM][TN];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < TM; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < TN; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-    const int n_kt = (K + kBK - 1) / kBK;
-    load_tile(0);
-    store_tile(0);
-    __syncthreads();
-    for (int kt = 0; kt < n_kt; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < n_kt) load_tile((kt + 1) * kBK);
+    // fragment rows
+    int arow[TM], brow[TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a) arow[a] = wm * (BM / WM) + a * 32 + i32;
+#pragma unroll
+    for (int b = 0; b < TN; ++b) brow[b] = wn * (BN / WN) + b * 32 + i32;
+
+    auto compute = [&](int buf_) {
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            bf16x8 fa[2], fb[2];
+            bf16x8 fa[TM], fb[TN];
 #pragma unroll
-            for (int a = 0; a < 2; ++a) {
-                const int r = wm * 64 + a * 32 + i32;
-                fa[a] = as_bf16x8(lds_a[buf][r * 8 + ((2 * ks + h) ^ (r & 7))]);
-            }
+            for (int a = 0; a < TM; ++a) fa[a] = __builtin_bit_cast(bf16x8, lds_a[buf_][arow[a] * 8 + ((2 * ks + h) ^ swz(arow[a]))]);
 #pragma unroll
-            for (int b = 0; b < 2; ++b) {
-                const int r = wn * 64 + b * 32 + i32;
-                fb[b] = as_bf16x8(lds_b[buf][r * 8 + ((2 * ks + h) ^ (r & 7))]);
-            }
+            for (int b = 0; b < TN; ++b) fb[b] = __builtin_bit_cast(bf16x8, lds_b[buf_][brow[b] * 8 + ((2 * ks + h) ^ swz(brow[b]))]);
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
+            for (int a = 0; a < TM; ++a)
 #pragma unroll
-                for (int b = 0; b < 2; ++b) acc[a][b] = mfma_32x32x16(fa[a], fb[b], acc[a][b]);
+                for (int b = 0; b < TN; ++b) acc[a][b] = mfma_32x32x16(fa[a], fb[b], acc[a][b]);
         }
+    };
+
+    // Software pipeline, per iteration kt: registers (tile kt+1, fetched one iteration ago) go to the
+    // other LDS buffer, the loads of tile kt+2 and the codes of tile kt+3 are issued, then tile kt is
+    // multiplied out of LDS while those loads are in flight.  One barrier per iteration.
+    const int n_kt = K / kBK;
+    load_codes();                 // codes of tile 0
+    load_tile();                  // tile 0
+    if (n_kt > 1) load_codes();   // codes of tile 1
+    store_tile(0);
+    if (n_kt > 1) load_tile();    // tile 1
+    if (n_kt > 2) load_codes();   // codes of tile 2
+    __syncthreads();
+    int kt = 0;
+    for (; kt + 3 < n_kt; ++kt) {
+        const int buf = kt & 1;
+        store_tile(buf ^ 1);
+        load_tile();
+        load_codes();
+        compute(buf);
+        __syncthreads();
+    }
+    for (; kt < n_kt; ++kt) {
+        const int buf = kt & 1;
         if (kt + 1 < n_kt) store_tile(buf ^ 1);
+        if (kt + 2 < n_kt) load_tile();
+        compute(buf);
         __syncthreads();
     }
 
-    // epilogue: bias, round to bf16 (or keep fp32), store.  acc[a][b][v] is C[m, n] with m = row(v, h), n = lane % 32.
-    uint16_t* __restrict__ C = (uint16_t*)P.c;
-    float* __restrict__ Cf = (float*)P.c;
-    const bool c_f32 = P.c_f32 != 0;
+    // epilogue.  acc[a][b][v] is C[m, n] with m = wave row base + 32a + acc_row(v, h), n = wave column base + 32b + lane % 32.
     const uint16_t* __restrict__ bias = (const uint16_t*)P.bias;
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-        const int n = n0 + wn * 64 + b * 32 + i32;
+    for (int b = 0; b < TN; ++b) {
+        const int n = n0 + wn * (BN / WN) + b * 32 + i32;
         if (n >= N) continue;
         const float bv = bias ? bf16_bits_to_f32(bias[n]) : 0.f;
+        if (P.c_mode == kCTransposedV) {
+            // C^T with tokens permuted inside 16-token blocks; P.ldc is the padded token count.  Rows
+            // m >= M of the last tile are finite copies of row M-1 (clamped loads) and are written too,
+            // so the padding never holds uninitialised bits.
+            uint16_t* __restrict__ C = (uint16_t*)P.c + (int64_t)n * P.ldc;
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
+            for (int a = 0; a < TM; ++a)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = m0 + wm * 64 + a * 32 + acc_row(v, h);
-                if (m < M) {
-                    if (c_f32) Cf[(int64_t)m * P.ldc + n] = acc[a][b][v] + bv;
-                    else C[(int64_t)m * P.ldc + n] = f32_to_bf16_bits(acc[a][b][v] + bv);
+                for (int blk = 0; blk < 2; ++blk) {
+                    const int mb = m0 + wm * (BM / WM) + a * 32 + 16 * blk;
+                    if (mb < P.ldc) {
+                        u32x4 w;
+                        w.x = pack_bf16x2(acc[a][b][8 * blk + 0] + bv, acc[a][b][8 * blk + 1] + bv);
+                        w.y = pack_bf16x2(acc[a][b][8 * blk + 2] + bv, acc[a][b][8 * blk + 3] + bv);
+                        w.z = pack_bf16x2(acc[a][b][8 * blk + 4] + bv, acc[a][b][8 * blk + 5] + bv);
+                        w.w = pack_bf16x2(acc[a][b][8 * blk + 6] + bv, acc[a][b][8 * blk + 7] + bv);
+                        *reinterpret_cast<u32x4*>(C + mb + 8 * h) = w;
+                    }
                 }
-            }
+        } else if (P.c_mode == kCF32) {
+            float* __restrict__ C = (float*)P.c;
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = m0 + wm * (BM / WM) + a * 32 + acc_row(v, h);
+                    if (m < M) C[(int64_t)m * P.ldc + n] = acc[a][b][v] + bv;
+                }
+        } else {
+            uint16_t* __restrict__ C = (uint16_t*)P.c;
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = m0 + wm * (BM / WM) + a * 32 + acc_row(v, h);
+                    if (m < M) C[(int64_t)m * P.ldc + n] = f32_to_bf16_bits(acc[a][b][v] + bv);
+                }
+        }
     }
 }
 
@@ -164,7 +263,7 @@ __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmBatch batch)
     const int pi = find_problem(batch, blockIdx.x);
     const GemmProblem& P = batch.p[pi];
     const int tile = blockIdx.x - batch.tile_begin[pi];
-    const int tn = tile % batch.tiles_n[pi], tm = tile / batch.tiles_n[pi];
+    const int tm = tile % batch.tiles_m[pi], tn = tile / batch.tiles_m[pi];
     const int m0 = tm * kFM, n0 = tn * kFN;
     const int M = P.M, N = P.N, K = P.K;
     const float* __restrict__ A = (const float*)P.a;
@@ -228,32 +327,69 @@ __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmBatch batch)
     }
 }
 
-int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hipStream_t s) {
-    if (n_problems > kMaxGemmProblems) return ASTRA_ERR_UNSUPPORTED;
-    const int bm = dtype == ASTRA_BF16 ? kBM : kFM, bn = dtype == ASTRA_BF16 ? kBN : kFN;
-    GemmBatch batch{};
+int g_gemm_force_cfg = -1;      // development override: 0 = 128x128 tiles, 1 = 256x256 tiles
+
+static int fill_batch(GemmBatch& batch, int dtype, const GemmProblem* problems, int n_problems, int bm, int bn, int* total_out) {
     int total = 0, n = 0;
     for (int i = 0; i < n_problems; ++i) {
         const GemmProblem& p = problems[i];
         if (p.M <= 0 || p.N <= 0) continue;
         if (p.K <= 0) return ASTRA_ERR_SHAPE;
         if (dtype == ASTRA_BF16) {
-            // 16-byte operand pieces: rows and gathered slices must start on 8-element boundaries
-            if (p.K % 8 != 0 || (!p.codes && p.lda % 8 != 0) || (p.codes && p.dg % 8 != 0)) return ASTRA_ERR_UNSUPPORTED;
+            // whole 64-wide contraction tiles; 16-byte operand pieces must not straddle rows or codewords
+            if (p.K % kBK != 0 || (!p.codes && p.lda % 8 != 0) || (p.codes && p.dg % 8 != 0)) return ASTRA_ERR_UNSUPPORTED;
+            if (p.c_mode == kCTransposedV && (p.ldc % 64 != 0 || p.ldc < p.M)) return ASTRA_ERR_SHAPE;
+            // operands are addressed with 32-bit byte offsets from their base
+            const int64_t lim = (int64_t)1 << 31;
+            if ((int64_t)p.M * p.lda * 2 >= lim || (int64_t)p.N * p.K * 2 >= lim) return ASTRA_ERR_UNSUPPORTED;
+            if (p.codes && ((int64_t)p.G * p.Kc * p.dg * 2 >= lim || (int64_t)p.M * p.G * 2 >= lim)) return ASTRA_ERR_UNSUPPORTED;
+        } else if (p.c_mode != kCF32) {
+            return ASTRA_ERR_UNSUPPORTED;
         }
         const int64_t tm = ceil_div(p.M, bm), tn = ceil_div(p.N, bn);
         if (tm * tn + total > 0x7fffffff) return ASTRA_ERR_SHAPE;
         batch.p[n] = p;
         batch.tile_begin[n] = total;
-        batch.tiles_n[n] = (int)tn;
+        batch.tiles_m[n] = (int)tm;
         total += (int)(tm * tn);
         ++n;
     }
     batch.n = n;
     for (int i = n; i <= kMaxGemmProblems; ++i) batch.tile_begin[i] = total;
+    *total_out = total;
+    return ASTRA_OK;
+}
+
+int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hipStream_t s) {
+    if (n_problems > kMaxGemmProblems) return ASTRA_ERR_UNSUPPORTED;
+    GemmBatch batch{};
+    int total = 0;
+    if (dtype != ASTRA_BF16) {
+        int rc = fill_batch(batch, dtype, problems, n_problems, kFM, kFN, &total);
+        if (rc) return rc;
+        if (total == 0) return ASTRA_OK;
+        gemm_nt_f32_kernel<<<total, 256, 0, s>>>(batch);
+        return launch_status();
+    }
+    bool code16 = false;
+    for (int i = 0; i < n_problems; ++i)
+        if (problems[i].codes && problems[i].code_bytes == 2) code16 = true;
+    // Large tiles quarter the operand traffic per flop; use them once they still fill most of the chip.
+    int rc = fill_batch(batch, dtype, problems, n_problems, 256, 256, &total);
+    if (rc) return rc;
+    bool big = total >= 128;
+    if (g_gemm_force_cfg >= 0) big = g_gemm_force_cfg == 1;
+    if (big) {
+        if (total == 0) return ASTRA_OK;
+        if (code16) gemm_nt_bf16_kernel<256, 256, 2, 4, true><<<total, 512, 0, s>>>(batch);
+        else gemm_nt_bf16_kernel<256, 256, 2, 4, false><<<total, 512, 0, s>>>(batch);
+        return launch_status();
+    }
+    rc = fill_batch(batch, dtype, problems, n_problems, 128, 128, &total);
+    if (rc) return rc;
     if (total == 0) return ASTRA_OK;
-    if (dtype == ASTRA_BF16) gemm_nt_bf16_kernel<<<total, 256, 0, s>>>(batch);
-    else gemm_nt_f32_kernel<<<total, 256, 0, s>>>(batch);
+    if (code16) gemm_nt_bf16_kernel<128, 128, 2, 2, true><<<total, 256, 0, s>>>(batch);
+    else gemm_nt_bf16_kernel<128, 128, 2, 2, false><<<total, 256, 0, s>>>(batch);
     return launch_status();
 }
 

@@ -32,9 +32,23 @@ int check_attn_desc(const astra_attn_desc* d) {
     return ASTRA_OK;
 }
 
+static AttnParams attn_params(const astra_attn_desc& d, const void* q, const void* k_local, const void* v_local,
+                              const void* k_hat, const void* v_hat, void* out, float* lse) {
+    AttnParams p{};
+    p.q = q; p.k_loc = k_local; p.v_loc = v_local; p.k_hat = k_hat; p.v_hat = v_hat;
+    p.out = out; p.lse = lse;
+    p.Hq = d.n_q_heads; p.Hkv = d.n_kv_heads; p.Tq = d.n_cls + d.n_local;
+    p.Tn_vis = d.causal ? d.n_nonlocal_before : d.n_nonlocal;
+    p.causal = d.causal;
+    p.scale = d.scale != 0.f ? d.scale : 1.f / sqrtf((float)d.head_dim);
+    return p;
+}
+
 struct LayerPlan {
     int Tq, Tn, Tn_vis, D, dq, dkv;
     bool need_xhat;
+    bool vt;                 // V, V-hat kept transposed for the attention kernel (bf16)
+    int ldv_loc, ldv_hat;    // padded token counts of the transposed V buffers
     size_t off_q, off_k, off_v, off_kh, off_vh, off_o, off_xhat, total;
 };
 
@@ -60,9 +74,12 @@ static int make_plan(const astra_layer_desc* desc, LayerPlan* pl) {
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
     pl->off_q = take((size_t)pl->Tq * pl->dq * eb);
     pl->off_k = take((size_t)pl->Tq * pl->dkv * eb);
-    pl->off_v = take((size_t)pl->Tq * pl->dkv * eb);
+    pl->vt = desc->vq.dtype == ASTRA_BF16;
+    pl->ldv_loc = (int)align_up((size_t)pl->Tq, 64);
+    pl->ldv_hat = (int)align_up((size_t)pl->Tn_vis, 64);
+    pl->off_v = take((size_t)(pl->vt ? pl->ldv_loc : pl->Tq) * pl->dkv * eb);
     pl->off_kh = take((size_t)pl->Tn_vis * pl->dkv * eb);
-    pl->off_vh = take((size_t)pl->Tn_vis * pl->dkv * eb);
+    pl->off_vh = take((size_t)(pl->vt ? pl->ldv_hat : pl->Tn_vis) * pl->dkv * eb);
     pl->off_o = take((size_t)pl->Tq * pl->dq * eb);
     pl->off_xhat = take(pl->need_xhat ? (size_t)pl->Tn_vis * pl->D * eb : 0);
     pl->total = off > 0 ? off : 256;
@@ -125,7 +142,8 @@ int astra_mixed_attention(const astra_attn_desc* desc, const void* q, const void
     if (!q || !k_local || !v_local || !out) return ASTRA_ERR_NULL;
     const int vis = desc->causal ? desc->n_nonlocal_before : desc->n_nonlocal;
     if (vis > 0 && (!k_hat || !v_hat)) return ASTRA_ERR_NULL;
-    return launch_attention(*desc, q, k_local, v_local, k_hat, v_hat, out, lse_out, (hipStream_t)stream);
+    const AttnParams ap = attn_params(*desc, q, k_local, v_local, k_hat, v_hat, out, lse_out);
+    return launch_attention(desc->dtype, ap, desc->head_dim, (hipStream_t)stream);
 }
 
 size_t astra_layer_workspace_bytes(const astra_layer_desc* desc) {
@@ -186,14 +204,20 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     local(pr[0], wq, bq, Q, pl.dq);
     local(pr[1], wk, bk, K, pl.dkv);
     local(pr[2], wv, bv, V, pl.dkv);
+    if (pl.vt) { pr[2].c_mode = kCTransposedV; pr[2].ldc = pl.ldv_loc; }
     nonlocal_(pr[3], wk, bk, Kh, pl.dkv);
     nonlocal_(pr[4], wv, bv, Vh, pl.dkv);
+    if (pl.vt) { pr[4].c_mode = kCTransposedV; pr[4].ldc = pl.ldv_hat; }
     rc = launch_gemm_batch(vq.dtype, pr, 5, s);
     if (rc) return rc;
     mark(2);
 
     // 3. mixed-precision attention (Eq. 1)
-    rc = launch_attention(at, Q, K, V, Kh, Vh, O, nullptr, s);
+    AttnParams ap = attn_params(at, Q, K, V, Kh, Vh, O, nullptr);
+    ap.v_transposed = pl.vt ? 1 : 0;
+    ap.ldv_loc = pl.ldv_loc;
+    ap.ldv_hat = pl.ldv_hat;
+    rc = launch_attention(vq.dtype, ap, at.head_dim, s);
     if (rc) return rc;
     mark(3);
 

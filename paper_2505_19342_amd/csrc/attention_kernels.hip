@@ -6,188 +6,307 @@
 
 namespace astra {
 
-struct AttnParams {
-    const void* q;        // [T_q, H_q, dh]
-    const void* k_loc;    // [T_q, H_kv, dh]
-    const void* v_loc;
-    const void* k_hat;    // [T_n, H_kv, dh]
-    const void* v_hat;
-    void* out;            // [T_q, H_q, dh]
-    float* lse;           // nullable [H_q, T_q]
-    int32_t Hq, Hkv, Tq;
-    int32_t Tn_vis;       // visible non-local rows (all of them, or those before the chunk when causal)
-    int32_t causal;
-    float scale;          // logit scale
-};
-
 // ------------------------------------------------------------------------------------------------
 // bf16, matrix cores, flash style (online softmax, nothing of size T_q x T_k is ever stored).
 //
-// A workgroup of 4 wavefronts owns 128 query rows of one head; wavefront w owns 32 of them.  Scores
-// are computed transposed, S^T = K_tile . Q^T (keys on the M side, queries on the N side of the
-// 32x32x16 MFMA), so that the 16 accumulator values of a lane all belong to ONE query: the running
-// max / sum of the online softmax are per-lane scalars, and the probabilities, rounded to bf16 in
-// place, already have the register layout of the B operand of O^T += V^T . P^T.  The only operand that
-// needs a transpose is V; it is read from its row-major LDS tile with the 64-bit transposing LDS read.
-// Key/value tiles of 64 rows are staged in LDS with XOR-swizzled 16-byte pieces.
+// Scores are computed transposed, S^T = K_tile . Q^T (keys on the M side, queries on the N side of the
+// 32x32x16 MFMA), so the 16 accumulator values of a lane all belong to ONE query: the running max / sum
+// of the online softmax are per-lane scalars, and the probabilities, rounded to bf16 in place, already
+// have the register layout of the B operand of O^T += V^T . P^T.
+//
+// A workgroup of 4 wavefronts owns 128 query rows of one head.  Wavefront w owns the 64 rows of query
+// group w & 1 (two 32-wide N blocks, so every K / V fragment read from LDS feeds two MFMAs) and walks
+// only the key/value tiles of parity w >> 1; the two wavefronts that share a query group merge their
+// (max, sum, O) triples through LDS at the end.  Tiles of 64 keys are double-buffered in LDS with
+// XOR-swizzled 16-byte pieces and fetched two steps ahead through registers.
+//
+// V is consumed as V^T.  With VT = true it arrives already transposed ([H_kv*dh, T_pad], tokens permuted
+// inside blocks of 16 as the projection kernel writes them) and fragments are plain 16-byte LDS reads;
+// with VT = false it arrives row-major [T, H_kv, dh] and is transposed by the 64-bit transposing LDS read.
+//
+// Workgroup order: ids are remapped so that each XCD (own L2) gets a contiguous run of heads, i.e. the
+// query heads of as few KV heads as possible, and inside a head the later (heavier under causal
+// masking) query blocks come first.
 // ------------------------------------------------------------------------------------------------
 constexpr int kAttQ = 128;   // query rows per workgroup
 constexpr int kAttKV = 64;   // key/value rows per tile
+constexpr int kXcdsA = 8;
+constexpr float kLazy = 8.f; // base-2 units
+
+__device__ __forceinline__ int xcd_remap_attn(int wg, int total) {
+    const int q = total / kXcdsA, r = total % kXcdsA;
+    const int xcd = wg % kXcdsA, slot = wg / kXcdsA;
+    return xcd < r ? xcd * (q + 1) + slot : r * (q + 1) + (xcd - r) * q + slot;
+}
 
 template <int DH>
 __device__ __forceinline__ int swz_k(int r) { return DH == 128 ? (r & 15) : ((r >> 1) & 7); }
+// row-major V tile read by the transposing load: 4 consecutive rows x 64 bytes must hit distinct banks
 template <int DH>
 __device__ __forceinline__ int swz_v(int r) { return DH == 128 ? ((r & 3) << 2) : (((r >> 1) & 1) << 2); }
+// transposed V tile: rows of 64 keys = 128 bytes, same rule as the GEMM operand tiles
+__device__ __forceinline__ int swz_vt(int r) { return (r >> 1) & 7; }
 
-template <int DH>
+template <int DH, bool VT>
 __global__ __launch_bounds__(256) void attn_bf16_kernel(const AttnParams p) {
-    constexpr int CPR = DH / 8;                // 16-byte pieces per row
+    constexpr int CPR = DH / 8;                // 16-byte pieces per K (and row-major V) row
     constexpr int NKS = DH / 16;               // contraction steps of Q.K
     constexpr int NDB = DH / 32;               // 32-wide blocks of the head dimension
     constexpr int PIECES = kAttKV * CPR;       // pieces per tile
-    __shared__ uint4 lds_k[PIECES];
-    __shared__ uint4 lds_v[PIECES];
+    constexpr int LPT = PIECES / 256;          // staging loads per thread per tile
+    // [buffer][parity] tiles
+    __shared__ u32x4 lds_k[2][2][PIECES];
+    __shared__ u32x4 lds_v[2][2][PIECES];
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform: keeps the tile bookkeeping in scalar registers
     const int i32 = lane & 31, h = lane >> 5;
-    const int head = blockIdx.y;
+    const int qg = wave & 1, par = wave >> 1;
+
+    const int n_qb = (p.Tq + kAttQ - 1) / kAttQ;
+    const int vt_id = xcd_remap_attn(blockIdx.x, gridDim.x);
+    const int head = vt_id / n_qb;
+    const int qb = n_qb - 1 - (vt_id % n_qb);
     const int hk = head / (p.Hq / p.Hkv);
-    // heavier (later) query blocks first under causal masking
-    const int qb = gridDim.x - 1 - blockIdx.x;
     const int q0 = qb * kAttQ;
     const int Tq = p.Tq;
     const int64_t q_ld = (int64_t)p.Hq * DH, kv_ld = (int64_t)p.Hkv * DH;
 
-    const int qrow = q0 + wave * 32 + i32;                 // this lane's query (N side)
-    const int qrow_ld = qrow < Tq ? qrow : Tq - 1;
-    const uint16_t* __restrict__ Q = (const uint16_t*)p.q + (int64_t)qrow_ld * q_ld + (int64_t)head * DH;
-    bf16x8 qf[NKS];
+    // this lane's two queries (N side): rows q0 + 64*qg + 32*nb + i32
+    int qrow[2];
+    bf16x8 qf[2][NKS];
 #pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) qf[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(Q + 16 * ks + 8 * h));
+    for (int nb = 0; nb < 2; ++nb) {
+        qrow[nb] = q0 + 64 * qg + 32 * nb + i32;
+        const int r = qrow[nb] < Tq ? qrow[nb] : Tq - 1;
+        const uint16_t* __restrict__ Q = (const uint16_t*)p.q + (int64_t)r * q_ld + (int64_t)head * DH;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks)
+            qf[nb][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Q + 16 * ks + 8 * h));
+    }
 
-    f32x16 acc_o[NDB];
+    f32x16 acc_o[NDB][2];
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc_o[db][v] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc_o[db][nb][v] = 0.f;
+    float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
     const float sl2 = p.scale * 1.4426950408889634f;       // logits in base-2 units
 
     const int n_hat_tiles = (p.Tn_vis + kAttKV - 1) / kAttKV;
     const int loc_rows = p.causal ? min(q0 + kAttQ, Tq) : Tq;     // local keys any row of this block may see
-    const int n_loc_tiles = (loc_rows + kAttKV - 1) / kAttKV;
-    const int wave_last_q = q0 + wave * 32 + 31;
+    const int n_tiles = n_hat_tiles + (loc_rows + kAttKV - 1) / kAttKV;
+    const int n_pairs = (n_tiles + 1) / 2;
+    const int wave_q_lo = q0 + 64 * qg;
 
-    for (int t = 0; t < n_hat_tiles + n_loc_tiles; ++t) {
+    // ---- staging: global -> LDS without passing through registers.  One wavefront instruction moves 64
+    // consecutive 16-byte LDS slots; the XOR swizzle is applied on the global side (the lane that owns
+    // slot (row, piece) fetches piece ^ swizzle(row) of that row).
+    auto issue_pair = [&](int pair, int buf) {
+#pragma unroll
+        for (int pp = 0; pp < 2; ++pp) {
+            int t = 2 * pair + pp;
+            t = t < n_tiles ? t : n_tiles - 1;                 // past the end: re-read the last tile, never used
+            const bool is_loc = t >= n_hat_tiles;
+            const int row0 = (is_loc ? t - n_hat_tiles : t) * kAttKV;
+            const int count = is_loc ? Tq : p.Tn_vis;
+            const uint16_t* __restrict__ Ks = (const uint16_t*)(is_loc ? p.k_loc : p.k_hat) + (int64_t)hk * DH;
+            const uint16_t* __restrict__ Vs = (const uint16_t*)(is_loc ? p.v_loc : p.v_hat);
+            const int64_t v_ld = is_loc ? p.ldv_loc : p.ldv_hat;
+            const uint32_t k_base = lds_byte_addr(&lds_k[buf][pp][0]), v_base = lds_byte_addr(&lds_v[buf][pp][0]);
+#pragma unroll
+            for (int it = 0; it < LPT; ++it) {
+                const int c = tid + 256 * it;                  // LDS slot of this lane
+                const uint32_t slot0 = (uint32_t)(64 * (wave + 4 * it)) * 16u;   // first slot of this wavefront instruction
+                const int r = c / CPR, ph = c % CPR;
+                const int rg = row0 + r < count ? row0 + r : count - 1;
+                dma_global_to_lds_16(Ks + (int64_t)rg * kv_ld + (ph ^ swz_k<DH>(r)) * 8, k_base + slot0);
+                if (VT) {
+                    const int d = c >> 3, ph8 = c & 7;          // V^T tile: [DH rows][8 pieces of 8 keys]
+                    dma_global_to_lds_16(Vs + ((int64_t)hk * DH + d) * v_ld + row0 + (ph8 ^ swz_vt(d)) * 8, v_base + slot0);
+                } else {
+                    dma_global_to_lds_16(Vs + (int64_t)hk * DH + (int64_t)rg * kv_ld + (ph ^ swz_v<DH>(r)) * 8, v_base + slot0);
+                }
+            }
+        }
+    };
+
+    auto compute_tile = [&](int buf, int t_in) {
+        const int t = t_in < n_tiles ? t_in : n_tiles - 1;
         const bool is_loc = t >= n_hat_tiles;
         const int row0 = (is_loc ? t - n_hat_tiles : t) * kAttKV;
-        const int count = is_loc ? Tq : p.Tn_vis;
-        const uint16_t* __restrict__ Ks = (const uint16_t*)(is_loc ? p.k_loc : p.k_hat) + (int64_t)hk * DH;
-        const uint16_t* __restrict__ Vs = (const uint16_t*)(is_loc ? p.v_loc : p.v_hat) + (int64_t)hk * DH;
-
-        __syncthreads();
-#pragma unroll
-        for (int it = 0; it < PIECES / 256; ++it) {
-            const int c = tid + 256 * it;
-            const int r = c / CPR, pc = c % CPR;
-            const int rg = row0 + r < count ? row0 + r : count - 1;
-            const uint4 kv = *reinterpret_cast<const uint4*>(Ks + (int64_t)rg * kv_ld + pc * 8);
-            const uint4 vv = *reinterpret_cast<const uint4*>(Vs + (int64_t)rg * kv_ld + pc * 8);
-            lds_k[r * CPR + (pc ^ swz_k<DH>(r))] = kv;
-            lds_v[r * CPR + (pc ^ swz_v<DH>(r))] = vv;
-        }
-        __syncthreads();
-
-        const bool diag = is_loc && p.causal && (row0 + kAttKV - 1 > q0 + wave * 32);   // some (q, k) pair of this wave is hidden
-        if (is_loc && p.causal && row0 > wave_last_q) continue;                        // whole tile hidden from this wave
+        // a tile index past the end (odd tile count) is processed with every key masked: the control flow
+        // stays the same for all wavefronts and iterations, LDS holds a finite copy of the last tile
+        const int count = t_in >= n_tiles ? 0 : (is_loc ? Tq : p.Tn_vis);
+        const bool diag = is_loc && p.causal && (row0 + kAttKV - 1 > wave_q_lo);     // some pair of this wave is hidden
         const bool ragged = row0 + kAttKV > count;
+        const u32x4* __restrict__ Kt = lds_k[buf][par];
+        const u32x4* __restrict__ Vt = lds_v[buf][par];
 
-        // S^T tile: 64 keys x 32 queries
-        f32x16 acc_s[2];
+        // S^T tile: 64 keys x 64 queries
+        f32x16 acc_s[2][2];
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc_s[mb][v] = 0.f;
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc_s[mb][nb][v] = 0.f;
             const int r = mb * 32 + i32;
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks) {
-                const bf16x8 kf = as_bf16x8(lds_k[r * CPR + ((2 * ks + h) ^ swz_k<DH>(r))]);
-                acc_s[mb] = mfma_32x32x16(kf, qf[ks], acc_s[mb]);
+                const bf16x8 kf = __builtin_bit_cast(bf16x8, Kt[r * CPR + ((2 * ks + h) ^ swz_k<DH>(r))]);
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb) acc_s[mb][nb] = mfma_32x32x16(kf, qf[nb][ks], acc_s[mb][nb]);
             }
         }
-        // scale, mask, running max
-        float mx = -INFINITY;
+        // masking (ragged source tail, causal diagonal): a wave-uniform, rarely taken pass of its own
+        if (ragged || diag) {
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+            for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                float s = acc_s[mb][v] * sl2;
-                if (ragged || diag) {
-                    const int key = row0 + mb * 32 + acc_row(v, h);
-                    if (key >= count || (diag && key > qrow)) s = -INFINITY;
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int key = row0 + mb * 32 + acc_row(v, h);
+                        if (key >= count || (diag && key > qrow[nb])) acc_s[mb][nb][v] = -INFINITY;
+                    }
+        }
+        // Online softmax per query (per lane and N block), in base-2 units.  The reference maximum m_run
+        // is only raised when a score exceeds it by more than kLazy (2^kLazy fits bf16 and fp32 easily):
+        // after the first tiles the accumulators are almost never rescaled.
+        bf16x8 pf[4][2];
+        float alpha[2];
+        bool rescale = false;
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, acc_s[mb][nb][v]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32)) * sl2;
+            alpha[nb] = 1.f;
+            if (mx > m_run[nb] + kLazy) {            // also taken for the first visible key (m_run = -inf)
+                alpha[nb] = __builtin_amdgcn_exp2f(m_run[nb] - mx);
+                m_run[nb] = mx;
+                rescale = true;
+            }
+            const float m_ref = m_run[nb] == -INFINITY ? 0.f : m_run[nb];
+            float lsum = 0.f;
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float e = __builtin_amdgcn_exp2f(fmaf(acc_s[mb][nb][v], sl2, -m_ref));
+                    lsum += e;
+                    pf[mb * 2 + (v >> 3)][nb][v & 7] = (__bf16)e;
                 }
-                acc_s[mb][v] = s;
-                mx = fmaxf(mx, s);
-            }
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx);
-        const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = exp2f(m_run - m_safe);
-        m_run = m_new;
-        float lsum = 0.f;
-        bf16x8 pf[4];
+            l_run[nb] = l_run[nb] * alpha[nb] + lsum;
+        }
+        if (__builtin_amdgcn_ballot_w64(rescale) != 0) {
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+            for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const float e = exp2f(acc_s[mb][v] - m_safe);
-                lsum += e;
-                pf[mb * 2 + (v >> 3)][v & 7] = (__bf16)e;
-            }
-        l_run = l_run * alpha + lsum;
+                for (int db = 0; db < NDB; ++db)
 #pragma unroll
-        for (int db = 0; db < NDB; ++db)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc_o[db][v] *= alpha;
-
+                    for (int v = 0; v < 16; ++v) acc_o[db][nb][v] *= alpha[nb];
+        }
         // O^T += V^T . P^T : contraction over the 64 keys in 4 steps of 16
-        const int s16 = lane & 15, q4 = lane >> 4;
 #pragma unroll
         for (int kstep = 0; kstep < 4; ++kstep) {
 #pragma unroll
             for (int db = 0; db < NDB; ++db) {
-                const int c = db * 4 + 2 * (q4 & 1) + ((s16 & 3) >> 1);
-                const int r_lo = 16 * kstep + 4 * h + (s16 >> 2);
-                const int r_hi = r_lo + 8;
-                const char* base = reinterpret_cast<const char*>(lds_v);
-                const s16x4 lo = lds_read_tr16_b64(base + (r_lo * CPR + (c ^ swz_v<DH>(r_lo))) * 16 + 8 * (s16 & 1));
-                const s16x4 hi = lds_read_tr16_b64(base + (r_hi * CPR + (c ^ swz_v<DH>(r_hi))) * 16 + 8 * (s16 & 1));
-                uint4 packed;
-                packed.x = (uint16_t)lo[0] | ((uint32_t)(uint16_t)lo[1] << 16);
-                packed.y = (uint16_t)lo[2] | ((uint32_t)(uint16_t)lo[3] << 16);
-                packed.z = (uint16_t)hi[0] | ((uint32_t)(uint16_t)hi[1] << 16);
-                packed.w = (uint16_t)hi[2] | ((uint32_t)(uint16_t)hi[3] << 16);
-                acc_o[db] = mfma_32x32x16(as_bf16x8(packed), pf[kstep], acc_o[db]);
+                bf16x8 vf;
+                if (VT) {
+                    const int d = db * 32 + i32;
+                    vf = __builtin_bit_cast(bf16x8, Vt[d * 8 + ((2 * kstep + h) ^ swz_vt(d))]);
+                } else {
+                    const int s16 = lane & 15, q4 = lane >> 4;
+                    const int c = db * 4 + 2 * (q4 & 1) + ((s16 & 3) >> 1);
+                    const int r_lo = 16 * kstep + 4 * h + (s16 >> 2);
+                    const int r_hi = r_lo + 8;
+                    const char* base = reinterpret_cast<const char*>(Vt);
+                    const s16x4 lo = lds_read_tr16_b64(base + (r_lo * CPR + (c ^ swz_v<DH>(r_lo))) * 16 + 8 * (s16 & 1));
+                    const s16x4 hi = lds_read_tr16_b64(base + (r_hi * CPR + (c ^ swz_v<DH>(r_hi))) * 16 + 8 * (s16 & 1));
+                    u32x4 packed;
+                    packed.x = (uint16_t)lo[0] | ((uint32_t)(uint16_t)lo[1] << 16);
+                    packed.y = (uint16_t)lo[2] | ((uint32_t)(uint16_t)lo[3] << 16);
+                    packed.z = (uint16_t)hi[0] | ((uint32_t)(uint16_t)hi[1] << 16);
+                    packed.w = (uint16_t)hi[2] | ((uint32_t)(uint16_t)hi[3] << 16);
+                    vf = __builtin_bit_cast(bf16x8, packed);
+                }
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb) acc_o[db][nb] = mfma_32x32x16(vf, pf[kstep][nb], acc_o[db][nb]);
             }
         }
+    };
+
+    // ---- pipeline over tile pairs: the transfers of pair i+1 run while pair i is consumed; one barrier per pair.
+    issue_pair(0, 0);
+    wait_vmem_all();
+    __syncthreads();
+    for (int pair = 0; pair < n_pairs; ++pair) {
+        const int buf = pair & 1;
+        if (pair + 1 < n_pairs) issue_pair(pair + 1, buf ^ 1);
+        compute_tile(buf, 2 * pair + par);
+        wait_vmem_all();
+        __syncthreads();
     }
 
-    // finish: merge the two half-waves' partial sums, normalise, store 4 consecutive head-dim values per lane
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
-    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    if (qrow < Tq) {
-        uint16_t* __restrict__ O = (uint16_t*)p.out + (int64_t)qrow * q_ld + (int64_t)head * DH;
+    // ---- merge the two parities of each query group through LDS (the tile buffers are free now)
+    float* xch = reinterpret_cast<float*>(&lds_k[0][0][0]);        // NDB*2*16*64 floats per query group (<= 32 KiB each)
+    float* xml = reinterpret_cast<float*>(&lds_v[0][0][0]);        // m, l per (query group, N block, lane)
+    float l_tot[2];
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) l_tot[nb] = l_run[nb] + __shfl_xor(l_run[nb], 32);
+    if (par == 1) {
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
-            for (int vq = 0; vq < 4; ++vq) {
-                uint2 w;
-                w.x = pack_bf16x2(acc_o[db][4 * vq + 0] * inv, acc_o[db][4 * vq + 1] * inv);
-                w.y = pack_bf16x2(acc_o[db][4 * vq + 2] * inv, acc_o[db][4 * vq + 3] * inv);
-                *reinterpret_cast<uint2*>(O + db * 32 + 8 * vq + 4 * h) = w;
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) xch[(((qg * NDB + db) * 2 + nb) * 16 + v) * 64 + lane] = acc_o[db][nb][v];
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+            xml[((qg * 2 + nb) * 2 + 0) * 64 + lane] = m_run[nb];
+            xml[((qg * 2 + nb) * 2 + 1) * 64 + lane] = l_tot[nb];
+        }
+    }
+    __syncthreads();
+    if (par == 0) {
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+            const float m1 = xml[((qg * 2 + nb) * 2 + 0) * 64 + lane];
+            const float l1 = xml[((qg * 2 + nb) * 2 + 1) * 64 + lane];
+            const float m = fmaxf(m_run[nb], m1);
+            const float m_safe = m == -INFINITY ? 0.f : m;
+            const float a0 = __builtin_amdgcn_exp2f(m_run[nb] - m_safe), a1 = __builtin_amdgcn_exp2f(m1 - m_safe);
+            const float l = l_tot[nb] * a0 + l1 * a1;
+            const float inv = l > 0.f ? 1.f / l : 0.f;
+            const float c0 = a0 * inv, c1 = a1 * inv;
+            if (qrow[nb] < Tq) {
+                uint16_t* __restrict__ O = (uint16_t*)p.out + (int64_t)qrow[nb] * q_ld + (int64_t)head * DH;
+#pragma unroll
+                for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                    for (int vq = 0; vq < 4; ++vq) {
+                        float o[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const int v = 4 * vq + e;
+                            o[e] = acc_o[db][nb][v] * c0 + xch[(((qg * NDB + db) * 2 + nb) * 16 + v) * 64 + lane] * c1;
+                        }
+                        u32x2 w;
+                        w.x = pack_bf16x2(o[0], o[1]);
+                        w.y = pack_bf16x2(o[2], o[3]);
+                        *reinterpret_cast<u32x2*>(O + db * 32 + 8 * vq + 4 * h) = w;
+                    }
+                if (p.lse && h == 0) p.lse[(int64_t)head * Tq + qrow[nb]] = (m + log2f(l)) * 0.6931471805599453f;
             }
-        if (p.lse && h == 0) p.lse[(int64_t)head * Tq + qrow] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
+        }
     }
 }
 
@@ -255,26 +374,27 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnParams p, int d
     if (p.lse && lane == 0) p.lse[(int64_t)head * p.Tq + row] = m_run + logf(l_run);
 }
 
-int launch_attention(const astra_attn_desc& d, const void* q, const void* k_local, const void* v_local,
-                     const void* k_hat, const void* v_hat, void* out, float* lse, hipStream_t s) {
-    AttnParams p{};
-    p.q = q; p.k_loc = k_local; p.v_loc = v_local; p.k_hat = k_hat; p.v_hat = v_hat;
-    p.out = out; p.lse = lse;
-    p.Hq = d.n_q_heads; p.Hkv = d.n_kv_heads; p.Tq = d.n_cls + d.n_local;
-    p.Tn_vis = d.causal ? d.n_nonlocal_before : d.n_nonlocal;
-    p.causal = d.causal;
-    p.scale = d.scale != 0.f ? d.scale : 1.f / sqrtf((float)d.head_dim);
+int launch_attention(int dtype, const AttnParams& p_in, int head_dim, hipStream_t s) {
+    AttnParams p = p_in;
     if (p.Tq == 0) return ASTRA_OK;
-    if (d.dtype == ASTRA_BF16) {
-        dim3 grid((unsigned)ceil_div(p.Tq, kAttQ), (unsigned)p.Hq);
-        if (d.head_dim == 128) attn_bf16_kernel<128><<<grid, 256, 0, s>>>(p);
-        else if (d.head_dim == 64) attn_bf16_kernel<64><<<grid, 256, 0, s>>>(p);
-        else return ASTRA_ERR_UNSUPPORTED;
+    if (dtype == ASTRA_BF16) {
+        const int64_t total = (int64_t)ceil_div(p.Tq, kAttQ) * p.Hq;
+        if (total > 0x7fffffff) return ASTRA_ERR_SHAPE;
+        const bool vt = p.v_transposed != 0;
+        if (head_dim == 128) {
+            if (vt) attn_bf16_kernel<128, true><<<(int)total, 256, 0, s>>>(p);
+            else attn_bf16_kernel<128, false><<<(int)total, 256, 0, s>>>(p);
+        } else if (head_dim == 64) {
+            if (vt) attn_bf16_kernel<64, true><<<(int)total, 256, 0, s>>>(p);
+            else attn_bf16_kernel<64, false><<<(int)total, 256, 0, s>>>(p);
+        } else {
+            return ASTRA_ERR_UNSUPPORTED;
+        }
     } else {
-        if (d.head_dim > 256) return ASTRA_ERR_UNSUPPORTED;
+        if (head_dim > 256 || p.v_transposed) return ASTRA_ERR_UNSUPPORTED;
         const int64_t blocks = ceil_div((int64_t)p.Hq * p.Tq, 4);
         if (blocks > 0x7fffffff) return ASTRA_ERR_SHAPE;
-        attn_f32_kernel<<<(int)blocks, 256, 0, s>>>(p, d.head_dim);
+        attn_f32_kernel<<<(int)blocks, 256, 0, s>>>(p, head_dim);
     }
     return launch_status();
 }

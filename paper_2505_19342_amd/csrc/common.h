@@ -46,6 +46,21 @@ __device__ __forceinline__ s16x4 lds_read_tr16_b64(const void* lds_ptr) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(lds_ptr));
 }
 
+// ---- direct global -> LDS transfers ------------------------------------------------------------
+// byte address of a __shared__ object inside the workgroup's LDS allocation
+__device__ __forceinline__ uint32_t lds_byte_addr(const void* p) {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)(p);
+}
+// One wavefront instruction: lane L copies the 16 bytes at its own global address to LDS byte address
+// lds_base + 16*L (lds_base wave-uniform).  Nothing passes through vector registers.  Completion is
+// counted by vmcnt; the compiler does not know about these transfers, so the caller waits with
+// wait_vmem_all() and then synchronises the workgroup before any wavefront reads the data.
+__device__ __forceinline__ void dma_global_to_lds_16(const void* gptr, uint32_t lds_base) {
+    const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base), "v"(gptr) : "memory");
+}
+__device__ __forceinline__ void wait_vmem_all() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 
 // ---- host side ---------------------------------------------------------------------------------
@@ -88,7 +103,21 @@ constexpr int kMaxGemmProblems = 6;
 int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hipStream_t s);
 extern int g_gemm_force_cfg;
 
-int launch_attention(const astra_attn_desc& d, const void* q, const void* k_local, const void* v_local,
-                     const void* k_hat, const void* v_hat, void* out, float* lse, hipStream_t s);
+struct AttnParams {
+    const void* q;        // [T_q, H_q, dh]
+    const void* k_loc;    // [T_q, H_kv, dh]
+    const void* v_loc;    // [T_q, H_kv, dh], or transposed [H_kv*dh, ldv_loc]
+    const void* k_hat;    // [T_n, H_kv, dh]
+    const void* v_hat;    // [T_n, H_kv, dh], or transposed [H_kv*dh, ldv_hat]
+    void* out;            // [T_q, H_q, dh]
+    float* lse;           // nullable [H_q, T_q]
+    int32_t Hq, Hkv, Tq;
+    int32_t Tn_vis;       // visible non-local rows (all of them, or those before the chunk when causal)
+    int32_t causal;
+    int32_t v_transposed; // bf16 only: V buffers are V^T in the projection kernel's kCTransposedV layout
+    int32_t ldv_loc, ldv_hat;   // padded token counts (multiples of 64) of the transposed V buffers
+    float scale;          // logit scale
+};
+int launch_attention(int dtype, const AttnParams& p, int head_dim, hipStream_t s);
 
 }  // namespace astra

@@ -14,11 +14,13 @@ namespace astra {
 // of the online softmax are per-lane scalars, and the probabilities, rounded to bf16 in place, already
 // have the register layout of the B operand of O^T += V^T . P^T.
 //
-// A workgroup of 4 wavefronts owns 128 query rows of one head.  Wavefront w owns the 64 rows of query
-// group w & 1 (two 32-wide N blocks, so every K / V fragment read from LDS feeds two MFMAs) and walks
-// only the key/value tiles of parity w >> 1; the two wavefronts that share a query group merge their
-// (max, sum, O) triples through LDS at the end.  Tiles of 64 keys are double-buffered in LDS with
-// XOR-swizzled 16-byte pieces and fetched two steps ahead through registers.
+// A workgroup of 8 wavefronts owns 128 query rows of one head.  Wavefront w owns the 32 rows of query
+// group w & 3 and walks only the key/value tiles of parity w >> 2; the two wavefronts that share a query
+// group merge their (max, sum, O) triples through LDS at the end.  With two wavefronts per SIMD, one can
+// run its softmax on the vector ALU while the other occupies the matrix core, and a wavefront's whole
+// state (O^T 64, S^T 32, Q 32, P 16 registers) stays in ordinary vector registers.  Tiles of 64 keys are
+// double-buffered in LDS with XOR-swizzled 16-byte pieces and arrive by direct global->LDS transfers
+// issued one pair of tiles ahead.
 //
 // V is consumed as V^T.  With VT = true it arrives already transposed ([H_kv*dh, T_pad], tokens permuted
 // inside blocks of 16 as the projection kernel writes them) and fragments are plain 16-byte LDS reads;
@@ -28,10 +30,11 @@ namespace astra {
 // query heads of as few KV heads as possible, and inside a head the later (heavier under causal
 // masking) query blocks come first.
 // ------------------------------------------------------------------------------------------------
-constexpr int kAttQ = 128;   // query rows per workgroup
-constexpr int kAttKV = 64;   // key/value rows per tile
+constexpr int kAttQ = 128;       // query rows per workgroup
+constexpr int kAttKV = 64;       // key/value rows per tile
+constexpr int kAttThreads = 512;
 constexpr int kXcdsA = 8;
-constexpr float kLazy = 8.f; // base-2 units
+constexpr float kLazy = 8.f;     // base-2 units
 
 __device__ __forceinline__ int xcd_remap_attn(int wg, int total) {
     const int q = total / kXcdsA, r = total % kXcdsA;
@@ -48,12 +51,12 @@ __device__ __forceinline__ int swz_v(int r) { return DH == 128 ? ((r & 3) << 2) 
 __device__ __forceinline__ int swz_vt(int r) { return (r >> 1) & 7; }
 
 template <int DH, bool VT>
-__global__ __launch_bounds__(256) void attn_bf16_kernel(const AttnParams p) {
+__global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams p) {
     constexpr int CPR = DH / 8;                // 16-byte pieces per K (and row-major V) row
     constexpr int NKS = DH / 16;               // contraction steps of Q.K
     constexpr int NDB = DH / 32;               // 32-wide blocks of the head dimension
     constexpr int PIECES = kAttKV * CPR;       // pieces per tile
-    constexpr int LPT = PIECES / 256;          // staging loads per thread per tile
+    constexpr int LPT = PIECES / kAttThreads;  // transfers per thread per tile
     // [buffer][parity] tiles
     __shared__ u32x4 lds_k[2][2][PIECES];
     __shared__ u32x4 lds_v[2][2][PIECES];
@@ -62,7 +65,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const AttnParams p) {
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform: keeps the tile bookkeeping in scalar registers
     const int i32 = lane & 31, h = lane >> 5;
-    const int qg = wave & 1, par = wave >> 1;
+    const int qg = wave & 3, par = wave >> 2;
 
     const int n_qb = (p.Tq + kAttQ - 1) / kAttQ;
     const int vt_id = xcd_remap_attn(blockIdx.x, gridDim.x);
@@ -73,38 +76,41 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const AttnParams p) {
     const int Tq = p.Tq;
     const int64_t q_ld = (int64_t)p.Hq * DH, kv_ld = (int64_t)p.Hkv * DH;
 
-    // this lane's two queries (N side): rows q0 + 64*qg + 32*nb + i32
-    int qrow[2];
-    bf16x8 qf[2][NKS];
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-        qrow[nb] = q0 + 64 * qg + 32 * nb + i32;
-        const int r = qrow[nb] < Tq ? qrow[nb] : Tq - 1;
+    // this lane's query (N side)
+    const int qrow = q0 + 32 * qg + i32;
+    bf16x8 qf[NKS];
+    {
+        const int r = qrow < Tq ? qrow : Tq - 1;
         const uint16_t* __restrict__ Q = (const uint16_t*)p.q + (int64_t)r * q_ld + (int64_t)head * DH;
 #pragma unroll
-        for (int ks = 0; ks < NKS; ++ks)
-            qf[nb][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Q + 16 * ks + 8 * h));
+        for (int ks = 0; ks < NKS; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Q + 16 * ks + 8 * h));
     }
 
-    f32x16 acc_o[NDB][2];
+    f32x16 acc_o[NDB];
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc_o[db][nb][v] = 0.f;
-    float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+        for (int v = 0; v < 16; ++v) acc_o[db][v] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
     const float sl2 = p.scale * 1.4426950408889634f;       // logits in base-2 units
 
     const int n_hat_tiles = (p.Tn_vis + kAttKV - 1) / kAttKV;
     const int loc_rows = p.causal ? min(q0 + kAttQ, Tq) : Tq;     // local keys any row of this block may see
     const int n_tiles = n_hat_tiles + (loc_rows + kAttKV - 1) / kAttKV;
     const int n_pairs = (n_tiles + 1) / 2;
-    const int wave_q_lo = q0 + 64 * qg;
+    const int wave_q_lo = q0 + 32 * qg;
 
     // ---- staging: global -> LDS without passing through registers.  One wavefront instruction moves 64
     // consecutive 16-byte LDS slots; the XOR swizzle is applied on the global side (the lane that owns
-    // slot (row, piece) fetches piece ^ swizzle(row) of that row).
+    // slot (row, piece) fetches piece ^ swizzle(row) of that row).  Slot c = tid + 512*it of a K tile is
+    // (row c / CPR, piece c % CPR); both swizzles are periodic in the row step between two `it`, so the
+    // piece a lane fetches is the same for every `it` and only the row term changes.
+    constexpr int ROW_STEP = kAttThreads / CPR;               // K rows between consecutive `it`
+    const int kr0 = tid / CPR, kph = tid % CPR;
+    const uint32_t kcol = (uint32_t)((kph ^ swz_k<DH>(kr0)) * 16);                 // bytes
+    const uint32_t vcol = VT ? (uint32_t)(((tid & 7) ^ swz_vt(tid >> 3)) * 16)      // V^T: row tid/8 + 64*it, piece tid%8
+                             : (uint32_t)((kph ^ swz_v<DH>(kr0)) * 16);
+    const uint32_t kv_ld_b = (uint32_t)kv_ld * 2u;
     auto issue_pair = [&](int pair, int buf) {
 #pragma unroll
         for (int pp = 0; pp < 2; ++pp) {
@@ -112,28 +118,25 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const AttnParams p) {
             t = t < n_tiles ? t : n_tiles - 1;                 // past the end: re-read the last tile, never used
             const bool is_loc = t >= n_hat_tiles;
             const int row0 = (is_loc ? t - n_hat_tiles : t) * kAttKV;
-            const int count = is_loc ? Tq : p.Tn_vis;
-            const uint16_t* __restrict__ Ks = (const uint16_t*)(is_loc ? p.k_loc : p.k_hat) + (int64_t)hk * DH;
-            const uint16_t* __restrict__ Vs = (const uint16_t*)(is_loc ? p.v_loc : p.v_hat);
-            const int64_t v_ld = is_loc ? p.ldv_loc : p.ldv_hat;
+            const int lim = (is_loc ? Tq : p.Tn_vis) - 1 - row0;                 // last valid row of the tile
+            const char* __restrict__ Kb = (const char*)(is_loc ? p.k_loc : p.k_hat) + ((int64_t)row0 * kv_ld + (int64_t)hk * DH) * 2;
             const uint32_t k_base = lds_byte_addr(&lds_k[buf][pp][0]), v_base = lds_byte_addr(&lds_v[buf][pp][0]);
+            const uint32_t v_ld_b = (uint32_t)(is_loc ? p.ldv_loc : p.ldv_hat) * 2u;
+            const char* __restrict__ Vb = VT ? (const char*)(is_loc ? p.v_loc : p.v_hat) + ((int64_t)hk * DH * v_ld_b + (int64_t)row0 * 2)
+                                             : (const char*)(is_loc ? p.v_loc : p.v_hat) + ((int64_t)row0 * kv_ld + (int64_t)hk * DH) * 2;
 #pragma unroll
             for (int it = 0; it < LPT; ++it) {
-                const int c = tid + 256 * it;                  // LDS slot of this lane
-                const uint32_t slot0 = (uint32_t)(64 * (wave + 4 * it)) * 16u;   // first slot of this wavefront instruction
-                const int r = c / CPR, ph = c % CPR;
-                const int rg = row0 + r < count ? row0 + r : count - 1;
-                dma_global_to_lds_16(Ks + (int64_t)rg * kv_ld + (ph ^ swz_k<DH>(r)) * 8, k_base + slot0);
-                if (VT) {
-                    const int d = c >> 3, ph8 = c & 7;          // V^T tile: [DH rows][8 pieces of 8 keys]
-                    dma_global_to_lds_16(Vs + ((int64_t)hk * DH + d) * v_ld + row0 + (ph8 ^ swz_vt(d)) * 8, v_base + slot0);
-                } else {
-                    dma_global_to_lds_16(Vs + (int64_t)hk * DH + (int64_t)rg * kv_ld + (ph ^ swz_v<DH>(r)) * 8, v_base + slot0);
-                }
+                const uint32_t slot0 = (uint32_t)(64 * (wave + 8 * it)) * 16u;   // first slot of this wavefront instruction
+                const int r = min(kr0 + ROW_STEP * it, lim);
+                const uint32_t koff = (uint32_t)r * kv_ld_b + kcol;
+                dma_global_to_lds_16(Kb, koff, k_base + slot0);
+                const uint32_t voff = VT ? (uint32_t)((tid >> 3) + 64 * it) * v_ld_b + vcol : koff - kcol + vcol;
+                dma_global_to_lds_16(Vb, voff, v_base + slot0);
             }
         }
     };
 
+    // ---- one 64-key tile: S^T (16 MFMAs), softmax, O^T update (16 MFMAs)
     auto compute_tile = [&](int buf, int t_in) {
         const int t = t_in < n_tiles ? t_in : n_tiles - 1;
         const bool is_loc = t >= n_hat_tiles;
@@ -142,77 +145,64 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const AttnParams p) {
         // stays the same for all wavefronts and iterations, LDS holds a finite copy of the last tile
         const int count = t_in >= n_tiles ? 0 : (is_loc ? Tq : p.Tn_vis);
         const bool diag = is_loc && p.causal && (row0 + kAttKV - 1 > wave_q_lo);     // some pair of this wave is hidden
-        const bool ragged = row0 + kAttKV > count;
+        const bool masked = diag || (row0 + kAttKV > count);
         const u32x4* __restrict__ Kt = lds_k[buf][par];
         const u32x4* __restrict__ Vt = lds_v[buf][par];
 
-        // S^T tile: 64 keys x 64 queries
-        f32x16 acc_s[2][2];
+        f32x16 acc_s[2];
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb) {
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc_s[mb][nb][v] = 0.f;
+            for (int v = 0; v < 16; ++v) acc_s[mb][v] = 0.f;
             const int r = mb * 32 + i32;
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks) {
                 const bf16x8 kf = __builtin_bit_cast(bf16x8, Kt[r * CPR + ((2 * ks + h) ^ swz_k<DH>(r))]);
-#pragma unroll
-                for (int nb = 0; nb < 2; ++nb) acc_s[mb][nb] = mfma_32x32x16(kf, qf[nb][ks], acc_s[mb][nb]);
+                acc_s[mb] = mfma_32x32x16(kf, qf[ks], acc_s[mb]);
             }
         }
         // masking (ragged source tail, causal diagonal): a wave-uniform, rarely taken pass of its own
-        if (ragged || diag) {
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int key = row0 + mb * 32 + acc_row(v, h);
-                        if (key >= count || (diag && key > qrow[nb])) acc_s[mb][nb][v] = -INFINITY;
-                    }
-        }
-        // Online softmax per query (per lane and N block), in base-2 units.  The reference maximum m_run
-        // is only raised when a score exceeds it by more than kLazy (2^kLazy fits bf16 and fp32 easily):
-        // after the first tiles the accumulators are almost never rescaled.
-        bf16x8 pf[4][2];
-        float alpha[2];
-        bool rescale = false;
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
-            float mx = -INFINITY;
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, acc_s[mb][nb][v]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32)) * sl2;
-            alpha[nb] = 1.f;
-            if (mx > m_run[nb] + kLazy) {            // also taken for the first visible key (m_run = -inf)
-                alpha[nb] = __builtin_amdgcn_exp2f(m_run[nb] - mx);
-                m_run[nb] = mx;
-                rescale = true;
-            }
-            const float m_ref = m_run[nb] == -INFINITY ? 0.f : m_run[nb];
-            float lsum = 0.f;
+        if (masked) {
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const float e = __builtin_amdgcn_exp2f(fmaf(acc_s[mb][nb][v], sl2, -m_ref));
-                    lsum += e;
-                    pf[mb * 2 + (v >> 3)][nb][v & 7] = (__bf16)e;
+                    const int key = row0 + mb * 32 + acc_row(v, h);
+                    if (key >= count || (diag && key > qrow)) acc_s[mb][v] = -INFINITY;
                 }
-            l_run[nb] = l_run[nb] * alpha[nb] + lsum;
         }
+        // Online softmax of this lane's query, in base-2 units.  The reference maximum m_run is only
+        // raised when a score exceeds it by more than kLazy (2^kLazy fits bf16 and fp32 easily): after
+        // the first tiles the accumulators are almost never rescaled.
+        float mx = -INFINITY;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, acc_s[mb][v]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32)) * sl2;
+        float alpha = 1.f;
+        const bool rescale = mx > m_run + kLazy;          // also true for the first visible key (m_run = -inf)
+        if (rescale) {
+            alpha = __builtin_amdgcn_exp2f(m_run - mx);
+            m_run = mx;
+        }
+        const float m_ref = m_run == -INFINITY ? 0.f : m_run;
+        bf16x8 pf[4];
+        float lsum = 0.f;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const float e = __builtin_amdgcn_exp2f(fmaf(acc_s[mb][v], sl2, -m_ref));
+                lsum += e;
+                pf[mb * 2 + (v >> 3)][v & 7] = (__bf16)e;
+            }
+        l_run = l_run * alpha + lsum;
         if (__builtin_amdgcn_ballot_w64(rescale) != 0) {
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
+            for (int db = 0; db < NDB; ++db)
 #pragma unroll
-                for (int db = 0; db < NDB; ++db)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) acc_o[db][nb][v] *= alpha[nb];
+                for (int v = 0; v < 16; ++v) acc_o[db][v] *= alpha;
         }
         // O^T += V^T . P^T : contraction over the 64 keys in 4 steps of 16
 #pragma unroll
@@ -238,8 +228,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const AttnParams p) {
                     packed.w = (uint16_t)hi[2] | ((uint32_t)(uint16_t)hi[3] << 16);
                     vf = __builtin_bit_cast(bf16x8, packed);
                 }
-#pragma unroll
-                for (int nb = 0; nb < 2; ++nb) acc_o[db][nb] = mfma_32x32x16(vf, pf[kstep][nb], acc_o[db][nb]);
+                acc_o[db] = mfma_32x32x16(vf, pf[kstep], acc_o[db]);
             }
         }
     };
@@ -257,55 +246,45 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const AttnParams p) {
     }
 
     // ---- merge the two parities of each query group through LDS (the tile buffers are free now)
-    float* xch = reinterpret_cast<float*>(&lds_k[0][0][0]);        // NDB*2*16*64 floats per query group (<= 32 KiB each)
-    float* xml = reinterpret_cast<float*>(&lds_v[0][0][0]);        // m, l per (query group, N block, lane)
-    float l_tot[2];
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb) l_tot[nb] = l_run[nb] + __shfl_xor(l_run[nb], 32);
+    float* xch = reinterpret_cast<float*>(&lds_k[0][0][0]);        // NDB*16*64 floats per query group (<= 16 KiB each)
+    float* xml = reinterpret_cast<float*>(&lds_v[0][0][0]);        // m, l per (query group, lane)
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
     if (par == 1) {
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) xch[(((qg * NDB + db) * 2 + nb) * 16 + v) * 64 + lane] = acc_o[db][nb][v];
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
-            xml[((qg * 2 + nb) * 2 + 0) * 64 + lane] = m_run[nb];
-            xml[((qg * 2 + nb) * 2 + 1) * 64 + lane] = l_tot[nb];
-        }
+            for (int v = 0; v < 16; ++v) xch[((qg * NDB + db) * 16 + v) * 64 + lane] = acc_o[db][v];
+        xml[(qg * 2 + 0) * 64 + lane] = m_run;
+        xml[(qg * 2 + 1) * 64 + lane] = l_tot;
     }
     __syncthreads();
     if (par == 0) {
+        const float m1 = xml[(qg * 2 + 0) * 64 + lane];
+        const float l1 = xml[(qg * 2 + 1) * 64 + lane];
+        const float m = fmaxf(m_run, m1);
+        const float m_safe = m == -INFINITY ? 0.f : m;
+        const float a0 = __builtin_amdgcn_exp2f(m_run - m_safe), a1 = __builtin_amdgcn_exp2f(m1 - m_safe);
+        const float l = l_tot * a0 + l1 * a1;
+        const float inv = l > 0.f ? 1.f / l : 0.f;
+        const float c0 = a0 * inv, c1 = a1 * inv;
+        if (qrow < Tq) {
+            uint16_t* __restrict__ O = (uint16_t*)p.out + (int64_t)qrow * q_ld + (int64_t)head * DH;
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
-            const float m1 = xml[((qg * 2 + nb) * 2 + 0) * 64 + lane];
-            const float l1 = xml[((qg * 2 + nb) * 2 + 1) * 64 + lane];
-            const float m = fmaxf(m_run[nb], m1);
-            const float m_safe = m == -INFINITY ? 0.f : m;
-            const float a0 = __builtin_amdgcn_exp2f(m_run[nb] - m_safe), a1 = __builtin_amdgcn_exp2f(m1 - m_safe);
-            const float l = l_tot[nb] * a0 + l1 * a1;
-            const float inv = l > 0.f ? 1.f / l : 0.f;
-            const float c0 = a0 * inv, c1 = a1 * inv;
-            if (qrow[nb] < Tq) {
-                uint16_t* __restrict__ O = (uint16_t*)p.out + (int64_t)qrow[nb] * q_ld + (int64_t)head * DH;
+            for (int db = 0; db < NDB; ++db)
 #pragma unroll
-                for (int db = 0; db < NDB; ++db)
+                for (int vq = 0; vq < 4; ++vq) {
+                    float o[4];
 #pragma unroll
-                    for (int vq = 0; vq < 4; ++vq) {
-                        float o[4];
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const int v = 4 * vq + e;
-                            o[e] = acc_o[db][nb][v] * c0 + xch[(((qg * NDB + db) * 2 + nb) * 16 + v) * 64 + lane] * c1;
-                        }
-                        u32x2 w;
-                        w.x = pack_bf16x2(o[0], o[1]);
-                        w.y = pack_bf16x2(o[2], o[3]);
-                        *reinterpret_cast<u32x2*>(O + db * 32 + 8 * vq + 4 * h) = w;
+                    for (int e = 0; e < 4; ++e) {
+                        const int v = 4 * vq + e;
+                        o[e] = acc_o[db][v] * c0 + xch[((qg * NDB + db) * 16 + v) * 64 + lane] * c1;
                     }
-                if (p.lse && h == 0) p.lse[(int64_t)head * Tq + qrow[nb]] = (m + log2f(l)) * 0.6931471805599453f;
-            }
+                    u32x2 w;
+                    w.x = pack_bf16x2(o[0], o[1]);
+                    w.y = pack_bf16x2(o[2], o[3]);
+                    *reinterpret_cast<u32x2*>(O + db * 32 + 8 * vq + 4 * h) = w;
+                }
+            if (p.lse && h == 0) p.lse[(int64_t)head * Tq + qrow] = (m + log2f(l)) * 0.6931471805599453f;
         }
     }
 }
@@ -382,11 +361,11 @@ int launch_attention(int dtype, const AttnParams& p_in, int head_dim, hipStream_
         if (total > 0x7fffffff) return ASTRA_ERR_SHAPE;
         const bool vt = p.v_transposed != 0;
         if (head_dim == 128) {
-            if (vt) attn_bf16_kernel<128, true><<<(int)total, 256, 0, s>>>(p);
-            else attn_bf16_kernel<128, false><<<(int)total, 256, 0, s>>>(p);
+            if (vt) attn_bf16_kernel<128, true><<<(int)total, kAttThreads, 0, s>>>(p);
+            else attn_bf16_kernel<128, false><<<(int)total, kAttThreads, 0, s>>>(p);
         } else if (head_dim == 64) {
-            if (vt) attn_bf16_kernel<64, true><<<(int)total, 256, 0, s>>>(p);
-            else attn_bf16_kernel<64, false><<<(int)total, 256, 0, s>>>(p);
+            if (vt) attn_bf16_kernel<64, true><<<(int)total, kAttThreads, 0, s>>>(p);
+            else attn_bf16_kernel<64, false><<<(int)total, kAttThreads, 0, s>>>(p);
         } else {
             return ASTRA_ERR_UNSUPPORTED;
         }

@@ -59,6 +59,13 @@ __device__ __forceinline__ void dma_global_to_lds_16(const void* gptr, uint32_t 
     const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base), "v"(gptr) : "memory");
 }
+// Same, with the global address split into a wave-uniform base (scalar registers) and a 32-bit byte
+// offset per lane.
+__device__ __forceinline__ void dma_global_to_lds_16(const void* gbase_uniform, uint32_t byte_off, uint32_t lds_base) {
+    const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(base), "v"(byte_off), "s"(gbase_uniform)
+                 : "memory");
+}
 __device__ __forceinline__ void wait_vmem_all() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }

@@ -101,7 +101,7 @@ def main():
     torch.cuda.synchronize()
 
     # ---- timed region: exactly `steps` calls, stage boundaries marked with HIP events on the launch stream
-    events = [B.HipEvents(5) for _ in range(args.steps)]
+    events = [B.HipEvents(7) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -109,7 +109,10 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    stage_ms = {s: float(np.mean([ev.elapsed_ms(j, j + 1) for ev in events])) for j, s in enumerate(STAGES)}
+    # events: 0 entry, 1 projections done, 2 attention done, 3 output projection done, 4 exit; 5/6 around the
+    # encode on its side stream (it overlaps the projections)
+    spans = {"vq_encode": (5, 6), "projections": (0, 1), "attention": (1, 2), "out_projection": (2, 3)}
+    stage_ms = {s: float(np.mean([ev.elapsed_ms(*spans[s]) for ev in events])) for s in STAGES}
     gpu_ms = float(np.mean([ev.elapsed_ms(0, 4) for ev in events]))
 
     flops = layer_flops(cfg, view["n_before"])

@@ -7,8 +7,11 @@
  *
  * Conventions (all entry points)
  *   - Every data pointer is a DEVICE pointer to a dense row-major array, 16-byte
- *     aligned, owned by the caller.  The library allocates nothing, frees nothing
+ *     aligned, owned by the caller.  The library allocates no memory, frees nothing
  *     and keeps no pointer after a call returns; scratch comes from `workspace`.
+ *     astra_layer_forward creates, on first use per device, one internal stream and
+ *     two events on which the encode overlaps the other stages; it is forked from and
+ *     joined back into `stream` inside the call.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *     only enqueue work: they never synchronise, and the outputs are ready when the
  *     stream reaches that point.  Calls on distinct streams may overlap.
@@ -133,9 +136,11 @@ int astra_layer_forward(const astra_layer_desc* desc, const void* x_local, const
                         void* workspace, size_t workspace_bytes, void* stream);
 
 /* astra_layer_forward with stage timing for benchmarks: identical work and results, and in addition
- * stage_events[0..4] (five hipEvent_t created by the caller with timing enabled, passed as void*; a
- * NULL entry is skipped) are recorded on `stream` before the encode and after the encode, the
- * Q/K/V/K-hat/V-hat projections, the attention and the output projection (Sec. 3.1 order). */
+ * seven hipEvent_t (created by the caller with timing enabled, passed as void*; a NULL entry is skipped)
+ * are recorded: [0] on `stream` at entry, [1] after the Q/K/V/K-hat/V-hat projections, [2] after the
+ * attention, [3] after the output projection, [4] at exit (after the encode has been joined), and on
+ * the stream the encode runs on [5] before and [6] after the encode (Sec. 3.1; the encode overlaps the
+ * other stages). */
 int astra_layer_forward_profiled(const astra_layer_desc* desc, const void* x_local, const void* codes_nonlocal,
                                  const void* codebook, const float* cnorm,
                                  const void* wq, const void* wk, const void* wv, const void* wo,

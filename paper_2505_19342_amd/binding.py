@@ -126,7 +126,7 @@ def astra_layer_forward(desc: LayerDesc, x_local, codes_nonlocal, codebook, cnor
 
 def astra_layer_forward_profiled(desc: LayerDesc, x_local, codes_nonlocal, codebook, cnorm, wq, wk, wv, wo,
                                  bq, bk, bv, bo, y_out, codes_local_out, workspace, stage_events):
-    """stage_events: a ctypes array of 5 hipEvent_t handles (see HipEvents)."""
+    """stage_events: a ctypes array of 7 hipEvent_t handles (see HipEvents and include/astra.h)."""
     nbytes = workspace.numel() * workspace.element_size()
     _check(load().astra_layer_forward_profiled(
         ctypes.byref(desc), _ptr(x_local), _ptr(codes_nonlocal), _ptr(codebook), _ptr(cnorm),

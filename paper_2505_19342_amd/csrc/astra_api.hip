@@ -1,4 +1,6 @@
 // C ABI of the library: argument checking and the per-layer orchestration (paper Sec. 3.1).
+#include <mutex>
+
 #include "common.h"
 
 namespace astra {
@@ -152,6 +154,32 @@ size_t astra_layer_workspace_bytes(const astra_layer_desc* desc) {
     return pl.total;
 }
 
+// The encode of the local rows depends on nothing else in the layer and nothing in the layer depends on
+// it, so it runs on a side stream while the projections (which leave a quarter of the compute units idle
+// at the benchmark shape) and the attention run on the caller's stream.  One side stream and two events
+// per device, created on first use (default priority, no device memory); the fork/join pair makes the
+// call behave as if everything were enqueued on the caller's stream.
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+    bool ok = false;
+};
+static std::mutex g_side_mutex;
+static SideStream g_side[16];
+
+static SideStream* side_stream_for_current_device() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return nullptr;
+    SideStream& ss = g_side[dev];
+    if (!ss.ok) {
+        if (hipStreamCreateWithFlags(&ss.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
+        if (hipEventCreateWithFlags(&ss.fork, hipEventDisableTiming) != hipSuccess) return nullptr;
+        if (hipEventCreateWithFlags(&ss.join, hipEventDisableTiming) != hipSuccess) return nullptr;
+        ss.ok = true;
+    }
+    return &ss;
+}
+
 static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local, const void* codes_nonlocal,
                               const void* codebook, const float* cnorm,
                               const void* wq, const void* wk, const void* wv, const void* wo,
@@ -169,23 +197,35 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     if (pl.Tn_vis > 0 && !codes_nonlocal) return ASTRA_ERR_NULL;
     if (!workspace || workspace_bytes < pl.total) return ASTRA_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
-    auto mark = [&](int i) { if (ev && ev[i]) (void)hipEventRecord((hipEvent_t)ev[i], s); };
-    mark(0);
+    auto mark = [&](int i, hipStream_t on) { if (ev && ev[i]) (void)hipEventRecord((hipEvent_t)ev[i], on); };
+    mark(0, s);
     const int eb = elem_bytes(vq.dtype);
     char* ws = (char*)workspace;
     void *Q = ws + pl.off_q, *K = ws + pl.off_k, *V = ws + pl.off_v, *Kh = ws + pl.off_kh, *Vh = ws + pl.off_vh,
          *O = ws + pl.off_o, *Xh = ws + pl.off_xhat;
 
-    // 1. indices this device transmits: encode the content rows (the class row is not encoded)
+    // 1. indices this device transmits: encode the content rows (the class row is not encoded), on the
+    //    side stream, joined at the end of the call
+    std::lock_guard<std::mutex> lock(g_side_mutex);
+    SideStream* side = at.n_local > 0 ? side_stream_for_current_device() : nullptr;
+    hipStream_t es = s;
+    if (side) {
+        if (hipEventRecord(side->fork, s) != hipSuccess || hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)
+            return ASTRA_ERR_HIP;
+        es = side->stream;
+    }
+    mark(5, es);
     rc = launch_vq_encode(vq, (const char*)x_local + (size_t)at.n_cls * pl.D * eb, pl.D, at.n_local, codebook, cnorm,
-                          codes_local_out, s);
-    if (rc) return rc;
-    mark(1);
+                          codes_local_out, es);
+    mark(6, es);
+    if (side && hipEventRecord(side->join, es) != hipSuccess) return ASTRA_ERR_HIP;
+    auto join = [&]() { return (side && hipStreamWaitEvent(s, side->join, 0) != hipSuccess) ? (int)ASTRA_ERR_HIP : (int)ASTRA_OK; };
+    if (rc) { (void)join(); return rc; }
 
     // 2. projections: Q, K, V of local rows; K-hat, V-hat of the rows rebuilt from the peers' codes
     if (pl.need_xhat && pl.Tn_vis > 0) {
         rc = launch_vq_decode(vq, codes_nonlocal, pl.Tn_vis, codebook, Xh, s);
-        if (rc) return rc;
+        if (rc) { (void)join(); return rc; }
     }
     GemmProblem pr[5] = {};
     auto local = [&](GemmProblem& g, const void* w, const void* b, void* c, int n) {
@@ -209,8 +249,8 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     nonlocal_(pr[4], wv, bv, Vh, pl.dkv);
     if (pl.vt) { pr[4].c_mode = kCTransposedV; pr[4].ldc = pl.ldv_hat; }
     rc = launch_gemm_batch(vq.dtype, pr, 5, s);
-    if (rc) return rc;
-    mark(2);
+    if (rc) { (void)join(); return rc; }
+    mark(1, s);
 
     // 3. mixed-precision attention (Eq. 1)
     AttnParams ap = attn_params(at, Q, K, V, Kh, Vh, O, nullptr);
@@ -218,16 +258,18 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     ap.ldv_loc = pl.ldv_loc;
     ap.ldv_hat = pl.ldv_hat;
     rc = launch_attention(vq.dtype, ap, at.head_dim, s);
-    if (rc) return rc;
-    mark(3);
+    if (rc) { (void)join(); return rc; }
+    mark(2, s);
 
     // 4. output projection
     GemmProblem po = {};
     po.a = O; po.b = wo; po.bias = bo; po.c = y_out; po.M = pl.Tq; po.N = pl.D; po.K = pl.dq; po.lda = pl.dq; po.ldc = pl.D;
     po.c_mode = kCF32;      // y leaves the layer as the fp32 accumulator, for both element types
     rc = launch_gemm_batch(vq.dtype, &po, 1, s);
-    mark(4);
-    return rc;
+    mark(3, s);
+    const int jrc = join();
+    mark(4, s);
+    return rc ? rc : jrc;
 }
 
 int astra_layer_forward(const astra_layer_desc* desc, const void* x_local, const void* codes_nonlocal,

@@ -185,13 +185,48 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_bf16_kernel(const GemmBa
     if (n_kt > 1) load_tile();    // tile 1
     if (n_kt > 2) load_codes();   // codes of tile 2
     __syncthreads();
+    // Steady state: the staging work of an iteration is cut into four slices and each slice follows the
+    // MFMAs of one contraction step, so LDS writes and global loads are issued while the matrix core is
+    // busy instead of in a block of their own.
+    static_assert(PA % 4 == 0 && PB % 4 == 0, "whole staging passes per contraction step");
     int kt = 0;
     for (; kt + 3 < n_kt; ++kt) {
         const int buf = kt & 1;
-        store_tile(buf ^ 1);
-        load_tile();
+        const uint32_t g_ = __umulhi((uint32_t)k_use, magic);
+        const uint32_t j_ = (uint32_t)k_use - g_ * (uint32_t)dg;
+        const uint32_t gbase_ = g_ * (uint32_t)Kc;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            bf16x8 fa[TM], fb[TN];
+#pragma unroll
+            for (int a = 0; a < TM; ++a) fa[a] = __builtin_bit_cast(bf16x8, lds_a[buf][arow[a] * 8 + ((2 * ks + h) ^ swz(arow[a]))]);
+#pragma unroll
+            for (int b = 0; b < TN; ++b) fb[b] = __builtin_bit_cast(bf16x8, lds_b[buf][brow[b] * 8 + ((2 * ks + h) ^ swz(brow[b]))]);
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < TN; ++b) acc[a][b] = mfma_32x32x16(fa[a], fb[b], acc[a][b]);
+            // slice ks: tile kt+1 to the other LDS buffer, then refill those registers with tile kt+2
+#pragma unroll
+            for (int it = ks * (PA / 4); it < (ks + 1) * (PA / 4); ++it) {
+                const int r_ = r0 + RPP * it;
+                lds_a[buf ^ 1][r_ * 8 + (kc ^ swz(r_))] = ra[it];
+                const uint32_t c_ = (uint32_t)(code[it] < Kc ? code[it] : Kc - 1);
+                const uint32_t goff_ = ((gbase_ + c_) * (uint32_t)dg + j_) * 2u;
+                ra[it] = *reinterpret_cast<const u32x4*>(a_base + ((goff_ & gmask) + aoff[it]));
+            }
+#pragma unroll
+            for (int it = ks * (PB / 4); it < (ks + 1) * (PB / 4); ++it) {
+                const int r_ = r0 + RPP * it;
+                lds_b[buf ^ 1][r_ * 8 + (kc ^ swz(r_))] = rb[it];
+                rb[it] = *reinterpret_cast<const u32x4*>(b_base + boff[it]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        a_base += a_step;
+        b_base += kBK * 2;
+        k_use += kBK;
         load_codes();
-        compute(buf);
         __syncthreads();
     }
     for (; kt < n_kt; ++kt) {
@@ -347,11 +382,12 @@ static int fill_batch(GemmBatch& batch, int dtype, const GemmProblem* problems, 
             return ASTRA_ERR_UNSUPPORTED;
         }
         const int64_t tm = ceil_div(p.M, bm), tn = ceil_div(p.N, bn);
-        if (tm * tn + total > 0x7fffffff) return ASTRA_ERR_SHAPE;
+        const int64_t nt = tm * tn;
+        if (nt + total > 0x7fffffff) return ASTRA_ERR_SHAPE;
         batch.p[n] = p;
         batch.tile_begin[n] = total;
         batch.tiles_m[n] = (int)tm;
-        total += (int)(tm * tn);
+        total += (int)nt;
         ++n;
     }
     batch.n = n;

@@ -241,6 +241,135 @@ __global__ __launch_bounds__(256) void vq_encode_bf16_kernel(const uint16_t* __r
     if (h == 0 && tok < n_tokens) codes[(int64_t)tok * G + g] = (CodeT)arg;
 }
 
+// ------------------------------------------------------------------------------------------------
+// Encode, bf16, fast path for groups of at most 64 values (dg a multiple of 8): same MFMA tile and
+// fused argmin as above, restructured for throughput.
+//   - The score is kept as a distance, ||c||^2 - 2 x.c: the token fragments are loaded once, negated and
+//     doubled (exact in bf16), and the accumulator is preloaded with ||c||^2 straight from LDS, so no
+//     vector-ALU work is spent on forming the score; the argmin costs a compare and two selects per value.
+//   - Codebook tiles (128 codewords) and their norms go from global memory straight into double-buffered
+//     LDS, one tile ahead of the one being multiplied.  Pieces beyond dg are never transferred: those LDS
+//     slots are zeroed once and meet zero token values.
+//   - Workgroup ids are remapped so that all token blocks of a group run on the same XCD and find the
+//     group's codebook in that XCD's L2.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ int enc_swz(int r) { return (r >> 1) & 7; }
+
+template <typename CodeT>
+__global__ __launch_bounds__(256) void vq_encode_bf16_fast_kernel(const uint16_t* __restrict__ x, int64_t ldx, int n_tokens,
+                                                                  const uint16_t* __restrict__ codebook,
+                                                                  const float* __restrict__ cnorm, CodeT* __restrict__ codes,
+                                                                  int G, int K, int dg, int n_tb) {
+    __shared__ u32x4 cb_lds[2][kEncCw * 8];      // 2 x 16 KiB: [128 codewords][8 pieces of 8 bf16], swizzled
+    __shared__ f32x4 cn_lds[2][kEncCw / 4];      // 2 x 512 B
+
+    // contiguous runs of workgroups per XCD; consecutive virtual ids share the group
+    const int total = gridDim.x;
+    const int q = total / 8, rr = total % 8, xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+    const int vid = xcd < rr ? xcd * (q + 1) + slot : rr * (q + 1) + (xcd - rr) * q + slot;
+    const int g = vid / n_tb, tb = vid % n_tb;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int i32 = lane & 31, h = lane >> 5;
+    const int n_pieces = dg >> 3;                       // valid 16-byte pieces per codeword
+    const int n_ks = (dg + 15) >> 4;                    // contraction steps of 16
+
+    // zero both tile buffers once (slots of pieces >= n_pieces stay zero for good)
+    for (int i = tid; i < 2 * kEncCw * 8; i += 256) (&cb_lds[0][0])[i] = u32x4{0u, 0u, 0u, 0u};
+
+    // this lane's token (N side), as -2x so that the MFMA accumulates ||c||^2 - 2 x.c
+    const int tok = tb * kEncTokens + wave * 32 + i32;
+    const int tok_ld = tok < n_tokens ? tok : n_tokens - 1;
+    const uint16_t* xrow = x + (int64_t)tok_ld * ldx + (int64_t)g * dg;
+    bf16x8 xfrag[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+        const int k = 16 * ks + 8 * h;
+        u32x4 raw = u32x4{0u, 0u, 0u, 0u};
+        if (k < dg) raw = *reinterpret_cast<const u32x4*>(xrow + k);
+        const bf16x8 xv = __builtin_bit_cast(bf16x8, raw);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) xfrag[ks][e] = (__bf16)(-2.f * (float)xv[e]);
+    }
+    __syncthreads();                                   // zero fill done before any transfer lands
+
+    const char* __restrict__ cb_g = (const char*)(codebook + (int64_t)g * K * dg);
+    const char* __restrict__ cn_g = (const char*)(cnorm + (int64_t)g * K);
+    const uint32_t row_b = (uint32_t)dg * 2u;
+    const int n_tiles = (K + kEncCw - 1) / kEncCw;
+    // transfer geometry: slot c = tid + 256*it is (codeword c/8, physical piece c%8) and receives logical
+    // piece (c%8) ^ swz(c/8); swz has period 16 codewords and 32 codewords separate two `it`
+    const int cw_l = tid >> 3;
+    const int piece = (tid & 7) ^ enc_swz(cw_l);
+    const bool piece_ok = piece < n_pieces;
+    auto issue_tile = [&](int t, int buf) {
+        const int cw0 = t * kEncCw;
+        const uint32_t base = lds_byte_addr(&cb_lds[buf][0]);
+        if (piece_ok) {
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                const int cw = min(cw0 + cw_l + 32 * it, K - 1);
+                dma_global_to_lds_16(cb_g, (uint32_t)cw * row_b + (uint32_t)piece * 16u, base + (uint32_t)(64 * (wave + 4 * it)) * 16u);
+            }
+        }
+        if (wave == 0 && lane < 32) {                   // 128 norms = 32 x 16 bytes (K is padded by clamping)
+            const int cwn = min(cw0 + 4 * lane, K - 4 > 0 ? K - 4 : 0);
+            dma_global_to_lds_16(cn_g, (uint32_t)cwn * 4u, lds_byte_addr(&cn_lds[buf][0]));
+        }
+    };
+
+    float best = INFINITY;
+    int arg = 0;
+    issue_tile(0, 0);
+    wait_vmem_all();
+    __syncthreads();
+    for (int t = 0; t < n_tiles; ++t) {
+        const int buf = t & 1;
+        if (t + 1 < n_tiles) issue_tile(t + 1, buf ^ 1);
+        const int cw0 = t * kEncCw;
+        f32x16 acc[4];
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+                const f32x4 cn = cn_lds[buf][mb * 8 + 2 * vq + h];     // rows 32*mb + 8*vq + 4*h .. +3
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[mb][4 * vq + e] = cn[e];
+            }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            if (ks < n_ks) {
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb) {
+                    const int row = mb * 32 + i32;
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, cb_lds[buf][row * 8 + ((2 * ks + h) ^ enc_swz(row))]);
+                    acc[mb] = mfma_32x32x16(a, xfrag[ks], acc[mb]);
+                }
+            }
+        }
+        // fused argmin: ascending codeword order inside the lane, strict '<' keeps the lowest index
+        const bool ragged = cw0 + kEncCw > K || (K & 3);
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int cw = cw0 + mb * 32 + acc_row(v, h);
+                float sc = acc[mb][v];
+                if (ragged && cw >= K) sc = INFINITY;
+                if (sc < best) { best = sc; arg = cw; }
+            }
+        wait_vmem_all();
+        __syncthreads();
+    }
+    // merge the two half-waves that hold the same token
+    const float ob = __shfl_xor(best, 32);
+    const int oa = __shfl_xor(arg, 32);
+    if (ob < best || (ob == best && oa < arg)) { best = ob; arg = oa; }
+    if (h == 0 && tok < n_tokens) codes[(int64_t)tok * G + g] = (CodeT)arg;
+}
+
 int launch_vq_encode(const astra_vq_desc& d, const void* x, int64_t ldx, int64_t n_tokens, const void* codebook,
                      const float* cnorm, void* codes, hipStream_t s) {
     if (n_tokens == 0) return ASTRA_OK;
@@ -248,7 +377,19 @@ int launch_vq_encode(const astra_vq_desc& d, const void* x, int64_t ldx, int64_t
     if (n_tokens > 0x7fffffff / 2) return ASTRA_ERR_SHAPE;
     if (d.dtype == ASTRA_BF16) {
         if (d.d_model % 8 != 0 && dg % 8 == 0) return ASTRA_ERR_UNSUPPORTED;   // 16-byte slices need aligned rows
-        dim3 grid((unsigned)ceil_div(n_tokens, kEncTokens), (unsigned)G);
+        const int64_t n_tb = ceil_div(n_tokens, kEncTokens);
+        // fast path: whole 16-byte pieces, one contraction tile, norms readable as aligned groups of 4
+        if (dg <= kEncKt && dg % 8 == 0 && K % 4 == 0 && n_tb * G <= 0x7fffffff && (int64_t)K * dg * 2 < ((int64_t)1 << 31)) {
+            const int total = (int)(n_tb * G);
+            if (d.code_type == ASTRA_CODE_U8)
+                vq_encode_bf16_fast_kernel<uint8_t><<<total, 256, 0, s>>>((const uint16_t*)x, ldx, (int)n_tokens, (const uint16_t*)codebook,
+                                                                          cnorm, (uint8_t*)codes, G, K, dg, (int)n_tb);
+            else
+                vq_encode_bf16_fast_kernel<uint16_t><<<total, 256, 0, s>>>((const uint16_t*)x, ldx, (int)n_tokens, (const uint16_t*)codebook,
+                                                                           cnorm, (uint16_t*)codes, G, K, dg, (int)n_tb);
+            return launch_status();
+        }
+        dim3 grid((unsigned)n_tb, (unsigned)G);
         if (G > 65535) return ASTRA_ERR_SHAPE;
         if (d.code_type == ASTRA_CODE_U8)
             vq_encode_bf16_kernel<uint8_t><<<grid, 256, 0, s>>>((const uint16_t*)x, ldx, (int)n_tokens, (const uint16_t*)codebook,

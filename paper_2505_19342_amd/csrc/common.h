@@ -67,6 +67,12 @@ __device__ __forceinline__ void dma_global_to_lds_16(const void* gbase_uniform, 
                  : "memory");
 }
 __device__ __forceinline__ void wait_vmem_all() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// wait until at most N of this wavefront's vector-memory instructions (they complete in order) are outstanding
+template <int N>
+__device__ __forceinline__ void wait_vmem() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 
@@ -109,6 +115,7 @@ struct GemmProblem {
 constexpr int kMaxGemmProblems = 6;
 int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hipStream_t s);
 extern int g_gemm_force_cfg;
+extern const int g_gemm_problem_size;
 
 struct AttnParams {
     const void* q;        // [T_q, H_q, dh]

@@ -363,6 +363,7 @@ __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmBatch batch)
 }
 
 int g_gemm_force_cfg = -1;      // development override: 0 = 128x128 tiles, 1 = 256x256 tiles
+extern const int g_gemm_problem_size = (int)sizeof(GemmProblem);   // lets a development harness detect a stale header
 
 static int fill_batch(GemmBatch& batch, int dtype, const GemmProblem* problems, int n_problems, int bm, int bn, int* total_out) {
     int total = 0, n = 0;

@@ -1,5 +1,7 @@
 // Grouped vector quantisation on gfx950: codeword norms, nearest-codeword encode, codebook-gather
 // decode (paper Sec. 2 "Vanilla VQ" / "Grouped VQ", Sec. 3.2 "Vector-Quantized Non-Local Tokens").
+#include <type_traits>
+
 #include "common.h"
 
 namespace astra {
@@ -255,13 +257,15 @@ __global__ __launch_bounds__(256) void vq_encode_bf16_kernel(const uint16_t* __r
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ int enc_swz(int r) { return (r >> 1) & 7; }
 
+constexpr int kEncBufs = 4;       // LDS tile buffers of the fast path: transfers run three tiles ahead
+
 template <typename CodeT>
 __global__ __launch_bounds__(256) void vq_encode_bf16_fast_kernel(const uint16_t* __restrict__ x, int64_t ldx, int n_tokens,
                                                                   const uint16_t* __restrict__ codebook,
                                                                   const float* __restrict__ cnorm, CodeT* __restrict__ codes,
                                                                   int G, int K, int dg, int n_tb) {
-    __shared__ u32x4 cb_lds[2][kEncCw * 8];      // 2 x 16 KiB: [128 codewords][8 pieces of 8 bf16], swizzled
-    __shared__ f32x4 cn_lds[2][kEncCw / 4];      // 2 x 512 B
+    __shared__ u32x4 cb_lds[kEncBufs][kEncCw * 8];      // 4 x 16 KiB: [128 codewords][8 pieces of 8 bf16], swizzled
+    __shared__ f32x4 cn_lds[kEncBufs][kEncCw / 4];      // 4 x 512 B
 
     // contiguous runs of workgroups per XCD; consecutive virtual ids share the group
     const int total = gridDim.x;
@@ -276,8 +280,8 @@ __global__ __launch_bounds__(256) void vq_encode_bf16_fast_kernel(const uint16_t
     const int n_pieces = dg >> 3;                       // valid 16-byte pieces per codeword
     const int n_ks = (dg + 15) >> 4;                    // contraction steps of 16
 
-    // zero both tile buffers once (slots of pieces >= n_pieces stay zero for good)
-    for (int i = tid; i < 2 * kEncCw * 8; i += 256) (&cb_lds[0][0])[i] = u32x4{0u, 0u, 0u, 0u};
+    // zero the tile buffers once (slots of pieces >= n_pieces stay zero for good)
+    for (int i = tid; i < kEncBufs * kEncCw * 8; i += 256) (&cb_lds[0][0])[i] = u32x4{0u, 0u, 0u, 0u};
 
     // this lane's token (N side), as -2x so that the MFMA accumulates ||c||^2 - 2 x.c
     const int tok = tb * kEncTokens + wave * 32 + i32;
@@ -299,35 +303,39 @@ __global__ __launch_bounds__(256) void vq_encode_bf16_fast_kernel(const uint16_t
     const char* __restrict__ cn_g = (const char*)(cnorm + (int64_t)g * K);
     const uint32_t row_b = (uint32_t)dg * 2u;
     const int n_tiles = (K + kEncCw - 1) / kEncCw;
-    // transfer geometry: slot c = tid + 256*it is (codeword c/8, physical piece c%8) and receives logical
-    // piece (c%8) ^ swz(c/8); swz has period 16 codewords and 32 codewords separate two `it`
+    // Transfer geometry: slot c = tid + 256*it is (codeword c/8, physical piece c%8) and receives logical
+    // piece (c%8) ^ swz(c/8); swz has period 16 codewords and 32 codewords separate two `it`.  Every
+    // wavefront issues exactly kEncDma transfers per tile (4 codebook passes + its quarter of the norms),
+    // so "tile t has landed" is a fixed vmcnt threshold.
+    constexpr int kEncDma = 5;
     const int cw_l = tid >> 3;
     const int piece = (tid & 7) ^ enc_swz(cw_l);
     const bool piece_ok = piece < n_pieces;
-    auto issue_tile = [&](int t, int buf) {
+    auto issue_tile = [&](int t) {
+        const int buf = t % kEncBufs;
         const int cw0 = t * kEncCw;
         const uint32_t base = lds_byte_addr(&cb_lds[buf][0]);
-        if (piece_ok) {
 #pragma unroll
-            for (int it = 0; it < 4; ++it) {
-                const int cw = min(cw0 + cw_l + 32 * it, K - 1);
+        for (int it = 0; it < 4; ++it) {
+            const int cw = min(cw0 + cw_l + 32 * it, K - 1);
+            if (piece_ok)
                 dma_global_to_lds_16(cb_g, (uint32_t)cw * row_b + (uint32_t)piece * 16u, base + (uint32_t)(64 * (wave + 4 * it)) * 16u);
-            }
         }
-        if (wave == 0 && lane < 32) {                   // 128 norms = 32 x 16 bytes (K is padded by clamping)
-            const int cwn = min(cw0 + 4 * lane, K - 4 > 0 ? K - 4 : 0);
-            dma_global_to_lds_16(cn_g, (uint32_t)cwn * 4u, lds_byte_addr(&cn_lds[buf][0]));
+        if (lane < 8) {                                 // 128 norms = 4 wavefronts x 8 lanes x 16 bytes
+            const int cwn = min(cw0 + 32 * wave + 4 * lane, K - 4);
+            dma_global_to_lds_16(cn_g, (uint32_t)cwn * 4u, lds_byte_addr(&cn_lds[buf][0]) + (uint32_t)wave * 128u);
         }
     };
 
+    // Running argmin of this lane.  The winner is remembered as (tile, slot) with slot = mb*16 + v, a
+    // small compile-time constant per accumulator value, so the loop spends exactly a compare and two
+    // selects per score; slots ascend with the codeword index inside a lane and strict '<' keeps the
+    // lowest index.
     float best = INFINITY;
-    int arg = 0;
-    issue_tile(0, 0);
-    wait_vmem_all();
-    __syncthreads();
-    for (int t = 0; t < n_tiles; ++t) {
-        const int buf = t & 1;
-        if (t + 1 < n_tiles) issue_tile(t + 1, buf ^ 1);
+    int arg_slot = 0, arg_tile = 0;
+    auto process_tile = [&](int t, auto ragged_tag) {
+        constexpr bool kRagged = decltype(ragged_tag)::value;
+        const int buf = t % kEncBufs;
         const int cw0 = t * kEncCw;
         f32x16 acc[4];
 #pragma unroll
@@ -349,20 +357,36 @@ __global__ __launch_bounds__(256) void vq_encode_bf16_fast_kernel(const uint16_t
                 }
             }
         }
-        // fused argmin: ascending codeword order inside the lane, strict '<' keeps the lowest index
-        const bool ragged = cw0 + kEncCw > K || (K & 3);
+        const float best_in = best;
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int cw = cw0 + mb * 32 + acc_row(v, h);
                 float sc = acc[mb][v];
-                if (ragged && cw >= K) sc = INFINITY;
-                if (sc < best) { best = sc; arg = cw; }
+                if (kRagged && cw0 + mb * 32 + acc_row(v, h) >= K) sc = INFINITY;   // codewords past K: last tile only
+                const bool better = sc < best;
+                best = better ? sc : best;
+                arg_slot = better ? (mb * 16 + v) : arg_slot;
             }
-        wait_vmem_all();
-        __syncthreads();
+        arg_tile = best < best_in ? t : arg_tile;
+    };
+
+#pragma unroll
+    for (int t = 0; t < kEncBufs - 1; ++t)
+        if (t < n_tiles) issue_tile(t);
+    const int n_full = K / kEncCw;                      // tiles without codewords past K
+    for (int t = 0; t < n_tiles; ++t) {
+        // tile t has landed once at most the transfers of the (up to two) younger tiles are outstanding
+        if (t + 2 < n_tiles) wait_vmem<2 * kEncDma>();
+        else if (t + 1 < n_tiles) wait_vmem<kEncDma>();
+        else wait_vmem<0>();
+        __syncthreads();        // everyone's share of tile t is visible; everyone is done with tile t-1
+        if (t + kEncBufs - 1 < n_tiles) issue_tile(t + kEncBufs - 1);     // into the buffer tile t-1 used
+        if (t < n_full) process_tile(t, std::false_type{});
+        else process_tile(t, std::true_type{});
     }
+    // (tile, slot) -> codeword index
+    int arg = arg_tile * kEncCw + (arg_slot >> 4) * 32 + acc_row(arg_slot & 15, h);
     // merge the two half-waves that hold the same token
     const float ob = __shfl_xor(best, 32);
     const int oa = __shfl_xor(arg, 32);

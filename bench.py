@@ -22,6 +22,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}       # MI355X dense MFMA peaks
+# HBM-side bytes per launch of the dominant kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs kept
+# under profiles/ (layer_llama3_8b_pmc_fetch_size.txt, ..._write_size.txt), each scaled by what the same counter
+# reads for a 256 MiB copy kernel: (59906.6 * 2.0 + 32544.1 * 1.0) KiB.  None for workloads not profiled.
+TRAFFIC_BYTES = {"llama3_8b_bf16": (59906.6 * 2.0 + 32544.1) * 1024.0}
 STAGES = ("vq_encode", "projections", "attention", "out_projection")
 
 
@@ -47,6 +51,9 @@ def main():
     ap.add_argument("--workload", default="llama3_8b_bf16")
     ap.add_argument("--rank", type=int, default=-1, help="simulated device (default: last = critical path under causal masking)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="before the warm-up, run one plain elementwise copy kernel reading and writing this many MiB "
+                         "(fp32): the reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one device's share on ONE GPU; the exchange of codes between devices is not "
@@ -96,6 +103,15 @@ def main():
     ws = torch.empty(max(B.astra_layer_workspace_bytes(desc), 256), dtype=torch.uint8, device=dev)
     call_args = (desc, x_local, codes_nl, codebook, cnorm, *w, None, None, None, None, y, codes_local, ws)
 
+    if args.calibration_copy_mib > 0:
+        n = args.calibration_copy_mib * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.mul(src, 1.0, out=dst)          # one elementwise kernel: reads n*4 bytes, writes n*4 bytes
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         B.astra_layer_forward(*call_args)
     torch.cuda.synchronize()
@@ -140,7 +156,9 @@ def main():
         "roofline": {"kernel": "gemm_nt_bf16_kernel (grouped Q/K/V/K-hat/V-hat projections)" if dt == "bf16"
                      else "gemm_nt_f32_kernel (grouped projections)",
                      "bound": "mfma" if dt == "bf16" else "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved / peak, "traffic": None},
+                     "frac": achieved / peak,
+                     "traffic": TRAFFIC_BYTES.get(cfg.name) if rank == cfg.n_dev - 1 else None,
+                     "flops_per_launch": flops[dom], "us_per_launch": stage_ms[dom] * 1e3},
     }
 
     if not args.no_cpu_baseline:

@@ -12,7 +12,12 @@ LIB_PATH = os.path.join(_HERE, "libastra_hip.so")
 
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-               "-mllvm", "-amdgpu-mfma-vgpr-form", "-Wno-unused-command-line-argument"]
+               "-Wno-unused-command-line-argument"]
+# Keeps MFMA accumulators in ordinary vector registers (no copies between the two register files around the
+# softmax / argmin arithmetic).  Not for the GEMM: its 256x256 tile on four wavefronts holds 256 accumulator
+# registers per lane, which only fit next to the operands when they live in the accumulation registers.
+VGPR_FORM_FLAGS = ["-mllvm", "-amdgpu-mfma-vgpr-form"]
+ACC_REGISTER_FILES = ("gemm_kernels.hip",)
 
 
 def build(verbose: bool = False) -> str:
@@ -24,7 +29,8 @@ def build(verbose: bool = False) -> str:
 
     def compile_one(src):
         obj = os.path.join(objdir, os.path.basename(src)[:-4] + ".o")
-        cmd = [hipcc, *HIPCC_FLAGS, "-c", src, "-o", obj]
+        extra = [] if os.path.basename(src) in ACC_REGISTER_FILES else VGPR_FORM_FLAGS
+        cmd = [hipcc, *HIPCC_FLAGS, *extra, "-c", src, "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError(f"hipcc failed on {src}:\n{r.stderr}")

@@ -4,6 +4,8 @@
 // non-local rows first and the local rows after them (softmax does not depend on key order).
 #include "common.h"
 
+#include <type_traits>
+
 namespace astra {
 
 // ------------------------------------------------------------------------------------------------
@@ -56,7 +58,8 @@ __global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams
     constexpr int NKS = DH / 16;               // contraction steps of Q.K
     constexpr int NDB = DH / 32;               // 32-wide blocks of the head dimension
     constexpr int PIECES = kAttKV * CPR;       // pieces per tile
-    constexpr int LPT = PIECES / kAttThreads;  // transfers per thread per tile
+    constexpr int kParThreads = kAttThreads / 2;           // threads of one key parity
+    constexpr int LPT = PIECES / kParThreads;  // transfers per thread per tile
     // [buffer][parity] tiles
     __shared__ u32x4 lds_k[2][2][PIECES];
     __shared__ u32x4 lds_v[2][2][PIECES];
@@ -66,6 +69,7 @@ __global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform: keeps the tile bookkeeping in scalar registers
     const int i32 = lane & 31, h = lane >> 5;
     const int qg = wave & 3, par = wave >> 2;
+    const int ptid = tid & (kParThreads - 1);
 
     const int n_qb = (p.Tq + kAttQ - 1) / kAttQ;
     const int vt_id = xcd_remap_attn(blockIdx.x, gridDim.x);
@@ -100,80 +104,155 @@ __global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams
     const int n_pairs = (n_tiles + 1) / 2;
     const int wave_q_lo = q0 + 32 * qg;
 
-    // ---- staging: global -> LDS without passing through registers.  One wavefront instruction moves 64
-    // consecutive 16-byte LDS slots; the XOR swizzle is applied on the global side (the lane that owns
-    // slot (row, piece) fetches piece ^ swizzle(row) of that row).  Slot c = tid + 512*it of a K tile is
-    // (row c / CPR, piece c % CPR); both swizzles are periodic in the row step between two `it`, so the
-    // piece a lane fetches is the same for every `it` and only the row term changes.
-    constexpr int ROW_STEP = kAttThreads / CPR;               // K rows between consecutive `it`
-    const int kr0 = tid / CPR, kph = tid % CPR;
+    // ---- tiles of this wavefront's parity: own iteration i works on tile 2i + par of the walk (visible
+    // non-local tiles first, local tiles after them).  An index past the end (odd tile count) is the last
+    // tile again with every key masked, so all wavefronts run the same number of iterations.
+    struct Tile {
+        bool is_loc;
+        int row0, count;
+    };
+    auto tile_of = [&](int i) {
+        const int t_in = 2 * i + par;
+        const int t = t_in < n_tiles ? t_in : n_tiles - 1;
+        Tile tl;
+        tl.is_loc = t >= n_hat_tiles;
+        tl.row0 = (tl.is_loc ? t - n_hat_tiles : t) * kAttKV;
+        tl.count = t_in >= n_tiles ? 0 : (tl.is_loc ? Tq : p.Tn_vis);
+        return tl;
+    };
+
+    // ---- staging: global -> LDS without passing through registers, by the four wavefronts of the parity that
+    // consumes the tile.  One wavefront instruction moves 64 consecutive 16-byte LDS slots; the XOR swizzle is
+    // applied on the global side (the lane that owns slot (row, piece) fetches piece ^ swizzle(row) of that row).
+    // Slot c = ptid + 256*it of a K tile is (row c / CPR, piece c % CPR); both swizzles are periodic in the row
+    // step between two `it`, so the piece a lane fetches is the same for every `it` and only the row changes.
+    constexpr int ROW_STEP = kParThreads / CPR;               // K rows between consecutive `it`
+    const int kr0 = ptid / CPR, kph = ptid % CPR;
     const uint32_t kcol = (uint32_t)((kph ^ swz_k<DH>(kr0)) * 16);                 // bytes
-    const uint32_t vcol = VT ? (uint32_t)(((tid & 7) ^ swz_vt(tid >> 3)) * 16)      // V^T: row tid/8 + 64*it, piece tid%8
+    const uint32_t vcol = VT ? (uint32_t)(((ptid & 7) ^ swz_vt(ptid >> 3)) * 16)    // V^T: row ptid/8 + 32*it, piece ptid%8
                              : (uint32_t)((kph ^ swz_v<DH>(kr0)) * 16);
     const uint32_t kv_ld_b = (uint32_t)kv_ld * 2u;
-    auto issue_pair = [&](int pair, int buf) {
-#pragma unroll
-        for (int pp = 0; pp < 2; ++pp) {
-            int t = 2 * pair + pp;
-            t = t < n_tiles ? t : n_tiles - 1;                 // past the end: re-read the last tile, never used
-            const bool is_loc = t >= n_hat_tiles;
-            const int row0 = (is_loc ? t - n_hat_tiles : t) * kAttKV;
-            const int lim = (is_loc ? Tq : p.Tn_vis) - 1 - row0;                 // last valid row of the tile
-            const char* __restrict__ Kb = (const char*)(is_loc ? p.k_loc : p.k_hat) + ((int64_t)row0 * kv_ld + (int64_t)hk * DH) * 2;
-            const uint32_t k_base = lds_byte_addr(&lds_k[buf][pp][0]), v_base = lds_byte_addr(&lds_v[buf][pp][0]);
-            const uint32_t v_ld_b = (uint32_t)(is_loc ? p.ldv_loc : p.ldv_hat) * 2u;
-            const char* __restrict__ Vb = VT ? (const char*)(is_loc ? p.v_loc : p.v_hat) + ((int64_t)hk * DH * v_ld_b + (int64_t)row0 * 2)
-                                             : (const char*)(is_loc ? p.v_loc : p.v_hat) + ((int64_t)row0 * kv_ld + (int64_t)hk * DH) * 2;
-#pragma unroll
-            for (int it = 0; it < LPT; ++it) {
-                const uint32_t slot0 = (uint32_t)(64 * (wave + 8 * it)) * 16u;   // first slot of this wavefront instruction
-                const int r = min(kr0 + ROW_STEP * it, lim);
-                const uint32_t koff = (uint32_t)r * kv_ld_b + kcol;
-                dma_global_to_lds_16(Kb, koff, k_base + slot0);
-                const uint32_t voff = VT ? (uint32_t)((tid >> 3) + 64 * it) * v_ld_b + vcol : koff - kcol + vcol;
-                dma_global_to_lds_16(Vb, voff, v_base + slot0);
-            }
+    const uint32_t wave_slot = (uint32_t)(64 * (wave & 3)) * 16u;
+    auto dma_k = [&](const Tile& tl, int buf, int it) {
+        const char* __restrict__ Kb = (const char*)(tl.is_loc ? p.k_loc : p.k_hat) + ((int64_t)tl.row0 * kv_ld + (int64_t)hk * DH) * 2;
+        const int lim = (tl.is_loc ? Tq : p.Tn_vis) - 1 - tl.row0;                 // last valid row of the tile
+        const int r = min(kr0 + ROW_STEP * it, lim);
+        dma_global_to_lds_16(Kb, (uint32_t)r * kv_ld_b + kcol, lds_byte_addr(&lds_k[buf][par][0]) + wave_slot + (uint32_t)it * 4096u);
+    };
+    auto dma_v = [&](const Tile& tl, int buf, int it) {
+        const uint32_t dst = lds_byte_addr(&lds_v[buf][par][0]) + wave_slot + (uint32_t)it * 4096u;
+        if (VT) {
+            const uint32_t v_ld_b = (uint32_t)(tl.is_loc ? p.ldv_loc : p.ldv_hat) * 2u;
+            const char* __restrict__ Vb = (const char*)(tl.is_loc ? p.v_loc : p.v_hat) + ((int64_t)hk * DH * v_ld_b + (int64_t)tl.row0 * 2);
+            dma_global_to_lds_16(Vb, (uint32_t)((ptid >> 3) + 32 * it) * v_ld_b + vcol, dst);
+        } else {
+            const char* __restrict__ Vb = (const char*)(tl.is_loc ? p.v_loc : p.v_hat) + ((int64_t)tl.row0 * kv_ld + (int64_t)hk * DH) * 2;
+            const int lim = (tl.is_loc ? Tq : p.Tn_vis) - 1 - tl.row0;
+            const int r = min(kr0 + ROW_STEP * it, lim);
+            dma_global_to_lds_16(Vb, (uint32_t)r * kv_ld_b + vcol, dst);
         }
     };
 
-    // ---- one 64-key tile: S^T (16 MFMAs), softmax, O^T update (16 MFMAs)
-    auto compute_tile = [&](int buf, int t_in) {
-        const int t = t_in < n_tiles ? t_in : n_tiles - 1;
-        const bool is_loc = t >= n_hat_tiles;
-        const int row0 = (is_loc ? t - n_hat_tiles : t) * kAttKV;
-        // a tile index past the end (odd tile count) is processed with every key masked: the control flow
-        // stays the same for all wavefronts and iterations, LDS holds a finite copy of the last tile
-        const int count = t_in >= n_tiles ? 0 : (is_loc ? Tq : p.Tn_vis);
-        const bool diag = is_loc && p.causal && (row0 + kAttKV - 1 > wave_q_lo);     // some pair of this wave is hidden
-        const bool masked = diag || (row0 + kAttKV > count);
-        const u32x4* __restrict__ Kt = lds_k[buf][par];
-        const u32x4* __restrict__ Vt = lds_v[buf][par];
-
-        f32x16 acc_s[2];
+    // ---- matrix-core phase of iteration i: O^T += V^T(i-1) . P^T(i-1) (PV, 16 MFMAs for dh = 128), then
+    // S^T(i) = K(i) . Q^T (QK, 16 MFMAs), in units of NDB / 4 MFMAs.  The fragments of unit u+1 are requested from
+    // LDS before the MFMAs of unit u are issued, and the transfers of the tiles needed one iteration later (K(i+1),
+    // V(i)) are issued one per unit between the MFMAs, so that no wavefront stalls on the memory pipeline's queue.
+    f32x16 acc_s[2];
+    bf16x8 pf[4];
+    constexpr int QK_UNITS = NKS / 2;
+    auto mm_phase = [&](int i) {
+        constexpr int NPV = 4, NU = NPV + QK_UNITS;
+        constexpr int NDMA = 2 * LPT;
+        const u32x4* __restrict__ Kt = lds_k[i & 1][par];
+        const u32x4* __restrict__ Vt = lds_v[(i & 1) ^ 1][par];
+        const Tile t_k = tile_of(i + 1), t_v = tile_of(i);
+        auto load_unit = [&](int u, bf16x8(&f)[4]) {
+            if (u < NPV) {
+                const int kstep = u;
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
+                for (int db = 0; db < NDB; ++db) {
+                    if (VT) {
+                        const int d = db * 32 + i32;
+                        f[db] = __builtin_bit_cast(bf16x8, Vt[d * 8 + ((2 * kstep + h) ^ swz_vt(d))]);
+                    } else {
+                        const int s16 = lane & 15, q4 = lane >> 4;
+                        const int c = db * 4 + 2 * (q4 & 1) + ((s16 & 3) >> 1);
+                        const int r_lo = 16 * kstep + 4 * h + (s16 >> 2);
+                        const int r_hi = r_lo + 8;
+                        const char* base = reinterpret_cast<const char*>(Vt);
+                        const s16x4 lo = lds_read_tr16_b64(base + (r_lo * CPR + (c ^ swz_v<DH>(r_lo))) * 16 + 8 * (s16 & 1));
+                        const s16x4 hi = lds_read_tr16_b64(base + (r_hi * CPR + (c ^ swz_v<DH>(r_hi))) * 16 + 8 * (s16 & 1));
+                        u32x4 packed;
+                        packed.x = (uint16_t)lo[0] | ((uint32_t)(uint16_t)lo[1] << 16);
+                        packed.y = (uint16_t)lo[2] | ((uint32_t)(uint16_t)lo[3] << 16);
+                        packed.z = (uint16_t)hi[0] | ((uint32_t)(uint16_t)hi[1] << 16);
+                        packed.w = (uint16_t)hi[2] | ((uint32_t)(uint16_t)hi[3] << 16);
+                        f[db] = __builtin_bit_cast(bf16x8, packed);
+                    }
+                }
+            } else {
+                const int g = u - NPV;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc_s[mb][v] = 0.f;
-            const int r = mb * 32 + i32;
+                for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) {
-                const bf16x8 kf = __builtin_bit_cast(bf16x8, Kt[r * CPR + ((2 * ks + h) ^ swz_k<DH>(r))]);
-                acc_s[mb] = mfma_32x32x16(kf, qf[ks], acc_s[mb]);
+                    for (int mb = 0; mb < 2; ++mb) {
+                        const int r = mb * 32 + i32, ks = 2 * g + j;
+                        f[j * 2 + mb] = __builtin_bit_cast(bf16x8, Kt[r * CPR + ((2 * ks + h) ^ swz_k<DH>(r))]);
+                    }
             }
+        };
+        auto compute_unit = [&](int u, const bf16x8(&f)[4]) {
+            if (u < NPV) {
+#pragma unroll
+                for (int db = 0; db < NDB; ++db) acc_o[db] = mfma_32x32x16(f[db], pf[u], acc_o[db]);
+            } else {
+                const int g = u - NPV;
+                if (g == 0) {
+#pragma unroll
+                    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) acc_s[mb][v] = 0.f;
+                }
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int mb = 0; mb < 2; ++mb) acc_s[mb] = mfma_32x32x16(f[j * 2 + mb], qf[2 * g + j], acc_s[mb]);
+            }
+        };
+        bf16x8 fa[4], fb[4];
+        load_unit(0, fa);
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            if (u + 1 < NU) load_unit(u + 1, (u & 1) ? fa : fb);
+            // spread the NDMA transfers over the NU units
+#pragma unroll
+            for (int x = u * NDMA / NU; x < (u + 1) * NDMA / NU; ++x) {
+                if (x < LPT) dma_k(t_k, (i & 1) ^ 1, x);
+                else dma_v(t_v, i & 1, x - LPT);
+            }
+            compute_unit(u, (u & 1) ? fb : fa);
+            __builtin_amdgcn_sched_barrier(0);
         }
+    };
+
+    // ---- vector-ALU phase of iteration i: masking and online softmax of S^T(i), in base-2 units, leaving the
+    // probabilities as the bf16 B operand of the next PV.  The reference maximum m_run is only raised when a score
+    // exceeds it by more than kLazy (2^kLazy fits bf16 and fp32 easily): after the first tiles the accumulators are
+    // almost never rescaled.
+    auto softmax_phase = [&](int i) {
+        const Tile tl = tile_of(i);
+        const bool diag = tl.is_loc && p.causal && (tl.row0 + kAttKV - 1 > wave_q_lo);     // some pair of this wave is hidden
+        const bool masked = diag || (tl.row0 + kAttKV > tl.count);
         // masking (ragged source tail, causal diagonal): a wave-uniform, rarely taken pass of its own
         if (masked) {
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int key = row0 + mb * 32 + acc_row(v, h);
-                    if (key >= count || (diag && key > qrow)) acc_s[mb][v] = -INFINITY;
+                    const int key = tl.row0 + mb * 32 + acc_row(v, h);
+                    if (key >= tl.count || (diag && key > qrow)) acc_s[mb][v] = -INFINITY;
                 }
         }
-        // Online softmax of this lane's query, in base-2 units.  The reference maximum m_run is only
-        // raised when a score exceeds it by more than kLazy (2^kLazy fits bf16 and fp32 easily): after
-        // the first tiles the accumulators are almost never rescaled.
         float mx = -INFINITY;
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
@@ -187,7 +266,6 @@ __global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams
             m_run = mx;
         }
         const float m_ref = m_run == -INFINITY ? 0.f : m_run;
-        bf16x8 pf[4];
         float lsum = 0.f;
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
@@ -204,46 +282,43 @@ __global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc_o[db][v] *= alpha;
         }
-        // O^T += V^T . P^T : contraction over the 64 keys in 4 steps of 16
-#pragma unroll
-        for (int kstep = 0; kstep < 4; ++kstep) {
-#pragma unroll
-            for (int db = 0; db < NDB; ++db) {
-                bf16x8 vf;
-                if (VT) {
-                    const int d = db * 32 + i32;
-                    vf = __builtin_bit_cast(bf16x8, Vt[d * 8 + ((2 * kstep + h) ^ swz_vt(d))]);
-                } else {
-                    const int s16 = lane & 15, q4 = lane >> 4;
-                    const int c = db * 4 + 2 * (q4 & 1) + ((s16 & 3) >> 1);
-                    const int r_lo = 16 * kstep + 4 * h + (s16 >> 2);
-                    const int r_hi = r_lo + 8;
-                    const char* base = reinterpret_cast<const char*>(Vt);
-                    const s16x4 lo = lds_read_tr16_b64(base + (r_lo * CPR + (c ^ swz_v<DH>(r_lo))) * 16 + 8 * (s16 & 1));
-                    const s16x4 hi = lds_read_tr16_b64(base + (r_hi * CPR + (c ^ swz_v<DH>(r_hi))) * 16 + 8 * (s16 & 1));
-                    u32x4 packed;
-                    packed.x = (uint16_t)lo[0] | ((uint32_t)(uint16_t)lo[1] << 16);
-                    packed.y = (uint16_t)lo[2] | ((uint32_t)(uint16_t)lo[3] << 16);
-                    packed.z = (uint16_t)hi[0] | ((uint32_t)(uint16_t)hi[1] << 16);
-                    packed.w = (uint16_t)hi[2] | ((uint32_t)(uint16_t)hi[3] << 16);
-                    vf = __builtin_bit_cast(bf16x8, packed);
-                }
-                acc_o[db] = mfma_32x32x16(vf, pf[kstep], acc_o[db]);
-            }
-        }
     };
 
-    // ---- pipeline over tile pairs: the transfers of pair i+1 run while pair i is consumed; one barrier per pair.
-    issue_pair(0, 0);
+    // ---- schedule.  The two wavefronts of a SIMD have different parities; parity 1 runs one phase behind parity 0,
+    // and a workgroup barrier closes every phase, so while one wavefront of a SIMD occupies the matrix core the
+    // other runs its softmax on the vector ALU:
+    //   parity 0:  QK(0) | sm(0) | PV(0) QK(1) | sm(1) | ... | sm(n-1) | PV(n-1) |
+    //   parity 1:        | QK(0) | sm(0) | PV(0) QK(1) | ... | PV(n-2) QK(n-1) | sm(n-1) | PV(n-1)
+    // A tile's buffer is rewritten (by transfers issued in a matrix-core phase) one barrier-closed iteration after
+    // its last reader, and every wavefront waits for its own transfers at the end of its softmax phase, before the
+    // barrier that precedes the phase which reads them.
+    // The loop body is the same for every iteration: the first PV multiplies zero probabilities with a zeroed V
+    // buffer and the last QK (on a finite copy of the last tile) is discarded, 32 of about 1000 MFMAs.
+    const int n_it = n_pairs;
+    {
+        const Tile t0 = tile_of(0);
+#pragma unroll
+        for (int it = 0; it < LPT; ++it) dma_k(t0, 0, it);
+        u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int it = 0; it < LPT; ++it) lds_v[1][par][ptid + kParThreads * it] = zero;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) pf[j] = __builtin_bit_cast(bf16x8, zero);
+    }
     wait_vmem_all();
     __syncthreads();
-    for (int pair = 0; pair < n_pairs; ++pair) {
-        const int buf = pair & 1;
-        if (pair + 1 < n_pairs) issue_pair(pair + 1, buf ^ 1);
-        compute_tile(buf, 2 * pair + par);
+    if (par == 1) __syncthreads();
+    for (int i = 0;; ++i) {
+        mm_phase(i);
+        __syncthreads();
+        if (i == n_it) break;
+        softmax_phase(i);
         wait_vmem_all();
         __syncthreads();
     }
+    wait_vmem_all();          // transfers issued by the last matrix-core phase land in buffers the merge reuses
+    if (par == 0) __syncthreads();
+    __syncthreads();
 
     // ---- merge the two parities of each query group through LDS (the tile buffers are free now)
     float* xch = reinterpret_cast<float*>(&lds_k[0][0][0]);        // NDB*16*64 floats per query group (<= 16 KiB each)

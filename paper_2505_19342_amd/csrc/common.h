@@ -66,12 +66,20 @@ __device__ __forceinline__ void dma_global_to_lds_16(const void* gbase_uniform, 
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(base), "v"(byte_off), "s"(gbase_uniform)
                  : "memory");
 }
-__device__ __forceinline__ void wait_vmem_all() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// The waits are emitted through the compiler's own s_waitcnt builtin (gfx9 encoding: vmcnt in bits 3:0 and
+// 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their maxima = no wait), not as inline assembly: the compiler's
+// wait-count bookkeeping then knows that its own earlier global loads have completed too and does not wait for
+// them again inside a pipelined loop, where such a wait would also drain the transfers in flight.
+__device__ __forceinline__ void wait_vmem_all() {
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    asm volatile("" ::: "memory");
+}
 // wait until at most N of this wavefront's vector-memory instructions (they complete in order) are outstanding
 template <int N>
 __device__ __forceinline__ void wait_vmem() {
     static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
+    asm volatile("" ::: "memory");
 }
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }

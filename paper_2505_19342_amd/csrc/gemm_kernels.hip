@@ -4,6 +4,8 @@
 // its A rows straight from the codebook through the token codes (decode fused into the operand load).
 #include "common.h"
 
+#include <type_traits>
+
 namespace astra {
 
 struct GemmBatch {
@@ -159,25 +161,77 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_bf16_kernel(const GemmBa
 #pragma unroll
     for (int b = 0; b < TN; ++b) brow[b] = wn * (BN / WN) + b * 32 + i32;
 
-    auto compute = [&](int buf_) {
+    // ---- main loop.  One tile of 64 along the contraction is four MFMA steps of 16.  Per step a wavefront
+    // issues TM*TN MFMAs on fragments it requested from LDS one step earlier (two fragment slots), and between those
+    // MFMAs, in program order, the "side jobs" of the step: the TM+TN fragment reads of the next step and a slice of
+    // the staging work (registers holding tile kt+1 -> other LDS buffer, refilled at once with the global loads of
+    // tile kt+2).  Nothing else is needed to keep a single wavefront per SIMD busy: LDS and global latencies are
+    // covered by the MFMAs issued meanwhile.  Staging is spread over steps 0..2; the workgroup barrier follows step 2,
+    // after which step 3 may read the first fragments of tile kt+1 from the buffer just filled, and the buffer of
+    // tile kt (all of whose fragments were requested before the barrier) is free for the next iteration's staging.
+    const int n_kt = K / kBK;
+    bf16x8 fa[2][TM], fb[2][TN];
+    auto read_frag = [&](int buf_, int ks, int slot, int j) {
+        if (j < TM) fa[slot][j] = __builtin_bit_cast(bf16x8, lds_a[buf_][arow[j] * 8 + ((2 * ks + h) ^ swz(arow[j]))]);
+        else fb[slot][j - TM] = __builtin_bit_cast(bf16x8, lds_b[buf_][brow[j - TM] * 8 + ((2 * ks + h) ^ swz(brow[j - TM]))]);
+    };
+    constexpr int NR = TM + TN, NM = TM * TN;
+    auto tile_steps = [&](int kt, auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;       // steady state: tiles kt+1, kt+2 and codes kt+3 all exist
+        const int buf = kt & 1;
+        const bool st = FULL || kt + 1 < n_kt, ld = FULL || kt + 2 < n_kt;
+        const uint32_t g_ = __umulhi((uint32_t)k_use, magic);
+        const uint32_t j_ = (uint32_t)k_use - g_ * (uint32_t)dg;
+        const uint32_t gbase_ = g_ * (uint32_t)Kc;
+        auto stage_a = [&](int it) {
+            const int r_ = r0 + RPP * it;
+            if (st) lds_a[buf ^ 1][r_ * 8 + (kc ^ swz(r_))] = ra[it];
+            if (ld) {
+                const uint32_t c_ = (uint32_t)(code[it] < Kc ? code[it] : Kc - 1);
+                const uint32_t goff_ = ((gbase_ + c_) * (uint32_t)dg + j_) * 2u;
+                ra[it] = *reinterpret_cast<const u32x4*>(a_base + ((goff_ & gmask) + aoff[it]));
+            }
+        };
+        auto stage_b = [&](int it) {
+            const int r_ = r0 + RPP * it;
+            if (st) lds_b[buf ^ 1][r_ * 8 + (kc ^ swz(r_))] = rb[it];
+            if (ld) rb[it] = *reinterpret_cast<const u32x4*>(b_base + boff[it]);
+        };
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            bf16x8 fa[TM], fb[TN];
+            const int cur = ks & 1, nxt = cur ^ 1;
+            // side jobs of this step: NR fragment reads, then (steps 0..2) the staging slice
+            const int a_lo = ks < 3 ? ks * PA / 3 : PA, a_hi = ks < 3 ? (ks + 1) * PA / 3 : PA;
+            const int b_lo = ks < 3 ? ks * PB / 3 : PB, b_hi = ks < 3 ? (ks + 1) * PB / 3 : PB;
+            const int nj = NR + (a_hi - a_lo) + (b_hi - b_lo);
+            const bool rd = ks < 3 || st;                     // step 3 reads the next tile, if there is one
 #pragma unroll
-            for (int a = 0; a < TM; ++a) fa[a] = __builtin_bit_cast(bf16x8, lds_a[buf_][arow[a] * 8 + ((2 * ks + h) ^ swz(arow[a]))]);
+            for (int m = 0; m < NM; ++m) {
+                const int a = m / TN, b = m % TN;
+                acc[a][b] = mfma_32x32x16(fa[cur][a], fb[cur][b], acc[a][b]);
 #pragma unroll
-            for (int b = 0; b < TN; ++b) fb[b] = __builtin_bit_cast(bf16x8, lds_b[buf_][brow[b] * 8 + ((2 * ks + h) ^ swz(brow[b]))]);
-#pragma unroll
-            for (int a = 0; a < TM; ++a)
-#pragma unroll
-                for (int b = 0; b < TN; ++b) acc[a][b] = mfma_32x32x16(fa[a], fb[b], acc[a][b]);
+                for (int j = m * nj / NM; j < (m + 1) * nj / NM; ++j) {
+                    if (j < NR) {
+                        if (rd) read_frag(ks < 3 ? buf : buf ^ 1, (ks + 1) & 3, nxt, j);
+                    } else if (j - NR < a_hi - a_lo) {
+                        stage_a(a_lo + j - NR);
+                    } else {
+                        stage_b(b_lo + j - NR - (a_hi - a_lo));
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);        // keep this order: the compiler would bunch the memory operations
+            }
+            if (ks == 2) __syncthreads();
+            __builtin_amdgcn_sched_barrier(0);
         }
+        if (ld) {
+            a_base += a_step;
+            b_base += kBK * 2;
+            k_use += kBK;
+        }
+        if (FULL || kt + 3 < n_kt) load_codes();
     };
 
-    // Software pipeline, per iteration kt: registers (tile kt+1, fetched one iteration ago) go to the
-    // other LDS buffer, the loads of tile kt+2 and the codes of tile kt+3 are issued, then tile kt is
-    // multiplied out of LDS while those loads are in flight.  One barrier per iteration.
-    const int n_kt = K / kBK;
     load_codes();                 // codes of tile 0
     load_tile();                  // tile 0
     if (n_kt > 1) load_codes();   // codes of tile 1
@@ -185,57 +239,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_bf16_kernel(const GemmBa
     if (n_kt > 1) load_tile();    // tile 1
     if (n_kt > 2) load_codes();   // codes of tile 2
     __syncthreads();
-    // Steady state: the staging work of an iteration is cut into four slices and each slice follows the
-    // MFMAs of one contraction step, so LDS writes and global loads are issued while the matrix core is
-    // busy instead of in a block of their own.
-    static_assert(PA % 4 == 0 && PB % 4 == 0, "whole staging passes per contraction step");
+#pragma unroll
+    for (int j = 0; j < NR; ++j) read_frag(0, 0, 0, j);
     int kt = 0;
-    for (; kt + 3 < n_kt; ++kt) {
-        const int buf = kt & 1;
-        const uint32_t g_ = __umulhi((uint32_t)k_use, magic);
-        const uint32_t j_ = (uint32_t)k_use - g_ * (uint32_t)dg;
-        const uint32_t gbase_ = g_ * (uint32_t)Kc;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            bf16x8 fa[TM], fb[TN];
-#pragma unroll
-            for (int a = 0; a < TM; ++a) fa[a] = __builtin_bit_cast(bf16x8, lds_a[buf][arow[a] * 8 + ((2 * ks + h) ^ swz(arow[a]))]);
-#pragma unroll
-            for (int b = 0; b < TN; ++b) fb[b] = __builtin_bit_cast(bf16x8, lds_b[buf][brow[b] * 8 + ((2 * ks + h) ^ swz(brow[b]))]);
-#pragma unroll
-            for (int a = 0; a < TM; ++a)
-#pragma unroll
-                for (int b = 0; b < TN; ++b) acc[a][b] = mfma_32x32x16(fa[a], fb[b], acc[a][b]);
-            // slice ks: tile kt+1 to the other LDS buffer, then refill those registers with tile kt+2
-#pragma unroll
-            for (int it = ks * (PA / 4); it < (ks + 1) * (PA / 4); ++it) {
-                const int r_ = r0 + RPP * it;
-                lds_a[buf ^ 1][r_ * 8 + (kc ^ swz(r_))] = ra[it];
-                const uint32_t c_ = (uint32_t)(code[it] < Kc ? code[it] : Kc - 1);
-                const uint32_t goff_ = ((gbase_ + c_) * (uint32_t)dg + j_) * 2u;
-                ra[it] = *reinterpret_cast<const u32x4*>(a_base + ((goff_ & gmask) + aoff[it]));
-            }
-#pragma unroll
-            for (int it = ks * (PB / 4); it < (ks + 1) * (PB / 4); ++it) {
-                const int r_ = r0 + RPP * it;
-                lds_b[buf ^ 1][r_ * 8 + (kc ^ swz(r_))] = rb[it];
-                rb[it] = *reinterpret_cast<const u32x4*>(b_base + boff[it]);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        a_base += a_step;
-        b_base += kBK * 2;
-        k_use += kBK;
-        load_codes();
-        __syncthreads();
-    }
-    for (; kt < n_kt; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < n_kt) store_tile(buf ^ 1);
-        if (kt + 2 < n_kt) load_tile();
-        compute(buf);
-        __syncthreads();
-    }
+    for (; kt + 3 < n_kt; ++kt) tile_steps(kt, std::true_type{});
+    for (; kt < n_kt; ++kt) tile_steps(kt, std::false_type{});
 
     // epilogue.  acc[a][b][v] is C[m, n] with m = wave row base + 32a + acc_row(v, h), n = wave column base + 32b + lane % 32.
     const uint16_t* __restrict__ bias = (const uint16_t*)P.bias;
@@ -415,7 +423,12 @@ int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hi
     int rc = fill_batch(batch, dtype, problems, n_problems, 256, 256, &total);
     if (rc) return rc;
     bool big = total >= 128;
-    if (g_gemm_force_cfg >= 0) big = g_gemm_force_cfg == 1;
+    if (g_gemm_force_cfg >= 0) big = g_gemm_force_cfg >= 1;
+    if (big && g_gemm_force_cfg == 2) {
+        if (code16) gemm_nt_bf16_kernel<256, 256, 2, 2, true><<<total, 256, 0, s>>>(batch);
+        else gemm_nt_bf16_kernel<256, 256, 2, 2, false><<<total, 256, 0, s>>>(batch);
+        return launch_status();
+    }
     if (big) {
         if (total == 0) return ASTRA_OK;
         if (code16) gemm_nt_bf16_kernel<256, 256, 2, 4, true><<<total, 512, 0, s>>>(batch);

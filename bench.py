@@ -135,9 +135,9 @@ def main():
     t1 = time.perf_counter()
     events = list(events.values())
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    # events: 0 entry, 1 projections done, 2 attention done, 3 output projection done, 4 exit; 5/6 around the
-    # encode on its side stream (it overlaps the projections)
-    spans = {"vq_encode": (5, 6), "projections": (0, 1), "attention": (1, 2), "out_projection": (2, 3)}
+    # events: 0 entry, 1 projection launch done, 5/6 around the encode if it ran as a kernel of its own (otherwise
+    # it ran inside the projection launch and 5..6 is empty), 2 attention done, 3 output projection done, 4 exit
+    spans = {"vq_encode": (5, 6), "projections": (0, 1), "attention": (6, 2), "out_projection": (2, 3)}
     stage_ms = {s: float(np.mean([ev.elapsed_ms(*spans[s]) for ev in events])) for s in STAGES}
     gpu_ms = float(np.mean([ev.elapsed_ms(0, 4) for ev in events]))
 

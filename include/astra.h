@@ -137,10 +137,12 @@ int astra_layer_forward(const astra_layer_desc* desc, const void* x_local, const
 
 /* astra_layer_forward with stage timing for benchmarks: identical work and results, and in addition
  * seven hipEvent_t (created by the caller with timing enabled, passed as void*; a NULL entry is skipped)
- * are recorded: [0] on `stream` at entry, [1] after the Q/K/V/K-hat/V-hat projections, [2] after the
- * attention, [3] after the output projection, [4] at exit (after the encode has been joined), and on
- * the stream the encode runs on [5] before and [6] after the encode (Sec. 3.1; the encode overlaps the
- * other stages). */
+ * are recorded on `stream`: [0] at entry, [1] after the launch that computes the Q/K/V/K-hat/V-hat
+ * projections, [5] and [6] before and after the encode of the local rows when it runs as a kernel of its
+ * own, [2] after the attention, [3] after the output projection, [4] at exit.  Where the shape allows,
+ * the encode (Sec. 3.1) runs INSIDE the projection launch, as extra workgroups on compute units the
+ * projection tiles leave idle: then [5] and [6] are recorded back to back and the span [0]..[1] covers
+ * both.  The attention is the span [6]..[2]. */
 int astra_layer_forward_profiled(const astra_layer_desc* desc, const void* x_local, const void* codes_nonlocal,
                                  const void* codebook, const float* cnorm,
                                  const void* wq, const void* wk, const void* wv, const void* wo,

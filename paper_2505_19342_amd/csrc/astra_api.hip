@@ -1,7 +1,7 @@
 // C ABI of the library: argument checking and the per-layer orchestration (paper Sec. 3.1).
-#include <mutex>
 
 #include "common.h"
+#include "vq_encode_body.h"
 
 namespace astra {
 
@@ -154,32 +154,6 @@ size_t astra_layer_workspace_bytes(const astra_layer_desc* desc) {
     return pl.total;
 }
 
-// The encode of the local rows depends on nothing else in the layer and nothing in the layer depends on
-// it, so it runs on a side stream while the projections (which leave a quarter of the compute units idle
-// at the benchmark shape) and the attention run on the caller's stream.  One side stream and two events
-// per device, created on first use (default priority, no device memory); the fork/join pair makes the
-// call behave as if everything were enqueued on the caller's stream.
-struct SideStream {
-    hipStream_t stream = nullptr;
-    hipEvent_t fork = nullptr, join = nullptr;
-    bool ok = false;
-};
-static std::mutex g_side_mutex;
-static SideStream g_side[16];
-
-static SideStream* side_stream_for_current_device() {
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return nullptr;
-    SideStream& ss = g_side[dev];
-    if (!ss.ok) {
-        if (hipStreamCreateWithFlags(&ss.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
-        if (hipEventCreateWithFlags(&ss.fork, hipEventDisableTiming) != hipSuccess) return nullptr;
-        if (hipEventCreateWithFlags(&ss.join, hipEventDisableTiming) != hipSuccess) return nullptr;
-        ss.ok = true;
-    }
-    return &ss;
-}
-
 static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local, const void* codes_nonlocal,
                               const void* codebook, const float* cnorm,
                               const void* wq, const void* wk, const void* wv, const void* wo,
@@ -204,28 +178,22 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     void *Q = ws + pl.off_q, *K = ws + pl.off_k, *V = ws + pl.off_v, *Kh = ws + pl.off_kh, *Vh = ws + pl.off_vh,
          *O = ws + pl.off_o, *Xh = ws + pl.off_xhat;
 
-    // 1. indices this device transmits: encode the content rows (the class row is not encoded), on the
-    //    side stream, joined at the end of the call
-    std::lock_guard<std::mutex> lock(g_side_mutex);
-    SideStream* side = at.n_local > 0 ? side_stream_for_current_device() : nullptr;
-    hipStream_t es = s;
-    if (side) {
-        if (hipEventRecord(side->fork, s) != hipSuccess || hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)
-            return ASTRA_ERR_HIP;
-        es = side->stream;
-    }
-    mark(5, es);
-    rc = launch_vq_encode(vq, (const char*)x_local + (size_t)at.n_cls * pl.D * eb, pl.D, at.n_local, codebook, cnorm,
-                          codes_local_out, es);
-    mark(6, es);
-    if (side && hipEventRecord(side->join, es) != hipSuccess) return ASTRA_ERR_HIP;
-    auto join = [&]() { return (side && hipStreamWaitEvent(s, side->join, 0) != hipSuccess) ? (int)ASTRA_ERR_HIP : (int)ASTRA_OK; };
-    if (rc) { (void)join(); return rc; }
+    // 1. indices this device transmits: the encode of the content rows (the class row is not encoded) depends on
+    //    nothing else in the layer and nothing in the layer depends on it.  It is offered to the projection launch,
+    //    which runs it as extra workgroups on compute units its tiles leave idle; if that launch does not take it
+    //    (other element type, tile count, group size), it runs as a kernel of its own on the same stream.
+    EncodeJob ej{};
+    ej.x = (const char*)x_local + (size_t)at.n_cls * pl.D * eb;
+    ej.codebook = codebook; ej.cnorm = cnorm; ej.codes = codes_local_out; ej.ldx = pl.D;
+    ej.n_tokens = at.n_local; ej.G = vq.n_groups; ej.K = vq.codebook_size; ej.dg = pl.D / vq.n_groups;
+    ej.code_bytes = code_bytes(vq.code_type);
+    const bool offer = vq.dtype == ASTRA_BF16 && at.n_local > 0 && pl.D % 8 == 0;
+    bool enc_fused = false;
 
     // 2. projections: Q, K, V of local rows; K-hat, V-hat of the rows rebuilt from the peers' codes
     if (pl.need_xhat && pl.Tn_vis > 0) {
         rc = launch_vq_decode(vq, codes_nonlocal, pl.Tn_vis, codebook, Xh, s);
-        if (rc) { (void)join(); return rc; }
+        if (rc) return rc;
     }
     GemmProblem pr[5] = {};
     auto local = [&](GemmProblem& g, const void* w, const void* b, void* c, int n) {
@@ -248,9 +216,15 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     nonlocal_(pr[3], wk, bk, Kh, pl.dkv);
     nonlocal_(pr[4], wv, bv, Vh, pl.dkv);
     if (pl.vt) { pr[4].c_mode = kCTransposedV; pr[4].ldc = pl.ldv_hat; }
-    rc = launch_gemm_batch(vq.dtype, pr, 5, s);
-    if (rc) { (void)join(); return rc; }
+    rc = launch_gemm_batch(vq.dtype, pr, 5, s, offer ? &ej : nullptr, offer ? &enc_fused : nullptr);
+    if (rc) return rc;
     mark(1, s);
+    mark(5, s);
+    if (!enc_fused && at.n_local > 0) {
+        rc = launch_vq_encode(vq, ej.x, pl.D, at.n_local, codebook, cnorm, codes_local_out, s);
+        if (rc) return rc;
+    }
+    mark(6, s);
 
     // 3. mixed-precision attention (Eq. 1)
     AttnParams ap = attn_params(at, Q, K, V, Kh, Vh, O, nullptr);
@@ -258,7 +232,7 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     ap.ldv_loc = pl.ldv_loc;
     ap.ldv_hat = pl.ldv_hat;
     rc = launch_attention(vq.dtype, ap, at.head_dim, s);
-    if (rc) { (void)join(); return rc; }
+    if (rc) return rc;
     mark(2, s);
 
     // 4. output projection
@@ -267,9 +241,8 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     po.c_mode = kCF32;      // y leaves the layer as the fp32 accumulator, for both element types
     rc = launch_gemm_batch(vq.dtype, &po, 1, s);
     mark(3, s);
-    const int jrc = join();
     mark(4, s);
-    return rc ? rc : jrc;
+    return rc;
 }
 
 int astra_layer_forward(const astra_layer_desc* desc, const void* x_local, const void* codes_nonlocal,

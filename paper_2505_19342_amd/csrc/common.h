@@ -121,7 +121,11 @@ struct GemmProblem {
     int32_t c_mode;     // how C is stored (bf16 problems; fp32 problems always store fp32 row-major)
 };
 constexpr int kMaxGemmProblems = 6;
-int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hipStream_t s);
+struct EncodeJob;
+// enc / enc_fused (both or neither): offers the VQ encode of the local rows to the launch; *enc_fused tells whether the
+// launch took it (extra workgroups) or the caller still has to run it.
+int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hipStream_t s, const EncodeJob* enc = nullptr,
+                      bool* enc_fused = nullptr);
 extern int g_gemm_force_cfg;
 extern const int g_gemm_problem_size;
 

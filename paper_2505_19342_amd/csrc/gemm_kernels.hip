@@ -3,6 +3,7 @@
 // codes, and the output projection.  Several problems run in one grouped launch; a problem may take
 // its A rows straight from the codebook through the token codes (decode fused into the operand load).
 #include "common.h"
+#include "vq_encode_body.h"
 
 #include <type_traits>
 
@@ -13,6 +14,8 @@ struct GemmBatch {
     int32_t tile_begin[kMaxGemmProblems + 1];
     int32_t tiles_m[kMaxGemmProblems];     // tiles along M of each problem (tile index = tn * tiles_m + tm)
     GemmProblem p[kMaxGemmProblems];
+    int32_t n_enc_wgs;                     // fused launch: workgroups beyond the GEMM tiles that run the VQ encode
+    EncodeJob enc;
 };
 
 __device__ __forceinline__ int find_problem(const GemmBatch& b, int tile) {
@@ -37,6 +40,7 @@ __device__ __forceinline__ int find_problem(const GemmBatch& b, int tile) {
 // ------------------------------------------------------------------------------------------------
 constexpr int kBK = 64;
 constexpr int kXcds = 8;
+constexpr int kCus = 256;         // compute units of the device the launch shapes are chosen for
 
 __device__ __forceinline__ int xcd_remap(int wg, int total) {
     const int q = total / kXcds, r = total % kXcds;
@@ -46,12 +50,26 @@ __device__ __forceinline__ int xcd_remap(int wg, int total) {
 
 __device__ __forceinline__ int swz(int r) { return (r >> 1) & 7; }
 
+// Fused launch of T GEMM tiles and E encode workgroups (E a multiple of 8): every XCD gets a contiguous range of
+// tiles, as with xcd_remap, followed by E/8 encode workgroups, so both kinds of work are spread over all XCDs.
+struct FusedId {
+    bool enc;
+    int idx;
+};
+__device__ __forceinline__ FusedId fused_id(int wg, int T, int E) {
+    const int xcd = wg % kXcds, slot = wg / kXcds;
+    const int tq = T / kXcds, tr = T % kXcds;
+    const int t_x = tq + (xcd < tr ? 1 : 0);
+    if (slot < t_x) return {false, xcd * tq + (xcd < tr ? xcd : tr) + slot};
+    return {true, xcd * (E / kXcds) + slot - t_x};
+}
+
 // position of token offset o (0..15) inside a 16-token block of the transposed-V layout: the 8 tokens
 // one half-wave holds of an MFMA accumulator column ({4h..4h+3} and {8+4h..8+4h+3}) become contiguous,
 // which is also the order the attention kernel's P^T operand keeps its 16 keys in.
 __device__ __forceinline__ int vt_pos(int o) { return 8 * ((o >> 2) & 1) + (o & 3) + 4 * (o >> 3); }
 
-template <int BM, int BN, int WM, int WN, bool CODE16>
+template <int BM, int BN, int WM, int WN, bool CODE16, bool ENC = false>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_bf16_kernel(const GemmBatch batch) {
     constexpr int THREADS = 64 * WM * WN;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;        // MFMA tiles per wavefront
@@ -60,7 +78,34 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_bf16_kernel(const GemmBa
     __shared__ u32x4 lds_a[2][BM * kBK / 8];
     __shared__ u32x4 lds_b[2][BN * kBK / 8];
 
-    const int vt = xcd_remap(blockIdx.x, gridDim.x);
+    int vt;
+    if (ENC) {
+        // The grid is the GEMM tiles plus batch.n_enc_wgs workgroups that encode the local rows (nothing in the
+        // projections depends on the codes or the other way round): they fill compute units the tiles leave idle.
+        // The encode reuses the operand buffers: its ring of codebook tiles is exactly lds_a, the norms sit in lds_b.
+        static_assert(!ENC || (sizeof(lds_a) == sizeof(u32x4) * kEncBufs * kEncCbSlots && sizeof(lds_b) >= sizeof(f32x4) * kEncBufs * kEncCnSlots),
+                      "encode ring must fit the operand buffers");
+        const FusedId id = fused_id(blockIdx.x, gridDim.x - batch.n_enc_wgs, batch.n_enc_wgs);
+        if (id.enc) {
+            u32x4* cb = &lds_a[0][0];
+            f32x4* cn = reinterpret_cast<f32x4*>(&lds_b[0][0]);
+            const EncodeJob& job = batch.enc;
+            vq_encode_fast_zero_lds<THREADS>(cb);
+            __syncthreads();                               // zero fill done before any transfer lands
+            const int n_items = job.G * job.n_tb;
+            const int chunk = (n_items + batch.n_enc_wgs - 1) / batch.n_enc_wgs;     // consecutive items share the group
+            const int hi = min((id.idx + 1) * chunk, n_items);
+            for (int item = id.idx * chunk; item < hi; ++item) {
+                if (job.code_bytes == 2) vq_encode_fast_body<THREADS, uint16_t>(job, item / job.n_tb, item % job.n_tb, cb, cn);
+                else vq_encode_fast_body<THREADS, uint8_t>(job, item / job.n_tb, item % job.n_tb, cb, cn);
+                __syncthreads();                           // all reads of this item's tiles done before the next item's transfers
+            }
+            return;
+        }
+        vt = id.idx;
+    } else {
+        vt = xcd_remap(blockIdx.x, gridDim.x);
+    }
     const int pi = find_problem(batch, vt);
     const GemmProblem& P = batch.p[pi];
     const int tile = vt - batch.tile_begin[pi];
@@ -405,7 +450,8 @@ static int fill_batch(GemmBatch& batch, int dtype, const GemmProblem* problems, 
     return ASTRA_OK;
 }
 
-int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hipStream_t s) {
+int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hipStream_t s, const EncodeJob* enc, bool* enc_fused) {
+    if (enc_fused) *enc_fused = false;
     if (n_problems > kMaxGemmProblems) return ASTRA_ERR_UNSUPPORTED;
     GemmBatch batch{};
     int total = 0;
@@ -424,6 +470,22 @@ int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hi
     if (rc) return rc;
     bool big = total >= 128;
     if (g_gemm_force_cfg >= 0) big = g_gemm_force_cfg >= 1;
+    // Fuse the encode into the launch when the tiles leave a good part of the last round of compute units idle.
+    if (big && enc && enc_fused && g_gemm_force_cfg < 0 && vq_encode_fast_ok(enc->K, enc->dg) && enc->n_tokens > 0) {
+        const int rem = total % kCus;
+        const int E = rem == 0 ? 0 : ((kCus - rem) & ~7);
+        const int64_t n_tb = ceil_div(enc->n_tokens, 256);
+        if (E >= 8 && E <= kCus / 2 && n_tb * enc->G <= 0x7fffffff) {
+            batch.n_enc_wgs = E;
+            batch.enc = *enc;
+            batch.enc.n_tb = (int)n_tb;
+            batch.enc.n_wgs = E;
+            if (code16) gemm_nt_bf16_kernel<256, 256, 2, 4, true, true><<<total + E, 512, 0, s>>>(batch);
+            else gemm_nt_bf16_kernel<256, 256, 2, 4, false, true><<<total + E, 512, 0, s>>>(batch);
+            *enc_fused = true;
+            return launch_status();
+        }
+    }
     if (big && g_gemm_force_cfg == 2) {
         if (code16) gemm_nt_bf16_kernel<256, 256, 2, 2, true><<<total, 256, 0, s>>>(batch);
         else gemm_nt_bf16_kernel<256, 256, 2, 2, false><<<total, 256, 0, s>>>(batch);

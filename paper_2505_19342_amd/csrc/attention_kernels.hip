@@ -309,7 +309,9 @@ __global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams
     __syncthreads();
     if (par == 1) __syncthreads();
     for (int i = 0;; ++i) {
+        __builtin_amdgcn_s_setprio(2);      // the matrix-core phase goes first when both wavefronts of the SIMD can issue
         mm_phase(i);
+        __builtin_amdgcn_s_setprio(0);
         __syncthreads();
         if (i == n_it) break;
         softmax_phase(i);

@@ -115,6 +115,11 @@ int astra_mixed_attention(const astra_attn_desc* desc, const void* q,
 /* Scratch bytes astra_layer_forward needs for this shape (0 on an invalid descriptor). */
 size_t astra_layer_workspace_bytes(const astra_layer_desc* desc);
 
+/* 1 if astra_layer_forward runs the encode of the local rows inside its projection launch for this shape
+ * (Sec. 3.1: the encode and the projections are independent), 0 if as a kernel of its own, an
+ * ASTRA_ERR_* code (negative) on an invalid descriptor.  Host-only, touches no device. */
+int astra_layer_encode_fused(const astra_layer_desc* desc);
+
 /* One Astra attention layer on one device (Sec. 3.1): encode the local content rows (the indices
  * this device would transmit), rebuild the peers' tokens from their codes, project local rows to
  * Q, K, V and rebuilt rows to K-hat, V-hat with the same weights, attend (Eq. 1), apply W_o.

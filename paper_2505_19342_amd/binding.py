@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libastra_hip.so")
 _lib = None
 
 EXPORTS = ("astra_vq_prepare", "astra_vq_encode", "astra_vq_decode", "astra_mixed_attention",
-           "astra_layer_workspace_bytes", "astra_layer_forward", "astra_layer_forward_profiled",
+           "astra_layer_workspace_bytes", "astra_layer_encode_fused", "astra_layer_forward", "astra_layer_forward_profiled",
            "astra_status_string", "astra_version")
 
 
@@ -56,6 +56,8 @@ def load(build_if_missing: bool = True):
     lib.astra_mixed_attention.argtypes = [ctypes.POINTER(AttnDesc)] + [vp] * 8
     lib.astra_layer_workspace_bytes.argtypes = [ctypes.POINTER(LayerDesc)]
     lib.astra_layer_workspace_bytes.restype = ctypes.c_size_t
+    lib.astra_layer_encode_fused.argtypes = [ctypes.POINTER(LayerDesc)]
+    lib.astra_layer_encode_fused.restype = ctypes.c_int
     lib.astra_layer_forward.argtypes = [ctypes.POINTER(LayerDesc)] + [vp] * 15 + [ctypes.c_size_t, vp]
     lib.astra_layer_forward_profiled.argtypes = [ctypes.POINTER(LayerDesc)] + [vp] * 15 + [ctypes.c_size_t, vp,
                                                                                      ctypes.POINTER(ctypes.c_void_p)]
@@ -113,6 +115,13 @@ def astra_mixed_attention(desc: AttnDesc, q, k_local, v_local, k_hat, v_hat, out
 
 def astra_layer_workspace_bytes(desc: LayerDesc) -> int:
     return int(load().astra_layer_workspace_bytes(ctypes.byref(desc)))
+
+
+def astra_layer_encode_fused(desc: LayerDesc) -> bool:
+    rc = int(load().astra_layer_encode_fused(ctypes.byref(desc)))
+    if rc < 0:
+        _check(rc, "astra_layer_encode_fused")
+    return rc == 1
 
 
 def astra_layer_forward(desc: LayerDesc, x_local, codes_nonlocal, codebook, cnorm, wq, wk, wv, wo,

@@ -159,17 +159,28 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
                               const void* wq, const void* wk, const void* wv, const void* wo,
                               const void* bq, const void* bk, const void* bv, const void* bo,
                               void* y_out, void* codes_local_out, void* workspace, size_t workspace_bytes, void* stream,
-                              void* const* ev) {
+                              void* const* ev, int* plan_encode_fused = nullptr) {
+    // plan_encode_fused: validate the shapes and report whether the projection launch would carry the encode;
+    // nothing is launched and no pointer is dereferenced
+    const bool plan_only = plan_encode_fused != nullptr;
     LayerPlan pl;
     int rc = make_plan(desc, &pl);
     if (rc) return rc;
     const astra_vq_desc& vq = desc->vq;
     const astra_attn_desc& at = desc->attn;
+    if (plan_only) *plan_encode_fused = 0;
     if (pl.Tq == 0) return ASTRA_OK;
-    if (!x_local || !codebook || !cnorm || !wq || !wk || !wv || !wo || !y_out) return ASTRA_ERR_NULL;
-    if (at.n_local > 0 && !codes_local_out) return ASTRA_ERR_NULL;
-    if (pl.Tn_vis > 0 && !codes_nonlocal) return ASTRA_ERR_NULL;
-    if (!workspace || workspace_bytes < pl.total) return ASTRA_ERR_WORKSPACE;
+    if (!plan_only) {
+        if (!x_local || !codebook || !cnorm || !wq || !wk || !wv || !wo || !y_out) return ASTRA_ERR_NULL;
+        if (at.n_local > 0 && !codes_local_out) return ASTRA_ERR_NULL;
+        if (pl.Tn_vis > 0 && !codes_nonlocal) return ASTRA_ERR_NULL;
+        if (!workspace || workspace_bytes < pl.total) return ASTRA_ERR_WORKSPACE;
+    } else {
+        // shapes only: any non-null address marks the gathered operand
+        x_local = &pl;
+        codes_nonlocal = &pl;
+        workspace = &pl;
+    }
     hipStream_t s = (hipStream_t)stream;
     auto mark = [&](int i, hipStream_t on) { if (ev && ev[i]) (void)hipEventRecord((hipEvent_t)ev[i], on); };
     mark(0, s);
@@ -191,7 +202,7 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     bool enc_fused = false;
 
     // 2. projections: Q, K, V of local rows; K-hat, V-hat of the rows rebuilt from the peers' codes
-    if (pl.need_xhat && pl.Tn_vis > 0) {
+    if (pl.need_xhat && pl.Tn_vis > 0 && !plan_only) {
         rc = launch_vq_decode(vq, codes_nonlocal, pl.Tn_vis, codebook, Xh, s);
         if (rc) return rc;
     }
@@ -216,7 +227,11 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     nonlocal_(pr[3], wk, bk, Kh, pl.dkv);
     nonlocal_(pr[4], wv, bv, Vh, pl.dkv);
     if (pl.vt) { pr[4].c_mode = kCTransposedV; pr[4].ldc = pl.ldv_hat; }
-    rc = launch_gemm_batch(vq.dtype, pr, 5, s, offer ? &ej : nullptr, offer ? &enc_fused : nullptr);
+    rc = launch_gemm_batch(vq.dtype, pr, 5, s, offer ? &ej : nullptr, offer ? &enc_fused : nullptr, plan_only);
+    if (plan_only) {
+        *plan_encode_fused = enc_fused ? 1 : 0;
+        return rc;
+    }
     if (rc) return rc;
     mark(1, s);
     mark(5, s);
@@ -243,6 +258,13 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     mark(3, s);
     mark(4, s);
     return rc;
+}
+
+int astra_layer_encode_fused(const astra_layer_desc* desc) {
+    int fused = 0;
+    const int rc = layer_forward_impl(desc, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+                                      nullptr, nullptr, nullptr, nullptr, nullptr, 0, nullptr, nullptr, &fused);
+    return rc ? rc : fused;
 }
 
 int astra_layer_forward(const astra_layer_desc* desc, const void* x_local, const void* codes_nonlocal,

@@ -123,9 +123,9 @@ struct GemmProblem {
 constexpr int kMaxGemmProblems = 6;
 struct EncodeJob;
 // enc / enc_fused (both or neither): offers the VQ encode of the local rows to the launch; *enc_fused tells whether the
-// launch took it (extra workgroups) or the caller still has to run it.
+// launch took it (extra workgroups) or the caller still has to run it.  plan_only: decide and validate, launch nothing.
 int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hipStream_t s, const EncodeJob* enc = nullptr,
-                      bool* enc_fused = nullptr);
+                      bool* enc_fused = nullptr, bool plan_only = false);
 extern int g_gemm_force_cfg;
 extern const int g_gemm_problem_size;
 

@@ -450,7 +450,8 @@ static int fill_batch(GemmBatch& batch, int dtype, const GemmProblem* problems, 
     return ASTRA_OK;
 }
 
-int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hipStream_t s, const EncodeJob* enc, bool* enc_fused) {
+int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hipStream_t s, const EncodeJob* enc, bool* enc_fused,
+                      bool plan_only) {
     if (enc_fused) *enc_fused = false;
     if (n_problems > kMaxGemmProblems) return ASTRA_ERR_UNSUPPORTED;
     GemmBatch batch{};
@@ -458,7 +459,7 @@ int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hi
     if (dtype != ASTRA_BF16) {
         int rc = fill_batch(batch, dtype, problems, n_problems, kFM, kFN, &total);
         if (rc) return rc;
-        if (total == 0) return ASTRA_OK;
+        if (total == 0 || plan_only) return ASTRA_OK;
         gemm_nt_f32_kernel<<<total, 256, 0, s>>>(batch);
         return launch_status();
     }
@@ -480,12 +481,14 @@ int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hi
             batch.enc = *enc;
             batch.enc.n_tb = (int)n_tb;
             batch.enc.n_wgs = E;
+            *enc_fused = true;
+            if (plan_only) return ASTRA_OK;
             if (code16) gemm_nt_bf16_kernel<256, 256, 2, 4, true, true><<<total + E, 512, 0, s>>>(batch);
             else gemm_nt_bf16_kernel<256, 256, 2, 4, false, true><<<total + E, 512, 0, s>>>(batch);
-            *enc_fused = true;
             return launch_status();
         }
     }
+    if (plan_only) return ASTRA_OK;
     if (big && g_gemm_force_cfg == 2) {
         if (code16) gemm_nt_bf16_kernel<256, 256, 2, 2, true><<<total, 256, 0, s>>>(batch);
         else gemm_nt_bf16_kernel<256, 256, 2, 2, false><<<total, 256, 0, s>>>(batch);

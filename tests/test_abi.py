@@ -51,3 +51,25 @@ def test_host_side_argument_checks_need_no_gpu():
     assert lib.astra_vq_encode(ctypes.byref(good.vq), None, 5, None, None, None, None) == -1
     assert lib.astra_vq_encode(ctypes.byref(good.vq), None, 0, None, None, None, None) == 0
     assert lib.astra_vq_encode(ctypes.byref(good.vq), None, -1, None, None, None, None) == -2
+
+
+def test_encode_fusion_plan_is_host_only():
+    """astra_layer_encode_fused decides from the shapes alone: the projection launch carries the encode when
+    its 256x256 tiles leave compute units idle in the last round (Llama-3-8B shape, ranks with non-local
+    rows), never for the small shapes or fp32; an invalid descriptor is an error, not a crash."""
+    from paper_2505_19342_amd import workloads as wl
+
+    def desc(cfg, rank):
+        tn = (cfg.n_dev - 1) * cfg.n_local
+        return B.LayerDesc(B.vq_desc(cfg.dtype, cfg.d_model, cfg.n_groups, cfg.codebook_size),
+                           B.attn_desc(cfg.dtype, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n_cls, cfg.n_local, tn,
+                                       cfg.causal, rank * cfg.n_local))
+
+    llama = wl.CONFIGS["llama3_8b_bf16"]
+    assert [B.astra_layer_encode_fused(desc(llama, r)) for r in range(llama.n_dev)] == [False, True, True, True]
+    for name in ("tiny_vit_f32", "vit_base_bf16", "gpt2_small_bf16"):
+        cfg = wl.CONFIGS[name]
+        assert not B.astra_layer_encode_fused(desc(cfg, cfg.n_dev - 1))
+    bad = desc(llama, 3)
+    bad.vq.n_groups = 7          # 4096 is not a multiple of 7
+    assert B.load().astra_layer_encode_fused(ctypes.byref(bad)) < 0

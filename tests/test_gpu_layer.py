@@ -94,6 +94,65 @@ def test_llama3_8b_shape_full_size(rank):
     run_case(wl.LLAMA3_8B, rank)
 
 
+def test_llama_dims_ragged_rows_take_the_fused_encode_path():
+    """Llama-3-8B widths with row counts that are multiples of nothing: 1000 of 3917 tokens on this device (the last
+    chunk), so the last tile of every projection and the last token block of the encode are ragged, and the tile
+    count still makes the projection launch carry the encode (the configuration bench.py times)."""
+    from gpu_util import LayerOnGpu, compare_codes
+    from paper_2505_19342_amd import binding as B
+    cfg = dataclasses.replace(wl.LLAMA3_8B, name="llama_ragged", seq_len=3917, seed=41)
+    data = wl.generate(cfg)
+    lo = 2917
+    x_local, x_nl = data["x"][lo:], data["x"][:lo]
+    codes_nl = oracle.vq_encode(x_nl, data["codebook"])
+    y_ref, codes_ref, gap = oracle.layer_forward(x_local, codes_nl, data["codebook"], data["wq"], data["wk"], data["wv"],
+                                                 data["wo"], n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, causal=True,
+                                                 n_before=lo, return_gap=True)
+    layer = LayerOnGpu(cfg, data, x_local, codes_nl, lo)
+    assert B.astra_layer_encode_fused(layer.desc)
+    layer.run()
+    y, codes = layer.results()
+    n_tie = compare_codes(codes, codes_ref, gap, NEAR_TIE)
+    err = np.abs(y - y_ref).max()
+    print(f"llama dims, 1000 local / 2917 non-local rows: max abs err {err:.3e}, near-tie codes {n_tie}/{codes.size}")
+    assert err <= Y_TOL["bf16"]
+    assert n_tie <= max(2, codes.size // 2000)
+
+
+def test_fused_encode_equals_the_standalone_encode_and_calls_repeat_bit_exactly():
+    """The encode inside the projection launch and astra_vq_encode run the same arithmetic in the same order: equal codes,
+    bit for bit.  Two calls of the layer, and the call with stage events, give identical bits too."""
+    import torch
+    from gpu_util import LayerOnGpu, empty_codes
+    from paper_2505_19342_amd import binding as B
+    cfg = wl.LLAMA3_8B
+    data = wl.generate(cfg)
+    view = wl.device_view(cfg, data, 2)
+    codes_nl = oracle.vq_encode(view["x_nonlocal"], data["codebook"])
+    layer = LayerOnGpu(cfg, data, view["x_local"], codes_nl, view["n_before"])
+    assert B.astra_layer_encode_fused(layer.desc)
+    layer.run()
+    torch.cuda.synchronize()
+    y1, c1 = layer.y.clone(), layer.codes_local.clone()
+    alone = empty_codes(cfg.n_local, cfg.n_groups, cfg.codebook_size)
+    B.astra_vq_encode(layer.desc.vq, layer.x_local, cfg.n_local, layer.codebook, layer.cnorm, alone)
+    torch.cuda.synchronize()
+    assert torch.equal(alone, c1)
+    layer.y.zero_()
+    layer.codes_local.zero_()
+    layer.run()
+    torch.cuda.synchronize()
+    assert torch.equal(layer.y, y1) and torch.equal(layer.codes_local, c1)
+    layer.y.zero_()
+    layer.codes_local.zero_()
+    ev = B.HipEvents(7)
+    B.astra_layer_forward_profiled(layer.desc, layer.x_local, layer.codes_nonlocal, layer.codebook, layer.cnorm, *layer.w,
+                                   *layer.b, layer.y, layer.codes_local, layer.workspace, ev.handles)
+    torch.cuda.synchronize()
+    assert torch.equal(layer.y, y1) and torch.equal(layer.codes_local, c1)
+    assert ev.elapsed_ms(0, 4) > 0
+
+
 def test_workspace_too_small_is_an_error():
     import torch
     from gpu_util import DEV, LayerOnGpu

@@ -18,11 +18,12 @@ namespace astra {
 //
 // A workgroup of 8 wavefronts owns 128 query rows of one head.  Wavefront w owns the 32 rows of query
 // group w & 3 and walks only the key/value tiles of parity w >> 2; the two wavefronts that share a query
-// group merge their (max, sum, O) triples through LDS at the end.  With two wavefronts per SIMD, one can
-// run its softmax on the vector ALU while the other occupies the matrix core, and a wavefront's whole
-// state (O^T 64, S^T 32, Q 32, P 16 registers) stays in ordinary vector registers.  Tiles of 64 keys are
-// double-buffered in LDS with XOR-swizzled 16-byte pieces and arrive by direct global->LDS transfers
-// issued one pair of tiles ahead.
+// group merge their (max, sum, O) triples through LDS at the end.  The two wavefronts of a SIMD have
+// different parities and are kept in opposite phases (see the schedule below): one runs its softmax on
+// the vector ALU while the other occupies the matrix core.  A wavefront's whole state (O^T 64, S^T 32,
+// Q 32, P 16 registers) stays in ordinary vector registers.  Tiles of 64 keys are double-buffered in LDS
+// with XOR-swizzled 16-byte pieces and arrive by direct global->LDS transfers, issued one iteration ahead
+// by the four wavefronts that will read them.
 //
 // V is consumed as V^T.  With VT = true it arrives already transposed ([H_kv*dh, T_pad], tokens permuted
 // inside blocks of 16 as the projection kernel writes them) and fragments are plain 16-byte LDS reads;

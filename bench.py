@@ -47,14 +47,18 @@ def layer_flops(cfg, n_before):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=200,
+                    help="untimed calls before the timed region; the chip needs some tens of milliseconds of load to reach its "
+                         "steady clock after the host-side set-up, during which it sat idle")
     ap.add_argument("--workload", default="llama3_8b_bf16")
     ap.add_argument("--rank", type=int, default=-1, help="simulated device (default: last = critical path under causal masking)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-every", type=int, default=8,
                     help="every N-th timed step is launched through astra_layer_forward_profiled (HIP events at the stage "
                          "boundaries, about 20 us of extra gaps per such step); the others through astra_layer_forward")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the measurements outside the timed region (matrix-core probe, stand-alone decode, other ranks)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the warm-up, run one plain elementwise copy kernel reading and writing this many MiB "
                          "(fp32): the reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -188,6 +192,61 @@ def main():
                      "traffic": TRAFFIC_BYTES.get(cfg.name) if rank == cfg.n_dev - 1 else None,
                      "flops_per_launch": dom_flops, "us_per_launch": stage_ms[dom] * 1e3},
     }
+
+    # percentiles of the GPU time of one call over the steps that carry events (events 0..4)
+    per_step = sorted(ev.elapsed_ms(0, 4) for ev in events)
+    result["gpu_ms_per_step_events_p10_p50_p90"] = [per_step[int(q * (len(per_step) - 1))] for q in (0.1, 0.5, 0.9)]
+
+    if not args.no_extras:
+        def timed(fn, n, warm=0):
+            for _ in range(1 + warm):      # after host-side set-up the chip is idle: bring it back to its steady clock
+                fn()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(n):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / n          # ms
+
+        # (1) the other simulated devices (under causal masking they see fewer non-local rows)
+        if cfg.causal and args.rank < 0:
+            per_rank = {}
+            for r in range(cfg.n_dev):
+                vr = wl.device_view(cfg, data, r)
+                xr = to_dev(vr["x_local"])
+                dr = B.LayerDesc(vq, B.attn_desc(dt, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n_cls, xr.shape[0] - cfg.n_cls,
+                                                 tn, cfg.causal, vr["n_before"]))
+                # the peers' codes in this rank's order: encode its non-local rows with the library
+                xn = to_dev(vr["x_nonlocal"])
+                cn = torch.empty((tn, G), dtype=code_t, device=dev)
+                B.astra_vq_encode(vq, xn, tn, codebook, cnorm, cn)
+                a_r = (dr, xr, cn, codebook, cnorm, *w, None, None, None, None, y, codes_local, ws)
+                per_rank[r] = timed(lambda: B.astra_layer_forward(*a_r), 100, warm=100)
+                del xr, xn, cn
+            result["per_rank_ms"] = per_rank
+            result["rank_mean_tokens_per_s"] = tq / (sum(per_rank.values()) / len(per_rank) * 1e-3)
+        # (2) the decode as a kernel of its own (inside the layer it is fused into the projection's operand load):
+        #     the HBM-bound step; algorithmic bytes = codes + codebook + rebuilt rows
+        t_v = view["n_before"] if cfg.causal else tn
+        if t_v > 0:
+            x_hat = torch.empty((t_v, D), dtype=x_local.dtype, device=dev)
+            ms = timed(lambda: B.astra_vq_decode(vq, codes_nl, t_v, codebook, x_hat), 200, warm=50)
+            eb = 2 if dt == "bf16" else 4
+            nbytes = t_v * G * codes_nl.element_size() + G * K * cfg.group_dim * eb + t_v * D * eb
+            result["decode_standalone"] = {"us": ms * 1e3, "algorithmic_bytes": nbytes, "GBps": nbytes / (ms * 1e-3) / 1e9,
+                                           "frac_of_hbm_8TBps": nbytes / (ms * 1e-3) / 8e12, "rows": t_v}
+            del x_hat
+        # (3) last, because it heats the chip: what the matrix cores of this machine deliver with nothing else in the loop, next to the published peak
+        if dt == "bf16":
+            n_blocks, iters = 1024, 2000
+            probe_out = torch.empty(n_blocks * 512, dtype=torch.float32, device=dev)
+            ms = timed(lambda: B.astra_probe_mfma_bf16(probe_out, n_blocks, iters), 5, warm=3)
+            tf = n_blocks * 8 * iters * 4 * 32768.0 / (ms * 1e-3) / 1e12
+            result["mfma_probe"] = {"tflops": tf, "frac_of_published_peak": tf / peak,
+                                    "dominant_kernel_frac_of_probe": achieved / tf,
+                                    "what": "astra_probe_mfma_bf16: 32x32x16 bf16 MFMAs on register operands only"}
+            del probe_out
 
     if not args.no_cpu_baseline:
         import oracle

@@ -156,6 +156,12 @@ int astra_layer_forward_profiled(const astra_layer_desc* desc, const void* x_loc
                                  void* workspace, size_t workspace_bytes, void* stream,
                                  void* const* stage_events);
 
+/* Measurement probe, not part of the method: n_blocks workgroups of 512 threads each run `iters` rounds of
+ * four independent 32x32x16 bf16 MFMAs per wavefront on register operands (no memory traffic in the loop)
+ * and store one float per thread to out [n_blocks * 512] (device).  Work = n_blocks * 8 * iters * 4 * 32768
+ * flop: the on-box matrix-core rate a benchmark can quote beside the published peak. */
+int astra_probe_mfma_bf16(float* out, int n_blocks, int iters, void* stream);
+
 const char* astra_status_string(int status);
 int astra_version(void);
 

@@ -15,7 +15,7 @@ _lib = None
 
 EXPORTS = ("astra_vq_prepare", "astra_vq_encode", "astra_vq_decode", "astra_mixed_attention",
            "astra_layer_workspace_bytes", "astra_layer_encode_fused", "astra_layer_forward", "astra_layer_forward_profiled",
-           "astra_status_string", "astra_version")
+           "astra_probe_mfma_bf16", "astra_status_string", "astra_version")
 
 
 class AstraError(RuntimeError):
@@ -56,6 +56,8 @@ def load(build_if_missing: bool = True):
     lib.astra_mixed_attention.argtypes = [ctypes.POINTER(AttnDesc)] + [vp] * 8
     lib.astra_layer_workspace_bytes.argtypes = [ctypes.POINTER(LayerDesc)]
     lib.astra_layer_workspace_bytes.restype = ctypes.c_size_t
+    lib.astra_probe_mfma_bf16.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    lib.astra_probe_mfma_bf16.restype = ctypes.c_int
     lib.astra_layer_encode_fused.argtypes = [ctypes.POINTER(LayerDesc)]
     lib.astra_layer_encode_fused.restype = ctypes.c_int
     lib.astra_layer_forward.argtypes = [ctypes.POINTER(LayerDesc)] + [vp] * 15 + [ctypes.c_size_t, vp]
@@ -115,6 +117,11 @@ def astra_mixed_attention(desc: AttnDesc, q, k_local, v_local, k_hat, v_hat, out
 
 def astra_layer_workspace_bytes(desc: LayerDesc) -> int:
     return int(load().astra_layer_workspace_bytes(ctypes.byref(desc)))
+
+
+def astra_probe_mfma_bf16(out, n_blocks: int, iters: int):
+    """out: float32 device tensor with at least n_blocks * 512 elements."""
+    _check(load().astra_probe_mfma_bf16(_ptr(out), n_blocks, iters, _stream()), "astra_probe_mfma_bf16")
 
 
 def astra_layer_encode_fused(desc: LayerDesc) -> bool:

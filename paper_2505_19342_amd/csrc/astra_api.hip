@@ -260,6 +260,11 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     return rc;
 }
 
+int astra_probe_mfma_bf16(float* out, int n_blocks, int iters, void* stream) {
+    if (!out) return ASTRA_ERR_NULL;
+    return launch_mfma_probe(out, n_blocks, iters, (hipStream_t)stream);
+}
+
 int astra_layer_encode_fused(const astra_layer_desc* desc) {
     int fused = 0;
     const int rc = layer_forward_impl(desc, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,

@@ -145,5 +145,6 @@ struct AttnParams {
     float scale;          // logit scale
 };
 int launch_attention(int dtype, const AttnParams& p, int head_dim, hipStream_t s);
+int launch_mfma_probe(float* out, int n_blocks, int iters, hipStream_t s);
 
 }  // namespace astra

@@ -28,7 +28,7 @@ _lib = None
 
 def build(force: bool = True) -> str:
     """Compile the C oracle with gcc (OpenMP over rows only)."""
-    if force or not os.path.exists(_LIB):
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O3", "-fopenmp", "-fPIC", "-shared", "-std=c11",
                "-fno-fast-math", "-ffp-contract=off", _SRC, "-o", _LIB, "-lm"]
         subprocess.run(cmd, check=True)
@@ -42,7 +42,8 @@ def _load():
         lib = ctypes.CDLL(_LIB)
         lib.oracle_num_threads.restype = ctypes.c_int
         for name in ("oracle_vq_encode", "oracle_vq_decode", "oracle_linear",
-                     "oracle_mixed_attention", "oracle_layer_forward"):
+                     "oracle_mixed_attention", "oracle_mixed_attention_valid",
+                     "oracle_layer_forward", "oracle_layer_forward_valid"):
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -115,11 +116,17 @@ def linear(x, w, bias=None):
     return out
 
 
+def _u8(a):
+    return None if a is None else np.ascontiguousarray(np.asarray(a) != 0, dtype=np.uint8)
+
+
 def mixed_attention(q, k_loc, v_loc, k_hat, v_hat, *, n_cls=0, causal=False, n_before=0,
-                    scale=0.0, return_lse=False, return_probs=False):
+                    scale=0.0, return_lse=False, return_probs=False, valid_hat=None):
     """Eq. 1 for one device.  q [T_q, H_q, dh]; k_loc/v_loc [T_q, H_kv, dh];
     k_hat/v_hat [T_n, H_kv, dh].  Returns out [T_q, H_q, dh] fp64
-    (+ lse [H_q, T_q], + probs [H_q, T_q, T_q+T_n] when asked)."""
+    (+ lse [H_q, T_q], + probs [H_q, T_q, T_q+T_n] when asked).
+    valid_hat (optional, [T_n] of 0/1): non-local tokens whose codes never arrived (0) are dropped
+    from the key/value set (Sec. 4.5, packet loss without retransmission)."""
     q, k_loc, v_loc, k_hat, v_hat = map(_f64, (q, k_loc, v_loc, k_hat, v_hat))
     Tq, Hq, dh = q.shape
     Hkv = k_loc.shape[1]
@@ -129,8 +136,10 @@ def mixed_attention(q, k_loc, v_loc, k_hat, v_hat, *, n_cls=0, causal=False, n_b
     out = np.empty((Tq, Hq, dh), dtype=np.float64)
     lse = np.empty((Hq, Tq), dtype=np.float64) if return_lse else None
     probs = np.empty((Hq, Tq, Tq + Tn), dtype=np.float64) if return_probs else None
-    rc = _load().oracle_mixed_attention(
-        _p(q), _p(k_loc), _p(v_loc), _p(k_hat), _p(v_hat), Hq, Hkv, dh,
+    valid_hat = _u8(valid_hat)
+    assert valid_hat is None or valid_hat.shape == (Tn,)
+    rc = _load().oracle_mixed_attention_valid(
+        _p(q), _p(k_loc), _p(v_loc), _p(k_hat), _p(v_hat), _p(valid_hat), Hq, Hkv, dh,
         int(n_cls), Tq - int(n_cls), Tn, int(bool(causal)), int(n_before),
         ctypes.c_double(scale), _p(out), _p(lse), _p(probs))
     if rc:
@@ -145,10 +154,11 @@ def mixed_attention(q, k_loc, v_loc, k_hat, v_hat, *, n_cls=0, causal=False, n_b
 
 def layer_forward(x_local, codes_nonlocal, codebook, wq, wk, wv, wo, *, n_q_heads, n_kv_heads,
                   n_cls=0, causal=False, n_before=0, scale=0.0,
-                  bq=None, bk=None, bv=None, bo=None, return_gap=False):
+                  bq=None, bk=None, bv=None, bo=None, return_gap=False, valid_nonlocal=None):
     """One device's layer (Sec. 3.1).  Weights in the paper's orientation
     ``[D_in, D_out]``.  Returns (y [T_q, D] fp64, codes_local [T_l, G] int32
-    [, gap [T_l, G]])."""
+    [, gap [T_l, G]]).  valid_nonlocal (optional, [T_n] of 0/1): rows whose codes never
+    arrived (0) are neither looked up nor attended to."""
     x_local = _f32(x_local)
     codebook = _f32(codebook)
     codes_nonlocal = _i32(codes_nonlocal)
@@ -165,8 +175,10 @@ def layer_forward(x_local, codes_nonlocal, codebook, wq, wk, wv, wo, *, n_q_head
     y = np.empty((Tq, D), dtype=np.float64)
     codes_local = np.empty((n_local, G), dtype=np.int32)
     gap = np.empty((n_local, G), dtype=np.float64) if return_gap else None
-    rc = _load().oracle_layer_forward(
-        _p(x_local), _p(codes_nonlocal), _p(codebook), D, G, K,
+    valid_nonlocal = _u8(valid_nonlocal)
+    assert valid_nonlocal is None or valid_nonlocal.shape == (Tn,)
+    rc = _load().oracle_layer_forward_valid(
+        _p(x_local), _p(codes_nonlocal), _p(valid_nonlocal), _p(codebook), D, G, K,
         _p(wq), _p(wk), _p(wv), _p(wo), _p(bq), _p(bk), _p(bv), _p(bo),
         n_q_heads, n_kv_heads, dh, int(n_cls), n_local, Tn,
         int(bool(causal)), int(n_before), ctypes.c_double(scale),

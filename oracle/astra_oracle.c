@@ -31,7 +31,10 @@
  *   - multi-head: Eq. 1 per head with d_k = head_dim; grouped-query attention
  *     shares KV head h / (H_q / H_kv) among consecutive query heads;
  *   - a class-token replica is an ordinary full-precision local row placed
- *     first; it is not encoded.
+ *     first; it is not encoded;
+ *   - (Sec. 4.5 "Non-Ideal Network Conditions", App. E: packet loss without retransmission; the paper does not
+ *     say what the receiver does) a non-local token whose codes never arrived is
+ *     dropped from the key/value set of every local query: the *_valid variants.
  *
  * Parity pins live in tests/ (brute force, closed forms, library routines,
  * invariants).  The numerical outputs of the authors' trained models are
@@ -139,12 +142,12 @@ int oracle_linear(const double* x, int64_t T, int d_in, int d_out,
  *                                            excluded pairs hold 0
  * Allowed keys of local row i: not causal -> every local and non-local row;
  * causal -> local rows j <= i and non-local rows t < n_before. */
-int oracle_mixed_attention(const double* q, const double* k_loc, const double* v_loc,
-                           const double* k_hat, const double* v_hat,
-                           int n_q_heads, int n_kv_heads, int head_dim,
-                           int n_cls, int n_local, int n_nonlocal,
-                           int causal, int n_before, double scale,
-                           double* out, double* lse, double* probs) {
+int oracle_mixed_attention_valid(const double* q, const double* k_loc, const double* v_loc,
+                                 const double* k_hat, const double* v_hat, const uint8_t* valid_hat,
+                                 int n_q_heads, int n_kv_heads, int head_dim,
+                                 int n_cls, int n_local, int n_nonlocal,
+                                 int causal, int n_before, double scale,
+                                 double* out, double* lse, double* probs) {
     if (n_q_heads <= 0 || n_kv_heads <= 0 || n_q_heads % n_kv_heads != 0 || head_dim <= 0) return -1;
     if (n_cls < 0 || n_local < 0 || n_nonlocal < 0) return -1;
     if (causal && (n_cls != 0 || n_before < 0 || n_before > n_nonlocal)) return -1;
@@ -167,6 +170,7 @@ int oracle_mixed_attention(const double* q, const double* k_loc, const double* v
                 const int is_local = j < Tq;
                 const int jj = is_local ? j : j - Tq;
                 allowed[j] = !causal ? 1 : (is_local ? (jj <= i) : (jj < n_before));
+                if (!is_local && valid_hat && !valid_hat[jj]) allowed[j] = 0;      /* code never arrived: the key is dropped */
                 if (!allowed[j]) continue;
                 const double* kj = (is_local ? k_loc : k_hat) + ((int64_t)jj * n_kv_heads + hk) * head_dim;
                 double dot = 0.0;
@@ -196,6 +200,17 @@ int oracle_mixed_attention(const double* q, const double* k_loc, const double* v
     return 0;
 }
 
+/* Eq. 1 with every non-local code present. */
+int oracle_mixed_attention(const double* q, const double* k_loc, const double* v_loc,
+                           const double* k_hat, const double* v_hat,
+                           int n_q_heads, int n_kv_heads, int head_dim,
+                           int n_cls, int n_local, int n_nonlocal,
+                           int causal, int n_before, double scale,
+                           double* out, double* lse, double* probs) {
+    return oracle_mixed_attention_valid(q, k_loc, v_loc, k_hat, v_hat, NULL, n_q_heads, n_kv_heads, head_dim,
+                                        n_cls, n_local, n_nonlocal, causal, n_before, scale, out, lse, probs);
+}
+
 /* One Astra attention layer on one device (Sec. 3.1):
  *   codes_local = encode(content rows of x_local)        -> what this device transmits
  *   X-hat       = decode(codes_nonlocal)                  -> what it rebuilds from its peers
@@ -204,8 +219,8 @@ int oracle_mixed_attention(const double* q, const double* k_loc, const double* v
  *   Y           = Attn(Q, K, K-hat, V, V-hat) W_o
  * x_local [T_q, D] with the class row (if any) first; weights [D_in, D_out];
  * biases nullable.  y [T_q, D] double, codes_local [n_local, G], gap nullable. */
-int oracle_layer_forward(const float* x_local, const int32_t* codes_nonlocal,
-                         const float* codebook, int D, int G, int K,
+int oracle_layer_forward_valid(const float* x_local, const int32_t* codes_nonlocal, const uint8_t* valid_nonlocal,
+                               const float* codebook, int D, int G, int K,
                          const float* wq, const float* wk, const float* wv, const float* wo,
                          const float* bq, const float* bk, const float* bv, const float* bo,
                          int n_q_heads, int n_kv_heads, int head_dim,
@@ -219,7 +234,16 @@ int oracle_layer_forward(const float* x_local, const int32_t* codes_nonlocal,
     if (rc) return rc;
 
     float* x_hat = (float*)malloc(sizeof(float) * ((int64_t)Tn * D + 1));
-    rc = oracle_vq_decode(codes_nonlocal, Tn, D, G, K, codebook, x_hat);
+    if (!valid_nonlocal) {
+        rc = oracle_vq_decode(codes_nonlocal, Tn, D, G, K, codebook, x_hat);
+    } else {
+        /* a row whose codes never arrived is not looked up (whatever sits in its slot is ignored); it is left
+         * zero and excluded from the attention below */
+        for (int64_t t = 0; t < Tn && !rc; ++t) {
+            if (valid_nonlocal[t]) rc = oracle_vq_decode(codes_nonlocal + t * G, 1, D, G, K, codebook, x_hat + t * (int64_t)D);
+            else memset(x_hat + t * (int64_t)D, 0, sizeof(float) * D);
+        }
+    }
     if (rc) { free(x_hat); return rc; }
 
     double* xl = (double*)malloc(sizeof(double) * ((int64_t)Tq * D + 1));
@@ -237,10 +261,24 @@ int oracle_layer_forward(const float* x_local, const int32_t* codes_nonlocal,
     oracle_linear(xl, Tq, D, dkv, wv, bv, Vl);
     oracle_linear(xh, Tn, D, dkv, wk, bk, Kh);
     oracle_linear(xh, Tn, D, dkv, wv, bv, Vh);
-    rc = oracle_mixed_attention(Q, Kl, Vl, Kh, Vh, n_q_heads, n_kv_heads, head_dim,
-                                n_cls, n_local, n_nonlocal, causal, n_before, scale,
-                                O, NULL, NULL);
+    rc = oracle_mixed_attention_valid(Q, Kl, Vl, Kh, Vh, valid_nonlocal, n_q_heads, n_kv_heads, head_dim,
+                                      n_cls, n_local, n_nonlocal, causal, n_before, scale,
+                                      O, NULL, NULL);
     if (!rc) oracle_linear(O, Tq, dq, D, wo, bo, y);
     free(x_hat); free(xl); free(xh); free(Q); free(Kl); free(Vl); free(Kh); free(Vh); free(O);
     return rc;
+}
+
+/* The layer with every non-local code present. */
+int oracle_layer_forward(const float* x_local, const int32_t* codes_nonlocal,
+                         const float* codebook, int D, int G, int K,
+                         const float* wq, const float* wk, const float* wv, const float* wo,
+                         const float* bq, const float* bk, const float* bv, const float* bo,
+                         int n_q_heads, int n_kv_heads, int head_dim,
+                         int n_cls, int n_local, int n_nonlocal,
+                         int causal, int n_before, double scale,
+                         double* y, int32_t* codes_local, double* gap_local) {
+    return oracle_layer_forward_valid(x_local, codes_nonlocal, NULL, codebook, D, G, K, wq, wk, wv, wo, bq, bk, bv, bo,
+                                      n_q_heads, n_kv_heads, head_dim, n_cls, n_local, n_nonlocal, causal, n_before,
+                                      scale, y, codes_local, gap_local);
 }

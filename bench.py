@@ -226,6 +226,13 @@ def main():
                 del xr, xn, cn
             result["per_rank_ms"] = per_rank
             result["rank_mean_tokens_per_s"] = tq / (sum(per_rank.values()) / len(per_rank) * 1e-3)
+        # the layer with 5 % of the peers' tokens lost (Sec. 4.5, packet loss without retransmission): same launches,
+        # the attention additionally masks the lost keys of every non-local tile
+        if tn > 0:
+            lost_rng = np.random.default_rng(cfg.seed + 500)
+            bits = torch.from_numpy(B.pack_valid_bits(lost_rng.random(tn) >= 0.05).view(np.int64).copy()).to(dev)
+            a_v = (desc, x_local, codes_nl, bits, codebook, cnorm, *w, None, None, None, None, y, codes_local, ws)
+            result["lost_codes_5pct_ms"] = timed(lambda: B.astra_layer_forward_valid(*a_v), 100, warm=50)
         # (2) the decode as a kernel of its own (inside the layer it is fused into the projection's operand load):
         #     the HBM-bound step; algorithmic bytes = codes + codebook + rebuilt rows
         t_v = view["n_before"] if cfg.causal else tn

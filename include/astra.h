@@ -112,6 +112,17 @@ int astra_mixed_attention(const astra_attn_desc* desc, const void* q,
                           const void* k_hat, const void* v_hat,
                           void* out, float* lse_out, void* stream);
 
+/* astra_mixed_attention when some non-local tokens' codes never arrived (Sec. 4.5 "Non-Ideal Network
+ * Conditions", App. E: packet loss without retransmission; the paper does not say what the receiver does,
+ * the reading here: such a token is dropped from the key/value set of every local query).
+ * valid_bits: device pointer, ceil(T_n / 64) 64-bit words, bit (t % 64) of word t / 64 set iff the codes
+ * of non-local token t arrived (bits at and beyond T_n are ignored); NULL = all arrived, then identical to
+ * astra_mixed_attention.  The k_hat / v_hat rows of a lost token may hold anything finite. */
+int astra_mixed_attention_valid(const astra_attn_desc* desc, const void* q,
+                                const void* k_local, const void* v_local,
+                                const void* k_hat, const void* v_hat, const uint64_t* valid_bits,
+                                void* out, float* lse_out, void* stream);
+
 /* Scratch bytes astra_layer_forward needs for this shape (0 on an invalid descriptor). */
 size_t astra_layer_workspace_bytes(const astra_layer_desc* desc);
 
@@ -139,6 +150,17 @@ int astra_layer_forward(const astra_layer_desc* desc, const void* x_local, const
                         const void* bq, const void* bk, const void* bv, const void* bo,
                         void* y_out, void* codes_local_out,
                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* astra_layer_forward with lost non-local tokens: valid_nonlocal_bits as valid_bits of
+ * astra_mixed_attention_valid, NULL = all arrived.  The codes_nonlocal row of a lost token may hold any
+ * value of the code type (it is read as min(code, K-1) and its projections are ignored). */
+int astra_layer_forward_valid(const astra_layer_desc* desc, const void* x_local, const void* codes_nonlocal,
+                              const uint64_t* valid_nonlocal_bits,
+                              const void* codebook, const float* cnorm,
+                              const void* wq, const void* wk, const void* wv, const void* wo,
+                              const void* bq, const void* bk, const void* bv, const void* bo,
+                              void* y_out, void* codes_local_out,
+                              void* workspace, size_t workspace_bytes, void* stream);
 
 /* astra_layer_forward with stage timing for benchmarks: identical work and results, and in addition
  * seven hipEvent_t (created by the caller with timing enabled, passed as void*; a NULL entry is skipped)

@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libastra_hip.so")
 _lib = None
 
 EXPORTS = ("astra_vq_prepare", "astra_vq_encode", "astra_vq_decode", "astra_mixed_attention",
+           "astra_mixed_attention_valid", "astra_layer_forward_valid",
            "astra_layer_workspace_bytes", "astra_layer_encode_fused", "astra_layer_forward", "astra_layer_forward_profiled",
            "astra_probe_mfma_bf16", "astra_status_string", "astra_version")
 
@@ -54,6 +55,8 @@ def load(build_if_missing: bool = True):
     lib.astra_vq_encode.argtypes = [ctypes.POINTER(VqDesc), vp, i64, vp, f32p, vp, vp]
     lib.astra_vq_decode.argtypes = [ctypes.POINTER(VqDesc), vp, i64, vp, vp, vp]
     lib.astra_mixed_attention.argtypes = [ctypes.POINTER(AttnDesc)] + [vp] * 8
+    lib.astra_mixed_attention_valid.argtypes = [ctypes.POINTER(AttnDesc)] + [vp] * 9
+    lib.astra_layer_forward_valid.argtypes = [ctypes.POINTER(LayerDesc)] + [vp] * 16 + [ctypes.c_size_t, vp]
     lib.astra_layer_workspace_bytes.argtypes = [ctypes.POINTER(LayerDesc)]
     lib.astra_layer_workspace_bytes.restype = ctypes.c_size_t
     lib.astra_probe_mfma_bf16.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
@@ -113,6 +116,31 @@ def astra_vq_decode(desc: VqDesc, codes, n_tokens: int, codebook, x_hat_out):
 def astra_mixed_attention(desc: AttnDesc, q, k_local, v_local, k_hat, v_hat, out, lse_out=None):
     _check(load().astra_mixed_attention(ctypes.byref(desc), _ptr(q), _ptr(k_local), _ptr(v_local), _ptr(k_hat), _ptr(v_hat),
                                         _ptr(out), _ptr(lse_out), _stream()), "astra_mixed_attention")
+
+
+def astra_mixed_attention_valid(desc: AttnDesc, q, k_local, v_local, k_hat, v_hat, valid_bits, out, lse_out=None):
+    """valid_bits: int64 device tensor of ceil(T_n / 64) words (see pack_valid_bits) or None."""
+    _check(load().astra_mixed_attention_valid(ctypes.byref(desc), _ptr(q), _ptr(k_local), _ptr(v_local), _ptr(k_hat), _ptr(v_hat),
+                                              _ptr(valid_bits), _ptr(out), _ptr(lse_out), _stream()), "astra_mixed_attention_valid")
+
+
+def astra_layer_forward_valid(desc: LayerDesc, x_local, codes_nonlocal, valid_bits, codebook, cnorm, wq, wk, wv, wo,
+                              bq, bk, bv, bo, y_out, codes_local_out, workspace):
+    nbytes = workspace.numel() * workspace.element_size()
+    _check(load().astra_layer_forward_valid(ctypes.byref(desc), _ptr(x_local), _ptr(codes_nonlocal), _ptr(valid_bits),
+                                            _ptr(codebook), _ptr(cnorm), _ptr(wq), _ptr(wk), _ptr(wv), _ptr(wo),
+                                            _ptr(bq), _ptr(bk), _ptr(bv), _ptr(bo), _ptr(y_out), _ptr(codes_local_out),
+                                            _ptr(workspace), nbytes, _stream()), "astra_layer_forward_valid")
+
+
+def pack_valid_bits(valid):
+    """Host helper: a 0/1 array [T_n] -> numpy uint64 words, bit (t % 64) of word t / 64 = valid[t]."""
+    import numpy as np
+    v = np.asarray(valid) != 0
+    n_words = (v.size + 63) // 64
+    padded = np.zeros(n_words * 64, dtype=np.uint8)
+    padded[:v.size] = v
+    return np.packbits(padded, bitorder="little").view(np.uint64)
 
 
 def astra_layer_workspace_bytes(desc: LayerDesc) -> int:

@@ -138,13 +138,20 @@ int astra_vq_decode(const astra_vq_desc* desc, const void* codes, int64_t n_toke
 
 int astra_mixed_attention(const astra_attn_desc* desc, const void* q, const void* k_local, const void* v_local,
                           const void* k_hat, const void* v_hat, void* out, float* lse_out, void* stream) {
+    return astra_mixed_attention_valid(desc, q, k_local, v_local, k_hat, v_hat, nullptr, out, lse_out, stream);
+}
+
+int astra_mixed_attention_valid(const astra_attn_desc* desc, const void* q, const void* k_local, const void* v_local,
+                                const void* k_hat, const void* v_hat, const uint64_t* valid_bits, void* out, float* lse_out,
+                                void* stream) {
     int rc = check_attn_desc(desc);
     if (rc) return rc;
     if (desc->n_cls + desc->n_local == 0) return ASTRA_OK;
     if (!q || !k_local || !v_local || !out) return ASTRA_ERR_NULL;
     const int vis = desc->causal ? desc->n_nonlocal_before : desc->n_nonlocal;
     if (vis > 0 && (!k_hat || !v_hat)) return ASTRA_ERR_NULL;
-    const AttnParams ap = attn_params(*desc, q, k_local, v_local, k_hat, v_hat, out, lse_out);
+    AttnParams ap = attn_params(*desc, q, k_local, v_local, k_hat, v_hat, out, lse_out);
+    ap.valid_bits = (const unsigned long long*)valid_bits;
     return launch_attention(desc->dtype, ap, desc->head_dim, (hipStream_t)stream);
 }
 
@@ -159,7 +166,7 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
                               const void* wq, const void* wk, const void* wv, const void* wo,
                               const void* bq, const void* bk, const void* bv, const void* bo,
                               void* y_out, void* codes_local_out, void* workspace, size_t workspace_bytes, void* stream,
-                              void* const* ev, int* plan_encode_fused = nullptr) {
+                              void* const* ev, int* plan_encode_fused = nullptr, const uint64_t* valid_bits = nullptr) {
     // plan_encode_fused: validate the shapes and report whether the projection launch would carry the encode;
     // nothing is launched and no pointer is dereferenced
     const bool plan_only = plan_encode_fused != nullptr;
@@ -244,6 +251,7 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     // 3. mixed-precision attention (Eq. 1)
     AttnParams ap = attn_params(at, Q, K, V, Kh, Vh, O, nullptr);
     ap.v_transposed = pl.vt ? 1 : 0;
+    ap.valid_bits = (const unsigned long long*)valid_bits;
     ap.ldv_loc = pl.ldv_loc;
     ap.ldv_hat = pl.ldv_hat;
     rc = launch_attention(vq.dtype, ap, at.head_dim, s);
@@ -279,6 +287,15 @@ int astra_layer_forward(const astra_layer_desc* desc, const void* x_local, const
                         void* y_out, void* codes_local_out, void* workspace, size_t workspace_bytes, void* stream) {
     return layer_forward_impl(desc, x_local, codes_nonlocal, codebook, cnorm, wq, wk, wv, wo, bq, bk, bv, bo, y_out,
                               codes_local_out, workspace, workspace_bytes, stream, nullptr);
+}
+
+int astra_layer_forward_valid(const astra_layer_desc* desc, const void* x_local, const void* codes_nonlocal,
+                              const uint64_t* valid_nonlocal_bits, const void* codebook, const float* cnorm,
+                              const void* wq, const void* wk, const void* wv, const void* wo,
+                              const void* bq, const void* bk, const void* bv, const void* bo,
+                              void* y_out, void* codes_local_out, void* workspace, size_t workspace_bytes, void* stream) {
+    return layer_forward_impl(desc, x_local, codes_nonlocal, codebook, cnorm, wq, wk, wv, wo, bq, bk, bv, bo, y_out,
+                              codes_local_out, workspace, workspace_bytes, stream, nullptr, nullptr, valid_nonlocal_bits);
 }
 
 int astra_layer_forward_profiled(const astra_layer_desc* desc, const void* x_local, const void* codes_nonlocal,

@@ -243,15 +243,22 @@ __global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams
     auto softmax_phase = [&](int i) {
         const Tile tl = tile_of(i);
         const bool diag = tl.is_loc && p.causal && (tl.row0 + kAttKV - 1 > wave_q_lo);     // some pair of this wave is hidden
-        const bool masked = diag || (tl.row0 + kAttKV > tl.count);
-        // masking (ragged source tail, causal diagonal): a wave-uniform, rarely taken pass of its own
+        // non-local keys of this tile whose codes never arrived (bit = key index inside the tile; tiles start at
+        // multiples of 64 keys, one word of the caller's bit array each; a wave-uniform scalar load)
+        unsigned long long lost = 0ull;
+        if (p.valid_bits != nullptr && !tl.is_loc && tl.count > 0) lost = ~load_uniform_u64(p.valid_bits + (tl.row0 >> 6));
+        const bool masked = diag || (tl.row0 + kAttKV > tl.count) || lost != 0ull;
+        // masking (ragged source tail, causal diagonal, lost codes): a wave-uniform pass of its own
         if (masked) {
+            // key index inside the tile = 32*mb + 4*h + c(v) with c(v) = acc_row(v, 0) <= 27: one shifted word per half
+            const uint32_t lost_w[2] = {(uint32_t)(lost >> (4 * h)), (uint32_t)(lost >> (32 + 4 * h))};
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int key = tl.row0 + mb * 32 + acc_row(v, h);
-                    if (key >= tl.count || (diag && key > qrow)) acc_s[mb][v] = -INFINITY;
+                    const bool drop = (key >= tl.count) | (diag & (key > qrow)) | (((lost_w[mb] >> acc_row(v, 0)) & 1u) != 0u);
+                    acc_s[mb][v] = drop ? -INFINITY : acc_s[mb][v];
                 }
         }
         float mx = -INFINITY;
@@ -392,7 +399,8 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnParams p, int d
         for (int base = 0; base < count; base += kWave) {
             const int j = base + lane;
             float s = -INFINITY;
-            if (j < count) {
+            const bool arrived = src != 0 || p.valid_bits == nullptr || j >= count || ((p.valid_bits[j >> 6] >> (j & 63)) & 1ull);
+            if (j < count && arrived) {
                 const float* kr = Kp + (int64_t)j * kv_ld;
                 float dot = 0.f;
                 for (int d = 0; d < dh; ++d) dot = fmaf(q[d], kr[d], dot);
@@ -400,9 +408,10 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnParams p, int d
             }
             float mx = s;
             for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
-            const float m_new = fmaxf(m_run, mx);          // finite: every chunk holds at least one key
-            const float alpha = expf(m_run - m_new);
-            const float e = j < count ? expf(s - m_new) : 0.f;
+            const float m_new = fmaxf(m_run, mx);          // -inf only while every key so far was lost
+            const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+            const float alpha = expf(m_run - m_safe);
+            const float e = (j < count && arrived) ? expf(s - m_safe) : 0.f;
             float sum = e;
             for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
             l_run = l_run * alpha + sum;

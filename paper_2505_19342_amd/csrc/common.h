@@ -82,6 +82,19 @@ __device__ __forceinline__ void wait_vmem() {
     asm volatile("" ::: "memory");
 }
 
+// A 64-bit word from a wave-uniform global address through the scalar data path (a read: no vector-memory counter
+// is involved, so transfers in flight are not waited for).  The caller has no LDS or scalar reads outstanding that it
+// cannot afford to wait for: the wait covers them all.
+__device__ __forceinline__ unsigned long long load_uniform_u64(const unsigned long long* p) {
+    unsigned long long v;
+    // readfirstlane returns a signed int: go through uint32_t before widening, or the low half would sign-extend
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)p);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uintptr_t)p >> 32));
+    const unsigned long long* up = (const unsigned long long*)(((uintptr_t)hi << 32) | (uintptr_t)lo);
+    asm volatile("s_load_dwordx2 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(up) : "memory");
+    return v;
+}
+
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 
 // ---- host side ---------------------------------------------------------------------------------
@@ -143,6 +156,9 @@ struct AttnParams {
     int32_t v_transposed; // bf16 only: V buffers are V^T in the projection kernel's kCTransposedV layout
     int32_t ldv_loc, ldv_hat;   // padded token counts (multiples of 64) of the transposed V buffers
     float scale;          // logit scale
+    // nullable: bit (t % 64) of word t / 64 is 1 if non-local token t's codes arrived; a token whose bit is 0 is
+    // dropped from the key/value set
+    const unsigned long long* valid_bits;
 };
 int launch_attention(int dtype, const AttnParams& p, int head_dim, hipStream_t s);
 int launch_mfma_probe(float* out, int n_blocks, int iters, hipStream_t s);

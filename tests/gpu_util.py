@@ -70,8 +70,14 @@ def gpu_vq_decode(codes: np.ndarray, codebook: np.ndarray, dtype: str) -> np.nda
     return to_host(out)
 
 
+def valid_bits_to_dev(valid):
+    """0/1 array [T_n] -> int64 device tensor holding the bit words the *_valid entry points take."""
+    words = B.pack_valid_bits(valid)
+    return torch.from_numpy(words.view(np.int64).copy()).to(DEV)
+
+
 def gpu_mixed_attention(q, k_loc, v_loc, k_hat, v_hat, dtype, *, n_cls=0, causal=False, n_before=0, scale=0.0,
-                        want_lse=False):
+                        want_lse=False, valid_hat=None):
     Tq, Hq, dh = q.shape
     Hkv = k_loc.shape[1]
     Tn = k_hat.shape[0]
@@ -79,7 +85,10 @@ def gpu_mixed_attention(q, k_loc, v_loc, k_hat, v_hat, dtype, *, n_cls=0, causal
     d = lambda a: to_dev(a, dtype) if a.shape[0] > 0 else None
     out = empty_like_dtype((Tq, Hq, dh), dtype)
     lse = torch.empty((Hq, Tq), dtype=torch.float32, device=DEV) if want_lse else None
-    B.astra_mixed_attention(desc, d(q), d(k_loc), d(v_loc), d(k_hat), d(v_hat), out, lse)
+    if valid_hat is None:
+        B.astra_mixed_attention(desc, d(q), d(k_loc), d(v_loc), d(k_hat), d(v_hat), out, lse)
+    else:
+        B.astra_mixed_attention_valid(desc, d(q), d(k_loc), d(v_loc), d(k_hat), d(v_hat), valid_bits_to_dev(valid_hat), out, lse)
     torch.cuda.synchronize()
     return (to_host(out), lse.cpu().numpy()) if want_lse else to_host(out)
 
@@ -106,7 +115,11 @@ class LayerOnGpu:
         self.codes_local = empty_codes(Tq - cfg.n_cls, G, K)
         self.workspace = torch.empty(max(B.astra_layer_workspace_bytes(self.desc), 256), dtype=torch.uint8, device=DEV)
 
-    def run(self):
+    def run(self, valid_nonlocal=None):
+        if valid_nonlocal is not None:
+            B.astra_layer_forward_valid(self.desc, self.x_local, self.codes_nonlocal, valid_bits_to_dev(valid_nonlocal),
+                                        self.codebook, self.cnorm, *self.w, *self.b, self.y, self.codes_local, self.workspace)
+            return
         B.astra_layer_forward(self.desc, self.x_local, self.codes_nonlocal, self.codebook, self.cnorm, *self.w, *self.b,
                               self.y, self.codes_local, self.workspace)
 

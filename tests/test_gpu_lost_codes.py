@@ -1,0 +1,102 @@
+"""GPU parity of the lost-code variants (Sec. 4.5 "Non-Ideal Network Conditions": packet loss without
+retransmission; a non-local token whose codes never arrived is dropped from the key/value set) through
+astra_mixed_attention_valid / astra_layer_forward_valid against the CPU oracle.  Same bars as the full path."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2505_19342_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"bf16": 2e-2, "f32": 2e-5}
+Y_TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def rand_case(seed, Tq, Tn, Hq, Hkv, dh, dtype):
+    rng = np.random.default_rng(seed)
+    f = lambda *s: rng.standard_normal(s).astype(np.float32)
+    arrs = [f(Tq, Hq, dh), f(Tq, Hkv, dh), f(Tq, Hkv, dh), f(Tn, Hkv, dh), f(Tn, Hkv, dh)]
+    return [wl.round_to_bf16(a) for a in arrs] if dtype == "bf16" else arrs
+
+
+CASES = [
+    # Tq, Tn, Hq, Hkv, dh, dtype, causal, n_before, lost fraction
+    (64, 192, 3, 3, 64, "f32", False, 0, 0.05),
+    (40, 150, 2, 2, 128, "f32", True, 97, 0.5),
+    (256, 768, 12, 12, 64, "bf16", False, 0, 0.05),
+    (256, 768, 12, 12, 64, "bf16", True, 512, 0.05),
+    (130, 333, 8, 2, 128, "bf16", False, 0, 0.3),        # ragged last word of the bit array
+    (200, 450, 8, 2, 128, "bf16", True, 333, 0.05),
+    (128, 256, 4, 4, 128, "bf16", False, 0, 1.0),        # everything lost: plain local attention
+    (128, 320, 4, 4, 64, "bf16", False, 0, -64.0),       # one whole 64-key tile lost, the rest present
+]
+
+
+@pytest.mark.parametrize("Tq,Tn,Hq,Hkv,dh,dtype,causal,n_before,lost", CASES)
+def test_attention_with_lost_tokens_matches_oracle(Tq, Tn, Hq, Hkv, dh, dtype, causal, n_before, lost):
+    from gpu_util import gpu_mixed_attention
+    q, k, v, kh, vh = rand_case(Tq + 3 * Tn, Tq, Tn, Hq, Hkv, dh, dtype)
+    rng = np.random.default_rng(Tn)
+    if lost < 0:
+        valid = np.ones(Tn, dtype=bool)
+        valid[64:128] = False
+    else:
+        valid = rng.random(Tn) >= lost
+    ref, ref_lse = oracle.mixed_attention(q, k, v, kh, vh, causal=causal, n_before=n_before, valid_hat=valid, return_lse=True)
+    got, lse = gpu_mixed_attention(q, k, v, kh, vh, dtype, causal=causal, n_before=n_before, want_lse=True, valid_hat=valid)
+    err = np.abs(got - ref).max()
+    print(f"lost {int((~valid).sum())}/{Tn}: max abs err {err:.3e}")
+    assert err <= TOL[dtype]
+    np.testing.assert_allclose(lse, ref_lse, atol=2e-3 if dtype == "bf16" else 1e-4)
+    # an all-ones mask is the unmasked call, bit for bit
+    a = gpu_mixed_attention(q, k, v, kh, vh, dtype, causal=causal, n_before=n_before, valid_hat=np.ones(Tn))
+    b = gpu_mixed_attention(q, k, v, kh, vh, dtype, causal=causal, n_before=n_before)
+    assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("cfg,rank", [(wl.TINY_VIT, 1), (wl.GPT2_SMALL, 3), (wl.VIT_BASE, 2)])
+def test_layer_with_lost_tokens_matches_oracle(cfg, rank):
+    from gpu_util import LayerOnGpu, compare_codes
+    data = wl.generate(cfg)
+    view = wl.device_view(cfg, data, rank)
+    codes_nl = oracle.vq_encode(view["x_nonlocal"], data["codebook"])
+    rng = np.random.default_rng(1234 + rank)
+    valid = rng.random(codes_nl.shape[0]) >= 0.05
+    valid[0] = False
+    garbage = codes_nl.copy()
+    garbage[~valid] = cfg.codebook_size - 1 if cfg.codebook_size > 255 else 255      # whatever was in the receive buffer
+    y_ref, codes_ref, gap = oracle.layer_forward(
+        view["x_local"], codes_nl, data["codebook"], data["wq"], data["wk"], data["wv"], data["wo"],
+        n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, n_cls=cfg.n_cls, causal=cfg.causal,
+        n_before=view["n_before"], return_gap=True, valid_nonlocal=valid)
+    layer = LayerOnGpu(cfg, data, view["x_local"], garbage, view["n_before"])
+    layer.run(valid_nonlocal=valid)
+    y, codes = layer.results()
+    compare_codes(codes, codes_ref, gap, 1e-5)
+    err = np.abs(y - y_ref).max()
+    print(f"{cfg.name} rank {rank}, {int((~valid).sum())} lost: max abs err {err:.3e}")
+    assert err <= Y_TOL[cfg.dtype]
+
+
+def test_llama_shape_layer_with_five_percent_lost():
+    """The benchmark workload (last rank) with 5 % of the peers' tokens lost."""
+    from gpu_util import LayerOnGpu, compare_codes
+    cfg = wl.LLAMA3_8B
+    data = wl.generate(cfg)
+    view = wl.device_view(cfg, data, cfg.n_dev - 1)
+    codes_nl = oracle.vq_encode(view["x_nonlocal"], data["codebook"])
+    valid = np.random.default_rng(77).random(codes_nl.shape[0]) >= 0.05
+    y_ref, codes_ref, gap = oracle.layer_forward(
+        view["x_local"], codes_nl, data["codebook"], data["wq"], data["wk"], data["wv"], data["wo"],
+        n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, causal=True, n_before=view["n_before"], return_gap=True,
+        valid_nonlocal=valid)
+    layer = LayerOnGpu(cfg, data, view["x_local"], codes_nl, view["n_before"])
+    layer.run(valid_nonlocal=valid)
+    y, codes = layer.results()
+    compare_codes(codes, codes_ref, gap, 1e-5)
+    err = np.abs(y - y_ref).max()
+    print(f"llama3_8b last rank, {int((~valid).sum())}/3072 lost: max abs err {err:.3e}")
+    assert err <= Y_TOL["bf16"]

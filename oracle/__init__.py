@@ -43,7 +43,8 @@ def _load():
         lib.oracle_num_threads.restype = ctypes.c_int
         for name in ("oracle_vq_encode", "oracle_vq_decode", "oracle_linear",
                      "oracle_mixed_attention", "oracle_mixed_attention_valid",
-                     "oracle_layer_forward", "oracle_layer_forward_valid"):
+                     "oracle_layer_forward", "oracle_layer_forward_valid",
+                     "oracle_norm", "oracle_mlp", "oracle_block_forward"):
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -186,3 +187,73 @@ def layer_forward(x_local, codes_nonlocal, codebook, wq, wk, wv, wo, *, n_q_head
     if rc:
         raise ValueError(f"oracle_layer_forward failed ({rc})")
     return (y, codes_local, gap) if return_gap else (y, codes_local)
+
+
+NORM_KINDS = {"layernorm": 0, "rmsnorm": 1}
+MLP_KINDS = {"gelu_tanh": 0, "gelu_erf": 1, "swiglu": 2}
+
+
+def norm(x, kind, eps, gain=None, bias=None):
+    """Row-wise LayerNorm / RMSNorm of x [T, D] in fp64 (the pre-norm of a Transformer block)."""
+    x = _f64(x)
+    gain, bias = _f32(gain), _f32(bias)
+    T, D = x.shape
+    out = np.empty((T, D), dtype=np.float64)
+    rc = _load().oracle_norm(_p(x), ctypes.c_int64(T), D, NORM_KINDS[kind], ctypes.c_double(eps), _p(gain), _p(bias), _p(out))
+    if rc:
+        raise ValueError(f"oracle_norm failed ({rc})")
+    return out
+
+
+def mlp(h, kind, w1, w2, b1=None, b2=None):
+    """Position-wise MLP (Sec. 3.1: run locally on each device).  h [T, D]; w1 [D, d_ff] (GELU kinds) or
+    [D, 2 d_ff] = [gate | up] (swiglu); w2 [d_ff, D].  fp64."""
+    h = _f64(h)
+    w1, w2, b1, b2 = map(_f32, (w1, w2, b1, b2))
+    T, D = h.shape
+    d_ff = w2.shape[0]
+    assert w1.shape == (D, 2 * d_ff if kind == "swiglu" else d_ff) and w2.shape == (d_ff, D)
+    out = np.empty((T, D), dtype=np.float64)
+    rc = _load().oracle_mlp(_p(h), ctypes.c_int64(T), D, d_ff, MLP_KINDS[kind], _p(w1), _p(b1), _p(w2), _p(b2), _p(out))
+    if rc:
+        raise ValueError(f"oracle_mlp failed ({rc})")
+    return out
+
+
+def block_forward(x, codes_nonlocal, codebook, wq, wk, wv, wo, *, norm_kind, eps, g1, g2, be1=None, be2=None,
+                  mlp_kind, w1, w2, b1=None, b2=None, n_q_heads, n_kv_heads, n_cls=0, causal=False, n_before=0,
+                  scale=0.0, bq=None, bk=None, bv=None, bo=None, valid_nonlocal=None, h_is_bf16=False):
+    """One Transformer block on one device (Sec. 3.1): out = r + mlp(norm2(r)), r = x + layer(norm1(x)).
+    x [T_q, D] is the fp64 residual stream.  Returns (x_out [T_q, D] fp64, codes_local [T_l, G] int32,
+    gap [T_l, G], h [T_q, D] fp32 = the normalised tensor that was quantised and projected)."""
+    x = _f64(x)
+    codebook = _f32(codebook)
+    codes_nonlocal = _i32(codes_nonlocal)
+    wq, wk, wv, wo, w1, w2 = map(_f32, (wq, wk, wv, wo, w1, w2))
+    bq, bk, bv, bo, b1, b2, g1, g2, be1, be2 = map(_f32, (bq, bk, bv, bo, b1, b2, g1, g2, be1, be2))
+    G, K, dg = codebook.shape
+    Tq, D = x.shape
+    Tn = codes_nonlocal.shape[0]
+    assert D == G * dg and codes_nonlocal.shape == (Tn, G)
+    dh = wq.shape[1] // n_q_heads
+    d_ff = w2.shape[0]
+    assert wq.shape == (D, n_q_heads * dh) and wk.shape == (D, n_kv_heads * dh)
+    assert wv.shape == (D, n_kv_heads * dh) and wo.shape == (n_q_heads * dh, D)
+    assert w1.shape == (D, 2 * d_ff if mlp_kind == "swiglu" else d_ff) and w2.shape == (d_ff, D)
+    n_local = Tq - int(n_cls)
+    x_out = np.empty((Tq, D), dtype=np.float64)
+    h = np.empty((Tq, D), dtype=np.float32)
+    codes_local = np.empty((n_local, G), dtype=np.int32)
+    gap = np.empty((n_local, G), dtype=np.float64)
+    valid_nonlocal = _u8(valid_nonlocal)
+    assert valid_nonlocal is None or valid_nonlocal.shape == (Tn,)
+    rc = _load().oracle_block_forward(
+        _p(x), _p(codes_nonlocal), _p(valid_nonlocal), _p(codebook), D, G, K,
+        NORM_KINDS[norm_kind], ctypes.c_double(eps), _p(g1), _p(be1), _p(g2), _p(be2),
+        _p(wq), _p(wk), _p(wv), _p(wo), _p(bq), _p(bk), _p(bv), _p(bo),
+        MLP_KINDS[mlp_kind], d_ff, _p(w1), _p(b1), _p(w2), _p(b2),
+        n_q_heads, n_kv_heads, dh, int(n_cls), n_local, Tn, int(bool(causal)), int(n_before), ctypes.c_double(scale),
+        int(bool(h_is_bf16)), _p(x_out), _p(codes_local), _p(gap), _p(h))
+    if rc:
+        raise ValueError(f"oracle_block_forward failed ({rc})")
+    return x_out, codes_local, gap, h

@@ -19,6 +19,7 @@
  *   oracle_linear           the linear projections named under Eq. 1
  *   oracle_mixed_attention  Sec. 3.2 Eq. 1, sigma(Q [K | K-hat]^T / sqrt(d_k)) [V | V-hat]
  *   oracle_layer_forward    Sec. 3.1 (per-block procedure on one device)
+ *   oracle_block_forward    Sec. 3.1, the whole block: norms, residuals and the local MLP around the layer
  *
  * Readings taken where the paper is silent (they are the library's too):
  *   - groups are contiguous slices [g*dg, (g+1)*dg) of the D-vector;
@@ -281,4 +282,126 @@ int oracle_layer_forward(const float* x_local, const int32_t* codes_nonlocal,
     return oracle_layer_forward_valid(x_local, codes_nonlocal, NULL, codebook, D, G, K, wq, wk, wv, wo, bq, bk, bv, bo,
                                       n_q_heads, n_kv_heads, head_dim, n_cls, n_local, n_nonlocal, causal, n_before,
                                       scale, y, codes_local, gap_local);
+}
+
+/* ------------------------------------------------------------------------------------------------
+ * One whole Transformer block on one device (Sec. 3.1: "Within each Transformer block ..." — local
+ * quantisation, exchange of indices, mixed-precision attention, then the position-wise MLP, "executed
+ * locally on each device without communication").  The paper uses the stock ViT / GPT-2 / Llama blocks
+ * and does not restate them; the pre-norm residual form of those models is taken:
+ *     h   = norm1(x)                      the tensor that feeds the projections is the one quantised
+ *     r   = x + layer(h)                  layer = oracle_layer_forward (Eq. 1 and W_o)
+ *     out = r + mlp(norm2(r))
+ * norm_kind 0: LayerNorm  (x - mean) / sqrt(var + eps) * gain + bias   (biased variance over the row)
+ *           1: RMSNorm    x / sqrt(mean(x^2) + eps) * gain
+ * mlp_kind  0: fc2(gelu_tanh(fc1(h)))   gelu_tanh(a) = a/2 (1 + tanh(sqrt(2/pi) (a + 0.044715 a^3)))   (GPT-2)
+ *           1: fc2(gelu_erf(fc1(h)))    gelu_erf(a)  = a/2 (1 + erf(a / sqrt 2))                        (ViT)
+ *           2: down(silu(gate(h)) * up(h)),  silu(a) = a / (1 + exp(-a)); w1 = [W_gate | W_up] as
+ *              [D, 2 d_ff] (gate columns first), no biases needed                                      (Llama)
+ * No rotary or learned positional encoding is applied.
+ * ------------------------------------------------------------------------------------------------ */
+int oracle_norm(const double* x, int64_t T, int D, int norm_kind, double eps,
+                const float* gain, const float* bias, double* out) {
+    if (T < 0 || D <= 0 || (norm_kind != 0 && norm_kind != 1)) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        const double* r = x + t * (int64_t)D;
+        double* o = out + t * (int64_t)D;
+        double mean = 0.0;
+        if (norm_kind == 0) {
+            for (int i = 0; i < D; ++i) mean += r[i];
+            mean /= D;
+        }
+        double var = 0.0;
+        for (int i = 0; i < D; ++i) var += (r[i] - mean) * (r[i] - mean);
+        var /= D;
+        const double inv = 1.0 / sqrt(var + eps);
+        for (int i = 0; i < D; ++i) {
+            double v = (r[i] - mean) * inv;
+            if (gain) v *= (double)gain[i];
+            if (norm_kind == 0 && bias) v += (double)bias[i];
+            o[i] = v;
+        }
+    }
+    return 0;
+}
+
+static double act_gelu_tanh(double a) { return 0.5 * a * (1.0 + tanh(0.7978845608028654 * (a + 0.044715 * a * a * a))); }
+static double act_gelu_erf(double a) { return 0.5 * a * (1.0 + erf(a * 0.7071067811865476)); }
+static double act_silu(double a) { return a / (1.0 + exp(-a)); }
+
+/* h [T, D] -> out [T, D].  w1 [D, d_ff] (kinds 0, 1) or [D, 2 d_ff] (kind 2); w2 [d_ff, D]. */
+int oracle_mlp(const double* h, int64_t T, int D, int d_ff, int mlp_kind,
+               const float* w1, const float* b1, const float* w2, const float* b2, double* out) {
+    if (T < 0 || D <= 0 || d_ff <= 0 || mlp_kind < 0 || mlp_kind > 2) return -1;
+    const int n1 = mlp_kind == 2 ? 2 * d_ff : d_ff;
+    double* a = (double*)malloc(sizeof(double) * ((int64_t)T * n1 + 1));
+    double* g = (double*)malloc(sizeof(double) * ((int64_t)T * d_ff + 1));
+    int rc = oracle_linear(h, T, D, n1, w1, b1, a);
+    if (!rc) {
+        for (int64_t t = 0; t < T; ++t)
+            for (int j = 0; j < d_ff; ++j) {
+                const double v = a[t * (int64_t)n1 + j];
+                double r;
+                if (mlp_kind == 0) r = act_gelu_tanh(v);
+                else if (mlp_kind == 1) r = act_gelu_erf(v);
+                else r = act_silu(v) * a[t * (int64_t)n1 + d_ff + j];
+                g[t * (int64_t)d_ff + j] = r;
+            }
+        rc = oracle_linear(g, T, d_ff, D, w2, b2, out);
+    }
+    free(a);
+    free(g);
+    return rc;
+}
+
+/* x [T_q, D] fp64 residual stream in, x_out [T_q, D] out.  The normalised tensor h = norm1(x) is rounded to the
+ * element type the layer's inputs have (h_is_bf16: bf16, round to nearest even; else fp32) before it enters the
+ * layer: an argmin is decided on it, and both sides must take that decision on the same values.  h_out (nullable)
+ * returns that tensor, which is what this device's peers would receive the codes of. */
+int oracle_block_forward(const double* x, const int32_t* codes_nonlocal, const uint8_t* valid_nonlocal,
+                         const float* codebook, int D, int G, int K,
+                         int norm_kind, double eps, const float* g1, const float* be1, const float* g2, const float* be2,
+                         const float* wq, const float* wk, const float* wv, const float* wo,
+                         const float* bq, const float* bk, const float* bv, const float* bo,
+                         int mlp_kind, int d_ff, const float* w1, const float* b1, const float* w2, const float* b2,
+                         int n_q_heads, int n_kv_heads, int head_dim,
+                         int n_cls, int n_local, int n_nonlocal, int causal, int n_before, double scale,
+                         int h_is_bf16,
+                         double* x_out, int32_t* codes_local, double* gap_local, float* h_out) {
+    const int Tq = n_cls + n_local;
+    const int64_t n = (int64_t)Tq * D;
+    double* h = (double*)malloc(sizeof(double) * (n + 1));
+    float* hf = (float*)malloc(sizeof(float) * (n + 1));
+    double* y = (double*)malloc(sizeof(double) * (n + 1));
+    double* r = (double*)malloc(sizeof(double) * (n + 1));
+    double* m = (double*)malloc(sizeof(double) * (n + 1));
+    int rc = oracle_norm(x, Tq, D, norm_kind, eps, g1, be1, h);
+    if (!rc) {
+        /* the layer takes its input in the device's element type */
+        for (int64_t i = 0; i < n; ++i) {
+            float f = (float)h[i];
+            if (h_is_bf16) {
+                uint32_t u;
+                memcpy(&u, &f, 4);
+                if ((u & 0x7f800000u) != 0x7f800000u) u += 0x7fffu + ((u >> 16) & 1u);      /* round to nearest even */
+                u &= 0xffff0000u;
+                memcpy(&f, &u, 4);
+            }
+            hf[i] = f;
+        }
+        if (h_out) memcpy(h_out, hf, sizeof(float) * n);
+        rc = oracle_layer_forward_valid(hf, codes_nonlocal, valid_nonlocal, codebook, D, G, K, wq, wk, wv, wo, bq, bk, bv, bo,
+                                        n_q_heads, n_kv_heads, head_dim, n_cls, n_local, n_nonlocal, causal, n_before,
+                                        scale, y, codes_local, gap_local);
+    }
+    if (!rc) {
+        for (int64_t i = 0; i < n; ++i) r[i] = x[i] + y[i];
+        rc = oracle_norm(r, Tq, D, norm_kind, eps, g2, be2, h);
+    }
+    if (!rc) rc = oracle_mlp(h, Tq, D, d_ff, mlp_kind, w1, b1, w2, b2, m);
+    if (!rc)
+        for (int64_t i = 0; i < n; ++i) x_out[i] = r[i] + m[i];
+    free(h); free(hf); free(y); free(r); free(m);
+    return rc;
 }

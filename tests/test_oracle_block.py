@@ -1,0 +1,217 @@
+"""Pins for the oracle's whole-block functions (Sec. 3.1: per block, local quantisation, the exchange of indices,
+mixed-precision attention, then the position-wise MLP run locally; the paper uses the stock pre-norm ViT / GPT-2 /
+Llama blocks).  The norms, activations and MLPs are pinned to the library routines of torch on the CPU in fp64, to
+closed forms and to invariances; the block's wiring (which tensor is normalised, quantised, added to what) is pinned
+by recomposing it from those library routines around the separately pinned layer, and by special cases in which a
+part of the block vanishes."""
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+import oracle
+from paper_2505_19342_amd import workloads as wl
+
+
+def t64(a):
+    return torch.from_numpy(np.asarray(a, dtype=np.float64))
+
+
+# ---------------------------------------------------------------- norms
+@pytest.mark.parametrize("D", [7, 64, 193])
+def test_layernorm_equals_library_routine(D):
+    rng = np.random.default_rng(D)
+    x = rng.standard_normal((11, D)) * 3.0 + 1.5
+    g = rng.standard_normal(D).astype(np.float32)
+    b = rng.standard_normal(D).astype(np.float32)
+    ref = F.layer_norm(t64(x), (D,), t64(g), t64(b), eps=1e-5).numpy()
+    np.testing.assert_allclose(oracle.norm(x, "layernorm", 1e-5, g, b), ref, rtol=1e-12, atol=1e-12)
+    ref = F.layer_norm(t64(x), (D,), None, None, eps=1e-6).numpy()
+    np.testing.assert_allclose(oracle.norm(x, "layernorm", 1e-6), ref, rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("D", [5, 128])
+def test_rmsnorm_equals_library_routine_and_closed_form(D):
+    rng = np.random.default_rng(D + 1)
+    x = rng.standard_normal((9, D)) * 2.0 + 0.7
+    g = rng.standard_normal(D).astype(np.float32)
+    ref = F.rms_norm(t64(x), (D,), t64(g), eps=1e-5).numpy()
+    np.testing.assert_allclose(oracle.norm(x, "rmsnorm", 1e-5, g), ref, rtol=1e-12, atol=1e-12)
+    # closed form: a constant row c maps to sign(c) (eps = 0, no gain); rows come out with unit mean square
+    const = np.full((1, D), -3.25)
+    np.testing.assert_allclose(oracle.norm(const, "rmsnorm", 0.0), -np.ones((1, D)), rtol=1e-14)
+    out = oracle.norm(x, "rmsnorm", 0.0)
+    np.testing.assert_allclose((out ** 2).mean(-1), 1.0, rtol=1e-13)
+
+
+def test_norm_invariances_tell_the_two_kinds_apart():
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((6, 40))
+    # LayerNorm ignores a shift and a positive rescale of the row (eps = 0); its rows have zero mean and unit variance
+    ln = oracle.norm(x, "layernorm", 0.0)
+    np.testing.assert_allclose(oracle.norm(2.5 * x + 7.0, "layernorm", 0.0), ln, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(ln.mean(-1), 0.0, atol=1e-14)
+    np.testing.assert_allclose(ln.var(-1), 1.0, rtol=1e-13)
+    # RMSNorm ignores the rescale but not the shift
+    rn = oracle.norm(x, "rmsnorm", 0.0)
+    np.testing.assert_allclose(oracle.norm(2.5 * x, "rmsnorm", 0.0), rn, rtol=1e-13)
+    assert np.abs(oracle.norm(x + 7.0, "rmsnorm", 0.0) - rn).max() > 0.1
+    # the bias is only applied by LayerNorm, after the gain
+    g, b = np.full(40, 2.0, np.float32), np.full(40, 0.5, np.float32)
+    np.testing.assert_allclose(oracle.norm(x, "layernorm", 0.0, g, b), 2.0 * ln + 0.5, rtol=1e-13, atol=1e-13)
+    # eps sits inside the square root, added to the variance: a zero row stays zero, a tiny row is damped by sqrt(eps)
+    tiny = np.full((1, 40), 1e-9)
+    tiny[0, ::2] *= -1.0
+    np.testing.assert_allclose(oracle.norm(tiny, "rmsnorm", 1e-4), tiny / 1e-2, rtol=1e-9)
+
+
+# ---------------------------------------------------------------- MLP
+@pytest.mark.parametrize("kind", ["gelu_tanh", "gelu_erf", "swiglu"])
+def test_mlp_equals_library_routines(kind):
+    rng = np.random.default_rng(11)
+    T, D, F_ = 13, 24, 40
+    h = rng.standard_normal((T, D)) * 1.5
+    w1 = (0.4 * rng.standard_normal((D, 2 * F_ if kind == "swiglu" else F_))).astype(np.float32)
+    w2 = (0.4 * rng.standard_normal((F_, D))).astype(np.float32)
+    b1 = rng.standard_normal(w1.shape[1]).astype(np.float32)
+    b2 = rng.standard_normal(D).astype(np.float32)
+    a = t64(h) @ t64(w1) + t64(b1)
+    if kind == "gelu_tanh":
+        g = F.gelu(a, approximate="tanh")
+    elif kind == "gelu_erf":
+        g = F.gelu(a)
+    else:
+        g = F.silu(a[:, :F_]) * a[:, F_:]           # gate columns first, then up
+    ref = (g @ t64(w2) + t64(b2)).numpy()
+    np.testing.assert_allclose(oracle.mlp(h, kind, w1, w2, b1, b2), ref, rtol=1e-11, atol=1e-11)
+    # without biases
+    a = t64(h) @ t64(w1)
+    g = {"gelu_tanh": lambda: F.gelu(a, approximate="tanh"), "gelu_erf": lambda: F.gelu(a),
+         "swiglu": lambda: F.silu(a[:, :F_]) * a[:, F_:]}[kind]()
+    np.testing.assert_allclose(oracle.mlp(h, kind, w1, w2), (g @ t64(w2)).numpy(), rtol=1e-11, atol=1e-11)
+
+
+def test_activation_closed_forms():
+    """One input, identity-like weights: mlp returns act(v).  Values from the definitions: gelu_erf(1) =
+    Phi(1) = 0.841344746068543, silu(1) = 1/(1+e^-1) = 0.731058578630005, gelu(0) = silu(0) = 0, and for large
+    |v| all three tend to max(v, 0)."""
+    one = np.ones((1, 1), np.float32)
+    f = lambda kind, v: oracle.mlp(np.array([[v]]), kind, one if kind != "swiglu" else np.ones((1, 2), np.float32), one,
+                                   None if kind != "swiglu" else np.array([0.0, 1.0], np.float32) - np.array([0.0, v], np.float32))[0, 0]
+    assert abs(f("gelu_erf", 1.0) - 0.841344746068543) < 1e-14
+    assert abs(f("swiglu", 1.0) - 0.731058578630005) < 1e-14          # up = v + (1 - v) = 1, so the output is silu(v)
+    assert abs(f("gelu_tanh", 1.0) - 0.841191990608276) < 1e-12        # 0.5 (1 + tanh(sqrt(2/pi) 1.044715))
+    for kind in ("gelu_tanh", "gelu_erf", "swiglu"):
+        assert f(kind, 0.0) == 0.0
+        assert abs(f(kind, 30.0) - 30.0) < 1e-9 and abs(f(kind, -30.0)) < 1e-9
+    # the tanh form is an approximation of the erf form: close, not equal
+    assert 1e-5 < abs(f("gelu_tanh", 1.0) - f("gelu_erf", 1.0)) < 1e-3
+
+
+# ---------------------------------------------------------------- whole block
+def block_inputs(rng, *, D=24, G=4, K=8, hq=4, hkv=2, dh=6, tq=9, tn=14, d_ff=40, mlp_kind="swiglu", biases=False):
+    f32 = lambda a: np.asarray(a, dtype=np.float32)
+    p = dict(
+        x=rng.standard_normal((tq, D)) * 2.0 + 0.3,
+        codes=rng.integers(0, K, (tn, G)).astype(np.int32),
+        cb=f32(rng.standard_normal((G, K, D // G))),
+        wq=f32(0.3 * rng.standard_normal((D, hq * dh))), wk=f32(0.3 * rng.standard_normal((D, hkv * dh))),
+        wv=f32(0.3 * rng.standard_normal((D, hkv * dh))), wo=f32(0.3 * rng.standard_normal((hq * dh, D))),
+        g1=f32(1.0 + 0.2 * rng.standard_normal(D)), g2=f32(1.0 + 0.2 * rng.standard_normal(D)),
+        be1=f32(0.2 * rng.standard_normal(D)), be2=f32(0.2 * rng.standard_normal(D)),
+        w1=f32(0.3 * rng.standard_normal((D, 2 * d_ff if mlp_kind == "swiglu" else d_ff))),
+        w2=f32(0.3 * rng.standard_normal((d_ff, D))))
+    if biases:
+        p.update(bq=f32(rng.standard_normal(hq * dh)), bk=f32(rng.standard_normal(hkv * dh)), bv=f32(rng.standard_normal(hkv * dh)),
+                 bo=f32(rng.standard_normal(D)), b1=f32(rng.standard_normal(p["w1"].shape[1])), b2=f32(rng.standard_normal(D)))
+    return p
+
+
+def run_block(p, norm_kind, mlp_kind, hq=4, hkv=2, **kw):
+    names = ("bq", "bk", "bv", "bo", "b1", "b2")
+    return oracle.block_forward(p["x"], p["codes"], p["cb"], p["wq"], p["wk"], p["wv"], p["wo"], norm_kind=norm_kind, eps=1e-5,
+                                g1=p["g1"], g2=p["g2"], be1=p["be1"], be2=p["be2"], mlp_kind=mlp_kind, w1=p["w1"], w2=p["w2"],
+                                n_q_heads=hq, n_kv_heads=hkv, **{n: p.get(n) for n in names}, **kw)
+
+
+@pytest.mark.parametrize("norm_kind,mlp_kind,biases,causal,n_cls", [
+    ("layernorm", "gelu_erf", True, False, 1), ("layernorm", "gelu_tanh", True, True, 0), ("rmsnorm", "swiglu", False, True, 0)])
+@pytest.mark.parametrize("h_is_bf16", [False, True])
+def test_block_wiring_recomposed_from_library_routines(norm_kind, mlp_kind, biases, causal, n_cls, h_is_bf16):
+    rng = np.random.default_rng(21)
+    p = block_inputs(rng, mlp_kind=mlp_kind, biases=biases)
+    D = p["x"].shape[1]
+    out, codes, gap, h = run_block(p, norm_kind, mlp_kind, causal=causal, n_before=5 if causal else 0, n_cls=n_cls, h_is_bf16=h_is_bf16)
+
+    def tnorm(v, g, b):
+        if norm_kind == "layernorm":
+            return F.layer_norm(v, (D,), t64(g), t64(b), eps=1e-5)
+        return F.rms_norm(v, (D,), t64(g), eps=1e-5)
+
+    x = t64(p["x"])
+    h_ref = tnorm(x, p["g1"], p["be1"]).to(torch.float32)
+    if h_is_bf16:
+        h_ref = h_ref.to(torch.bfloat16).to(torch.float32)          # the library's round-to-nearest-even
+    np.testing.assert_array_equal(h, h_ref.numpy())
+    if h_is_bf16:
+        assert not np.any(h.view(np.uint32) & 0xFFFF)
+    # the layer works on h: its codes are the codes of h's content rows (not of x), and it is added to x, not to h
+    y, codes_ref = oracle.layer_forward(h, p["codes"], p["cb"], p["wq"], p["wk"], p["wv"], p["wo"], n_q_heads=4, n_kv_heads=2,
+                                        n_cls=n_cls, causal=causal, n_before=5 if causal else 0,
+                                        bq=p.get("bq"), bk=p.get("bk"), bv=p.get("bv"), bo=p.get("bo"))
+    np.testing.assert_array_equal(codes, codes_ref)
+    np.testing.assert_array_equal(codes, oracle.vq_encode(h[n_cls:], p["cb"]))
+    r = x + t64(y)
+    a = tnorm(r, p["g2"], p["be2"]) @ t64(p["w1"])
+    if biases:
+        a = a + t64(p["b1"])
+    F_ = p["w2"].shape[0]
+    g = {"gelu_tanh": lambda: F.gelu(a, approximate="tanh"), "gelu_erf": lambda: F.gelu(a),
+         "swiglu": lambda: F.silu(a[:, :F_]) * a[:, F_:]}[mlp_kind]()
+    m = g @ t64(p["w2"])
+    if biases:
+        m = m + t64(p["b2"])
+    np.testing.assert_allclose(out, (r + m).numpy(), rtol=1e-11, atol=1e-11)
+
+
+def test_block_special_cases():
+    rng = np.random.default_rng(22)
+    p = block_inputs(rng, mlp_kind="gelu_erf", biases=False)
+    full, *_ = run_block(p, "layernorm", "gelu_erf")
+    # W_2 = 0 (no b_2): the MLP vanishes and the block is x + layer(norm1(x))
+    q = dict(p, w2=np.zeros_like(p["w2"]))
+    out, _, _, h = run_block(q, "layernorm", "gelu_erf")
+    y, _ = oracle.layer_forward(h, p["codes"], p["cb"], p["wq"], p["wk"], p["wv"], p["wo"], n_q_heads=4, n_kv_heads=2)
+    np.testing.assert_allclose(out, p["x"] + y, rtol=1e-13, atol=1e-13)
+    assert np.abs(full - out).max() > 1e-3
+    # W_o = 0: the attention vanishes and the block is x + mlp(norm2(x)); the codes are still those of norm1(x)
+    q = dict(p, wo=np.zeros_like(p["wo"]))
+    out, codes, _, h = run_block(q, "layernorm", "gelu_erf")
+    ref = p["x"] + oracle.mlp(oracle.norm(p["x"], "layernorm", 1e-5, p["g2"], p["be2"]), "gelu_erf", p["w1"], p["w2"])
+    np.testing.assert_allclose(out, ref, rtol=1e-13, atol=1e-13)
+    np.testing.assert_array_equal(codes, oracle.vq_encode(h, p["cb"]))
+    # both zero: the identity
+    q = dict(p, wo=np.zeros_like(p["wo"]), w2=np.zeros_like(p["w2"]))
+    np.testing.assert_array_equal(run_block(q, "layernorm", "gelu_erf")[0], p["x"])
+    # norm1 and norm2 use their own parameters: swapping them changes the result
+    q = dict(p, g1=p["g2"], g2=p["g1"])
+    assert np.abs(run_block(q, "layernorm", "gelu_erf")[0] - full).max() > 1e-3
+
+
+def test_block_passes_lost_codes_through():
+    rng = np.random.default_rng(23)
+    p = block_inputs(rng)
+    valid = rng.random(14) > 0.4
+    out, *_ = run_block(p, "rmsnorm", "swiglu", valid_nonlocal=valid)
+    q = dict(p, codes=p["codes"][valid])
+    ref, *_ = run_block(q, "rmsnorm", "swiglu")
+    np.testing.assert_allclose(out, ref, rtol=1e-12, atol=1e-12)
+
+
+def test_bf16_rounding_of_h_matches_the_input_generator():
+    """The rounding the oracle applies to norm1(x) is the one the seeded generators apply to every bf16 tensor."""
+    rng = np.random.default_rng(24)
+    p = block_inputs(rng)
+    _, _, _, h32 = run_block(p, "rmsnorm", "swiglu", h_is_bf16=False)
+    _, _, _, h16 = run_block(p, "rmsnorm", "swiglu", h_is_bf16=True)
+    np.testing.assert_array_equal(h16, wl.round_to_bf16(h32))

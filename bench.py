@@ -233,6 +233,35 @@ def main():
             bits = torch.from_numpy(B.pack_valid_bits(lost_rng.random(tn) >= 0.05).view(np.int64).copy()).to(dev)
             a_v = (desc, x_local, codes_nl, bits, codebook, cnorm, *w, None, None, None, None, y, codes_local, ws)
             result["lost_codes_5pct_ms"] = timed(lambda: B.astra_layer_forward_valid(*a_v), 100, warm=50)
+        # the whole Transformer block around the layer (Sec. 3.1: norm, layer, residual, norm, local MLP, residual) for
+        # the model this workload stands in for; the peers' codes are reused as they are (their values do not change the work)
+        bcfg = next((b for b in wl.BLOCK_CONFIGS.values() if b.layer.name == cfg.name), None)
+        if bcfg is not None:
+            bdata = wl.generate_block(bcfg)
+            bview = wl.device_view(cfg, bdata, rank)
+            f32dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev)
+            bt = {"codebook": codebook, "cnorm": cnorm, "wq": w[0], "wk": w[1], "wv": w[2], "wo": w[3],
+                  "w1": to_dev(np.ascontiguousarray(bdata["w1"].T)), "w2": to_dev(np.ascontiguousarray(bdata["w2"].T)),
+                  "norm1_gain": f32dev(bdata["g1"]), "norm2_gain": f32dev(bdata["g2"])}
+            if bcfg.norm_kind == "layernorm":
+                bt.update(norm1_bias=f32dev(bdata["be1"]), norm2_bias=f32dev(bdata["be2"]))
+            for n in ("bq", "bk", "bv", "bo", "b1", "b2"):
+                if bdata.get(n) is not None:
+                    bt[n] = to_dev(bdata[n])
+            bdesc = B.block_desc(desc, bcfg.norm_kind, bcfg.mlp_kind, bcfg.d_ff, bcfg.eps)
+            bw = B.block_weights(**bt)
+            bx = f32dev(bview["x_local"])
+            bout = torch.empty_like(bx)
+            bws = torch.empty(max(B.astra_block_workspace_bytes(bdesc), 256), dtype=torch.uint8, device=dev)
+            b_args = (bdesc, bw, bx, codes_nl, None, bout, codes_local, None, bws)
+            ms = timed(lambda: B.astra_block_forward(*b_args), 200, warm=100)
+            n1 = 2 * bcfg.d_ff if bcfg.mlp_kind == "swiglu" else bcfg.d_ff
+            mlp_flops = 2.0 * tq * D * n1 + 2.0 * tq * bcfg.d_ff * D
+            result["block"] = {"workload": bcfg.name, "ms": ms, "tokens_per_s": tq / (ms * 1e-3),
+                               "flops": total_flops + mlp_flops, "tflops": (total_flops + mlp_flops) / (ms * 1e-3) / 1e12,
+                               "mfma_frac": (total_flops + mlp_flops) / (ms * 1e-3) / 1e12 / peak,
+                               "mlp_and_norms_ms": ms - ms_per_step, "mlp_tflops": mlp_flops / ((ms - ms_per_step) * 1e-3) / 1e12}
+            del bt, bw, bx, bout, bws, bdata
         # (2) the decode as a kernel of its own (inside the layer it is fused into the projection's operand load):
         #     the HBM-bound step; algorithmic bytes = codes + codebook + rebuilt rows
         t_v = view["n_before"] if cfg.causal else tn

@@ -9,9 +9,7 @@
  *   - Every data pointer is a DEVICE pointer to a dense row-major array, 16-byte
  *     aligned, owned by the caller.  The library allocates no memory, frees nothing
  *     and keeps no pointer after a call returns; scratch comes from `workspace`.
- *     astra_layer_forward creates, on first use per device, one internal stream and
- *     two events on which the encode overlaps the other stages; it is forked from and
- *     joined back into `stream` inside the call.
+ *     All work of a call is enqueued on the caller's stream, in order.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *     only enqueue work: they never synchronise, and the outputs are ready when the
  *     stream reaches that point.  Calls on distinct streams may overlap.
@@ -177,6 +175,64 @@ int astra_layer_forward_profiled(const astra_layer_desc* desc, const void* x_loc
                                  void* y_out, void* codes_local_out,
                                  void* workspace, size_t workspace_bytes, void* stream,
                                  void* const* stage_events);
+
+/* ---- one whole Transformer block on one device -------------------------------------------------
+ * Sec. 3.1: per block, a device quantises its local token embeddings, exchanges indices, attends with
+ * the mixed-precision layer and then runs the position-wise MLP locally, without communication.  The
+ * paper keeps the stock ViT / GPT-2 / Llama blocks around the layer; the pre-norm residual form of
+ * those models is what this entry point computes:
+ *     h     = norm1(x)                 stored in the layer's element type; h is the tensor that is
+ *                                      quantised (codes_local_out) and projected
+ *     r     = x + astra_layer_forward(h, ...)
+ *     x_out = r + mlp(norm2(r))
+ * norm_kind  ASTRA_NORM_LAYER: (v - mean) / sqrt(var + eps) * gain + bias (biased variance)
+ *            ASTRA_NORM_RMS:   v / sqrt(mean(v^2) + eps) * gain (the bias pointers are ignored)
+ * mlp_kind   ASTRA_MLP_GELU_TANH: fc2(gelu(fc1(v))), gelu(a) = a/2 (1 + tanh(sqrt(2/pi)(a + 0.044715 a^3)))
+ *            ASTRA_MLP_GELU_ERF:  the same with gelu(a) = a/2 (1 + erf(a / sqrt 2))
+ *            ASTRA_MLP_SWIGLU:    down(silu(gate(v)) * up(v)), silu(a) = a / (1 + exp(-a)); w1 holds the gate
+ *                                 rows first, then the up rows
+ * The residual stream (x, x_out) is fp32 for both element types; h, the MLP's hidden rows and everything
+ * inside the layer use the element type (products accumulate in fp32).  No positional encoding is applied. */
+enum { ASTRA_NORM_LAYER = 0, ASTRA_NORM_RMS = 1 };
+enum { ASTRA_MLP_GELU_TANH = 0, ASTRA_MLP_GELU_ERF = 1, ASTRA_MLP_SWIGLU = 2 };
+
+typedef struct {
+    astra_layer_desc layer;
+    int32_t norm_kind;
+    int32_t mlp_kind;
+    int32_t d_ff;               /* hidden width of the MLP; a multiple of 64 for bf16 */
+    float eps;                  /* >= 0, inside the square root of both norms */
+} astra_block_desc;
+
+/* Device pointers, owned by the caller.  Matrices and their biases are in the element type and stored
+ * [out_features, in_features]; norm parameters are fp32 [D].  Nullable: every bias, the gains (= 1) and the
+ * norm biases (= 0). */
+typedef struct {
+    const void* codebook;       /* [G, K, dg] */
+    const float* cnorm;         /* [G, K] from astra_vq_prepare */
+    const void *wq, *wk, *wv, *wo, *bq, *bk, *bv, *bo;      /* as for astra_layer_forward */
+    const float *norm1_gain, *norm1_bias, *norm2_gain, *norm2_bias;
+    const void* w1;             /* [d_ff, D], or [2 d_ff, D] for ASTRA_MLP_SWIGLU (gate rows, then up rows) */
+    const void* b1;             /* [d_ff] or [2 d_ff] */
+    const void* w2;             /* [D, d_ff] */
+    const void* b2;             /* [D] */
+} astra_block_weights;
+
+/* Scratch bytes astra_block_forward needs (the layer's workspace included; 0 on an invalid descriptor). */
+size_t astra_block_workspace_bytes(const astra_block_desc* desc);
+
+/*   x               [T_q, D] fp32 residual stream entering the block, class row first when n_cls == 1
+ *   codes_nonlocal  [T_n, G]: the peers' codes of THEIR norm1 outputs for this block
+ *   valid_nonlocal_bits  nullable, as for astra_layer_forward_valid
+ *   x_out           [T_q, D] fp32; may be x itself (in place)
+ *   codes_local_out [T_l, G]: codes of the content rows of h
+ *   h_out           nullable [T_q, D] in the element type: receives h
+ *   workspace       at least astra_block_workspace_bytes(desc) bytes, 256-byte aligned
+ * All shapes are validated before the first launch. */
+int astra_block_forward(const astra_block_desc* desc, const astra_block_weights* weights, const float* x,
+                        const void* codes_nonlocal, const uint64_t* valid_nonlocal_bits,
+                        float* x_out, void* codes_local_out, void* h_out,
+                        void* workspace, size_t workspace_bytes, void* stream);
 
 /* Measurement probe, not part of the method: n_blocks workgroups of 512 threads each run `iters` rounds of
  * four independent 32x32x16 bf16 MFMAs per wavefront on register operands (no memory traffic in the loop)

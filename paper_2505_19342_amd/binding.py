@@ -16,7 +16,12 @@ _lib = None
 EXPORTS = ("astra_vq_prepare", "astra_vq_encode", "astra_vq_decode", "astra_mixed_attention",
            "astra_mixed_attention_valid", "astra_layer_forward_valid",
            "astra_layer_workspace_bytes", "astra_layer_encode_fused", "astra_layer_forward", "astra_layer_forward_profiled",
+           "astra_block_workspace_bytes", "astra_block_forward",
            "astra_probe_mfma_bf16", "astra_status_string", "astra_version")
+ASTRA_NORM_LAYER, ASTRA_NORM_RMS = 0, 1
+ASTRA_MLP_GELU_TANH, ASTRA_MLP_GELU_ERF, ASTRA_MLP_SWIGLU = 0, 1, 2
+NORM_KINDS = {"layernorm": ASTRA_NORM_LAYER, "rmsnorm": ASTRA_NORM_RMS}
+MLP_KINDS = {"gelu_tanh": ASTRA_MLP_GELU_TANH, "gelu_erf": ASTRA_MLP_GELU_ERF, "swiglu": ASTRA_MLP_SWIGLU}
 
 
 class AstraError(RuntimeError):
@@ -37,6 +42,19 @@ class AttnDesc(ctypes.Structure):
 
 class LayerDesc(ctypes.Structure):
     _fields_ = [("vq", VqDesc), ("attn", AttnDesc)]
+
+
+class BlockDesc(ctypes.Structure):
+    _fields_ = [("layer", LayerDesc), ("norm_kind", ctypes.c_int32), ("mlp_kind", ctypes.c_int32), ("d_ff", ctypes.c_int32),
+                ("eps", ctypes.c_float)]
+
+
+_BLOCK_WEIGHT_NAMES = ("codebook", "cnorm", "wq", "wk", "wv", "wo", "bq", "bk", "bv", "bo",
+                       "norm1_gain", "norm1_bias", "norm2_gain", "norm2_bias", "w1", "b1", "w2", "b2")
+
+
+class BlockWeights(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in _BLOCK_WEIGHT_NAMES]
 
 
 def load(build_if_missing: bool = True):
@@ -66,6 +84,10 @@ def load(build_if_missing: bool = True):
     lib.astra_layer_forward.argtypes = [ctypes.POINTER(LayerDesc)] + [vp] * 15 + [ctypes.c_size_t, vp]
     lib.astra_layer_forward_profiled.argtypes = [ctypes.POINTER(LayerDesc)] + [vp] * 15 + [ctypes.c_size_t, vp,
                                                                                      ctypes.POINTER(ctypes.c_void_p)]
+    lib.astra_block_workspace_bytes.argtypes = [ctypes.POINTER(BlockDesc)]
+    lib.astra_block_workspace_bytes.restype = ctypes.c_size_t
+    lib.astra_block_forward.argtypes = [ctypes.POINTER(BlockDesc), ctypes.POINTER(BlockWeights)] + [vp] * 7 + [ctypes.c_size_t, vp]
+    lib.astra_block_forward.restype = ctypes.c_int
     lib.astra_status_string.argtypes = [ctypes.c_int]
     lib.astra_status_string.restype = ctypes.c_char_p
     lib.astra_version.restype = ctypes.c_int
@@ -147,6 +169,31 @@ def astra_layer_workspace_bytes(desc: LayerDesc) -> int:
     return int(load().astra_layer_workspace_bytes(ctypes.byref(desc)))
 
 
+def astra_block_workspace_bytes(desc: BlockDesc) -> int:
+    return int(load().astra_block_workspace_bytes(ctypes.byref(desc)))
+
+
+def block_weights(**tensors) -> BlockWeights:
+    """Device tensors by the field names of astra_block_weights (missing or None = NULL).  The caller keeps the
+    tensors alive: the structure holds bare addresses."""
+    unknown = set(tensors) - set(_BLOCK_WEIGHT_NAMES)
+    if unknown:
+        raise AstraError(f"unknown block weight(s): {sorted(unknown)}")
+    w = BlockWeights()
+    for n in _BLOCK_WEIGHT_NAMES:
+        p = _ptr(tensors.get(n))
+        setattr(w, n, p.value if p is not None else None)
+    return w
+
+
+def astra_block_forward(desc: BlockDesc, weights: BlockWeights, x, codes_nonlocal, valid_bits, x_out, codes_local_out, h_out,
+                        workspace):
+    nbytes = workspace.numel() * workspace.element_size()
+    _check(load().astra_block_forward(ctypes.byref(desc), ctypes.byref(weights), _ptr(x), _ptr(codes_nonlocal), _ptr(valid_bits),
+                                      _ptr(x_out), _ptr(codes_local_out), _ptr(h_out), _ptr(workspace), nbytes, _stream()),
+           "astra_block_forward")
+
+
 def astra_probe_mfma_bf16(out, n_blocks: int, iters: int):
     """out: float32 device tensor with at least n_blocks * 512 elements."""
     _check(load().astra_probe_mfma_bf16(_ptr(out), n_blocks, iters, _stream()), "astra_probe_mfma_bf16")
@@ -221,3 +268,7 @@ def attn_desc(dtype: str, n_q_heads: int, n_kv_heads: int, head_dim: int, n_cls:
               causal: bool, n_before: int = 0, scale: float = 0.0) -> AttnDesc:
     return AttnDesc(ASTRA_BF16 if dtype == "bf16" else ASTRA_F32, n_q_heads, n_kv_heads, head_dim, n_cls, n_local,
                     n_nonlocal, int(bool(causal)), n_before if causal else 0, scale)
+
+
+def block_desc(layer: LayerDesc, norm_kind: str, mlp_kind: str, d_ff: int, eps: float) -> BlockDesc:
+    return BlockDesc(layer, NORM_KINDS[norm_kind], MLP_KINDS[mlp_kind], d_ff, eps)

@@ -88,6 +88,35 @@ static int make_plan(const astra_layer_desc* desc, LayerPlan* pl) {
     return ASTRA_OK;
 }
 
+struct BlockPlan {
+    LayerPlan layer;
+    int d_ff;
+    size_t off_h, off_a, off_a2, total;     // after the layer's own workspace: normalised rows, MLP hidden rows
+};
+
+static int make_block_plan(const astra_block_desc* desc, BlockPlan* bp) {
+    if (!desc) return ASTRA_ERR_NULL;
+    int rc = make_plan(&desc->layer, &bp->layer);
+    if (rc) return rc;
+    if (desc->norm_kind != ASTRA_NORM_LAYER && desc->norm_kind != ASTRA_NORM_RMS) return ASTRA_ERR_SHAPE;
+    if (desc->mlp_kind != ASTRA_MLP_GELU_TANH && desc->mlp_kind != ASTRA_MLP_GELU_ERF && desc->mlp_kind != ASTRA_MLP_SWIGLU)
+        return ASTRA_ERR_SHAPE;
+    if (desc->d_ff <= 0 || desc->d_ff > (1 << 24) || !(desc->eps >= 0.f)) return ASTRA_ERR_SHAPE;
+    const int dtype = desc->layer.vq.dtype;
+    if (dtype == ASTRA_BF16 && desc->d_ff % 64 != 0) return ASTRA_ERR_UNSUPPORTED;     // d_ff is a contraction length
+    const int eb = elem_bytes(dtype);
+    const LayerPlan& pl = bp->layer;
+    bp->d_ff = desc->d_ff;
+    size_t off = pl.total;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    bp->off_h = take((size_t)pl.Tq * pl.D * eb);
+    bp->off_a = take((size_t)pl.Tq * desc->d_ff * eb);
+    // fp32 has no fused gate: the first GEMM leaves [T_q, 2 d_ff], a second kernel forms the product
+    bp->off_a2 = take(dtype != ASTRA_BF16 && desc->mlp_kind == ASTRA_MLP_SWIGLU ? (size_t)pl.Tq * 2 * desc->d_ff * eb : 0);
+    bp->total = off;
+    return ASTRA_OK;
+}
+
 }  // namespace astra
 
 using namespace astra;
@@ -166,7 +195,8 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
                               const void* wq, const void* wk, const void* wv, const void* wo,
                               const void* bq, const void* bk, const void* bv, const void* bo,
                               void* y_out, void* codes_local_out, void* workspace, size_t workspace_bytes, void* stream,
-                              void* const* ev, int* plan_encode_fused = nullptr, const uint64_t* valid_bits = nullptr) {
+                              void* const* ev, int* plan_encode_fused = nullptr, const uint64_t* valid_bits = nullptr,
+                              const float* residual = nullptr) {
     // plan_encode_fused: validate the shapes and report whether the projection launch would carry the encode;
     // nothing is launched and no pointer is dereferenced
     const bool plan_only = plan_encode_fused != nullptr;
@@ -262,6 +292,7 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     GemmProblem po = {};
     po.a = O; po.b = wo; po.bias = bo; po.c = y_out; po.M = pl.Tq; po.N = pl.D; po.K = pl.dq; po.lda = pl.dq; po.ldc = pl.D;
     po.c_mode = kCF32;      // y leaves the layer as the fp32 accumulator, for both element types
+    po.residual = residual; // inside a block: y_out = residual + layer output
     rc = launch_gemm_batch(vq.dtype, &po, 1, s);
     mark(3, s);
     mark(4, s);
@@ -296,6 +327,78 @@ int astra_layer_forward_valid(const astra_layer_desc* desc, const void* x_local,
                               void* y_out, void* codes_local_out, void* workspace, size_t workspace_bytes, void* stream) {
     return layer_forward_impl(desc, x_local, codes_nonlocal, codebook, cnorm, wq, wk, wv, wo, bq, bk, bv, bo, y_out,
                               codes_local_out, workspace, workspace_bytes, stream, nullptr, nullptr, valid_nonlocal_bits);
+}
+
+size_t astra_block_workspace_bytes(const astra_block_desc* desc) {
+    BlockPlan bp;
+    if (make_block_plan(desc, &bp) != ASTRA_OK) return 0;
+    return bp.total;
+}
+
+int astra_block_forward(const astra_block_desc* desc, const astra_block_weights* w, const float* x, const void* codes_nonlocal,
+                        const uint64_t* valid_nonlocal_bits, float* x_out, void* codes_local_out, void* h_out,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+    BlockPlan bp;
+    int rc = make_block_plan(desc, &bp);
+    if (rc) return rc;
+    const LayerPlan& pl = bp.layer;
+    if (pl.Tq == 0) return ASTRA_OK;
+    if (!w || !x || !x_out) return ASTRA_ERR_NULL;
+    if (!w->codebook || !w->cnorm || !w->wq || !w->wk || !w->wv || !w->wo || !w->w1 || !w->w2) return ASTRA_ERR_NULL;
+    if (desc->layer.attn.n_local > 0 && !codes_local_out) return ASTRA_ERR_NULL;
+    if (pl.Tn_vis > 0 && !codes_nonlocal) return ASTRA_ERR_NULL;
+    if (!workspace || workspace_bytes < bp.total) return ASTRA_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    const int dtype = desc->layer.vq.dtype;
+    char* ws = (char*)workspace;
+    void* h = h_out ? h_out : (void*)(ws + bp.off_h);
+    void* a = ws + bp.off_a;
+    const int F = bp.d_ff;
+    // every launch of the block is validated before the first one is made
+    int fused = 0;
+    rc = layer_forward_impl(&desc->layer, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+                            nullptr, nullptr, nullptr, nullptr, nullptr, 0, nullptr, nullptr, &fused);
+    if (rc) return rc;
+
+    // x_out = r + mlp(h2), h2 = norm2(r) in the slot of the normalised rows of the first half (dead by then, unless
+    // the caller asked for them in h_out)
+    void* h2 = ws + bp.off_h;
+    GemmProblem g1 = {};
+    g1.a = h2; g1.b = w->w1; g1.bias = w->b1; g1.c = a; g1.M = pl.Tq; g1.K = pl.D; g1.lda = pl.D;
+    if (desc->mlp_kind == ASTRA_MLP_SWIGLU) {
+        g1.N = 2 * F;
+        if (dtype == ASTRA_BF16) { g1.c_mode = kCSwiGLU; g1.ldc = F; }
+        else { g1.c = ws + bp.off_a2; g1.c_mode = kCF32; g1.ldc = 2 * F; }
+    } else {
+        g1.N = F; g1.ldc = F;
+        g1.c_mode = dtype == ASTRA_BF16 ? kCBf16 : kCF32;
+        g1.act = desc->mlp_kind == ASTRA_MLP_GELU_TANH ? kActGeluTanh : kActGeluErf;
+    }
+    GemmProblem g2 = {};
+    g2.a = a; g2.b = w->w2; g2.bias = w->b2; g2.c = x_out; g2.M = pl.Tq; g2.N = pl.D; g2.K = F; g2.lda = F; g2.ldc = pl.D;
+    g2.c_mode = kCF32;
+    g2.residual = x_out;
+    rc = launch_gemm_batch(dtype, &g1, 1, s, nullptr, nullptr, true);
+    if (rc) return rc;
+    rc = launch_gemm_batch(dtype, &g2, 1, s, nullptr, nullptr, true);
+    if (rc) return rc;
+
+    // h = norm1(x) in the layer's element type: the tensor that is quantised and projected
+    rc = launch_norm(dtype, desc->norm_kind, x, pl.Tq, pl.D, desc->eps, w->norm1_gain, w->norm1_bias, h, s);
+    if (rc) return rc;
+    // r = x + layer(h), written to x_out by the output projection's epilogue
+    rc = layer_forward_impl(&desc->layer, h, codes_nonlocal, w->codebook, w->cnorm, w->wq, w->wk, w->wv, w->wo, w->bq, w->bk, w->bv,
+                            w->bo, x_out, codes_local_out, workspace, pl.total, stream, nullptr, nullptr, valid_nonlocal_bits, x);
+    if (rc) return rc;
+    rc = launch_norm(dtype, desc->norm_kind, x_out, pl.Tq, pl.D, desc->eps, w->norm2_gain, w->norm2_bias, h2, s);
+    if (rc) return rc;
+    rc = launch_gemm_batch(dtype, &g1, 1, s);
+    if (rc) return rc;
+    if (desc->mlp_kind == ASTRA_MLP_SWIGLU && dtype != ASTRA_BF16) {
+        rc = launch_swiglu_f32((const float*)(ws + bp.off_a2), pl.Tq, F, (float*)a, s);
+        if (rc) return rc;
+    }
+    return launch_gemm_batch(dtype, &g2, 1, s);
 }
 
 int astra_layer_forward_profiled(const astra_layer_desc* desc, const void* x_local, const void* codes_nonlocal,

@@ -119,7 +119,10 @@ int launch_vq_decode(const astra_vq_desc& d, const void* codes, int64_t n_tokens
 // rows of A are not read from `a` but rebuilt on the fly: A[m, g*dg + j] = codebook[g, codes[m, g], j].
 enum { kCBf16 = 0,          // bf16, row-major [M, ldc]
        kCF32 = 1,           // fp32 (the unrounded accumulator), row-major [M, ldc]
-       kCTransposedV = 2 }; // bf16, C^T as [N, ldc] with the M index permuted inside blocks of 16 (see vt_pos)
+       kCTransposedV = 2,   // bf16, C^T as [N, ldc] with the M index permuted inside blocks of 16 (see vt_pos)
+       kCSwiGLU = 3 };      // B = [gate rows | up rows] ([N, K], N = 2F): C[m, f] = silu(A.gate_f) * (A.up_f), [M, ldc] of F columns
+// applied to A.B^T + bias before the store (kCBf16 and kCF32 stores); the constants are those of the stock GPT-2 / ViT MLPs
+enum { kActNone = 0, kActGeluTanh = 1, kActGeluErf = 2 };
 
 struct GemmProblem {
     const void* a;
@@ -132,6 +135,8 @@ struct GemmProblem {
     int32_t lda, ldc;
     int32_t G, Kc, dg, code_bytes;
     int32_t c_mode;     // how C is stored (bf16 problems; fp32 problems always store fp32 row-major)
+    int32_t act;        // kAct*
+    const float* residual;   // kCF32 only, nullable: fp32 [M, ldc] added to the result (may be C itself)
 };
 constexpr int kMaxGemmProblems = 6;
 struct EncodeJob;
@@ -141,6 +146,13 @@ int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hi
                       bool* enc_fused = nullptr, bool plan_only = false);
 extern int g_gemm_force_cfg;
 extern const int g_gemm_problem_size;
+
+// Row-wise LayerNorm (kind 0) / RMSNorm (kind 1) of the fp32 residual stream x [T, D] into the element type of the layer
+// (out [T, D]); gain, bias fp32 [D], nullable.
+int launch_norm(int dtype, int kind, const float* x, int64_t T, int D, float eps, const float* gain, const float* bias, void* out,
+                hipStream_t s);
+// out[t, f] = silu(a[t, f]) * a[t, F + f] for fp32 a [T, 2F]
+int launch_swiglu_f32(const float* a, int64_t T, int F, float* out, hipStream_t s);
 
 struct AttnParams {
     const void* q;        // [T_q, H_q, dh]

@@ -50,6 +50,21 @@ __device__ __forceinline__ int xcd_remap(int wg, int total) {
 
 __device__ __forceinline__ int swz(int r) { return (r >> 1) & 7; }
 
+// Activations of the position-wise MLP that follows the attention layer inside a block (paper Sec. 3.1), applied in
+// the epilogue.  x * sigmoid(2u) is 0.5 x (1 + tanh u).  FAST uses the hardware exponential (results are rounded to
+// bf16 afterwards); otherwise the library routines.
+template <bool FAST>
+__device__ __forceinline__ float silu(float v) { return v / (1.f + (FAST ? __expf(-v) : expf(-v))); }
+template <bool FAST>
+__device__ __forceinline__ float apply_act(float v, int act) {
+    if (act == kActGeluTanh) {
+        const float u = 0.7978845608028654f * (v + 0.044715f * v * v * v);
+        return FAST ? v / (1.f + __expf(-2.f * u)) : 0.5f * v * (1.f + tanhf(u));
+    }
+    if (act == kActGeluErf) return 0.5f * v * (1.f + erff(v * 0.7071067811865476f));
+    return v;
+}
+
 // Fused launch of T GEMM tiles and E encode workgroups (E a multiple of 8): every XCD gets a contiguous range of
 // tiles, as with xcd_remap, followed by E/8 encode workgroups, so both kinds of work are spread over all XCDs.
 struct FusedId {
@@ -69,7 +84,9 @@ __device__ __forceinline__ FusedId fused_id(int wg, int T, int E) {
 // which is also the order the attention kernel's P^T operand keeps its 16 keys in.
 __device__ __forceinline__ int vt_pos(int o) { return 8 * ((o >> 2) & 1) + (o & 3) + 4 * (o >> 3); }
 
-template <int BM, int BN, int WM, int WN, bool CODE16, bool ENC = false>
+// MLP: the instantiation carries the epilogues of the block's MLP (activation, gated product, residual add); the
+// projection launches of the attention layer use the instantiation without them.
+template <int BM, int BN, int WM, int WN, bool CODE16, bool ENC = false, bool MLP = false>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_bf16_kernel(const GemmBatch batch) {
     constexpr int THREADS = 64 * WM * WN;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;        // MFMA tiles per wavefront
@@ -146,6 +163,15 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_bf16_kernel(const GemmBa
     for (int it = 0; it < PB; ++it) {
         int rb = n0 + r0 + RPP * it;
         rb = rb < N ? rb : N - 1;
+        if (MLP && TN % 2 == 0 && P.c_mode == kCSwiGLU) {
+            // tile row r of B -> weight row such that, in every wavefront, MFMA column tiles b < TN/2 hold gate rows and
+            // tiles b + TN/2 the up rows of the same BN/WN/2 output columns: both factors of an output meet in one lane
+            const int rr = r0 + RPP * it, Fh = N >> 1;
+            const int wn_r = rr / (32 * TN), b_r = (rr % (32 * TN)) / 32, i_r = rr % 32;
+            int col = n0 / 2 + wn_r * (16 * TN) + (b_r % (TN / 2)) * 32 + i_r;
+            col = col < Fh ? col : Fh - 1;
+            rb = (b_r >= TN / 2 ? Fh : 0) + col;
+        }
         boff[it] = ((uint32_t)rb * (uint32_t)K + kc * 8) * 2u;
     }
     int k_code = kc * 8;              // contraction index of this thread's piece in the tile whose codes are fetched next
@@ -292,6 +318,27 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_bf16_kernel(const GemmBa
 
     // epilogue.  acc[a][b][v] is C[m, n] with m = wave row base + 32a + acc_row(v, h), n = wave column base + 32b + lane % 32.
     const uint16_t* __restrict__ bias = (const uint16_t*)P.bias;
+    if (MLP && P.c_mode == kCSwiGLU) {
+        if constexpr (MLP && TN % 2 == 0) {
+            const int Fh = N >> 1;
+            uint16_t* __restrict__ C = (uint16_t*)P.c;
+#pragma unroll
+            for (int b = 0; b < TN / 2; ++b) {
+                const int col = n0 / 2 + wn * (16 * TN) + b * 32 + i32;
+                if (col >= Fh) continue;
+                const float bg = bias ? bf16_bits_to_f32(bias[col]) : 0.f, bu = bias ? bf16_bits_to_f32(bias[Fh + col]) : 0.f;
+#pragma unroll
+                for (int a = 0; a < TM; ++a)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int m = m0 + wm * (BM / WM) + a * 32 + acc_row(v, h);
+                        if (m < M) C[(int64_t)m * P.ldc + col] = f32_to_bf16_bits(silu<true>(acc[a][b][v] + bg) * (acc[a][b + TN / 2][v] + bu));
+                    }
+            }
+        }
+        return;
+    }
+    const int act = MLP ? P.act : kActNone;
 #pragma unroll
     for (int b = 0; b < TN; ++b) {
         const int n = n0 + wn * (BN / WN) + b * 32 + i32;
@@ -317,13 +364,18 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_bf16_kernel(const GemmBa
                     }
                 }
         } else if (P.c_mode == kCF32) {
-            float* __restrict__ C = (float*)P.c;
+            float* C = (float*)P.c;                       // may be the residual itself: no restrict
+            const float* R = MLP ? P.residual : nullptr;
 #pragma unroll
             for (int a = 0; a < TM; ++a)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int m = m0 + wm * (BM / WM) + a * 32 + acc_row(v, h);
-                    if (m < M) C[(int64_t)m * P.ldc + n] = acc[a][b][v] + bv;
+                    if (m < M) {
+                        const int64_t at = (int64_t)m * P.ldc + n;
+                        const float r = apply_act<true>(acc[a][b][v] + bv, act);
+                        C[at] = R ? r + R[at] : r;
+                    }
                 }
         } else {
             uint16_t* __restrict__ C = (uint16_t*)P.c;
@@ -332,7 +384,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_bf16_kernel(const GemmBa
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int m = m0 + wm * (BM / WM) + a * 32 + acc_row(v, h);
-                    if (m < M) C[(int64_t)m * P.ldc + n] = f32_to_bf16_bits(acc[a][b][v] + bv);
+                    if (m < M) C[(int64_t)m * P.ldc + n] = f32_to_bf16_bits(apply_act<true>(acc[a][b][v] + bv, act));
                 }
         }
     }
@@ -401,7 +453,7 @@ __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmBatch batch)
         }
         __syncthreads();
     }
-    float* __restrict__ C = (float*)P.c;
+    float* C = (float*)P.c;                               // may be the residual itself: no restrict
     const float* __restrict__ bias = (const float*)P.bias;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -410,7 +462,11 @@ __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmBatch batch)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int n = n0 + tx * 4 + j;
-            if (n < N) C[(int64_t)m * P.ldc + n] = acc[i][j] + (bias ? bias[n] : 0.f);
+            if (n < N) {
+                const int64_t at = (int64_t)m * P.ldc + n;
+                const float r = apply_act<false>(acc[i][j] + (bias ? bias[n] : 0.f), P.act);
+                C[at] = P.residual ? r + P.residual[at] : r;
+            }
         }
     }
 }
@@ -428,6 +484,9 @@ static int fill_batch(GemmBatch& batch, int dtype, const GemmProblem* problems, 
             // whole 64-wide contraction tiles; 16-byte operand pieces must not straddle rows or codewords
             if (p.K % kBK != 0 || (!p.codes && p.lda % 8 != 0) || (p.codes && p.dg % 8 != 0)) return ASTRA_ERR_UNSUPPORTED;
             if (p.c_mode == kCTransposedV && (p.ldc % 64 != 0 || p.ldc < p.M)) return ASTRA_ERR_SHAPE;
+            if (p.c_mode == kCSwiGLU && (p.N % 2 != 0 || p.ldc < p.N / 2)) return ASTRA_ERR_SHAPE;
+            if (p.c_mode != kCF32 && p.residual) return ASTRA_ERR_UNSUPPORTED;
+            if ((p.c_mode == kCTransposedV || p.c_mode == kCSwiGLU) && p.act != kActNone) return ASTRA_ERR_UNSUPPORTED;
             // operands are addressed with 32-bit byte offsets from their base
             const int64_t lim = (int64_t)1 << 31;
             if ((int64_t)p.M * p.lda * 2 >= lim || (int64_t)p.N * p.K * 2 >= lim) return ASTRA_ERR_UNSUPPORTED;
@@ -463,9 +522,26 @@ int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hi
         gemm_nt_f32_kernel<<<total, 256, 0, s>>>(batch);
         return launch_status();
     }
-    bool code16 = false;
-    for (int i = 0; i < n_problems; ++i)
+    bool code16 = false, mlp = false;
+    for (int i = 0; i < n_problems; ++i) {
         if (problems[i].codes && problems[i].code_bytes == 2) code16 = true;
+        if (problems[i].c_mode == kCSwiGLU || problems[i].act != kActNone || problems[i].residual) mlp = true;
+    }
+    if (mlp) {
+        // the MLP's GEMMs and the residual-adding output projection: plain A rows, one problem per launch
+        if (n_problems != 1 || problems[0].codes) return ASTRA_ERR_UNSUPPORTED;
+        int rc = fill_batch(batch, dtype, problems, n_problems, 256, 256, &total);
+        if (rc) return rc;
+        if (total >= 128) {
+            if (!plan_only) gemm_nt_bf16_kernel<256, 256, 2, 4, false, false, true><<<total, 512, 0, s>>>(batch);
+            return plan_only ? ASTRA_OK : launch_status();
+        }
+        rc = fill_batch(batch, dtype, problems, n_problems, 128, 128, &total);
+        if (rc) return rc;
+        if (total == 0 || plan_only) return ASTRA_OK;
+        gemm_nt_bf16_kernel<128, 128, 2, 2, false, false, true><<<total, 256, 0, s>>>(batch);
+        return launch_status();
+    }
     // Large tiles quarter the operand traffic per flop; use them once they still fill most of the chip.
     int rc = fill_batch(batch, dtype, problems, n_problems, 256, 256, &total);
     if (rc) return rc;

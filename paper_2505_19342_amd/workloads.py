@@ -140,3 +140,53 @@ def device_view(cfg: LayerConfig, data: dict, rank: int) -> dict:
     x_nonlocal = np.concatenate([x[:lo], x[hi:]], axis=0)
     return {"x_local": np.ascontiguousarray(x_local), "x_nonlocal": np.ascontiguousarray(x_nonlocal),
             "n_before": lo, "rank": rank}
+
+
+# ---- whole blocks (Sec. 3.1: the layer inside the stock pre-norm block of each model) ------------------------
+@dataclass(frozen=True)
+class BlockConfig:
+    name: str
+    layer: LayerConfig
+    norm_kind: str        # "layernorm" | "rmsnorm"
+    mlp_kind: str         # "gelu_tanh" | "gelu_erf" | "swiglu"
+    d_ff: int
+    eps: float
+    biases: bool          # linear layers carry biases (ViT, GPT-2) or not (Llama)
+
+
+TINY_VIT_BLOCK = BlockConfig("tiny_vit_block_f32", TINY_VIT, "layernorm", "gelu_erf", 768, 1e-6, True)
+VIT_BASE_BLOCK = BlockConfig("vit_base_block_bf16", VIT_BASE, "layernorm", "gelu_erf", 3072, 1e-6, True)
+GPT2_SMALL_BLOCK = BlockConfig("gpt2_small_block_bf16", GPT2_SMALL, "layernorm", "gelu_tanh", 3072, 1e-5, True)
+LLAMA3_8B_BLOCK = BlockConfig("llama3_8b_block_bf16", LLAMA3_8B, "rmsnorm", "swiglu", 14336, 1e-5, False)
+BLOCK_CONFIGS = {c.name: c for c in (TINY_VIT_BLOCK, VIT_BASE_BLOCK, GPT2_SMALL_BLOCK, LLAMA3_8B_BLOCK)}
+
+
+def generate_block(bcfg: BlockConfig) -> dict:
+    """Tensors of one block call.  Everything generate() gives for the layer (codebook, wq..wo; its "x" and "cls"
+    become the fp32 residual stream after a rescale and a per-channel offset, and are NOT rounded: the stream is fp32
+    for both element types), plus norm parameters (fp32), MLP weights w1 [D, d_ff] or [D, 2 d_ff] (gate | up) and
+    w2 [d_ff, D] in the paper's orientation, and biases when the model has them."""
+    cfg = bcfg.layer
+    out = generate(cfg)
+    rng = np.random.default_rng(cfg.seed + 7919)
+    d, f = cfg.d_model, bcfg.d_ff
+    offset = (0.3 * rng.standard_normal(d)).astype(np.float32)
+    stream_rng = np.random.default_rng(cfg.seed)            # the same draws as generate(), kept unrounded
+    out["x"] = (1.7 * _embeddings(stream_rng, cfg.seq_len, d, cfg.dist) + offset).astype(np.float32)
+    if cfg.n_cls:
+        out["cls"] = (1.7 * stream_rng.standard_normal((cfg.n_dev, d), dtype=np.float32) + offset).astype(np.float32)
+    for name in ("g1", "g2"):
+        out[name] = (1.0 + 0.1 * rng.standard_normal(d)).astype(np.float32)
+    for name in ("be1", "be2"):
+        out[name] = (0.1 * rng.standard_normal(d)).astype(np.float32)
+    n1 = 2 * f if bcfg.mlp_kind == "swiglu" else f
+    mats = {"w1": (0.02 * rng.standard_normal((d, n1), dtype=np.float32)).astype(np.float32),
+            "w2": (0.02 * rng.standard_normal((f, d), dtype=np.float32)).astype(np.float32)}
+    if bcfg.biases:
+        dq, dkv = cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
+        for name, n in (("bq", dq), ("bk", dkv), ("bv", dkv), ("bo", d), ("b1", n1), ("b2", d)):
+            mats[name] = (0.1 * rng.standard_normal(n)).astype(np.float32)
+    if cfg.dtype == "bf16":
+        mats = {k: round_to_bf16(v) for k, v in mats.items()}
+    out.update(mats)
+    return out

@@ -135,3 +135,49 @@ def compare_codes(gpu_codes, ref_codes, gap, tol=1e-5):
     bad = diff & ~(gap < tol)
     assert not bad.any(), f"{int(bad.sum())} codes differ away from near-ties (of {diff.size}); first at {np.argwhere(bad)[0]}"
     return int(diff.sum())
+
+
+class BlockOnGpu:
+    """Device-resident tensors of one block call (matrices stored [out, in] as the ABI asks; the residual stream and
+    the norm parameters are fp32 for both element types)."""
+
+    def __init__(self, bcfg, data, x_local, codes_nonlocal, n_before, in_place=False, want_h=True):
+        cfg = bcfg.layer
+        dt = cfg.dtype
+        self.bcfg, self.cfg = bcfg, cfg
+        G, K = cfg.n_groups, cfg.codebook_size
+        Tq, Tn = x_local.shape[0], codes_nonlocal.shape[0]
+        layer = B.LayerDesc(
+            B.vq_desc(dt, cfg.d_model, G, K),
+            B.attn_desc(dt, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n_cls, Tq - cfg.n_cls, Tn, cfg.causal, n_before))
+        self.desc = B.block_desc(layer, bcfg.norm_kind, bcfg.mlp_kind, bcfg.d_ff, bcfg.eps)
+        f32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(DEV)
+        self.x = f32(x_local)
+        self.codes_nonlocal = codes_to_dev(codes_nonlocal, K) if Tn > 0 else None
+        t = {"codebook": to_dev(data["codebook"], dt)}
+        t["cnorm"] = torch.empty((G, K), dtype=torch.float32, device=DEV)
+        B.astra_vq_prepare(layer.vq, t["codebook"], t["cnorm"])
+        for n in ("wq", "wk", "wv", "wo", "w1", "w2"):
+            t[n] = to_dev(np.ascontiguousarray(data[n].T), dt)
+        for n in ("bq", "bk", "bv", "bo", "b1", "b2"):
+            if data.get(n) is not None:
+                t[n] = to_dev(data[n], dt)
+        for n, src in (("norm1_gain", "g1"), ("norm1_bias", "be1"), ("norm2_gain", "g2"), ("norm2_bias", "be2")):
+            if data.get(src) is not None and not (bcfg.norm_kind == "rmsnorm" and n.endswith("bias")):
+                t[n] = f32(data[src])
+        self.tensors = t                                   # keeps the device memory alive
+        self.weights = B.block_weights(**t)
+        self.x_out = self.x if in_place else torch.empty_like(self.x)
+        self.codes_local = empty_codes(Tq - cfg.n_cls, G, K)
+        self.h = empty_like_dtype((Tq, cfg.d_model), dt) if want_h else None
+        self.workspace = torch.empty(max(B.astra_block_workspace_bytes(self.desc), 256), dtype=torch.uint8, device=DEV)
+
+    def run(self, valid_nonlocal=None):
+        vb = None if valid_nonlocal is None else valid_bits_to_dev(valid_nonlocal)
+        B.astra_block_forward(self.desc, self.weights, self.x, self.codes_nonlocal, vb, self.x_out, self.codes_local, self.h,
+                              self.workspace)
+
+    def results(self):
+        torch.cuda.synchronize()
+        return (self.x_out.cpu().numpy(), codes_to_host(self.codes_local, self.cfg.codebook_size),
+                None if self.h is None else to_host(self.h))

@@ -1,0 +1,174 @@
+"""GPU parity: one whole Transformer block on one device (norm1 -> Astra layer -> residual -> norm2 -> MLP ->
+residual; Sec. 3.1) through astra_block_forward against the CPU oracle, on the seeded block workloads.
+Bars: block output max-abs <= 1e-4 (fp32); for bf16 the layer's 2e-2 plus 2^-6 rms(out - x): the two bf16-stored
+MLP intermediates (norm2 output, hidden activation) each carry a relative rounding error of up to 2^-9 per element,
+which reaches every output as a random sum proportional to the output's own scale (about 2^-9 * 1.5 rms, largest of
+millions of outputs about 5.3 sigma; tests/test_oracle_block.py reproduces the figure on the CPU).  The normalised tensor h, which is what gets quantised:
+fp32 within 1e-5; bf16 bit-equal to the oracle's (fp64 norm, rounded once) except for a counted few elements that
+sit on a rounding boundary and come out one bf16 step away (or within 2e-6 where the result cancels to near zero).  Codes of group slices whose h agrees with the
+oracle's: bit-exact except near-ties (oracle gap < 1e-5 relative); codes of the few slices whose h differs: any
+codeword that the differing h can justify (its distance to the oracle's h exceeds the best by no more than
+2 |e| (|h - c'| + |h - c*|), e the difference of the two h slices)."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2505_19342_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+OUT_TOL = {"f32": 1e-4, "bf16": 2e-2}
+NEAR_TIE = 1e-5
+
+
+def peer_codes(bcfg, data, x_nonlocal):
+    """What the peers would have sent: the codes of THEIR norm1 outputs, in the layer's element type."""
+    cfg = bcfg.layer
+    h = oracle.norm(x_nonlocal, bcfg.norm_kind, bcfg.eps, data["g1"], data["be1"]).astype(np.float32)
+    if cfg.dtype == "bf16":
+        h = wl.round_to_bf16(h)
+    return oracle.vq_encode(h, data["codebook"])
+
+
+def check_h_and_codes(cfg, h, h_ref, codes, codes_ref, gap, codebook):
+    G, K, dg = codebook.shape
+    n_cls = cfg.n_cls
+    if cfg.dtype == "f32":
+        assert np.abs(h - h_ref).max() <= 1e-5
+        same = np.ones(codes.shape, dtype=bool)
+    else:
+        diff = h != h_ref
+        # one bf16 step at most (2^-7 relative is the largest step next to a value); where gain * v + bias cancels to
+        # a tiny value, the fp32 rounding of the O(1) terms (a few 1e-7) spans several steps of the result
+        assert np.all(np.abs(h - h_ref)[diff] <= np.abs(h_ref)[diff] * 2.0 ** -7 + 2e-6)
+        assert diff.mean() <= 1e-3, f"{diff.mean():.2e} of h differs from the oracle's rounding"
+        same = ~diff[n_cls:].reshape(-1, G, dg).any(-1)
+    d = codes != codes_ref
+    bad = d & same & ~(gap < NEAR_TIE)
+    assert not bad.any(), f"{int(bad.sum())} codes differ away from near-ties; first at {np.argwhere(bad)[0]}"
+    n_tie = int((d & same).sum())
+    # slices whose h differs: the chosen codeword must be justified by the differing h
+    ts, gs = np.nonzero(d & ~same)
+    for t, g in zip(ts, gs):
+        hs = h_ref[n_cls + t, g * dg:(g + 1) * dg].astype(np.float64)
+        e = h[n_cls + t, g * dg:(g + 1) * dg].astype(np.float64) - hs
+        r_gpu = np.linalg.norm(hs - codebook[g, codes[t, g]])
+        r_ref = np.linalg.norm(hs - codebook[g, codes_ref[t, g]])
+        assert r_gpu ** 2 - r_ref ** 2 <= 2 * np.linalg.norm(e) * (r_gpu + r_ref) + NEAR_TIE * r_ref ** 2
+    return n_tie, int((~same).sum()), len(ts)
+
+
+def run_case(bcfg, rank, in_place=False, valid=None):
+    from gpu_util import BlockOnGpu
+    cfg = bcfg.layer
+    data = wl.generate_block(bcfg)
+    view = wl.device_view(cfg, data, rank)
+    codes_nl = peer_codes(bcfg, data, view["x_nonlocal"])
+    names = ("bq", "bk", "bv", "bo", "b1", "b2")
+    out_ref, codes_ref, gap, h_ref = oracle.block_forward(
+        view["x_local"], codes_nl, data["codebook"], data["wq"], data["wk"], data["wv"], data["wo"],
+        norm_kind=bcfg.norm_kind, eps=bcfg.eps, g1=data["g1"], g2=data["g2"], be1=data["be1"], be2=data["be2"],
+        mlp_kind=bcfg.mlp_kind, w1=data["w1"], w2=data["w2"], n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads,
+        n_cls=cfg.n_cls, causal=cfg.causal, n_before=view["n_before"], valid_nonlocal=valid,
+        h_is_bf16=cfg.dtype == "bf16", **{n: data.get(n) for n in names})
+    blk = BlockOnGpu(bcfg, data, view["x_local"], codes_nl, view["n_before"], in_place=in_place)
+    blk.run(valid)
+    out, codes, h = blk.results()
+    n_tie, n_slices, n_other = check_h_and_codes(cfg, h, h_ref, codes, codes_ref, gap, data["codebook"])
+    err = np.abs(out - out_ref).max()
+    print(f"{bcfg.name} rank {rank}: max abs err {err:.3e} (|out| max {np.abs(out_ref).max():.2f}), near-tie codes {n_tie}/{codes.size}, "
+          f"slices with a differing h {n_slices} ({n_other} of them chose another codeword)")
+    tol = OUT_TOL[cfg.dtype]
+    if cfg.dtype == "bf16":
+        tol += 2.0 ** -6 * float(np.sqrt(np.mean((out_ref - view["x_local"]) ** 2)))
+    assert err <= tol, f"{err:.3e} > {tol:.3e}"
+    assert n_tie <= max(2, codes.size // 2000)
+    return out
+
+
+@pytest.mark.parametrize("rank", [0, 3])
+def test_tiny_vit_block_f32(rank):
+    run_case(wl.TINY_VIT_BLOCK, rank)
+
+
+@pytest.mark.parametrize("rank", [0, 2])
+def test_vit_base_block_bf16_layernorm_gelu_erf_class_row(rank):
+    run_case(wl.VIT_BASE_BLOCK, rank)
+
+
+@pytest.mark.parametrize("rank", [0, 3])
+def test_gpt2_small_block_bf16_layernorm_gelu_tanh_causal(rank):
+    run_case(wl.GPT2_SMALL_BLOCK, rank)
+
+
+def small_llama(seq_len=1148, d_ff=1792, seed=51, dtype="bf16"):
+    """Llama-3-8B widths (D 4096, 32/8 heads of 128, G 64, K 1024) with fewer rows and a narrower MLP: 287 local rows
+    (ragged against every tile size) and d_ff = 7 * 256."""
+    layer = dataclasses.replace(wl.LLAMA3_8B, name="llama_small", seq_len=seq_len, seed=seed, dtype=dtype)
+    return dataclasses.replace(wl.LLAMA3_8B_BLOCK, name="llama_small_block", layer=layer, d_ff=d_ff)
+
+
+@pytest.mark.parametrize("rank", [1, 3])
+def test_llama_width_block_bf16_rmsnorm_swiglu(rank):
+    run_case(small_llama(), rank)
+
+
+def test_swiglu_ragged_hidden_width_and_f32_gate():
+    """d_ff that is not a multiple of the gate tile (64 | d_ff only), and the fp32 path's separate gate kernel."""
+    layer = dataclasses.replace(wl.GPT2_SMALL, name="swiglu_ragged", seq_len=420, seed=52)
+    run_case(dataclasses.replace(wl.LLAMA3_8B_BLOCK, name="swiglu_ragged_block", layer=layer, d_ff=1216), 1)
+    layer = dataclasses.replace(wl.TINY_VIT, name="swiglu_f32", seed=53)
+    run_case(dataclasses.replace(wl.LLAMA3_8B_BLOCK, name="swiglu_f32_block", layer=layer, d_ff=200, norm_kind="rmsnorm"), 2)
+
+
+def test_large_tiles_with_a_ragged_gate_tile():
+    """1024 local rows and d_ff = 65 * 64: the gated GEMM runs on 256 x 256 tiles whose last column tile is half empty."""
+    layer = dataclasses.replace(wl.GPT2_SMALL, name="swiglu_big_ragged", seq_len=4096, seed=54)
+    run_case(dataclasses.replace(wl.LLAMA3_8B_BLOCK, name="swiglu_big_ragged_block", layer=layer, d_ff=4160), 2)
+
+
+def test_block_in_place_equals_out_of_place_and_repeats_bit_exactly():
+    a = run_case(wl.GPT2_SMALL_BLOCK, 1)
+    b = run_case(wl.GPT2_SMALL_BLOCK, 1, in_place=True)
+    np.testing.assert_array_equal(a, b)
+    c = run_case(wl.GPT2_SMALL_BLOCK, 1)
+    np.testing.assert_array_equal(a, c)
+
+
+def test_block_with_lost_codes():
+    bcfg = wl.GPT2_SMALL_BLOCK
+    rng = np.random.default_rng(5)
+    valid = (rng.random(bcfg.layer.n_nonlocal) > 0.1).astype(np.uint8)
+    a = run_case(bcfg, 3, valid=valid)
+    b = run_case(bcfg, 3)
+    assert np.abs(a - b).max() > 1e-3          # the lost rows matter
+
+
+def test_llama3_8b_block_full_size():
+    run_case(wl.LLAMA3_8B_BLOCK, 3)
+
+
+def test_block_argument_errors_launch_nothing():
+    import torch
+    from gpu_util import BlockOnGpu
+    from paper_2505_19342_amd import binding as B
+    bcfg = wl.TINY_VIT_BLOCK
+    data = wl.generate_block(bcfg)
+    view = wl.device_view(bcfg.layer, data, 0)
+    codes_nl = peer_codes(bcfg, data, view["x_nonlocal"])
+    blk = BlockOnGpu(bcfg, data, view["x_local"], codes_nl, view["n_before"])
+    blk.x_out.fill_(-7.0)
+    small = torch.empty(256, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(B.AstraError, match="workspace"):
+        B.astra_block_forward(blk.desc, blk.weights, blk.x, blk.codes_nonlocal, None, blk.x_out, blk.codes_local, blk.h, small)
+    bad = B.block_desc(blk.desc.layer, "layernorm", "gelu_erf", 0, 1e-6)
+    with pytest.raises(B.AstraError):
+        B.astra_block_forward(bad, blk.weights, blk.x, blk.codes_nonlocal, None, blk.x_out, blk.codes_local, blk.h, blk.workspace)
+    assert B.astra_block_workspace_bytes(bad) == 0
+    w = B.block_weights(**{k: v for k, v in blk.tensors.items() if k != "w2"})
+    with pytest.raises(B.AstraError, match="NULL"):
+        B.astra_block_forward(blk.desc, w, blk.x, blk.codes_nonlocal, None, blk.x_out, blk.codes_local, blk.h, blk.workspace)
+    torch.cuda.synchronize()
+    assert bool((blk.x_out == -7.0).all())

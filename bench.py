@@ -59,6 +59,8 @@ def main():
                          "boundaries, about 20 us of extra gaps per such step); the others through astra_layer_forward")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the measurements outside the timed region (matrix-core probe, stand-alone decode, other ranks)")
+    ap.add_argument("--extras", default="all",
+                    help="comma list of the measurements outside the timed region to run: ranks, lost, block, decode, probe (default all)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the warm-up, run one plain elementwise copy kernel reading and writing this many MiB "
                          "(fp32): the reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -197,7 +199,8 @@ def main():
     per_step = sorted(ev.elapsed_ms(0, 4) for ev in events)
     result["gpu_ms_per_step_events_p10_p50_p90"] = [per_step[int(q * (len(per_step) - 1))] for q in (0.1, 0.5, 0.9)]
 
-    if not args.no_extras:
+    extras = set() if args.no_extras else set(("ranks,lost,block,decode,probe" if args.extras == "all" else args.extras).split(","))
+    if extras:
         def timed(fn, n, warm=0):
             for _ in range(1 + warm):      # after host-side set-up the chip is idle: bring it back to its steady clock
                 fn()
@@ -210,7 +213,7 @@ def main():
             return a.elapsed_time(b) / n          # ms
 
         # (1) the other simulated devices (under causal masking they see fewer non-local rows)
-        if cfg.causal and args.rank < 0:
+        if "ranks" in extras and cfg.causal and args.rank < 0:
             per_rank = {}
             for r in range(cfg.n_dev):
                 vr = wl.device_view(cfg, data, r)
@@ -228,7 +231,7 @@ def main():
             result["rank_mean_tokens_per_s"] = tq / (sum(per_rank.values()) / len(per_rank) * 1e-3)
         # the layer with 5 % of the peers' tokens lost (Sec. 4.5, packet loss without retransmission): same launches,
         # the attention additionally masks the lost keys of every non-local tile
-        if tn > 0:
+        if "lost" in extras and tn > 0:
             lost_rng = np.random.default_rng(cfg.seed + 500)
             bits = torch.from_numpy(B.pack_valid_bits(lost_rng.random(tn) >= 0.05).view(np.int64).copy()).to(dev)
             a_v = (desc, x_local, codes_nl, bits, codebook, cnorm, *w, None, None, None, None, y, codes_local, ws)
@@ -236,7 +239,7 @@ def main():
         # the whole Transformer block around the layer (Sec. 3.1: norm, layer, residual, norm, local MLP, residual) for
         # the model this workload stands in for; the peers' codes are reused as they are (their values do not change the work)
         bcfg = next((b for b in wl.BLOCK_CONFIGS.values() if b.layer.name == cfg.name), None)
-        if bcfg is not None:
+        if "block" in extras and bcfg is not None:
             bdata = wl.generate_block(bcfg)
             bview = wl.device_view(cfg, bdata, rank)
             f32dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev)
@@ -265,7 +268,7 @@ def main():
         # (2) the decode as a kernel of its own (inside the layer it is fused into the projection's operand load):
         #     the HBM-bound step; algorithmic bytes = codes + codebook + rebuilt rows
         t_v = view["n_before"] if cfg.causal else tn
-        if t_v > 0:
+        if "decode" in extras and t_v > 0:
             x_hat = torch.empty((t_v, D), dtype=x_local.dtype, device=dev)
             ms = timed(lambda: B.astra_vq_decode(vq, codes_nl, t_v, codebook, x_hat), 200, warm=50)
             eb = 2 if dt == "bf16" else 4
@@ -274,7 +277,7 @@ def main():
                                            "frac_of_hbm_8TBps": nbytes / (ms * 1e-3) / 8e12, "rows": t_v}
             del x_hat
         # (3) last, because it heats the chip: what the matrix cores of this machine deliver with nothing else in the loop, next to the published peak
-        if dt == "bf16":
+        if "probe" in extras and dt == "bf16":
             n_blocks, iters = 1024, 2000
             probe_out = torch.empty(n_blocks * 512, dtype=torch.float32, device=dev)
             ms = timed(lambda: B.astra_probe_mfma_bf16(probe_out, n_blocks, iters), 5, warm=3)

@@ -91,7 +91,8 @@ static int make_plan(const astra_layer_desc* desc, LayerPlan* pl) {
 struct BlockPlan {
     LayerPlan layer;
     int d_ff;
-    size_t off_h, off_a, off_a2, total;     // after the layer's own workspace: normalised rows, MLP hidden rows
+    size_t off_h, off_a, off_a2, off_split, split_bytes, total;     // after the layer's own workspace: normalised rows, MLP hidden
+                                                                    // rows, partial sums of the second MLP product
 };
 
 static int make_block_plan(const astra_block_desc* desc, BlockPlan* bp) {
@@ -113,6 +114,8 @@ static int make_block_plan(const astra_block_desc* desc, BlockPlan* bp) {
     bp->off_a = take((size_t)pl.Tq * desc->d_ff * eb);
     // fp32 has no fused gate: the first GEMM leaves [T_q, 2 d_ff], a second kernel forms the product
     bp->off_a2 = take(dtype != ASTRA_BF16 && desc->mlp_kind == ASTRA_MLP_SWIGLU ? (size_t)pl.Tq * 2 * desc->d_ff * eb : 0);
+    bp->split_bytes = gemm_split_workspace_bytes(dtype, pl.Tq, pl.D, desc->d_ff);
+    bp->off_split = take(bp->split_bytes);
     bp->total = off;
     return ASTRA_OK;
 }
@@ -398,7 +401,7 @@ int astra_block_forward(const astra_block_desc* desc, const astra_block_weights*
         rc = launch_swiglu_f32((const float*)(ws + bp.off_a2), pl.Tq, F, (float*)a, s);
         if (rc) return rc;
     }
-    return launch_gemm_batch(dtype, &g2, 1, s);
+    return launch_gemm_batch(dtype, &g2, 1, s, nullptr, nullptr, false, ws + bp.off_split, bp.split_bytes);
 }
 
 int astra_layer_forward_profiled(const astra_layer_desc* desc, const void* x_local, const void* codes_nonlocal,

@@ -1,0 +1,443 @@
+// The bf16 matrix-core GEMM tile kernel C[M,N] = A[M,K] . B[N,K]^T shared by the attention layer's projection launches
+// (paper: the projections named under Eq. 1) and by the MLP of the block around the layer (Sec. 3.1).
+#pragma once
+#include "common.h"
+#include "vq_encode_body.h"
+
+#include <type_traits>
+
+namespace astra {
+
+struct GemmBatch {
+    int32_t n;
+    int32_t tile_begin[kMaxGemmProblems + 1];
+    int32_t tiles_m[kMaxGemmProblems];     // tiles along M of each problem (tile index = tn * tiles_m + tm)
+    GemmProblem p[kMaxGemmProblems];
+    int32_t n_enc_wgs;                     // fused launch: workgroups beyond the GEMM tiles that run the VQ encode
+    EncodeJob enc;
+    int32_t n_split, k_split;              // split contraction (one problem): the grid is n_split copies of the tiles, copy s
+                                           // contracts k in [s * k_split, (s + 1) * k_split) into slice s of an fp32 buffer
+};
+
+__device__ __forceinline__ int find_problem(const GemmBatch& b, int tile) {
+    int p = 0;
+    while (p + 1 < b.n && tile >= b.tile_begin[p + 1]) ++p;
+    return p;
+}
+
+// ------------------------------------------------------------------------------------------------
+// bf16, matrix cores.  A workgroup of WM x WN wavefronts owns a BM x BN output tile; each wavefront
+// owns a (BM/WM) x (BN/WN) sub-tile made of 32x32x16 MFMA tiles.  The contraction runs in steps of 64
+// through double-buffered LDS: while the matrix cores work on tile kt, the registers hold tile kt+1
+// (fetched one iteration earlier) on its way to the other LDS buffer, the loads of tile kt+2 are in
+// flight and, for gathered A rows, the codes of tile kt+3 are being fetched.  LDS tiles are
+// [rows][8 pieces of 8 bf16]; piece p of row r sits at p ^ ((r >> 1) & 7): rows are 128 bytes, the
+// LDS has 64 four-byte banks, so the 16-byte fragment reads of 16 consecutive rows touch every bank once.
+//
+// Workgroup -> tile mapping: hardware hands consecutive workgroup ids to the 8 XCDs round-robin, each
+// with its own L2.  Ids are remapped so that every XCD gets one contiguous range of tiles, walked with
+// the M index fastest: the tiles an XCD runs at the same time share their weight (B) panel and draw
+// their A panels from a few rows, so most operand traffic is served by that XCD's L2.
+// ------------------------------------------------------------------------------------------------
+constexpr int kBK = 64;
+constexpr int kXcds = 8;
+constexpr int kCus = 256;         // compute units of the device the launch shapes are chosen for
+
+__device__ __forceinline__ int xcd_remap(int wg, int total) {
+    const int q = total / kXcds, r = total % kXcds;
+    const int xcd = wg % kXcds, slot = wg / kXcds;
+    return xcd < r ? xcd * (q + 1) + slot : r * (q + 1) + (xcd - r) * q + slot;
+}
+
+__device__ __forceinline__ int swz(int r) { return (r >> 1) & 7; }
+
+// Activations of the position-wise MLP that follows the attention layer inside a block (paper Sec. 3.1), applied in
+// the epilogue.  x * sigmoid(2u) is 0.5 x (1 + tanh u).  FAST uses the hardware exponential (results are rounded to
+// bf16 afterwards); otherwise the library routines.
+template <bool FAST>
+__device__ __forceinline__ float silu(float v) { return v / (1.f + (FAST ? __expf(-v) : expf(-v))); }
+template <bool FAST>
+__device__ __forceinline__ float apply_act(float v, int act) {
+    if (act == kActGeluTanh) {
+        const float u = 0.7978845608028654f * (v + 0.044715f * v * v * v);
+        return FAST ? v / (1.f + __expf(-2.f * u)) : 0.5f * v * (1.f + tanhf(u));
+    }
+    if (act == kActGeluErf) return 0.5f * v * (1.f + erff(v * 0.7071067811865476f));
+    return v;
+}
+
+// Fused launch of T GEMM tiles and E encode workgroups (E a multiple of 8): every XCD gets a contiguous range of
+// tiles, as with xcd_remap, followed by E/8 encode workgroups, so both kinds of work are spread over all XCDs.
+struct FusedId {
+    bool enc;
+    int idx;
+};
+__device__ __forceinline__ FusedId fused_id(int wg, int T, int E) {
+    const int xcd = wg % kXcds, slot = wg / kXcds;
+    const int tq = T / kXcds, tr = T % kXcds;
+    const int t_x = tq + (xcd < tr ? 1 : 0);
+    if (slot < t_x) return {false, xcd * tq + (xcd < tr ? xcd : tr) + slot};
+    return {true, xcd * (E / kXcds) + slot - t_x};
+}
+
+// position of token offset o (0..15) inside a 16-token block of the transposed-V layout: the 8 tokens
+// one half-wave holds of an MFMA accumulator column ({4h..4h+3} and {8+4h..8+4h+3}) become contiguous,
+// which is also the order the attention kernel's P^T operand keeps its 16 keys in.
+__device__ __forceinline__ int vt_pos(int o) { return 8 * ((o >> 2) & 1) + (o & 3) + 4 * (o >> 3); }
+
+int launch_gemm_mlp(int epi, bool big, const GemmBatch& batch, int grid, hipStream_t s);
+int launch_split_reduce(const float* part, int n_split, const GemmProblem& p, hipStream_t s);
+int gemm_split_factor(int dtype, int64_t M, int64_t N, int64_t K);
+
+// EPI selects the epilogue at compile time.  kEpiLayer is the attention layer's: the store follows the problem's c_mode
+// (bf16, fp32, transposed V).  The others belong to the block around the layer (one plain-A problem per launch) and each
+// carries exactly one form, so that the tail of a launch that runs as a single round of workgroups stays short:
+//   kEpiResidualF32  fp32 store of A.B^T + bias, accumulation started from `residual` when it is set
+//   kEpiSplit        the contraction slice batch.k_split of copy blockIdx / tiles, raw fp32 partial sums
+//   kEpiGeluTanh / kEpiGeluErf   bf16 store of gelu(A.B^T + bias)
+//   kEpiSwiGLU       bf16 store of silu(A.gate^T + b_g) * (A.up^T + b_u)
+enum { kEpiLayer = 0, kEpiResidualF32 = 1, kEpiSplit = 2, kEpiGeluTanh = 3, kEpiGeluErf = 4, kEpiSwiGLU = 5 };
+
+template <int BM, int BN, int WM, int WN, bool CODE16, bool ENC = false, int EPI = kEpiLayer>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_nt_bf16_kernel(const GemmBatch batch) {
+    constexpr int THREADS = 64 * WM * WN;
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;        // MFMA tiles per wavefront
+    constexpr int RPP = THREADS / 8;                           // rows staged per pass
+    constexpr int PA = BM / RPP, PB = BN / RPP;                // staging passes per thread
+    __shared__ u32x4 lds_a[2][BM * kBK / 8];
+    __shared__ u32x4 lds_b[2][BN * kBK / 8];
+
+    int vt;
+    if (ENC) {
+        // The grid is the GEMM tiles plus batch.n_enc_wgs workgroups that encode the local rows (nothing in the
+        // projections depends on the codes or the other way round): they fill compute units the tiles leave idle.
+        // The encode reuses the operand buffers: its ring of codebook tiles is exactly lds_a, the norms sit in lds_b.
+        static_assert(!ENC || (sizeof(lds_a) == sizeof(u32x4) * kEncBufs * kEncCbSlots && sizeof(lds_b) >= sizeof(f32x4) * kEncBufs * kEncCnSlots),
+                      "encode ring must fit the operand buffers");
+        const FusedId id = fused_id(blockIdx.x, gridDim.x - batch.n_enc_wgs, batch.n_enc_wgs);
+        if (id.enc) {
+            u32x4* cb = &lds_a[0][0];
+            f32x4* cn = reinterpret_cast<f32x4*>(&lds_b[0][0]);
+            const EncodeJob& job = batch.enc;
+            vq_encode_fast_zero_lds<THREADS>(cb);
+            __syncthreads();                               // zero fill done before any transfer lands
+            const int n_items = job.G * job.n_tb;
+            const int chunk = (n_items + batch.n_enc_wgs - 1) / batch.n_enc_wgs;     // consecutive items share the group
+            const int hi = min((id.idx + 1) * chunk, n_items);
+            for (int item = id.idx * chunk; item < hi; ++item) {
+                if (job.code_bytes == 2) vq_encode_fast_body<THREADS, uint16_t>(job, item / job.n_tb, item % job.n_tb, cb, cn);
+                else vq_encode_fast_body<THREADS, uint8_t>(job, item / job.n_tb, item % job.n_tb, cb, cn);
+                __syncthreads();                           // all reads of this item's tiles done before the next item's transfers
+            }
+            return;
+        }
+        vt = id.idx;
+    } else {
+        vt = xcd_remap(blockIdx.x, gridDim.x);
+    }
+    int split = 0;
+    if (EPI == kEpiSplit) {
+        const int tiles = batch.tile_begin[batch.n];
+        split = vt / tiles;
+        vt -= split * tiles;
+    }
+    const int pi = find_problem(batch, vt);
+    const GemmProblem& P = batch.p[pi];
+    const int tile = vt - batch.tile_begin[pi];
+    const int tiles_m = batch.tiles_m[pi];
+    const int tm = tile % tiles_m, tn = tile / tiles_m;
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int M = P.M, N = P.N, K = P.K;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int i32 = lane & 31, h = lane >> 5;
+    const int wm = wave / WN, wn = wave % WN;
+    const int kc = tid & 7, r0 = tid >> 3;      // staging: 16-byte piece kc of rows r0 + RPP * it
+
+    // One straight-line loader serves plain and gathered A rows.  For gathered rows the piece at
+    // contraction index k lies in group g = k / dg at offset j = k - g*dg of codeword codes[row, g];
+    // for plain rows the code load is a harmless read of the first bytes of A and the gathered offset is
+    // discarded by a select.  k / dg is a multiply-high by ceil(2^32 / dg), exact for k, dg < 2^16.
+    // Addresses are a wave-uniform base (scalar registers, advanced once per tile) plus a 32-bit byte
+    // offset per thread, which keeps the per-row state to one register.
+    const bool gather = P.codes != nullptr;
+    const int dg = gather ? P.dg : 1, Kc = gather ? P.Kc : 1, G = gather ? P.G : 0;
+    const uint32_t magic = gather ? (uint32_t)(0x100000000ull / (uint32_t)dg) + 1u : 0u;
+    const char* __restrict__ a_base = (const char*)(gather ? P.codebook : P.a);   // plain A advances 128 bytes per tile
+    const int a_step = gather ? 0 : kBK * 2;
+    const uint32_t gmask = gather ? 0xffffffffu : 0u;                           // keeps the gathered offset, or zeroes it
+    const char* __restrict__ b_base = (const char*)P.b;
+    if (EPI == kEpiSplit) {                    // plain A only: both operands start at this copy's slice of the contraction
+        a_base += (int64_t)split * batch.k_split * 2;
+        b_base += (int64_t)split * batch.k_split * 2;
+    }
+    const char* __restrict__ c_base = (const char*)(gather ? P.codes : P.a);
+    uint32_t aoff[PA], coff[PA], boff[PB];
+#pragma unroll
+    for (int it = 0; it < PA; ++it) {
+        int ra = m0 + r0 + RPP * it;
+        ra = ra < M ? ra : M - 1;
+        aoff[it] = gather ? 0u : ((uint32_t)ra * (uint32_t)P.lda + kc * 8) * 2u;
+        coff[it] = (uint32_t)ra * (uint32_t)G * (CODE16 ? 2u : 1u);
+    }
+#pragma unroll
+    for (int it = 0; it < PB; ++it) {
+        int rb = n0 + r0 + RPP * it;
+        rb = rb < N ? rb : N - 1;
+        if (EPI == kEpiSwiGLU) {
+            // tile row r of B -> weight row such that, in every wavefront, MFMA column tiles b < TN/2 hold gate rows and
+            // tiles b + TN/2 the up rows of the same BN/WN/2 output columns: both factors of an output meet in one lane
+            const int rr = r0 + RPP * it, Fh = N >> 1;
+            const int wn_r = rr / (32 * TN), b_r = (rr % (32 * TN)) / 32, i_r = rr % 32;
+            int col = n0 / 2 + wn_r * (16 * TN) + (b_r % (TN / 2)) * 32 + i_r;
+            col = col < Fh ? col : Fh - 1;
+            rb = (b_r >= TN / 2 ? Fh : 0) + col;
+        }
+        boff[it] = ((uint32_t)rb * (uint32_t)K + kc * 8) * 2u;
+    }
+    int k_code = kc * 8;              // contraction index of this thread's piece in the tile whose codes are fetched next
+    int k_use = kc * 8;               // ... in the tile whose operand pieces are fetched next
+    int code[PA];
+    u32x4 ra[PA], rb[PB];
+
+    auto load_codes = [&]() {
+        const uint32_t g_ = __umulhi((uint32_t)k_code, magic) * (CODE16 ? 2u : 1u);
+#pragma unroll
+        for (int it = 0; it < PA; ++it) {
+            if (CODE16) code[it] = *reinterpret_cast<const uint16_t*>(c_base + (coff[it] + g_));
+            else code[it] = *reinterpret_cast<const uint8_t*>(c_base + (coff[it] + g_));
+        }
+        k_code += kBK;
+    };
+    auto load_tile = [&]() {
+        const uint32_t g_ = __umulhi((uint32_t)k_use, magic);
+        const uint32_t j_ = (uint32_t)k_use - g_ * (uint32_t)dg;
+        const uint32_t gbase_ = g_ * (uint32_t)Kc;
+#pragma unroll
+        for (int it = 0; it < PA; ++it) {
+            const uint32_t c_ = (uint32_t)(code[it] < Kc ? code[it] : Kc - 1);
+            const uint32_t goff_ = ((gbase_ + c_) * (uint32_t)dg + j_) * 2u;
+            ra[it] = *reinterpret_cast<const u32x4*>(a_base + ((goff_ & gmask) + aoff[it]));
+        }
+#pragma unroll
+        for (int it = 0; it < PB; ++it) rb[it] = *reinterpret_cast<const u32x4*>(b_base + boff[it]);
+        a_base += a_step;
+        b_base += kBK * 2;
+        k_use += kBK;
+    };
+    auto store_tile = [&](int buf_) {
+#pragma unroll
+        for (int it = 0; it < PA; ++it) {
+            const int r_ = r0 + RPP * it;
+            lds_a[buf_][r_ * 8 + (kc ^ swz(r_))] = ra[it];
+        }
+#pragma unroll
+        for (int it = 0; it < PB; ++it) {
+            const int r_ = r0 + RPP * it;
+            lds_b[buf_][r_ * 8 + (kc ^ swz(r_))] = rb[it];
+        }
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    if (EPI == kEpiResidualF32 && P.residual != nullptr) {
+        // The residual is where the accumulation starts: its loads are issued here, all at once, and land while the first
+        // operand tiles are fetched.  (Added in the epilogue, every load would be a round trip to memory in front of a store.)
+        // Rows and columns beyond the problem are clamped: those accumulators are never stored.
+        const char* __restrict__ R = (const char*)P.residual;
+        const uint32_t ldc = (uint32_t)P.ldc;
+#pragma unroll
+        for (int b = 0; b < TN; ++b) {
+            const int n = min(n0 + wn * (BN / WN) + b * 32 + i32, N - 1);
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = min(m0 + wm * (BM / WM) + a * 32 + acc_row(v, h), M - 1);
+                    acc[a][b][v] = *reinterpret_cast<const float*>(R + ((uint32_t)m * ldc + (uint32_t)n) * 4u);
+                }
+        }
+    }
+
+    // fragment rows
+    int arow[TM], brow[TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a) arow[a] = wm * (BM / WM) + a * 32 + i32;
+#pragma unroll
+    for (int b = 0; b < TN; ++b) brow[b] = wn * (BN / WN) + b * 32 + i32;
+
+    // ---- main loop.  One tile of 64 along the contraction is four MFMA steps of 16.  Per step a wavefront
+    // issues TM*TN MFMAs on fragments it requested from LDS one step earlier (two fragment slots), and between those
+    // MFMAs, in program order, the "side jobs" of the step: the TM+TN fragment reads of the next step and a slice of
+    // the staging work (registers holding tile kt+1 -> other LDS buffer, refilled at once with the global loads of
+    // tile kt+2).  Nothing else is needed to keep a single wavefront per SIMD busy: LDS and global latencies are
+    // covered by the MFMAs issued meanwhile.  Staging is spread over steps 0..2; the workgroup barrier follows step 2,
+    // after which step 3 may read the first fragments of tile kt+1 from the buffer just filled, and the buffer of
+    // tile kt (all of whose fragments were requested before the barrier) is free for the next iteration's staging.
+    const int n_kt = (EPI == kEpiSplit ? batch.k_split : K) / kBK;
+    bf16x8 fa[2][TM], fb[2][TN];
+    auto read_frag = [&](int buf_, int ks, int slot, int j) {
+        if (j < TM) fa[slot][j] = __builtin_bit_cast(bf16x8, lds_a[buf_][arow[j] * 8 + ((2 * ks + h) ^ swz(arow[j]))]);
+        else fb[slot][j - TM] = __builtin_bit_cast(bf16x8, lds_b[buf_][brow[j - TM] * 8 + ((2 * ks + h) ^ swz(brow[j - TM]))]);
+    };
+    constexpr int NR = TM + TN, NM = TM * TN;
+    auto tile_steps = [&](int kt, auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;       // steady state: tiles kt+1, kt+2 and codes kt+3 all exist
+        const int buf = kt & 1;
+        const bool st = FULL || kt + 1 < n_kt, ld = FULL || kt + 2 < n_kt;
+        const uint32_t g_ = __umulhi((uint32_t)k_use, magic);
+        const uint32_t j_ = (uint32_t)k_use - g_ * (uint32_t)dg;
+        const uint32_t gbase_ = g_ * (uint32_t)Kc;
+        auto stage_a = [&](int it) {
+            const int r_ = r0 + RPP * it;
+            if (st) lds_a[buf ^ 1][r_ * 8 + (kc ^ swz(r_))] = ra[it];
+            if (ld) {
+                const uint32_t c_ = (uint32_t)(code[it] < Kc ? code[it] : Kc - 1);
+                const uint32_t goff_ = ((gbase_ + c_) * (uint32_t)dg + j_) * 2u;
+                ra[it] = *reinterpret_cast<const u32x4*>(a_base + ((goff_ & gmask) + aoff[it]));
+            }
+        };
+        auto stage_b = [&](int it) {
+            const int r_ = r0 + RPP * it;
+            if (st) lds_b[buf ^ 1][r_ * 8 + (kc ^ swz(r_))] = rb[it];
+            if (ld) rb[it] = *reinterpret_cast<const u32x4*>(b_base + boff[it]);
+        };
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const int cur = ks & 1, nxt = cur ^ 1;
+            // side jobs of this step: NR fragment reads, then (steps 0..2) the staging slice
+            const int a_lo = ks < 3 ? ks * PA / 3 : PA, a_hi = ks < 3 ? (ks + 1) * PA / 3 : PA;
+            const int b_lo = ks < 3 ? ks * PB / 3 : PB, b_hi = ks < 3 ? (ks + 1) * PB / 3 : PB;
+            const int nj = NR + (a_hi - a_lo) + (b_hi - b_lo);
+            const bool rd = ks < 3 || st;                     // step 3 reads the next tile, if there is one
+#pragma unroll
+            for (int m = 0; m < NM; ++m) {
+                const int a = m / TN, b = m % TN;
+                acc[a][b] = mfma_32x32x16(fa[cur][a], fb[cur][b], acc[a][b]);
+#pragma unroll
+                for (int j = m * nj / NM; j < (m + 1) * nj / NM; ++j) {
+                    if (j < NR) {
+                        if (rd) read_frag(ks < 3 ? buf : buf ^ 1, (ks + 1) & 3, nxt, j);
+                    } else if (j - NR < a_hi - a_lo) {
+                        stage_a(a_lo + j - NR);
+                    } else {
+                        stage_b(b_lo + j - NR - (a_hi - a_lo));
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);        // keep this order: the compiler would bunch the memory operations
+            }
+            if (ks == 2) __syncthreads();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (ld) {
+            a_base += a_step;
+            b_base += kBK * 2;
+            k_use += kBK;
+        }
+        if (FULL || kt + 3 < n_kt) load_codes();
+    };
+
+    load_codes();                 // codes of tile 0
+    load_tile();                  // tile 0
+    if (n_kt > 1) load_codes();   // codes of tile 1
+    store_tile(0);
+    if (n_kt > 1) load_tile();    // tile 1
+    if (n_kt > 2) load_codes();   // codes of tile 2
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < NR; ++j) read_frag(0, 0, 0, j);
+    int kt = 0;
+    for (; kt + 3 < n_kt; ++kt) tile_steps(kt, std::true_type{});
+    for (; kt < n_kt; ++kt) tile_steps(kt, std::false_type{});
+
+    // epilogue.  acc[a][b][v] is C[m, n] with m = wave row base + 32a + acc_row(v, h), n = wave column base + 32b + lane % 32.
+    const uint16_t* __restrict__ bias = (const uint16_t*)P.bias;
+    if constexpr (EPI == kEpiSplit) {
+        // partial sums: slice `split` of the fp32 buffer, [M, N] dense; bias and residual are added by the reduction
+        float* __restrict__ C = (float*)P.c + (int64_t)split * M * N;
+#pragma unroll
+        for (int b = 0; b < TN; ++b) {
+            const int n = n0 + wn * (BN / WN) + b * 32 + i32;
+            if (n >= N) continue;
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = m0 + wm * (BM / WM) + a * 32 + acc_row(v, h);
+                    if (m < M) C[(int64_t)m * N + n] = acc[a][b][v];
+                }
+        }
+    } else if constexpr (EPI == kEpiSwiGLU) {
+        static_assert(EPI != kEpiSwiGLU || TN % 2 == 0, "gate and up tiles pair up inside a wavefront");
+        const int Fh = N >> 1;
+        uint16_t* __restrict__ C = (uint16_t*)P.c;
+#pragma unroll
+        for (int b = 0; b < TN / 2; ++b) {
+            const int col = n0 / 2 + wn * (16 * TN) + b * 32 + i32;
+            if (col >= Fh) continue;
+            const float bg = bias ? bf16_bits_to_f32(bias[col]) : 0.f, bu = bias ? bf16_bits_to_f32(bias[Fh + col]) : 0.f;
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = m0 + wm * (BM / WM) + a * 32 + acc_row(v, h);
+                    if (m < M) C[(int64_t)m * P.ldc + col] = f32_to_bf16_bits(silu<true>(acc[a][b][v] + bg) * (acc[a][b + TN / 2][v] + bu));
+                }
+        }
+    } else {
+#pragma unroll
+        for (int b = 0; b < TN; ++b) {
+            const int n = n0 + wn * (BN / WN) + b * 32 + i32;
+            if (n >= N) continue;
+            const float bv = bias ? bf16_bits_to_f32(bias[n]) : 0.f;
+            if (EPI == kEpiLayer && P.c_mode == kCTransposedV) {
+                // C^T with tokens permuted inside 16-token blocks; P.ldc is the padded token count.  Rows
+                // m >= M of the last tile are finite copies of row M-1 (clamped loads) and are written too,
+                // so the padding never holds uninitialised bits.
+                uint16_t* __restrict__ C = (uint16_t*)P.c + (int64_t)n * P.ldc;
+#pragma unroll
+                for (int a = 0; a < TM; ++a)
+#pragma unroll
+                    for (int blk = 0; blk < 2; ++blk) {
+                        const int mb = m0 + wm * (BM / WM) + a * 32 + 16 * blk;
+                        if (mb < P.ldc) {
+                            u32x4 w;
+                            w.x = pack_bf16x2(acc[a][b][8 * blk + 0] + bv, acc[a][b][8 * blk + 1] + bv);
+                            w.y = pack_bf16x2(acc[a][b][8 * blk + 2] + bv, acc[a][b][8 * blk + 3] + bv);
+                            w.z = pack_bf16x2(acc[a][b][8 * blk + 4] + bv, acc[a][b][8 * blk + 5] + bv);
+                            w.w = pack_bf16x2(acc[a][b][8 * blk + 6] + bv, acc[a][b][8 * blk + 7] + bv);
+                            *reinterpret_cast<u32x4*>(C + mb + 8 * h) = w;
+                        }
+                    }
+            } else if (EPI == kEpiResidualF32 || (EPI == kEpiLayer && P.c_mode == kCF32)) {
+                float* C = (float*)P.c;                       // may be the residual itself (already inside acc): no restrict
+#pragma unroll
+                for (int a = 0; a < TM; ++a)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int m = m0 + wm * (BM / WM) + a * 32 + acc_row(v, h);
+                        if (m < M) C[(int64_t)m * P.ldc + n] = acc[a][b][v] + bv;
+                    }
+            } else {
+                constexpr int ACT = EPI == kEpiGeluTanh ? kActGeluTanh : EPI == kEpiGeluErf ? kActGeluErf : kActNone;
+                uint16_t* __restrict__ C = (uint16_t*)P.c;
+#pragma unroll
+                for (int a = 0; a < TM; ++a)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int m = m0 + wm * (BM / WM) + a * 32 + acc_row(v, h);
+                        if (m < M) C[(int64_t)m * P.ldc + n] = f32_to_bf16_bits(apply_act<true>(acc[a][b][v] + bv, ACT));
+                    }
+            }
+        }
+    }
+}
+
+}  // namespace astra

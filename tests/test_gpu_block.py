@@ -115,6 +115,12 @@ def test_llama_width_block_bf16_rmsnorm_swiglu(rank):
     run_case(small_llama(), rank)
 
 
+def test_split_contraction_with_ragged_rows():
+    """287 rows x 4096 columns is 32 large tiles, d_ff = 16384: the second MLP product is cut into 8 slices of the
+    contraction whose partial sums are added in a fixed order by a reduction kernel (with the residual)."""
+    run_case(small_llama(d_ff=16384, seed=55), 2)
+
+
 def test_swiglu_ragged_hidden_width_and_f32_gate():
     """d_ff that is not a multiple of the gate tile (64 | d_ff only), and the fp32 path's separate gate kernel."""
     layer = dataclasses.replace(wl.GPT2_SMALL, name="swiglu_ragged", seq_len=420, seed=52)

@@ -60,7 +60,7 @@ def main():
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the measurements outside the timed region (matrix-core probe, stand-alone decode, other ranks)")
     ap.add_argument("--extras", default="all",
-                    help="comma list of the measurements outside the timed region to run: ranks, lost, block, decode, probe (default all)")
+                    help="comma list of the measurements outside the timed region to run: ranks, lost, block, stack (needs block), decode, probe (default all)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the warm-up, run one plain elementwise copy kernel reading and writing this many MiB "
                          "(fp32): the reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -199,7 +199,7 @@ def main():
     per_step = sorted(ev.elapsed_ms(0, 4) for ev in events)
     result["gpu_ms_per_step_events_p10_p50_p90"] = [per_step[int(q * (len(per_step) - 1))] for q in (0.1, 0.5, 0.9)]
 
-    extras = set() if args.no_extras else set(("ranks,lost,block,decode,probe" if args.extras == "all" else args.extras).split(","))
+    extras = set() if args.no_extras else set(("ranks,lost,block,stack,decode,probe" if args.extras == "all" else args.extras).split(","))
     if extras:
         def timed(fn, n, warm=0):
             for _ in range(1 + warm):      # after host-side set-up the chip is idle: bring it back to its steady clock
@@ -264,6 +264,30 @@ def main():
                                "flops": total_flops + mlp_flops, "tflops": (total_flops + mlp_flops) / (ms * 1e-3) / 1e12,
                                "mfma_frac": (total_flops + mlp_flops) / (ms * 1e-3) / 1e12 / peak,
                                "mlp_and_norms_ms": ms - ms_per_step, "mlp_tflops": mlp_flops / ((ms - ms_per_step) * 1e-3) / 1e12}
+            # L such blocks in sequence = this device's share of the whole model's prefill (12 blocks for the ViT-Base and
+            # GPT-2 shapes, 32 for Llama-3-8B): distinct random weights and codes per block, generated on the device
+            if "stack" in extras:
+                n_layers = 32 if "llama" in cfg.name else 12
+                gen = torch.Generator(device=dev).manual_seed(cfg.seed + 77)
+                tdt = torch.bfloat16 if dt == "bf16" else torch.float32
+                rnd = lambda *shape: (0.02 * torch.randn(*shape, generator=gen, device=dev, dtype=torch.float32)).to(tdt)
+                dq, dkv = cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
+                keep, w_list, codes_in, codes_out = [], [], [], []
+                for l in range(n_layers):
+                    lt = dict(bt)
+                    lt.update(wq=rnd(dq, D), wk=rnd(dkv, D), wv=rnd(dkv, D), wo=rnd(D, dq), w1=rnd(n1, D), w2=rnd(D, bcfg.d_ff))
+                    keep.append(lt)
+                    w_list.append(B.block_weights(**lt))
+                    codes_in.append(torch.randint(0, K, (tn, G), generator=gen, device=dev, dtype=torch.int32).to(code_t))
+                    codes_out.append(torch.empty_like(codes_local))
+                s_args = (bdesc, w_list, bx, codes_in, None, bout, codes_out, bws)
+                ms_stack = timed(lambda: B.astra_stack_forward(*s_args), 10, warm=3)
+                result["stack"] = {"workload": bcfg.name, "n_layers": n_layers, "ms": ms_stack, "ms_per_block": ms_stack / n_layers,
+                                   "tokens_per_s": tq / (ms_stack * 1e-3),
+                                   "tflops": n_layers * (total_flops + mlp_flops) / (ms_stack * 1e-3) / 1e12,
+                                   "what": "astra_stack_forward: this device's share of one prefill pass through all blocks "
+                                           "(the exchange of codes between blocks is not timed: they are resident inputs)"}
+                del keep, w_list, codes_in, codes_out
             del bt, bw, bx, bout, bws, bdata
         # (2) the decode as a kernel of its own (inside the layer it is fused into the projection's operand load):
         #     the HBM-bound step; algorithmic bytes = codes + codebook + rebuilt rows

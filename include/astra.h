@@ -234,6 +234,23 @@ int astra_block_forward(const astra_block_desc* desc, const astra_block_weights*
                         float* x_out, void* codes_local_out, void* h_out,
                         void* workspace, size_t workspace_bytes, void* stream);
 
+/* n_layers blocks in sequence on one device's share of the model (Sec. 3.1: the model is L such blocks; between
+ * two blocks the only thing a device needs from its peers is their codes for the next block).  Block l reads the
+ * stream block l-1 wrote; every block has the shape `desc` and its own weights and codes:
+ *   weights              HOST array of n_layers astra_block_weights (each holding device pointers)
+ *   x, x_out             as for astra_block_forward (device; may alias)
+ *   codes_nonlocal       HOST array of n_layers device pointers, [T_n, G] each: what the peers sent for block l
+ *   valid_nonlocal_bits  NULL, or a HOST array of n_layers device pointers (entries may be NULL)
+ *   codes_local_out      HOST array of n_layers device pointers, [T_l, G] each: what this device sends for block l
+ *   workspace            astra_block_workspace_bytes(desc) bytes, shared by all blocks
+ * Everything is validated before the first launch; the host arrays are not referenced after the call returns.
+ * The distributed class token's final mean over the devices' replicas (Sec. 3.3) crosses devices and is not part
+ * of this call. */
+int astra_stack_forward(const astra_block_desc* desc, int32_t n_layers, const astra_block_weights* weights,
+                        const float* x, const void* const* codes_nonlocal, const uint64_t* const* valid_nonlocal_bits,
+                        float* x_out, void* const* codes_local_out,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
 /* Measurement probe, not part of the method: n_blocks workgroups of 512 threads each run `iters` rounds of
  * four independent 32x32x16 bf16 MFMAs per wavefront on register operands (no memory traffic in the loop)
  * and store one float per thread to out [n_blocks * 512] (device).  Work = n_blocks * 8 * iters * 4 * 32768

@@ -257,3 +257,54 @@ def block_forward(x, codes_nonlocal, codebook, wq, wk, wv, wo, *, norm_kind, eps
     if rc:
         raise ValueError(f"oracle_block_forward failed ({rc})")
     return x_out, codes_local, gap, h
+
+
+def model_forward(x_all, layers, *, n_dev, n_q_heads, n_kv_heads, norm_kind, eps, mlp_kind, causal=False, cls=None,
+                  h_is_bf16=False, lost=None):
+    """The whole multi-device procedure of Sec. 3.1 simulated on the CPU: the sequence x_all [N, D] (fp64 residual
+    stream entering block 0) is cut into n_dev contiguous chunks; per block every device normalises and quantises its
+    chunk, the codes are exchanged, and every device runs block_forward on its chunk with the others' codes
+    (non-local rows in sequence order).  cls [n_dev, D] (optional): one class-token replica per device, first local
+    row, never quantised; after the last block the replicas are averaged (Sec. 3.3).
+    layers: list of dicts with codebook, wq, wk, wv, wo, g1, g2, w1, w2 and optionally be1, be2, bq, bk, bv, bo, b1, b2.
+    lost (optional): lost[l][d] = 0/1 array over device d's non-local tokens at block l (1 = arrived).
+    Returns dict: x [n_dev][T_q, D] final streams, codes [L][n_dev] (what each device sent), codes_nonlocal [L][n_dev]
+    (what each device received), cls_pooled [D] or None."""
+    x_all = _f64(x_all)
+    N = x_all.shape[0]
+    assert N % n_dev == 0
+    tl = N // n_dev
+    n_cls = 0 if cls is None else 1
+    streams = []
+    for d in range(n_dev):
+        chunk = x_all[d * tl:(d + 1) * tl]
+        streams.append(chunk if cls is None else np.concatenate([_f64(cls)[d:d + 1], chunk], axis=0))
+    sent, received = [], []
+    for l, p in enumerate(layers):
+        opt = {k: p.get(k) for k in ("be1", "be2", "bq", "bk", "bv", "bo", "b1", "b2")}
+        # phase 1: every device quantises the content rows of its normalised chunk
+        codes = []
+        for d in range(n_dev):
+            h = norm(streams[d], norm_kind, eps, p["g1"], opt["be1"]).astype(np.float32)
+            if h_is_bf16:
+                u = h.view(np.uint32)
+                h = ((u + (((u >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF))) & np.uint32(0xFFFF0000)).view(np.float32)
+            codes.append(vq_encode(h[n_cls:], p["codebook"]))
+        # phase 2: exchange, then every device runs its block
+        nxt, rec = [], []
+        for d in range(n_dev):
+            nl = np.concatenate([codes[e] for e in range(n_dev) if e != d], axis=0)
+            out, c_loc, _, _ = block_forward(
+                streams[d], nl, p["codebook"], p["wq"], p["wk"], p["wv"], p["wo"], norm_kind=norm_kind, eps=eps,
+                g1=p["g1"], g2=p["g2"], be1=opt["be1"], be2=opt["be2"], mlp_kind=mlp_kind, w1=p["w1"], w2=p["w2"],
+                b1=opt["b1"], b2=opt["b2"], n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, n_cls=n_cls, causal=causal,
+                n_before=d * tl if causal else 0, bq=opt["bq"], bk=opt["bk"], bv=opt["bv"], bo=opt["bo"],
+                valid_nonlocal=None if lost is None else lost[l][d], h_is_bf16=h_is_bf16)
+            assert np.array_equal(c_loc, codes[d])          # the block quantises the same tensor phase 1 did
+            nxt.append(out)
+            rec.append(nl)
+        streams = nxt
+        sent.append(codes)
+        received.append(rec)
+    pooled = None if cls is None else np.mean(np.stack([s[0] for s in streams]), axis=0)
+    return {"x": streams, "codes": sent, "codes_nonlocal": received, "cls_pooled": pooled}

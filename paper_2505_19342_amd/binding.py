@@ -16,7 +16,7 @@ _lib = None
 EXPORTS = ("astra_vq_prepare", "astra_vq_encode", "astra_vq_decode", "astra_mixed_attention",
            "astra_mixed_attention_valid", "astra_layer_forward_valid",
            "astra_layer_workspace_bytes", "astra_layer_encode_fused", "astra_layer_forward", "astra_layer_forward_profiled",
-           "astra_block_workspace_bytes", "astra_block_forward",
+           "astra_block_workspace_bytes", "astra_block_forward", "astra_stack_forward",
            "astra_probe_mfma_bf16", "astra_status_string", "astra_version")
 ASTRA_NORM_LAYER, ASTRA_NORM_RMS = 0, 1
 ASTRA_MLP_GELU_TANH, ASTRA_MLP_GELU_ERF, ASTRA_MLP_SWIGLU = 0, 1, 2
@@ -88,6 +88,10 @@ def load(build_if_missing: bool = True):
     lib.astra_block_workspace_bytes.restype = ctypes.c_size_t
     lib.astra_block_forward.argtypes = [ctypes.POINTER(BlockDesc), ctypes.POINTER(BlockWeights)] + [vp] * 7 + [ctypes.c_size_t, vp]
     lib.astra_block_forward.restype = ctypes.c_int
+    pp = ctypes.POINTER(ctypes.c_void_p)
+    lib.astra_stack_forward.argtypes = [ctypes.POINTER(BlockDesc), ctypes.c_int32, ctypes.POINTER(BlockWeights), vp, pp, pp, vp, pp,
+                                        vp, ctypes.c_size_t, vp]
+    lib.astra_stack_forward.restype = ctypes.c_int
     lib.astra_status_string.argtypes = [ctypes.c_int]
     lib.astra_status_string.restype = ctypes.c_char_p
     lib.astra_version.restype = ctypes.c_int
@@ -192,6 +196,27 @@ def astra_block_forward(desc: BlockDesc, weights: BlockWeights, x, codes_nonloca
     _check(load().astra_block_forward(ctypes.byref(desc), ctypes.byref(weights), _ptr(x), _ptr(codes_nonlocal), _ptr(valid_bits),
                                       _ptr(x_out), _ptr(codes_local_out), _ptr(h_out), _ptr(workspace), nbytes, _stream()),
            "astra_block_forward")
+
+
+def _ptr_array(tensors):
+    arr = (ctypes.c_void_p * len(tensors))()
+    for i, t in enumerate(tensors):
+        p = _ptr(t)
+        arr[i] = p.value if p is not None else None
+    return arr
+
+
+def astra_stack_forward(desc: BlockDesc, weights, x, codes_nonlocal, valid_bits, x_out, codes_local_out, workspace):
+    """weights: list of BlockWeights (one per block); codes_nonlocal, codes_local_out: lists of device tensors;
+    valid_bits: None or a list of (tensor | None)."""
+    n = len(weights)
+    if len(codes_nonlocal) != n or len(codes_local_out) != n or (valid_bits is not None and len(valid_bits) != n):
+        raise AstraError("one entry per block required")
+    w_arr = (BlockWeights * n)(*weights)
+    nbytes = workspace.numel() * workspace.element_size()
+    _check(load().astra_stack_forward(ctypes.byref(desc), n, w_arr, _ptr(x), _ptr_array(codes_nonlocal),
+                                      None if valid_bits is None else _ptr_array(valid_bits), _ptr(x_out),
+                                      _ptr_array(codes_local_out), _ptr(workspace), nbytes, _stream()), "astra_stack_forward")
 
 
 def astra_probe_mfma_bf16(out, n_blocks: int, iters: int):

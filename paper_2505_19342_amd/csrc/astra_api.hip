@@ -338,9 +338,10 @@ size_t astra_block_workspace_bytes(const astra_block_desc* desc) {
     return bp.total;
 }
 
-int astra_block_forward(const astra_block_desc* desc, const astra_block_weights* w, const float* x, const void* codes_nonlocal,
-                        const uint64_t* valid_nonlocal_bits, float* x_out, void* codes_local_out, void* h_out,
-                        void* workspace, size_t workspace_bytes, void* stream) {
+// validate_only: every check of the call, no launch
+static int block_forward_impl(const astra_block_desc* desc, const astra_block_weights* w, const float* x, const void* codes_nonlocal,
+                              const uint64_t* valid_nonlocal_bits, float* x_out, void* codes_local_out, void* h_out,
+                              void* workspace, size_t workspace_bytes, void* stream, bool validate_only) {
     BlockPlan bp;
     int rc = make_block_plan(desc, &bp);
     if (rc) return rc;
@@ -385,6 +386,7 @@ int astra_block_forward(const astra_block_desc* desc, const astra_block_weights*
     if (rc) return rc;
     rc = launch_gemm_batch(dtype, &g2, 1, s, nullptr, nullptr, true);
     if (rc) return rc;
+    if (validate_only) return ASTRA_OK;
 
     // h = norm1(x) in the layer's element type: the tensor that is quantised and projected
     rc = launch_norm(dtype, desc->norm_kind, x, pl.Tq, pl.D, desc->eps, w->norm1_gain, w->norm1_bias, h, s);
@@ -402,6 +404,31 @@ int astra_block_forward(const astra_block_desc* desc, const astra_block_weights*
         if (rc) return rc;
     }
     return launch_gemm_batch(dtype, &g2, 1, s, nullptr, nullptr, false, ws + bp.off_split, bp.split_bytes);
+}
+
+int astra_block_forward(const astra_block_desc* desc, const astra_block_weights* w, const float* x, const void* codes_nonlocal,
+                        const uint64_t* valid_nonlocal_bits, float* x_out, void* codes_local_out, void* h_out,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+    return block_forward_impl(desc, w, x, codes_nonlocal, valid_nonlocal_bits, x_out, codes_local_out, h_out, workspace,
+                              workspace_bytes, stream, false);
+}
+
+int astra_stack_forward(const astra_block_desc* desc, int32_t n_layers, const astra_block_weights* weights, const float* x,
+                        const void* const* codes_nonlocal, const uint64_t* const* valid_nonlocal_bits, float* x_out,
+                        void* const* codes_local_out, void* workspace, size_t workspace_bytes, void* stream) {
+    if (n_layers < 0) return ASTRA_ERR_SHAPE;
+    if (!desc) return ASTRA_ERR_NULL;
+    if (n_layers == 0) return ASTRA_OK;
+    if (!weights || !codes_nonlocal || !codes_local_out) return ASTRA_ERR_NULL;
+    // two passes: validate every block, then launch them; block 0 reads x, the others continue in place on x_out
+    for (int pass = 0; pass < 2; ++pass)
+        for (int l = 0; l < n_layers; ++l) {
+            const int rc = block_forward_impl(desc, &weights[l], l == 0 ? x : x_out, codes_nonlocal[l],
+                                              valid_nonlocal_bits ? valid_nonlocal_bits[l] : nullptr, x_out, codes_local_out[l],
+                                              nullptr, workspace, workspace_bytes, stream, pass == 0);
+            if (rc) return rc;
+        }
+    return ASTRA_OK;
 }
 
 int astra_layer_forward_profiled(const astra_layer_desc* desc, const void* x_local, const void* codes_nonlocal,

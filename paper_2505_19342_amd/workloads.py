@@ -190,3 +190,19 @@ def generate_block(bcfg: BlockConfig) -> dict:
         mats = {k: round_to_bf16(v) for k, v in mats.items()}
     out.update(mats)
     return out
+
+
+def generate_stack(bcfg: BlockConfig, n_layers: int) -> dict:
+    """Tensors of n_layers blocks: {"x": [N, D] fp32 stream entering block 0, "cls": [n_dev, D] (if n_cls),
+    "layers": list of per-block dicts as generate_block() gives them (without x / cls), block l drawn with seed
+    layer.seed + 1000 * l}."""
+    first = generate_block(bcfg)
+    out = {"x": first.pop("x"), "layers": [first]}
+    if "cls" in first:
+        out["cls"] = first.pop("cls")
+    for l in range(1, n_layers):
+        p = generate_block(replace(bcfg, layer=replace(bcfg.layer, seed=bcfg.layer.seed + 1000 * l)))
+        p.pop("x")
+        p.pop("cls", None)
+        out["layers"].append(p)
+    return out

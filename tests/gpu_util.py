@@ -181,3 +181,26 @@ class BlockOnGpu:
         torch.cuda.synchronize()
         return (self.x_out.cpu().numpy(), codes_to_host(self.codes_local, self.cfg.codebook_size),
                 None if self.h is None else to_host(self.h))
+
+
+class StackOnGpu:
+    """n_layers blocks of one device: per-block weights and codes on the device, one shared workspace."""
+
+    def __init__(self, bcfg, layers, x_local, codes_nonlocal_per_layer, n_before):
+        self.blocks = [BlockOnGpu(bcfg, p, x_local, c, n_before, want_h=False) for p, c in zip(layers, codes_nonlocal_per_layer)]
+        b0 = self.blocks[0]
+        self.cfg, self.desc, self.x, self.x_out, self.workspace = b0.cfg, b0.desc, b0.x, b0.x_out, b0.workspace
+
+    def run(self):
+        B.astra_stack_forward(self.desc, [b.weights for b in self.blocks], self.x, [b.codes_nonlocal for b in self.blocks], None,
+                              self.x_out, [b.codes_local for b in self.blocks], self.workspace)
+
+    def run_block_by_block(self):
+        for i, b in enumerate(self.blocks):
+            B.astra_block_forward(self.desc, b.weights, self.x if i == 0 else self.x_out, b.codes_nonlocal, None, self.x_out,
+                                  b.codes_local, None, self.workspace)
+
+    def results(self):
+        torch.cuda.synchronize()
+        K = self.cfg.codebook_size
+        return self.x_out.cpu().numpy(), [codes_to_host(b.codes_local, K) for b in self.blocks]

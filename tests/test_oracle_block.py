@@ -237,3 +237,85 @@ def test_bf16_storage_of_the_mlp_intermediates_costs_about_2_to_the_minus_9_of_t
     err = stored - exact
     assert 0.8 * 2.0 ** -9 <= err.std() / rms <= 2.5 * 2.0 ** -9
     assert 2.0 ** -9 <= np.abs(err).max() / rms <= 2.0 ** -6
+
+
+# ---------------------------------------------------------------- the multi-device model (Sec. 3.1, 3.3)
+def test_model_with_lossless_codebooks_equals_the_single_device_transformer():
+    """If every normalised token is itself a codeword (G = 1, the codebook of each block lists the exact norm1 outputs),
+    quantisation is lossless, and the multi-device procedure must reproduce an ordinary pre-norm Transformer run on
+    the whole sequence on one device, here composed from torch's library routines (full softmax attention).  Two
+    blocks, three devices, non-causal and causal."""
+    rng = np.random.default_rng(41)
+    N, D, hq, dh, d_ff, n_dev, L = 12, 16, 2, 8, 24, 3, 2
+    for causal in (False, True):
+        x = rng.standard_normal((N, D)) * 1.5
+        layers, ref = [], t64(x)
+        for l in range(L):
+            f32 = lambda a: np.asarray(a, dtype=np.float32)
+            p = dict(wq=f32(0.3 * rng.standard_normal((D, hq * dh))), wk=f32(0.3 * rng.standard_normal((D, hq * dh))),
+                     wv=f32(0.3 * rng.standard_normal((D, hq * dh))), wo=f32(0.3 * rng.standard_normal((hq * dh, D))),
+                     g1=f32(1 + 0.2 * rng.standard_normal(D)), g2=f32(1 + 0.2 * rng.standard_normal(D)),
+                     be1=f32(0.2 * rng.standard_normal(D)), be2=f32(0.2 * rng.standard_normal(D)),
+                     w1=f32(0.3 * rng.standard_normal((D, d_ff))), w2=f32(0.3 * rng.standard_normal((d_ff, D))),
+                     b1=f32(rng.standard_normal(d_ff)), b2=f32(rng.standard_normal(D)))
+            # the single-device Transformer block on the whole sequence, in torch fp64
+            h = F.layer_norm(ref, (D,), t64(p["g1"]), t64(p["be1"]), eps=1e-5)
+            h32 = h.to(torch.float32)                       # the element type the layer sees
+            p["codebook"] = h32.numpy()[None, :, :].copy()  # G = 1, K = N: every token is its own codeword
+            hq_ = h32.to(torch.float64)
+            q = (hq_ @ t64(p["wq"])).view(N, hq, dh).transpose(0, 1)
+            k = (hq_ @ t64(p["wk"])).view(N, hq, dh).transpose(0, 1)
+            v = (hq_ @ t64(p["wv"])).view(N, hq, dh).transpose(0, 1)
+            o = F.scaled_dot_product_attention(q, k, v, is_causal=causal).transpose(0, 1).reshape(N, hq * dh)
+            r = ref + o @ t64(p["wo"])
+            m = F.gelu(F.layer_norm(r, (D,), t64(p["g2"]), t64(p["be2"]), eps=1e-5) @ t64(p["w1"]) + t64(p["b1"])) @ t64(p["w2"]) + t64(p["b2"])
+            ref = r + m
+            layers.append(p)
+            # the codebook of block l+1 needs the exact stream, which the loop carries in `ref`
+        got = oracle.model_forward(x, layers, n_dev=n_dev, n_q_heads=hq, n_kv_heads=hq, norm_kind="layernorm", eps=1e-5,
+                                   mlp_kind="gelu_erf", causal=causal)
+        out = np.concatenate(got["x"], axis=0)
+        # lossless up to fp64 rounding of the streams: codewords were built from the torch stream, so a near-tie between
+        # two tokens' codewords cannot flip (distinct random tokens are far apart)
+        np.testing.assert_allclose(out, ref.numpy(), rtol=1e-9, atol=1e-9)
+        for l in range(L):
+            sent = np.concatenate(got["codes"][l], axis=0)[:, 0]
+            np.testing.assert_array_equal(sent, np.arange(N))          # every token chose itself
+
+
+def test_model_exchange_order_class_rows_and_pooling():
+    rng = np.random.default_rng(42)
+    N, D, n_dev, L = 12, 16, 3, 2
+    layers = []
+    for l in range(L):
+        p = block_inputs(rng, D=D, G=2, K=8, hq=2, hkv=2, dh=4, tq=1, tn=1, d_ff=24, mlp_kind="gelu_tanh", biases=True)
+        p["codebook"] = p.pop("cb")
+        layers.append({k: v for k, v in p.items() if k not in ("x", "codes")})
+    x = rng.standard_normal((N, D))
+    cls = rng.standard_normal((n_dev, D))
+    got = oracle.model_forward(x, layers, n_dev=n_dev, n_q_heads=2, n_kv_heads=2, norm_kind="layernorm", eps=1e-5,
+                               mlp_kind="gelu_tanh", cls=cls)
+    tl = N // n_dev
+    for l in range(L):
+        for d in range(n_dev):
+            # what a device receives is what the others sent, in sequence order; class rows are never sent
+            assert got["codes"][l][d].shape == (tl, 2)
+            want = np.concatenate([got["codes"][l][e] for e in range(n_dev) if e != d])
+            np.testing.assert_array_equal(got["codes_nonlocal"][l][d], want)
+    assert all(s.shape == (tl + 1, D) for s in got["x"])
+    np.testing.assert_allclose(got["cls_pooled"], np.mean([s[0] for s in got["x"]], axis=0), rtol=1e-15)
+    # one block of the model = block_forward on each device with the exchanged codes
+    p = layers[0]
+    first = oracle.model_forward(x, layers[:1], n_dev=n_dev, n_q_heads=2, n_kv_heads=2, norm_kind="layernorm", eps=1e-5,
+                                 mlp_kind="gelu_tanh", cls=cls)
+    d = 1
+    xd = np.concatenate([cls[d:d + 1], x[d * tl:(d + 1) * tl]])
+    ref, *_ = oracle.block_forward(xd, first["codes_nonlocal"][0][d], p["codebook"], p["wq"], p["wk"], p["wv"], p["wo"],
+                                   norm_kind="layernorm", eps=1e-5, g1=p["g1"], g2=p["g2"], be1=p["be1"], be2=p["be2"],
+                                   mlp_kind="gelu_tanh", w1=p["w1"], w2=p["w2"], b1=p["b1"], b2=p["b2"], n_q_heads=2, n_kv_heads=2,
+                                   n_cls=1, bq=p["bq"], bk=p["bk"], bv=p["bv"], bo=p["bo"])
+    np.testing.assert_array_equal(first["x"][d], ref)
+    # blocks are applied in order: swapping the two blocks changes the result
+    swapped = oracle.model_forward(x, layers[::-1], n_dev=n_dev, n_q_heads=2, n_kv_heads=2, norm_kind="layernorm", eps=1e-5,
+                                   mlp_kind="gelu_tanh", cls=cls)
+    assert np.abs(swapped["x"][0] - got["x"][0]).max() > 1e-3

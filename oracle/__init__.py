@@ -44,7 +44,7 @@ def _load():
         for name in ("oracle_vq_encode", "oracle_vq_decode", "oracle_linear",
                      "oracle_mixed_attention", "oracle_mixed_attention_valid",
                      "oracle_layer_forward", "oracle_layer_forward_valid",
-                     "oracle_norm", "oracle_mlp", "oracle_block_forward"):
+                     "oracle_norm", "oracle_mlp", "oracle_block_forward", "oracle_layer_forward_kv"):
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -308,3 +308,39 @@ def model_forward(x_all, layers, *, n_dev, n_q_heads, n_kv_heads, norm_kind, eps
         received.append(rec)
     pooled = None if cls is None else np.mean(np.stack([s[0] for s in streams]), axis=0)
     return {"x": streams, "codes": sent, "codes_nonlocal": received, "cls_pooled": pooled}
+
+
+def layer_forward_kv(x_local, codes_k_nonlocal, codes_v_nonlocal, codebook_k, codebook_v, wq, wk, wv, wo, *, n_q_heads,
+                     n_kv_heads, n_cls=0, causal=False, n_before=0, scale=0.0, bq=None, bk=None, bv=None, bo=None,
+                     valid_nonlocal=None, kv_is_bf16=False):
+    """The layer with K and V quantised after projection (App. memory cost: two codebooks per layer of dimension
+    H_kv * dh).  codebook_k, codebook_v [G, K, dkv / G]; codes_*_nonlocal [T_n, G].  Returns dict: y [T_q, D] fp64,
+    codes_k, codes_v [T_l, G] int32 (what this device sends), gap_k, gap_v, k, v [T_q, dkv] fp32 (K and V as stored)."""
+    x_local = _f32(x_local)
+    codebook_k, codebook_v = _f32(codebook_k), _f32(codebook_v)
+    codes_k_nonlocal, codes_v_nonlocal = _i32(codes_k_nonlocal), _i32(codes_v_nonlocal)
+    wq, wk, wv, wo = map(_f32, (wq, wk, wv, wo))
+    bq, bk, bv, bo = map(_f32, (bq, bk, bv, bo))
+    G, K, dg = codebook_k.shape
+    Tq, D = x_local.shape
+    Tn = codes_k_nonlocal.shape[0]
+    dh = wq.shape[1] // n_q_heads
+    dkv = n_kv_heads * dh
+    assert codebook_v.shape == (G, K, dg) and G * dg == dkv
+    assert codes_k_nonlocal.shape == (Tn, G) and codes_v_nonlocal.shape == (Tn, G)
+    assert wq.shape == (D, n_q_heads * dh) and wk.shape == (D, dkv) and wv.shape == (D, dkv) and wo.shape == (n_q_heads * dh, D)
+    n_local = Tq - int(n_cls)
+    y = np.empty((Tq, D), dtype=np.float64)
+    ck, cv = np.empty((n_local, G), dtype=np.int32), np.empty((n_local, G), dtype=np.int32)
+    gk, gv = np.empty((n_local, G), dtype=np.float64), np.empty((n_local, G), dtype=np.float64)
+    k, v = np.empty((Tq, dkv), dtype=np.float32), np.empty((Tq, dkv), dtype=np.float32)
+    valid_nonlocal = _u8(valid_nonlocal)
+    assert valid_nonlocal is None or valid_nonlocal.shape == (Tn,)
+    rc = _load().oracle_layer_forward_kv(
+        _p(x_local), _p(codes_k_nonlocal), _p(codes_v_nonlocal), _p(valid_nonlocal), _p(codebook_k), _p(codebook_v), D, G, K,
+        _p(wq), _p(wk), _p(wv), _p(wo), _p(bq), _p(bk), _p(bv), _p(bo), n_q_heads, n_kv_heads, dh,
+        int(n_cls), n_local, Tn, int(bool(causal)), int(n_before), ctypes.c_double(scale), int(bool(kv_is_bf16)),
+        _p(y), _p(ck), _p(cv), _p(gk), _p(gv), _p(k), _p(v))
+    if rc:
+        raise ValueError(f"oracle_layer_forward_kv failed ({rc})")
+    return {"y": y, "codes_k": ck, "codes_v": cv, "gap_k": gk, "gap_v": gv, "k": k, "v": v}

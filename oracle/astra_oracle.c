@@ -20,6 +20,7 @@
  *   oracle_mixed_attention  Sec. 3.2 Eq. 1, sigma(Q [K | K-hat]^T / sqrt(d_k)) [V | V-hat]
  *   oracle_layer_forward    Sec. 3.1 (per-block procedure on one device)
  *   oracle_block_forward    Sec. 3.1, the whole block: norms, residuals and the local MLP around the layer
+ *   oracle_layer_forward_kv the layer with K and V quantised after projection (App. memory cost: C = 2, d = 1024)
  *
  * Readings taken where the paper is silent (they are the library's too):
  *   - groups are contiguous slices [g*dg, (g+1)*dg) of the D-vector;
@@ -403,5 +404,88 @@ int oracle_block_forward(const double* x, const int32_t* codes_nonlocal, const u
     if (!rc)
         for (int64_t i = 0; i < n; ++i) x_out[i] = r[i] + m[i];
     free(h); free(hf); free(y); free(r); free(m);
+    return rc;
+}
+
+/* ------------------------------------------------------------------------------------------------
+ * The layer with keys and values quantised AFTER projection (App. "Memory Cost Analysis": Llama-3-8B uses
+ * C = 2 codebooks per layer of hidden dimension d = 1024 = H_kv * dh, which is also what the 640 = 32 * 2 * 10
+ * bits per token of the Llama results imply; the main text's Sec. 3.2 quantises the embeddings instead — the two
+ * are different variants and both are kept).  On one device:
+ *   Q, K, V        = x_local W_q, x_local W_k, x_local W_v          K, V stored in the element type
+ *   codes_k_local  = encode(content rows of K; K codebook)  \   what this device transmits, and what a KV cache
+ *   codes_v_local  = encode(content rows of V; V codebook)  /   keeps of it on the other devices
+ *   K-hat, V-hat   = decode(codes_k_nonlocal), decode(codes_v_nonlocal)     no projection of rebuilt rows
+ *   Y              = Attn(Q, K, K-hat, V, V-hat) W_o                        (Eq. 1 unchanged)
+ * codebook_k, codebook_v [G, K, dkv / G].  kv_is_bf16: K and V are rounded to bf16 (nearest even) before they are
+ * quantised and attended to, as the device stores them; else to fp32.  k_out, v_out (nullable, [T_q, dkv] fp32)
+ * return those stored tensors.
+ * ------------------------------------------------------------------------------------------------ */
+static float round_elem(double v, int to_bf16) {
+    float f = (float)v;
+    if (to_bf16) {
+        uint32_t u;
+        memcpy(&u, &f, 4);
+        if ((u & 0x7f800000u) != 0x7f800000u) u += 0x7fffu + ((u >> 16) & 1u);
+        u &= 0xffff0000u;
+        memcpy(&f, &u, 4);
+    }
+    return f;
+}
+
+int oracle_layer_forward_kv(const float* x_local, const int32_t* codes_k_nonlocal, const int32_t* codes_v_nonlocal,
+                            const uint8_t* valid_nonlocal, const float* codebook_k, const float* codebook_v,
+                            int D, int G, int K,
+                            const float* wq, const float* wk, const float* wv, const float* wo,
+                            const float* bq, const float* bk, const float* bv, const float* bo,
+                            int n_q_heads, int n_kv_heads, int head_dim,
+                            int n_cls, int n_local, int n_nonlocal, int causal, int n_before, double scale,
+                            int kv_is_bf16,
+                            double* y, int32_t* codes_k_local, int32_t* codes_v_local, double* gap_k, double* gap_v,
+                            float* k_out, float* v_out) {
+    const int Tq = n_cls + n_local, Tn = n_nonlocal;
+    const int dq = n_q_heads * head_dim, dkv = n_kv_heads * head_dim;
+    if (G <= 0 || dkv % G != 0) return -1;
+    double* xl = (double*)malloc(sizeof(double) * ((int64_t)Tq * D + 1));
+    for (int64_t i = 0; i < (int64_t)Tq * D; ++i) xl[i] = (double)x_local[i];
+    double* Q = (double*)malloc(sizeof(double) * ((int64_t)Tq * dq + 1));
+    double* Kl = (double*)malloc(sizeof(double) * ((int64_t)Tq * dkv + 1));
+    double* Vl = (double*)malloc(sizeof(double) * ((int64_t)Tq * dkv + 1));
+    float* Kf = (float*)malloc(sizeof(float) * ((int64_t)Tq * dkv + 1));
+    float* Vf = (float*)malloc(sizeof(float) * ((int64_t)Tq * dkv + 1));
+    float* Khf = (float*)calloc((int64_t)Tn * dkv + 1, sizeof(float));
+    float* Vhf = (float*)calloc((int64_t)Tn * dkv + 1, sizeof(float));
+    double* Kh = (double*)malloc(sizeof(double) * ((int64_t)Tn * dkv + 1));
+    double* Vh = (double*)malloc(sizeof(double) * ((int64_t)Tn * dkv + 1));
+    double* O = (double*)malloc(sizeof(double) * ((int64_t)Tq * dq + 1));
+    oracle_linear(xl, Tq, D, dq, wq, bq, Q);
+    oracle_linear(xl, Tq, D, dkv, wk, bk, Kl);
+    oracle_linear(xl, Tq, D, dkv, wv, bv, Vl);
+    /* K and V as the device stores them: that is what gets quantised and what the local attention uses */
+    for (int64_t i = 0; i < (int64_t)Tq * dkv; ++i) {
+        Kf[i] = round_elem(Kl[i], kv_is_bf16);
+        Vf[i] = round_elem(Vl[i], kv_is_bf16);
+        Kl[i] = (double)Kf[i];
+        Vl[i] = (double)Vf[i];
+    }
+    if (k_out) memcpy(k_out, Kf, sizeof(float) * (int64_t)Tq * dkv);
+    if (v_out) memcpy(v_out, Vf, sizeof(float) * (int64_t)Tq * dkv);
+    int rc = oracle_vq_encode(Kf + (int64_t)n_cls * dkv, n_local, dkv, G, K, codebook_k, codes_k_local, gap_k);
+    if (!rc) rc = oracle_vq_encode(Vf + (int64_t)n_cls * dkv, n_local, dkv, G, K, codebook_v, codes_v_local, gap_v);
+    /* rows whose codes never arrived are not looked up; they stay zero and are excluded from the attention */
+    for (int64_t t = 0; t < Tn && !rc; ++t) {
+        if (valid_nonlocal && !valid_nonlocal[t]) continue;
+        rc = oracle_vq_decode(codes_k_nonlocal + t * G, 1, dkv, G, K, codebook_k, Khf + t * (int64_t)dkv);
+        if (!rc) rc = oracle_vq_decode(codes_v_nonlocal + t * G, 1, dkv, G, K, codebook_v, Vhf + t * (int64_t)dkv);
+    }
+    for (int64_t i = 0; i < (int64_t)Tn * dkv; ++i) {
+        Kh[i] = (double)Khf[i];
+        Vh[i] = (double)Vhf[i];
+    }
+    if (!rc)
+        rc = oracle_mixed_attention_valid(Q, Kl, Vl, Kh, Vh, valid_nonlocal, n_q_heads, n_kv_heads, head_dim, n_cls, n_local,
+                                          n_nonlocal, causal, n_before, scale, O, NULL, NULL);
+    if (!rc) oracle_linear(O, Tq, dq, D, wo, bo, y);
+    free(xl); free(Q); free(Kl); free(Vl); free(Kf); free(Vf); free(Khf); free(Vhf); free(Kh); free(Vh); free(O);
     return rc;
 }

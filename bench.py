@@ -60,7 +60,7 @@ def main():
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the measurements outside the timed region (matrix-core probe, stand-alone decode, other ranks)")
     ap.add_argument("--extras", default="all",
-                    help="comma list of the measurements outside the timed region to run: ranks, lost, block, stack (needs block), decode, probe (default all)")
+                    help="comma list of the measurements outside the timed region to run: ranks, lost, block, stack (needs block), kv, decode, probe (default all)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the warm-up, run one plain elementwise copy kernel reading and writing this many MiB "
                          "(fp32): the reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -199,7 +199,7 @@ def main():
     per_step = sorted(ev.elapsed_ms(0, 4) for ev in events)
     result["gpu_ms_per_step_events_p10_p50_p90"] = [per_step[int(q * (len(per_step) - 1))] for q in (0.1, 0.5, 0.9)]
 
-    extras = set() if args.no_extras else set(("ranks,lost,block,stack,decode,probe" if args.extras == "all" else args.extras).split(","))
+    extras = set() if args.no_extras else set(("ranks,lost,block,stack,kv,decode,probe" if args.extras == "all" else args.extras).split(","))
     if extras:
         def timed(fn, n, warm=0):
             for _ in range(1 + warm):      # after host-side set-up the chip is idle: bring it back to its steady clock
@@ -289,6 +289,34 @@ def main():
                                            "(the exchange of codes between blocks is not timed: they are resident inputs)"}
                 del keep, w_list, codes_in, codes_out
             del bt, bw, bx, bout, bws, bdata
+        # the variant that quantises K and V after projection (App. memory cost: C = 2 codebooks of dimension H_kv * dh; the
+        # paper's Llama configuration): local projections only, two encodes, the peers' K-hat / V-hat looked up from codes
+        if "kv" in extras and tn > 0:
+            kdata = wl.generate_kv(cfg)
+            gk = kdata["codebook_k"].shape[0]
+            dkv = cfg.n_kv_heads * cfg.head_dim
+            vqk = B.vq_desc(dt, dkv, gk, K)
+            cbk, cbv = to_dev(kdata["codebook_k"]), to_dev(kdata["codebook_v"])
+            cnk = torch.empty((gk, K), dtype=torch.float32, device=dev)
+            cnv = torch.empty_like(cnk)
+            B.astra_vq_prepare(vqk, cbk, cnk)
+            B.astra_vq_prepare(vqk, cbv, cnv)
+            kgen = torch.Generator(device=dev).manual_seed(cfg.seed + 78)
+            ck_nl = torch.randint(0, K, (tn, gk), generator=kgen, device=dev, dtype=torch.int32).to(code_t)
+            cv_nl = torch.randint(0, K, (tn, gk), generator=kgen, device=dev, dtype=torch.int32).to(code_t)
+            kdesc = B.LayerKvDesc(vqk, desc.attn, D)
+            ck_l = torch.empty((tq - cfg.n_cls, gk), dtype=code_t, device=dev)
+            cv_l = torch.empty_like(ck_l)
+            kws = torch.empty(max(B.astra_layer_kv_workspace_bytes(kdesc), 256), dtype=torch.uint8, device=dev)
+            k_args = (kdesc, x_local, ck_nl, cv_nl, None, cbk, cnk, cbv, cnv, *w, None, None, None, None, y, ck_l, cv_l, None, None, kws)
+            ms = timed(lambda: B.astra_layer_forward_kv(*k_args), 300, warm=100)
+            kv_flops = (2.0 * tq * D * (cfg.n_q_heads * cfg.head_dim + 2 * dkv) + 2 * 2.0 * (tq - cfg.n_cls) * dkv * K
+                        + flops["attention"] + flops["out_projection"])
+            result["kv_variant"] = {"G_kv": gk, "bits_per_token": 2 * gk * int(np.ceil(np.log2(K))), "ms": ms,
+                                    "tokens_per_s": tq / (ms * 1e-3), "flops": kv_flops, "tflops": kv_flops / (ms * 1e-3) / 1e12,
+                                    "vs_embedding_space_layer": ms / ms_per_step,
+                                    "what": "astra_layer_forward_kv at the same shape: no projection of rebuilt rows"}
+            del cbk, cbv, ck_nl, cv_nl, kws
         # (2) the decode as a kernel of its own (inside the layer it is fused into the projection's operand load):
         #     the HBM-bound step; algorithmic bytes = codes + codebook + rebuilt rows
         t_v = view["n_before"] if cfg.causal else tn

@@ -176,6 +176,38 @@ int astra_layer_forward_profiled(const astra_layer_desc* desc, const void* x_loc
                                  void* workspace, size_t workspace_bytes, void* stream,
                                  void* const* stage_events);
 
+/* ---- the layer with keys and values quantised after projection ------------------------------------
+ * App. "Memory Cost Analysis" describes Llama-3-8B with C = 2 codebooks per layer of hidden dimension
+ * d = 1024 = H_kv * dh (and its 640 = 32 * 2 * 10 bits per token say the same): each device projects its
+ * local rows, quantises its K rows with a K codebook and its V rows with a V codebook, transmits both code
+ * streams, and looks its peers' K-hat and V-hat up directly: no projection of rebuilt rows, and the received
+ * codes are what a KV cache keeps of the non-local tokens.  Eq. 1 is unchanged.
+ *   vq                describes BOTH codebooks; vq.d_model must equal n_kv_heads * head_dim
+ *   d_model           D, width of x_local and y_out
+ *   codes_k_nonlocal, codes_v_nonlocal  [T_n, G] in sequence order; valid_nonlocal_bits as for
+ *                     astra_layer_forward_valid (nullable)
+ *   codebook_k/v [G, K, dkv/G], cnorm_k/v [G, K] from astra_vq_prepare
+ *   y_out             [T_q, D] fp32
+ *   codes_k_local_out, codes_v_local_out  [T_l, G]: codes of the content rows of K and V as stored
+ *   k_out, v_out      nullable [T_q, dkv] in the element type: receive K and V of the local rows (the rows a
+ *                     KV cache keeps at full precision); when NULL they live in the workspace only
+ * bf16 needs dkv / G to be a multiple of 8. */
+typedef struct {
+    astra_vq_desc vq;
+    astra_attn_desc attn;
+    int32_t d_model;
+} astra_layer_kv_desc;
+
+size_t astra_layer_kv_workspace_bytes(const astra_layer_kv_desc* desc);
+
+int astra_layer_forward_kv(const astra_layer_kv_desc* desc, const void* x_local,
+                           const void* codes_k_nonlocal, const void* codes_v_nonlocal, const uint64_t* valid_nonlocal_bits,
+                           const void* codebook_k, const float* cnorm_k, const void* codebook_v, const float* cnorm_v,
+                           const void* wq, const void* wk, const void* wv, const void* wo,
+                           const void* bq, const void* bk, const void* bv, const void* bo,
+                           void* y_out, void* codes_k_local_out, void* codes_v_local_out, void* k_out, void* v_out,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- one whole Transformer block on one device -------------------------------------------------
  * Sec. 3.1: per block, a device quantises its local token embeddings, exchanges indices, attends with
  * the mixed-precision layer and then runs the position-wise MLP locally, without communication.  The

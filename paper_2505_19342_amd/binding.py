@@ -17,6 +17,7 @@ EXPORTS = ("astra_vq_prepare", "astra_vq_encode", "astra_vq_decode", "astra_mixe
            "astra_mixed_attention_valid", "astra_layer_forward_valid",
            "astra_layer_workspace_bytes", "astra_layer_encode_fused", "astra_layer_forward", "astra_layer_forward_profiled",
            "astra_block_workspace_bytes", "astra_block_forward", "astra_stack_forward",
+           "astra_layer_kv_workspace_bytes", "astra_layer_forward_kv",
            "astra_probe_mfma_bf16", "astra_status_string", "astra_version")
 ASTRA_NORM_LAYER, ASTRA_NORM_RMS = 0, 1
 ASTRA_MLP_GELU_TANH, ASTRA_MLP_GELU_ERF, ASTRA_MLP_SWIGLU = 0, 1, 2
@@ -42,6 +43,10 @@ class AttnDesc(ctypes.Structure):
 
 class LayerDesc(ctypes.Structure):
     _fields_ = [("vq", VqDesc), ("attn", AttnDesc)]
+
+
+class LayerKvDesc(ctypes.Structure):
+    _fields_ = [("vq", VqDesc), ("attn", AttnDesc), ("d_model", ctypes.c_int32)]
 
 
 class BlockDesc(ctypes.Structure):
@@ -88,6 +93,10 @@ def load(build_if_missing: bool = True):
     lib.astra_block_workspace_bytes.restype = ctypes.c_size_t
     lib.astra_block_forward.argtypes = [ctypes.POINTER(BlockDesc), ctypes.POINTER(BlockWeights)] + [vp] * 7 + [ctypes.c_size_t, vp]
     lib.astra_block_forward.restype = ctypes.c_int
+    lib.astra_layer_kv_workspace_bytes.argtypes = [ctypes.POINTER(LayerKvDesc)]
+    lib.astra_layer_kv_workspace_bytes.restype = ctypes.c_size_t
+    lib.astra_layer_forward_kv.argtypes = [ctypes.POINTER(LayerKvDesc)] + [vp] * 22 + [ctypes.c_size_t, vp]
+    lib.astra_layer_forward_kv.restype = ctypes.c_int
     pp = ctypes.POINTER(ctypes.c_void_p)
     lib.astra_stack_forward.argtypes = [ctypes.POINTER(BlockDesc), ctypes.c_int32, ctypes.POINTER(BlockWeights), vp, pp, pp, vp, pp,
                                         vp, ctypes.c_size_t, vp]
@@ -196,6 +205,21 @@ def astra_block_forward(desc: BlockDesc, weights: BlockWeights, x, codes_nonloca
     _check(load().astra_block_forward(ctypes.byref(desc), ctypes.byref(weights), _ptr(x), _ptr(codes_nonlocal), _ptr(valid_bits),
                                       _ptr(x_out), _ptr(codes_local_out), _ptr(h_out), _ptr(workspace), nbytes, _stream()),
            "astra_block_forward")
+
+
+def astra_layer_kv_workspace_bytes(desc: LayerKvDesc) -> int:
+    return int(load().astra_layer_kv_workspace_bytes(ctypes.byref(desc)))
+
+
+def astra_layer_forward_kv(desc: LayerKvDesc, x_local, codes_k_nonlocal, codes_v_nonlocal, valid_bits, codebook_k, cnorm_k,
+                           codebook_v, cnorm_v, wq, wk, wv, wo, bq, bk, bv, bo, y_out, codes_k_local_out, codes_v_local_out,
+                           k_out, v_out, workspace):
+    nbytes = workspace.numel() * workspace.element_size()
+    _check(load().astra_layer_forward_kv(
+        ctypes.byref(desc), _ptr(x_local), _ptr(codes_k_nonlocal), _ptr(codes_v_nonlocal), _ptr(valid_bits), _ptr(codebook_k),
+        _ptr(cnorm_k), _ptr(codebook_v), _ptr(cnorm_v), _ptr(wq), _ptr(wk), _ptr(wv), _ptr(wo), _ptr(bq), _ptr(bk), _ptr(bv),
+        _ptr(bo), _ptr(y_out), _ptr(codes_k_local_out), _ptr(codes_v_local_out), _ptr(k_out), _ptr(v_out), _ptr(workspace),
+        nbytes, _stream()), "astra_layer_forward_kv")
 
 
 def _ptr_array(tensors):

@@ -88,6 +88,46 @@ static int make_plan(const astra_layer_desc* desc, LayerPlan* pl) {
     return ASTRA_OK;
 }
 
+struct KvPlan {
+    int Tq, Tn, Tn_vis, D, dq, dkv;
+    bool vt;
+    int ldv_loc, ldv_hat;
+    size_t off_q, off_k, off_v, off_vt, off_kh, off_vh, off_o, total;
+};
+
+static int make_kv_plan(const astra_layer_kv_desc* desc, KvPlan* pl) {
+    if (!desc) return ASTRA_ERR_NULL;
+    int rc = check_vq_desc(&desc->vq);
+    if (rc) return rc;
+    rc = check_attn_desc(&desc->attn);
+    if (rc) return rc;
+    if (desc->vq.dtype != desc->attn.dtype) return ASTRA_ERR_DTYPE;
+    const astra_attn_desc& a = desc->attn;
+    if (desc->d_model <= 0 || desc->vq.d_model != a.n_kv_heads * a.head_dim) return ASTRA_ERR_SHAPE;
+    const int dtype = desc->vq.dtype, eb = elem_bytes(dtype);
+    pl->Tq = a.n_cls + a.n_local;
+    pl->Tn = a.n_nonlocal;
+    pl->Tn_vis = a.causal ? a.n_nonlocal_before : a.n_nonlocal;
+    pl->D = desc->d_model;
+    pl->dq = a.n_q_heads * a.head_dim;
+    pl->dkv = a.n_kv_heads * a.head_dim;
+    pl->vt = dtype == ASTRA_BF16;
+    if (pl->vt && ((pl->dkv / desc->vq.n_groups) % 8 != 0 || pl->D % 64 != 0)) return ASTRA_ERR_UNSUPPORTED;
+    pl->ldv_loc = (int)align_up((size_t)pl->Tq, 64);
+    pl->ldv_hat = (int)align_up((size_t)pl->Tn_vis, 64);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    pl->off_q = take((size_t)pl->Tq * pl->dq * eb);
+    pl->off_k = take((size_t)pl->Tq * pl->dkv * eb);
+    pl->off_v = take((size_t)pl->Tq * pl->dkv * eb);
+    pl->off_vt = take(pl->vt ? (size_t)pl->ldv_loc * pl->dkv * eb : 0);
+    pl->off_kh = take((size_t)pl->Tn_vis * pl->dkv * eb);
+    pl->off_vh = take((size_t)(pl->vt ? pl->ldv_hat : pl->Tn_vis) * pl->dkv * eb);
+    pl->off_o = take((size_t)pl->Tq * pl->dq * eb);
+    pl->total = off > 0 ? off : 256;
+    return ASTRA_OK;
+}
+
 struct BlockPlan {
     LayerPlan layer;
     int d_ff;
@@ -330,6 +370,87 @@ int astra_layer_forward_valid(const astra_layer_desc* desc, const void* x_local,
                               void* y_out, void* codes_local_out, void* workspace, size_t workspace_bytes, void* stream) {
     return layer_forward_impl(desc, x_local, codes_nonlocal, codebook, cnorm, wq, wk, wv, wo, bq, bk, bv, bo, y_out,
                               codes_local_out, workspace, workspace_bytes, stream, nullptr, nullptr, valid_nonlocal_bits);
+}
+
+size_t astra_layer_kv_workspace_bytes(const astra_layer_kv_desc* desc) {
+    KvPlan pl;
+    if (make_kv_plan(desc, &pl) != ASTRA_OK) return 0;
+    return pl.total;
+}
+
+int astra_layer_forward_kv(const astra_layer_kv_desc* desc, const void* x_local, const void* codes_k_nonlocal,
+                           const void* codes_v_nonlocal, const uint64_t* valid_nonlocal_bits, const void* codebook_k,
+                           const float* cnorm_k, const void* codebook_v, const float* cnorm_v, const void* wq, const void* wk,
+                           const void* wv, const void* wo, const void* bq, const void* bk, const void* bv, const void* bo,
+                           void* y_out, void* codes_k_local_out, void* codes_v_local_out, void* k_out, void* v_out,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+    KvPlan pl;
+    int rc = make_kv_plan(desc, &pl);
+    if (rc) return rc;
+    if (pl.Tq == 0) return ASTRA_OK;
+    const astra_vq_desc& vq = desc->vq;
+    const astra_attn_desc& at = desc->attn;
+    if (!x_local || !codebook_k || !cnorm_k || !codebook_v || !cnorm_v || !wq || !wk || !wv || !wo || !y_out) return ASTRA_ERR_NULL;
+    if (at.n_local > 0 && (!codes_k_local_out || !codes_v_local_out)) return ASTRA_ERR_NULL;
+    if (pl.Tn_vis > 0 && (!codes_k_nonlocal || !codes_v_nonlocal)) return ASTRA_ERR_NULL;
+    if (!workspace || workspace_bytes < pl.total) return ASTRA_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    const int dtype = vq.dtype, eb = elem_bytes(dtype);
+    char* ws = (char*)workspace;
+    void *Q = ws + pl.off_q, *K = k_out ? k_out : ws + pl.off_k, *V = v_out ? v_out : ws + pl.off_v, *Vt = ws + pl.off_vt,
+         *Kh = ws + pl.off_kh, *Vh = ws + pl.off_vh, *O = ws + pl.off_o;
+
+    // 1. projections of the local rows only; K and V row-major, as they are quantised and cached
+    GemmProblem pr[3] = {};
+    auto local = [&](GemmProblem& g, const void* w, const void* b, void* c, int n) {
+        g.a = x_local; g.b = w; g.bias = b; g.c = c; g.M = pl.Tq; g.N = n; g.K = pl.D; g.lda = pl.D; g.ldc = n;
+        g.c_mode = dtype == ASTRA_BF16 ? kCBf16 : kCF32;
+    };
+    local(pr[0], wq, bq, Q, pl.dq);
+    local(pr[1], wk, bk, K, pl.dkv);
+    local(pr[2], wv, bv, V, pl.dkv);
+    GemmProblem po = {};
+    po.a = O; po.b = wo; po.bias = bo; po.c = y_out; po.M = pl.Tq; po.N = pl.D; po.K = pl.dq; po.lda = pl.dq; po.ldc = pl.D;
+    po.c_mode = kCF32;
+    rc = launch_gemm_batch(dtype, pr, 3, s, nullptr, nullptr, true);      // both GEMM launches validated before anything runs
+    if (rc) return rc;
+    rc = launch_gemm_batch(dtype, &po, 1, s, nullptr, nullptr, true);
+    if (rc) return rc;
+    rc = launch_gemm_batch(dtype, pr, 3, s);
+    if (rc) return rc;
+
+    // 2. what this device transmits: codes of the content rows of K and of V (the class row is not sent)
+    if (at.n_local > 0) {
+        rc = launch_vq_encode(vq, (const char*)K + (size_t)at.n_cls * pl.dkv * eb, pl.dkv, at.n_local, codebook_k, cnorm_k,
+                              codes_k_local_out, s);
+        if (rc) return rc;
+        rc = launch_vq_encode(vq, (const char*)V + (size_t)at.n_cls * pl.dkv * eb, pl.dkv, at.n_local, codebook_v, cnorm_v,
+                              codes_v_local_out, s);
+        if (rc) return rc;
+    }
+
+    // 3. the peers' keys and values, looked up from their codes; values go straight into the attention's layout
+    if (pl.Tn_vis > 0) {
+        rc = launch_vq_decode(vq, codes_k_nonlocal, pl.Tn_vis, codebook_k, Kh, s);
+        if (rc) return rc;
+        if (pl.vt) rc = launch_vt_pack(vq, nullptr, 0, codes_v_nonlocal, codebook_v, pl.Tn_vis, pl.dkv, Vh, pl.ldv_hat, s);
+        else rc = launch_vq_decode(vq, codes_v_nonlocal, pl.Tn_vis, codebook_v, Vh, s);
+        if (rc) return rc;
+    }
+    if (pl.vt) {
+        rc = launch_vt_pack(vq, V, pl.dkv, nullptr, nullptr, pl.Tq, pl.dkv, Vt, pl.ldv_loc, s);
+        if (rc) return rc;
+    }
+
+    // 4. mixed-precision attention (Eq. 1) and the output projection
+    AttnParams ap = attn_params(at, Q, K, pl.vt ? Vt : V, Kh, Vh, O, nullptr);
+    ap.v_transposed = pl.vt ? 1 : 0;
+    ap.valid_bits = (const unsigned long long*)valid_nonlocal_bits;
+    ap.ldv_loc = pl.ldv_loc;
+    ap.ldv_hat = pl.ldv_hat;
+    rc = launch_attention(dtype, ap, at.head_dim, s);
+    if (rc) return rc;
+    return launch_gemm_batch(dtype, &po, 1, s);
 }
 
 size_t astra_block_workspace_bytes(const astra_block_desc* desc) {

@@ -115,6 +115,9 @@ int launch_vq_encode(const astra_vq_desc& d, const void* x, int64_t ldx, int64_t
 int launch_vq_decode(const astra_vq_desc& d, const void* codes, int64_t n_tokens, const void* codebook,
                      void* x_hat, hipStream_t s);
 
+int launch_vt_pack(const astra_vq_desc& d, const void* src, int64_t ld_src, const void* codes, const void* codebook, int T, int C,
+                   void* dst, int ldv, hipStream_t s);
+
 // One C[M,N] = A[M,K] . B[N,K]^T (+ bias[N]) problem of a grouped launch.  When `codes` is set the
 // rows of A are not read from `a` but rebuilt on the fly: A[m, g*dg + j] = codebook[g, codes[m, g], j].
 enum { kCBf16 = 0,          // bf16, row-major [M, ldc]

@@ -87,6 +87,86 @@ int launch_vq_decode(const astra_vq_desc& d, const void* codes, int64_t n_tokens
 }
 
 // ------------------------------------------------------------------------------------------------
+// Rows -> the transposed layout the bf16 attention kernel reads its values in: dst [C, ldv] with the token index
+// permuted inside blocks of 16 (offsets 0-3, 8-11, 4-7, 12-15: bits 2 and 3 of the offset swapped), columns beyond
+// T zero.  The rows are either a dense matrix src [T, ld_src] or, for values that arrive as codes (the variant that
+// quantises K and V after projection), looked up in the codebook on the way (GATHER; dg a multiple of 8).
+// One workgroup moves 64 tokens x 64 channels through LDS: 16-byte pieces in, 16-byte pieces (8 tokens of one
+// channel) out, 8 consecutive threads writing 128 contiguous bytes.
+// ------------------------------------------------------------------------------------------------
+constexpr int kVtStride = 72;      // halfwords per LDS row: 16-byte aligned, and 8 rows of one column fall into 8 different banks
+
+template <bool GATHER, typename CodeT>
+__global__ __launch_bounds__(256) void vt_pack_kernel(const uint16_t* __restrict__ src, int64_t ld_src, const CodeT* __restrict__ codes,
+                                                      const uint16_t* __restrict__ codebook, int T, int G, int K, int dg,
+                                                      uint16_t* __restrict__ dst, int ldv) {
+    __shared__ __attribute__((aligned(16))) uint16_t tile[64 * kVtStride];
+    const int t0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int piece = tid + 256 * it;
+        const int tl = piece >> 3, pc = piece & 7;
+        const int t = t0 + tl, c = c0 + 8 * pc;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (t < T) {
+            if (GATHER) {
+                const int g = c / dg, j = c - g * dg;
+                int code = (int)codes[(int64_t)t * G + g];
+                code = code < K ? code : K - 1;
+                v = *reinterpret_cast<const u32x4*>(codebook + ((int64_t)g * K + code) * dg + j);
+            } else {
+                v = *reinterpret_cast<const u32x4*>(src + (int64_t)t * ld_src + c);
+            }
+        }
+        *reinterpret_cast<u32x4*>(&tile[tl * kVtStride + 8 * pc]) = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int q = tid & 7;                      // which run of 8 positions of the 64 tokens
+        const int c = (tid >> 3) + 32 * it;
+        const int blk = q >> 1, half = q & 1;
+        uint16_t e[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int p = 8 * half + i;
+            const int o = (((p >> 2) & 1) << 3) | ((p >> 3) << 2) | (p & 3);
+            e[i] = tile[(16 * blk + o) * kVtStride + c];
+        }
+        u32x4 w;
+        w.x = e[0] | ((uint32_t)e[1] << 16);
+        w.y = e[2] | ((uint32_t)e[3] << 16);
+        w.z = e[4] | ((uint32_t)e[5] << 16);
+        w.w = e[6] | ((uint32_t)e[7] << 16);
+        *reinterpret_cast<u32x4*>(dst + (int64_t)(c0 + c) * ldv + t0 + 8 * q) = w;
+    }
+}
+
+// src != nullptr: plain rows; else codes + codebook (d describes the codebook; d.d_model = C).
+int launch_vt_pack(const astra_vq_desc& d, const void* src, int64_t ld_src, const void* codes, const void* codebook, int T, int C,
+                   void* dst, int ldv, hipStream_t s) {
+    if (d.dtype != ASTRA_BF16 || C % 64 != 0 || ldv % 64 != 0 || ldv < T || T < 0) return ASTRA_ERR_UNSUPPORTED;
+    if (ldv == 0) return ASTRA_OK;
+    const dim3 grid(ldv / 64, C / 64);
+    uint16_t* out = (uint16_t*)dst;
+    if (src) {
+        if (ld_src % 8 != 0) return ASTRA_ERR_UNSUPPORTED;
+        vt_pack_kernel<false, uint8_t><<<grid, 256, 0, s>>>((const uint16_t*)src, ld_src, nullptr, nullptr, T, 0, 0, 0, out, ldv);
+        return launch_status();
+    }
+    const int dg = d.d_model / d.n_groups;
+    if (dg % 8 != 0 || d.d_model != C) return ASTRA_ERR_UNSUPPORTED;
+    if (d.code_type == ASTRA_CODE_U16)
+        vt_pack_kernel<true, uint16_t><<<grid, 256, 0, s>>>(nullptr, 0, (const uint16_t*)codes, (const uint16_t*)codebook, T, d.n_groups,
+                                                            d.codebook_size, dg, out, ldv);
+    else
+        vt_pack_kernel<true, uint8_t><<<grid, 256, 0, s>>>(nullptr, 0, (const uint8_t*)codes, (const uint16_t*)codebook, T, d.n_groups,
+                                                           d.codebook_size, dg, out, ldv);
+    return launch_status();
+}
+
+// ------------------------------------------------------------------------------------------------
 // Encode, fp32: one wavefront per (token, group).  Lanes stride over the codewords and evaluate the
 // definition sum_j (x_j - c_j)^2 directly; the wavefront then reduces (distance, index)
 // lexicographically so that the lowest index wins a tie.

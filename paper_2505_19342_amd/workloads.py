@@ -206,3 +206,23 @@ def generate_stack(bcfg: BlockConfig, n_layers: int) -> dict:
         p.pop("cls", None)
         out["layers"].append(p)
     return out
+
+
+# ---- the variant that quantises K and V after projection (App. memory cost: C = 2 codebooks of dimension H_kv * dh) ----
+KV_GROUPS = {"tiny_vit_f32": 4, "vit_base_bf16": 16, "gpt2_small_bf16": 32, "llama3_8b_bf16": 32}
+
+
+def generate_kv(cfg: LayerConfig, n_groups_kv: int | None = None) -> dict:
+    """generate(cfg) plus the two codebooks of the KV-space variant, codebook_k and codebook_v [G_kv, K, dkv / G_kv]
+    ~ N(0, 1.3^2) (the scale of K = X W_k for unit-variance rows and N(0, 0.02^2) weights at D = 4096); the X-space
+    codebook of generate() stays in the dict but is not used by that variant.  Llama: G_kv = 32, K = 1024, i.e. the
+    640 bits per token of the paper's Llama results."""
+    out = generate(cfg)
+    g = n_groups_kv if n_groups_kv is not None else KV_GROUPS.get(cfg.name, cfg.n_groups)
+    dkv = cfg.n_kv_heads * cfg.head_dim
+    assert dkv % g == 0
+    rng = np.random.default_rng(cfg.seed + 4243)
+    for name in ("codebook_k", "codebook_v"):
+        cb = (1.3 * rng.standard_normal((g, cfg.codebook_size, dkv // g), dtype=np.float32)).astype(np.float32)
+        out[name] = round_to_bf16(cb) if cfg.dtype == "bf16" else cb
+    return out

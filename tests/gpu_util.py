@@ -204,3 +204,80 @@ class StackOnGpu:
         torch.cuda.synchronize()
         K = self.cfg.codebook_size
         return self.x_out.cpu().numpy(), [codes_to_host(b.codes_local, K) for b in self.blocks]
+
+
+def check_h_and_codes(dtype, n_cls, h, h_ref, codes, codes_ref, gap, codebook, near_tie=1e-5):
+    """h: the tensor that was quantised (GPU's and the oracle's, [n_cls + T, G * dg]); codes [T, G] of its content rows.
+    fp32: h within 1e-5 and codes under the near-tie rule.  bf16: h bit-equal except a counted few elements one bf16
+    step away (or within 2e-6 where the value cancels to near zero); codes of group slices whose h agrees under the
+    near-tie rule; codes of slices whose h differs by e must be justified by it:
+    |h - c'|^2 - |h - c*|^2 <= 2 |e| (|h - c'| + |h - c*|).  Returns (near-tie codes, differing slices, of those with
+    another codeword)."""
+    G, K, dg = codebook.shape
+    NEAR_TIE = near_tie
+    if dtype == "f32":
+        assert np.abs(h - h_ref).max() <= 1e-5
+        same = np.ones(codes.shape, dtype=bool)
+    else:
+        diff = h != h_ref
+        # one bf16 step at most (2^-7 relative is the largest step next to a value); where gain * v + bias cancels to
+        # a tiny value, the fp32 rounding of the O(1) terms (a few 1e-7) spans several steps of the result
+        assert np.all(np.abs(h - h_ref)[diff] <= np.abs(h_ref)[diff] * 2.0 ** -7 + 2e-6)
+        assert diff.mean() <= 1e-3, f"{diff.mean():.2e} of h differs from the oracle's rounding"
+        same = ~diff[n_cls:].reshape(-1, G, dg).any(-1)
+    d = codes != codes_ref
+    bad = d & same & ~(gap < NEAR_TIE)
+    assert not bad.any(), f"{int(bad.sum())} codes differ away from near-ties; first at {np.argwhere(bad)[0]}"
+    n_tie = int((d & same).sum())
+    # slices whose h differs: the chosen codeword must be justified by the differing h
+    ts, gs = np.nonzero(d & ~same)
+    for t, g in zip(ts, gs):
+        hs = h_ref[n_cls + t, g * dg:(g + 1) * dg].astype(np.float64)
+        e = h[n_cls + t, g * dg:(g + 1) * dg].astype(np.float64) - hs
+        r_gpu = np.linalg.norm(hs - codebook[g, codes[t, g]])
+        r_ref = np.linalg.norm(hs - codebook[g, codes_ref[t, g]])
+        assert r_gpu ** 2 - r_ref ** 2 <= 2 * np.linalg.norm(e) * (r_gpu + r_ref) + NEAR_TIE * r_ref ** 2
+    return n_tie, int((~same).sum()), len(ts)
+
+
+class KvLayerOnGpu:
+    """Device-resident tensors of one call of the layer that quantises K and V after projection."""
+
+    def __init__(self, cfg, data, x_local, codes_k_nonlocal, codes_v_nonlocal, n_before, biases=None):
+        dt = cfg.dtype
+        self.cfg = cfg
+        G, K, dg = data["codebook_k"].shape
+        dkv = cfg.n_kv_heads * cfg.head_dim
+        Tq, Tn = x_local.shape[0], codes_k_nonlocal.shape[0]
+        self.desc = B.LayerKvDesc(
+            B.vq_desc(dt, dkv, G, K),
+            B.attn_desc(dt, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n_cls, Tq - cfg.n_cls, Tn, cfg.causal, n_before),
+            cfg.d_model)
+        self.x_local = to_dev(x_local, dt)
+        self.ck = codes_to_dev(codes_k_nonlocal, K) if Tn > 0 else None
+        self.cv = codes_to_dev(codes_v_nonlocal, K) if Tn > 0 else None
+        self.cbk, self.cbv = to_dev(data["codebook_k"], dt), to_dev(data["codebook_v"], dt)
+        self.cnk = torch.empty((G, K), dtype=torch.float32, device=DEV)
+        self.cnv = torch.empty((G, K), dtype=torch.float32, device=DEV)
+        B.astra_vq_prepare(self.desc.vq, self.cbk, self.cnk)
+        B.astra_vq_prepare(self.desc.vq, self.cbv, self.cnv)
+        self.w = [to_dev(np.ascontiguousarray(data[n].T), dt) for n in ("wq", "wk", "wv", "wo")]
+        self.b = [None] * 4 if biases is None else [to_dev(b, dt) for b in biases]
+        self.y = torch.empty((Tq, cfg.d_model), dtype=torch.float32, device=DEV)
+        self.codes_k = empty_codes(Tq - cfg.n_cls, G, K)
+        self.codes_v = empty_codes(Tq - cfg.n_cls, G, K)
+        self.k = empty_like_dtype((Tq, dkv), dt)
+        self.v = empty_like_dtype((Tq, dkv), dt)
+        self.workspace = torch.empty(max(B.astra_layer_kv_workspace_bytes(self.desc), 256), dtype=torch.uint8, device=DEV)
+
+    def run(self, valid_nonlocal=None, keep_kv=True):
+        vb = None if valid_nonlocal is None else valid_bits_to_dev(valid_nonlocal)
+        B.astra_layer_forward_kv(self.desc, self.x_local, self.ck, self.cv, vb, self.cbk, self.cnk, self.cbv, self.cnv, *self.w,
+                                 *self.b, self.y, self.codes_k, self.codes_v, self.k if keep_kv else None,
+                                 self.v if keep_kv else None, self.workspace)
+
+    def results(self):
+        torch.cuda.synchronize()
+        K = self.desc.vq.codebook_size
+        return {"y": self.y.cpu().numpy(), "codes_k": codes_to_host(self.codes_k, K), "codes_v": codes_to_host(self.codes_v, K),
+                "k": to_host(self.k), "v": to_host(self.v)}

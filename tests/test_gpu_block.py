@@ -32,36 +32,8 @@ def peer_codes(bcfg, data, x_nonlocal):
     return oracle.vq_encode(h, data["codebook"])
 
 
-def check_h_and_codes(cfg, h, h_ref, codes, codes_ref, gap, codebook):
-    G, K, dg = codebook.shape
-    n_cls = cfg.n_cls
-    if cfg.dtype == "f32":
-        assert np.abs(h - h_ref).max() <= 1e-5
-        same = np.ones(codes.shape, dtype=bool)
-    else:
-        diff = h != h_ref
-        # one bf16 step at most (2^-7 relative is the largest step next to a value); where gain * v + bias cancels to
-        # a tiny value, the fp32 rounding of the O(1) terms (a few 1e-7) spans several steps of the result
-        assert np.all(np.abs(h - h_ref)[diff] <= np.abs(h_ref)[diff] * 2.0 ** -7 + 2e-6)
-        assert diff.mean() <= 1e-3, f"{diff.mean():.2e} of h differs from the oracle's rounding"
-        same = ~diff[n_cls:].reshape(-1, G, dg).any(-1)
-    d = codes != codes_ref
-    bad = d & same & ~(gap < NEAR_TIE)
-    assert not bad.any(), f"{int(bad.sum())} codes differ away from near-ties; first at {np.argwhere(bad)[0]}"
-    n_tie = int((d & same).sum())
-    # slices whose h differs: the chosen codeword must be justified by the differing h
-    ts, gs = np.nonzero(d & ~same)
-    for t, g in zip(ts, gs):
-        hs = h_ref[n_cls + t, g * dg:(g + 1) * dg].astype(np.float64)
-        e = h[n_cls + t, g * dg:(g + 1) * dg].astype(np.float64) - hs
-        r_gpu = np.linalg.norm(hs - codebook[g, codes[t, g]])
-        r_ref = np.linalg.norm(hs - codebook[g, codes_ref[t, g]])
-        assert r_gpu ** 2 - r_ref ** 2 <= 2 * np.linalg.norm(e) * (r_gpu + r_ref) + NEAR_TIE * r_ref ** 2
-    return n_tie, int((~same).sum()), len(ts)
-
-
 def run_case(bcfg, rank, in_place=False, valid=None):
-    from gpu_util import BlockOnGpu
+    from gpu_util import BlockOnGpu, check_h_and_codes
     cfg = bcfg.layer
     data = wl.generate_block(bcfg)
     view = wl.device_view(cfg, data, rank)
@@ -76,7 +48,7 @@ def run_case(bcfg, rank, in_place=False, valid=None):
     blk = BlockOnGpu(bcfg, data, view["x_local"], codes_nl, view["n_before"], in_place=in_place)
     blk.run(valid)
     out, codes, h = blk.results()
-    n_tie, n_slices, n_other = check_h_and_codes(cfg, h, h_ref, codes, codes_ref, gap, data["codebook"])
+    n_tie, n_slices, n_other = check_h_and_codes(cfg.dtype, cfg.n_cls, h, h_ref, codes, codes_ref, gap, data["codebook"])
     err = np.abs(out - out_ref).max()
     print(f"{bcfg.name} rank {rank}: max abs err {err:.3e} (|out| max {np.abs(out_ref).max():.2f}), near-tie codes {n_tie}/{codes.size}, "
           f"slices with a differing h {n_slices} ({n_other} of them chose another codeword)")

@@ -44,7 +44,8 @@ def _load():
         for name in ("oracle_vq_encode", "oracle_vq_decode", "oracle_linear",
                      "oracle_mixed_attention", "oracle_mixed_attention_valid",
                      "oracle_layer_forward", "oracle_layer_forward_valid",
-                     "oracle_norm", "oracle_mlp", "oracle_block_forward", "oracle_layer_forward_kv"):
+                     "oracle_norm", "oracle_mlp", "oracle_block_forward", "oracle_layer_forward_kv",
+                     "oracle_decode_attention"):
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -344,3 +345,26 @@ def layer_forward_kv(x_local, codes_k_nonlocal, codes_v_nonlocal, codebook_k, co
     if rc:
         raise ValueError(f"oracle_layer_forward_kv failed ({rc})")
     return {"y": y, "codes_k": ck, "codes_v": cv, "gap_k": gk, "gap_v": gv, "k": k, "v": v}
+
+
+def decode_attention(q, k_loc, v_loc, codes_k, codes_v, codebook_k, codebook_v, *, scale=0.0, valid=None, return_lse=False):
+    """One decoding step over a KV cache whose non-local part is VQ indices (App. memory cost).  q [H_q, dh];
+    k_loc, v_loc [n_local, H_kv, dh]; codes_k, codes_v [n_nonlocal, G]; codebooks [G, K, dkv / G].
+    Returns out [H_q, dh] fp64 (+ lse [H_q])."""
+    q, k_loc, v_loc = map(_f64, (q, k_loc, v_loc))
+    codes_k, codes_v = _i32(codes_k), _i32(codes_v)
+    codebook_k, codebook_v = _f32(codebook_k), _f32(codebook_v)
+    Hq, dh = q.shape
+    n_local, Hkv = k_loc.shape[0], k_loc.shape[1]
+    G, K, dg = codebook_k.shape
+    Tn = codes_k.shape[0]
+    assert k_loc.shape == (n_local, Hkv, dh) and v_loc.shape == (n_local, Hkv, dh)
+    assert codes_k.shape == (Tn, G) and codes_v.shape == (Tn, G) and codebook_v.shape == (G, K, dg) and G * dg == Hkv * dh
+    valid = _u8(valid)
+    out = np.empty((Hq, dh), dtype=np.float64)
+    lse = np.empty(Hq, dtype=np.float64)
+    rc = _load().oracle_decode_attention(_p(q), _p(k_loc), _p(v_loc), _p(codes_k), _p(codes_v), _p(valid), _p(codebook_k),
+                                         _p(codebook_v), G, K, Hq, Hkv, dh, n_local, Tn, ctypes.c_double(scale), _p(out), _p(lse))
+    if rc:
+        raise ValueError(f"oracle_decode_attention failed ({rc})")
+    return (out, lse) if return_lse else out

@@ -21,6 +21,7 @@
  *   oracle_layer_forward    Sec. 3.1 (per-block procedure on one device)
  *   oracle_block_forward    Sec. 3.1, the whole block: norms, residuals and the local MLP around the layer
  *   oracle_layer_forward_kv the layer with K and V quantised after projection (App. memory cost: C = 2, d = 1024)
+ *   oracle_decode_attention one decoding step over a KV cache whose non-local part is VQ indices (App. memory cost)
  *
  * Readings taken where the paper is silent (they are the library's too):
  *   - groups are contiguous slices [g*dg, (g+1)*dg) of the D-vector;
@@ -487,5 +488,80 @@ int oracle_layer_forward_kv(const float* x_local, const int32_t* codes_k_nonloca
                                           n_nonlocal, causal, n_before, scale, O, NULL, NULL);
     if (!rc) oracle_linear(O, Tq, dq, D, wo, bo, y);
     free(xl); free(Q); free(Kl); free(Vl); free(Kf); free(Vf); free(Khf); free(Vhf); free(Kh); free(Vh); free(O);
+    return rc;
+}
+
+/* ------------------------------------------------------------------------------------------------
+ * One decoding step over a KV cache whose non-local part is kept as VQ indices (App. "Memory Cost Analysis": each
+ * device keeps its local tokens' keys and values at full precision and the non-local ones as one index per group per
+ * token; Sec. 3.1: after the parallel encoding, autoregressive decoding proceeds on the single device that holds the
+ * most recent token).  The new token's query attends to every cached token (all of them precede it):
+ *   K-hat, V-hat = decode(codes_k), decode(codes_v)                      two codebooks, as in oracle_layer_forward_kv
+ *   out[h]       = softmax_t( q[h] . [K_loc | K-hat][t, h / rep] * scale ) [V_loc | V-hat]
+ * q [H_q, dh]; k_loc, v_loc [n_local, H_kv, dh] (the new token's own row included by the caller);
+ * codes_k, codes_v [n_nonlocal, G]; valid (nullable) marks non-local tokens whose codes exist; out [H_q, dh];
+ * lse (nullable) [H_q].  scale 0 means 1/sqrt(dh).
+ * ------------------------------------------------------------------------------------------------ */
+int oracle_decode_attention(const double* q, const double* k_loc, const double* v_loc,
+                            const int32_t* codes_k, const int32_t* codes_v, const uint8_t* valid,
+                            const float* codebook_k, const float* codebook_v, int G, int K,
+                            int n_q_heads, int n_kv_heads, int head_dim, int n_local, int n_nonlocal, double scale,
+                            double* out, double* lse) {
+    const int dkv = n_kv_heads * head_dim;
+    if (n_q_heads <= 0 || n_kv_heads <= 0 || n_q_heads % n_kv_heads != 0 || G <= 0 || dkv % G != 0) return -1;
+    const int rep = n_q_heads / n_kv_heads;
+    const int T = n_local + n_nonlocal;
+    if (scale == 0.0) scale = 1.0 / sqrt((double)head_dim);
+    float* khf = (float*)calloc((int64_t)n_nonlocal * dkv + 1, sizeof(float));
+    float* vhf = (float*)calloc((int64_t)n_nonlocal * dkv + 1, sizeof(float));
+    int rc = 0;
+    for (int64_t t = 0; t < n_nonlocal && !rc; ++t) {
+        if (valid && !valid[t]) continue;
+        rc = oracle_vq_decode(codes_k + t * G, 1, dkv, G, K, codebook_k, khf + t * (int64_t)dkv);
+        if (!rc) rc = oracle_vq_decode(codes_v + t * G, 1, dkv, G, K, codebook_v, vhf + t * (int64_t)dkv);
+    }
+    double* s = (double*)malloc(sizeof(double) * (T + 1));
+    for (int h = 0; h < n_q_heads && !rc; ++h) {
+        const int j = h / rep;
+        const double* qh = q + (int64_t)h * head_dim;
+        double m = -INFINITY;
+        for (int t = 0; t < T; ++t) {
+            double acc = 0.0;
+            if (t < n_local) {
+                const double* kr = k_loc + ((int64_t)t * n_kv_heads + j) * head_dim;
+                for (int c = 0; c < head_dim; ++c) acc += qh[c] * kr[c];
+            } else if (!valid || valid[t - n_local]) {
+                const float* kr = khf + ((int64_t)(t - n_local) * n_kv_heads + j) * head_dim;
+                for (int c = 0; c < head_dim; ++c) acc += qh[c] * (double)kr[c];
+            } else {
+                s[t] = -INFINITY;
+                continue;
+            }
+            s[t] = acc * scale;
+            if (s[t] > m) m = s[t];
+        }
+        double l = 0.0;
+        double* oh = out + (int64_t)h * head_dim;
+        for (int c = 0; c < head_dim; ++c) oh[c] = 0.0;
+        if (m == -INFINITY) {                    /* nothing to attend to */
+            if (lse) lse[h] = -INFINITY;
+            continue;
+        }
+        for (int t = 0; t < T; ++t) {
+            if (s[t] == -INFINITY) continue;
+            const double p = exp(s[t] - m);
+            l += p;
+            if (t < n_local) {
+                const double* vr = v_loc + ((int64_t)t * n_kv_heads + j) * head_dim;
+                for (int c = 0; c < head_dim; ++c) oh[c] += p * vr[c];
+            } else {
+                const float* vr = vhf + ((int64_t)(t - n_local) * n_kv_heads + j) * head_dim;
+                for (int c = 0; c < head_dim; ++c) oh[c] += p * (double)vr[c];
+            }
+        }
+        for (int c = 0; c < head_dim; ++c) oh[c] /= l;
+        if (lse) lse[h] = m + log(l);
+    }
+    free(khf); free(vhf); free(s);
     return rc;
 }

@@ -60,7 +60,7 @@ def main():
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the measurements outside the timed region (matrix-core probe, stand-alone decode, other ranks)")
     ap.add_argument("--extras", default="all",
-                    help="comma list of the measurements outside the timed region to run: ranks, lost, block, stack (needs block), kv, decode, probe (default all)")
+                    help="comma list of the measurements outside the timed region to run: ranks, lost, block, stack (needs block), kv, kvcache, decode, probe (default all)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the warm-up, run one plain elementwise copy kernel reading and writing this many MiB "
                          "(fp32): the reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -199,7 +199,7 @@ def main():
     per_step = sorted(ev.elapsed_ms(0, 4) for ev in events)
     result["gpu_ms_per_step_events_p10_p50_p90"] = [per_step[int(q * (len(per_step) - 1))] for q in (0.1, 0.5, 0.9)]
 
-    extras = set() if args.no_extras else set(("ranks,lost,block,stack,kv,decode,probe" if args.extras == "all" else args.extras).split(","))
+    extras = set() if args.no_extras else set(("ranks,lost,block,stack,kv,kvcache,decode,probe" if args.extras == "all" else args.extras).split(","))
     if extras:
         def timed(fn, n, warm=0):
             for _ in range(1 + warm):      # after host-side set-up the chip is idle: bring it back to its steady clock
@@ -317,6 +317,41 @@ def main():
                                     "vs_embedding_space_layer": ms / ms_per_step,
                                     "what": "astra_layer_forward_kv at the same shape: no projection of rebuilt rows"}
             del cbk, cbv, ck_nl, cv_nl, kws
+        # one decoding step over an index KV cache (App. memory cost; Sec. 3.1 hand-off to single-device decoding), per layer:
+        # the cache a prefill of this workload leaves on the last device, and a 32 times longer one
+        if "kvcache" in extras and tn > 0:
+            kdata = wl.generate_kv(cfg)
+            gk = kdata["codebook_k"].shape[0]
+            dkv = cfg.n_kv_heads * cfg.head_dim
+            vqk = B.vq_desc(dt, dkv, gk, K)
+            cbk, cbv = to_dev(kdata["codebook_k"]), to_dev(kdata["codebook_v"])
+            dgen = torch.Generator(device=dev).manual_seed(cfg.seed + 79)
+            tdt = torch.bfloat16 if dt == "bf16" else torch.float32
+            eb = 2 if dt == "bf16" else 4
+            steps_out = []
+            for mult in (1, 32):
+                nl_rows, loc_rows = tn * mult, (tq - cfg.n_cls) * mult + 1
+                kc = torch.randn((loc_rows, cfg.n_kv_heads, cfg.head_dim), generator=dgen, device=dev, dtype=torch.float32).to(tdt)
+                vc = torch.randn((loc_rows, cfg.n_kv_heads, cfg.head_dim), generator=dgen, device=dev, dtype=torch.float32).to(tdt)
+                qd = torch.randn((cfg.n_q_heads, cfg.head_dim), generator=dgen, device=dev, dtype=torch.float32).to(tdt)
+                ckd = torch.randint(0, K, (nl_rows, gk), generator=dgen, device=dev, dtype=torch.int32).to(code_t)
+                cvd = torch.randint(0, K, (nl_rows, gk), generator=dgen, device=dev, dtype=torch.int32).to(code_t)
+                ddesc = B.DecodeDesc(vqk, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, loc_rows, nl_rows, 0.0)
+                od = torch.empty((cfg.n_q_heads, cfg.head_dim), dtype=tdt, device=dev)
+                dws = torch.empty(max(B.astra_decode_attention_workspace_bytes(ddesc), 256), dtype=torch.uint8, device=dev)
+                d_args = (ddesc, qd, kc, vc, ckd, cvd, None, cbk, cbv, od, None, dws)
+                ms = timed(lambda: B.astra_decode_attention(*d_args), 300, warm=50)
+                cache_bytes = 2 * loc_rows * dkv * eb + 2 * nl_rows * gk * ckd.element_size()
+                nbytes = cache_bytes + 2 * gk * K * (dkv // gk) * eb + 2 * cfg.n_q_heads * cfg.head_dim * eb
+                steps_out.append({"cached_tokens": loc_rows + nl_rows, "local_rows": loc_rows, "index_rows": nl_rows, "us": ms * 1e3,
+                                  "algorithmic_bytes": nbytes, "GBps": nbytes / (ms * 1e-3) / 1e9,
+                                  "frac_of_hbm_8TBps": nbytes / (ms * 1e-3) / 8e12,
+                                  "cache_bytes_per_layer": cache_bytes,
+                                  "cache_vs_full_precision": cache_bytes / (2.0 * (loc_rows + nl_rows) * dkv * eb)})
+                del kc, vc, ckd, cvd, dws
+            result["decode_step_index_kv_cache"] = {"G_kv": gk, "steps": steps_out,
+                                                    "what": "astra_decode_attention: one query over full-precision local K/V plus code streams; "
+                                                            "bytes = cache + both codebooks + q + out"}
         # (2) the decode as a kernel of its own (inside the layer it is fused into the projection's operand load):
         #     the HBM-bound step; algorithmic bytes = codes + codebook + rebuilt rows
         t_v = view["n_before"] if cfg.causal else tn

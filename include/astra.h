@@ -208,6 +208,36 @@ int astra_layer_forward_kv(const astra_layer_kv_desc* desc, const void* x_local,
                            void* y_out, void* codes_k_local_out, void* codes_v_local_out, void* k_out, void* v_out,
                            void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- one decoding step over an index KV cache ------------------------------------------------------
+ * App. "Memory Cost Analysis": each device keeps the keys and values of its local tokens at full precision
+ * and those of the non-local tokens as VQ indices (one per group per token, the code streams of
+ * astra_layer_forward_kv); Sec. 3.1: after the parallel encoding, autoregressive decoding proceeds on the
+ * device that holds the most recent token.  The new token's query attends to every cached token:
+ *   out[h] = softmax_t( q[h] . [K_cache | K-hat][t, h / (H_q/H_kv)] * scale ) [V_cache | V-hat],
+ *   K-hat, V-hat = the rows the codes select from codebook_k, codebook_v (never materialised: key scores are
+ *   sums of entries of a per-query table q . codeword, value rows are picked from the codebook).
+ *   vq            both codebooks, vq.d_model = n_kv_heads * head_dim; vq.dtype = element type of q, caches,
+ *                 codebooks and out; (H_kv*dh)/G and head_dim even, head_dim <= 256, H_q/H_kv <= 8
+ *   q [H_q, dh]; k_cache, v_cache [n_local, H_kv, dh] (the new token's own row included by the caller);
+ *   codes_k, codes_v [n_nonlocal, G]; valid_bits nullable, as for astra_mixed_attention_valid
+ *   out [H_q, dh]; lse_out nullable [H_q] fp32.  With nothing to attend to, out = 0 and lse = -inf.
+ *   workspace     astra_decode_attention_workspace_bytes(desc) bytes (the table and per-chunk partial results)
+ * Results are independent of the run (no atomics). */
+typedef struct {
+    astra_vq_desc vq;
+    int32_t n_q_heads, n_kv_heads, head_dim;
+    int32_t n_local;
+    int32_t n_nonlocal;
+    float scale;                /* 0 means 1 / sqrt(head_dim) */
+} astra_decode_desc;
+
+size_t astra_decode_attention_workspace_bytes(const astra_decode_desc* desc);
+
+int astra_decode_attention(const astra_decode_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                           const void* codes_k, const void* codes_v, const uint64_t* valid_bits,
+                           const void* codebook_k, const void* codebook_v, void* out, float* lse_out,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- one whole Transformer block on one device -------------------------------------------------
  * Sec. 3.1: per block, a device quantises its local token embeddings, exchanges indices, attends with
  * the mixed-precision layer and then runs the position-wise MLP locally, without communication.  The

@@ -18,6 +18,7 @@ EXPORTS = ("astra_vq_prepare", "astra_vq_encode", "astra_vq_decode", "astra_mixe
            "astra_layer_workspace_bytes", "astra_layer_encode_fused", "astra_layer_forward", "astra_layer_forward_profiled",
            "astra_block_workspace_bytes", "astra_block_forward", "astra_stack_forward",
            "astra_layer_kv_workspace_bytes", "astra_layer_forward_kv",
+           "astra_decode_attention_workspace_bytes", "astra_decode_attention",
            "astra_probe_mfma_bf16", "astra_status_string", "astra_version")
 ASTRA_NORM_LAYER, ASTRA_NORM_RMS = 0, 1
 ASTRA_MLP_GELU_TANH, ASTRA_MLP_GELU_ERF, ASTRA_MLP_SWIGLU = 0, 1, 2
@@ -47,6 +48,11 @@ class LayerDesc(ctypes.Structure):
 
 class LayerKvDesc(ctypes.Structure):
     _fields_ = [("vq", VqDesc), ("attn", AttnDesc), ("d_model", ctypes.c_int32)]
+
+
+class DecodeDesc(ctypes.Structure):
+    _fields_ = [("vq", VqDesc), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("n_local", ctypes.c_int32), ("n_nonlocal", ctypes.c_int32), ("scale", ctypes.c_float)]
 
 
 class BlockDesc(ctypes.Structure):
@@ -97,6 +103,10 @@ def load(build_if_missing: bool = True):
     lib.astra_layer_kv_workspace_bytes.restype = ctypes.c_size_t
     lib.astra_layer_forward_kv.argtypes = [ctypes.POINTER(LayerKvDesc)] + [vp] * 22 + [ctypes.c_size_t, vp]
     lib.astra_layer_forward_kv.restype = ctypes.c_int
+    lib.astra_decode_attention_workspace_bytes.argtypes = [ctypes.POINTER(DecodeDesc)]
+    lib.astra_decode_attention_workspace_bytes.restype = ctypes.c_size_t
+    lib.astra_decode_attention.argtypes = [ctypes.POINTER(DecodeDesc)] + [vp] * 11 + [ctypes.c_size_t, vp]
+    lib.astra_decode_attention.restype = ctypes.c_int
     pp = ctypes.POINTER(ctypes.c_void_p)
     lib.astra_stack_forward.argtypes = [ctypes.POINTER(BlockDesc), ctypes.c_int32, ctypes.POINTER(BlockWeights), vp, pp, pp, vp, pp,
                                         vp, ctypes.c_size_t, vp]
@@ -220,6 +230,18 @@ def astra_layer_forward_kv(desc: LayerKvDesc, x_local, codes_k_nonlocal, codes_v
         _ptr(cnorm_k), _ptr(codebook_v), _ptr(cnorm_v), _ptr(wq), _ptr(wk), _ptr(wv), _ptr(wo), _ptr(bq), _ptr(bk), _ptr(bv),
         _ptr(bo), _ptr(y_out), _ptr(codes_k_local_out), _ptr(codes_v_local_out), _ptr(k_out), _ptr(v_out), _ptr(workspace),
         nbytes, _stream()), "astra_layer_forward_kv")
+
+
+def astra_decode_attention_workspace_bytes(desc: DecodeDesc) -> int:
+    return int(load().astra_decode_attention_workspace_bytes(ctypes.byref(desc)))
+
+
+def astra_decode_attention(desc: DecodeDesc, q, k_cache, v_cache, codes_k, codes_v, valid_bits, codebook_k, codebook_v, out,
+                           lse_out, workspace):
+    nbytes = workspace.numel() * workspace.element_size()
+    _check(load().astra_decode_attention(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(codes_k), _ptr(codes_v),
+                                         _ptr(valid_bits), _ptr(codebook_k), _ptr(codebook_v), _ptr(out), _ptr(lse_out),
+                                         _ptr(workspace), nbytes, _stream()), "astra_decode_attention")
 
 
 def _ptr_array(tensors):

@@ -73,3 +73,46 @@ def test_encode_fusion_plan_is_host_only():
     bad = desc(llama, 3)
     bad.vq.n_groups = 7          # 4096 is not a multiple of 7
     assert B.load().astra_layer_encode_fused(ctypes.byref(bad)) < 0
+
+
+def test_block_kv_and_decode_planning_is_host_only():
+    """Workspace sizes and argument checks of the entry points around the layer are decided on the host: the sizes
+    cover the buffers the calls need, invalid descriptors give 0 / an error code, NULL pointers are reported."""
+    lib = B.load()
+    assert ctypes.sizeof(B.BlockDesc) == 76 and ctypes.sizeof(B.LayerKvDesc) == 64 and ctypes.sizeof(B.DecodeDesc) == 44
+    assert ctypes.sizeof(B.BlockWeights) == 18 * ctypes.sizeof(ctypes.c_void_p)
+    layer = B.LayerDesc(B.vq_desc("bf16", 4096, 64, 1024), B.attn_desc("bf16", 32, 8, 128, 0, 1024, 3072, True, 3072))
+    blk = B.block_desc(layer, "rmsnorm", "swiglu", 14336, 1e-5)
+    need = B.astra_block_workspace_bytes(blk)
+    lay = B.astra_layer_workspace_bytes(layer)
+    # layer workspace + normalised rows + hidden rows + four fp32 slices of the split second MLP product
+    assert need >= lay + 1024 * 4096 * 2 + 1024 * 14336 * 2 + 4 * 1024 * 4096 * 4
+    assert B.astra_block_workspace_bytes(B.block_desc(layer, "rmsnorm", "swiglu", 14336 + 8, 1e-5)) == 0      # d_ff % 64 for bf16
+    assert B.astra_block_workspace_bytes(B.block_desc(layer, "rmsnorm", "swiglu", 0, 1e-5)) == 0
+    bad = B.block_desc(layer, "rmsnorm", "swiglu", 14336, 1e-5)
+    bad.norm_kind = 5
+    assert B.astra_block_workspace_bytes(bad) == 0
+    assert lib.astra_block_forward(ctypes.byref(blk), None, None, None, None, None, None, None, None, 0, None) == -1
+    assert lib.astra_stack_forward(ctypes.byref(blk), -1, None, None, None, None, None, None, None, 0, None) == -2
+    assert lib.astra_stack_forward(ctypes.byref(blk), 0, None, None, None, None, None, None, None, 0, None) == 0
+    assert lib.astra_stack_forward(ctypes.byref(blk), 2, None, None, None, None, None, None, None, 0, None) == -1
+
+    kv = B.LayerKvDesc(B.vq_desc("bf16", 1024, 32, 1024), layer.attn, 4096)
+    need = B.astra_layer_kv_workspace_bytes(kv)
+    # Q, O: 1024 x 4096; K, V, V^T: 1024 x 1024; K-hat, V-hat^T: 3072 x 1024 (bf16)
+    assert need >= 2 * (2 * 1024 * 4096 + 3 * 1024 * 1024 + 2 * 3072 * 1024)
+    kv.vq.d_model = 4096                        # the codebooks must span H_kv * dh
+    assert B.astra_layer_kv_workspace_bytes(kv) == 0
+
+    dec = B.DecodeDesc(B.vq_desc("bf16", 1024, 32, 1024), 32, 8, 128, 1025, 3072, 0.0)
+    need = B.astra_decode_attention_workspace_bytes(dec)
+    assert need >= 32 * 4 * 1024 * 4            # the table: 32 query heads x 4 groups per head x 1024 entries, fp32
+    assert lib.astra_decode_attention(ctypes.byref(dec), None, None, None, None, None, None, None, None, None, None, None, 0, None) == -1
+    for field, value in (("n_q_heads", 12), ("head_dim", 100), ("n_local", -1)):      # 12 % 8; 8 * 100 != 1024; negative
+        d = B.DecodeDesc(B.vq_desc("bf16", 1024, 32, 1024), 32, 8, 128, 1025, 3072, 0.0)
+        setattr(d, field, value)
+        assert B.astra_decode_attention_workspace_bytes(d) == 0
+    three = B.DecodeDesc(B.vq_desc("bf16", 1024, 32, 1024), 24, 8, 128, 10, 10, 0.0)  # 3 query heads per KV head: no kernel
+    assert B.astra_decode_attention_workspace_bytes(three) == 0
+    empty = B.DecodeDesc(B.vq_desc("bf16", 1024, 32, 1024), 32, 8, 128, 0, 0, 0.0)
+    assert B.astra_decode_attention_workspace_bytes(empty) > 0

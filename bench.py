@@ -380,13 +380,17 @@ def main():
         if K > 256:
             codes_nl_host = codes_nl_host.view(np.uint16)
         oracle.num_threads()            # load outside the timed part
-        c0 = time.perf_counter()
-        oracle.layer_forward(view["x_local"], codes_nl_host.astype(np.int32), data["codebook"], data["wq"], data["wk"],
-                             data["wv"], data["wo"], n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, n_cls=cfg.n_cls,
-                             causal=cfg.causal, n_before=view["n_before"])
+        # whole layer calls of the same workload and rank, repeated until about 10 s of CPU work have been timed
+        # (at most 8 calls); the oracle is the checker as it stands, never tuned for this
+        n_calls, c0 = 0, time.perf_counter()
+        while n_calls < 8 and (n_calls == 0 or time.perf_counter() - c0 < 10.0):
+            oracle.layer_forward(view["x_local"], codes_nl_host.astype(np.int32), data["codebook"], data["wq"], data["wk"],
+                                 data["wv"], data["wo"], n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, n_cls=cfg.n_cls,
+                                 causal=cfg.causal, n_before=view["n_before"])
+            n_calls += 1
         c1 = time.perf_counter()
-        result["cpu_baseline"] = {"value": tq / (c1 - c0), "unit": "tokens/s", "cores": oracle.num_threads(),
-                                  "kind": "oracle", "sample": f"one whole layer call of the same workload ({tq} local rows), "
+        result["cpu_baseline"] = {"value": n_calls * tq / (c1 - c0), "unit": "tokens/s", "cores": oracle.num_threads(),
+                                  "kind": "oracle", "sample": f"{n_calls} whole layer calls of the same workload ({tq} local rows each), "
                                   f"{c1 - c0:.2f} s, fp64 C/OpenMP oracle"}
     print(json.dumps(result))
 

@@ -45,7 +45,7 @@ def _load():
                      "oracle_mixed_attention", "oracle_mixed_attention_valid",
                      "oracle_layer_forward", "oracle_layer_forward_valid",
                      "oracle_norm", "oracle_mlp", "oracle_block_forward", "oracle_layer_forward_kv",
-                     "oracle_decode_attention"):
+                     "oracle_decode_attention", "oracle_codebook_stats", "oracle_codebook_update", "oracle_navq"):
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -368,3 +368,53 @@ def decode_attention(q, k_loc, v_loc, codes_k, codes_v, codebook_k, codebook_v, 
     if rc:
         raise ValueError(f"oracle_decode_attention failed ({rc})")
     return (out, lse) if return_lse else out
+
+
+def codebook_stats(x, codes, codebook):
+    """Per-codeword statistics of an assignment (Sec. 3.2 training of the VQ module): counts [G, K] int64,
+    sums [G, K, dg] fp64, sqerr [G] fp64 = sum_t ||x[t, slice g] - codebook[g, codes[t, g]]||^2 (Eq. 2's commitment
+    term is beta * sqerr.sum())."""
+    x, codes, codebook = _f32(x), _i32(codes), _f32(codebook)
+    G, K, dg = codebook.shape
+    T, D = x.shape
+    assert D == G * dg and codes.shape == (T, G)
+    counts = np.empty((G, K), dtype=np.int64)
+    sums = np.empty((G, K, dg), dtype=np.float64)
+    sqerr = np.empty(G, dtype=np.float64)
+    rc = _load().oracle_codebook_stats(_p(x), _p(codes), _p(codebook), ctypes.c_int64(T), D, G, K, _p(counts), _p(sums), _p(sqerr))
+    if rc:
+        raise ValueError(f"oracle_codebook_stats failed ({rc})")
+    return counts, sums, sqerr
+
+
+def codebook_update(counts, sums, codebook_old, gamma=0.0, ema_n=None, ema_m=None):
+    """EMA update of the codebook (gamma in (0, 1); ema_n [G, K], ema_m [G, K, dg] fp64 are updated in place), or with
+    gamma = 0 one K-means centroid step.  A codeword whose (averaged) count is zero keeps its old value.
+    Returns the new codebook [G, K, dg] fp64."""
+    counts = np.ascontiguousarray(counts, dtype=np.int64)
+    sums = _f64(sums)
+    codebook_old = _f32(codebook_old)
+    G, K, dg = codebook_old.shape
+    assert counts.shape == (G, K) and sums.shape == (G, K, dg)
+    for a in (ema_n, ema_m):
+        assert a is None or (a.dtype == np.float64 and a.flags["C_CONTIGUOUS"])
+    out = np.empty((G, K, dg), dtype=np.float64)
+    rc = _load().oracle_codebook_update(_p(counts), _p(sums), ctypes.c_double(gamma), _p(ema_n), _p(ema_m), _p(codebook_old),
+                                        G, K, dg, _p(out))
+    if rc:
+        raise ValueError(f"oracle_codebook_update failed ({rc})")
+    return out
+
+
+def navq(codes, codebook, mu, l_factor, z, lam):
+    """NAVQ (Sec. 3.3): x_tilde = decode(codes) + lam * (mu + z @ l_factor.T), z standard normal draws passed in."""
+    codes, codebook, mu, l_factor, z = _i32(codes), _f32(codebook), _f32(mu), _f32(l_factor), _f32(z)
+    G, K, dg = codebook.shape
+    T, D = z.shape
+    assert D == G * dg and codes.shape == (T, G) and mu.shape == (D,) and l_factor.shape == (D, D)
+    out = np.empty((T, D), dtype=np.float64)
+    rc = _load().oracle_navq(_p(codes), _p(codebook), ctypes.c_int64(T), D, G, K, _p(mu), _p(l_factor), _p(z),
+                             ctypes.c_double(lam), _p(out))
+    if rc:
+        raise ValueError(f"oracle_navq failed ({rc})")
+    return out

@@ -22,6 +22,7 @@
  *   oracle_block_forward    Sec. 3.1, the whole block: norms, residuals and the local MLP around the layer
  *   oracle_layer_forward_kv the layer with K and V quantised after projection (App. memory cost: C = 2, d = 1024)
  *   oracle_decode_attention one decoding step over a KV cache whose non-local part is VQ indices (App. memory cost)
+ *   oracle_codebook_stats / oracle_codebook_update / oracle_navq   training-side VQ operations (Sec. 3.2, Eq. 2, Sec. 3.3)
  *
  * Readings taken where the paper is silent (they are the library's too):
  *   - groups are contiguous slices [g*dg, (g+1)*dg) of the D-vector;
@@ -563,5 +564,77 @@ int oracle_decode_attention(const double* q, const double* k_loc, const double* 
         if (lse) lse[h] = m + log(l);
     }
     free(khf); free(vhf); free(s);
+    return rc;
+}
+
+/* ------------------------------------------------------------------------------------------------
+ * Training-side operations of the VQ module (Sec. 3.2 "The VQ module is jointly trained ...": K-means
+ * initialisation over token embeddings, exponential-moving-average updates during fine-tuning, the commitment
+ * term of Eq. 2; Sec. 3.3 NAVQ).  Forward arithmetic only; gradients are outside this build.
+ * ------------------------------------------------------------------------------------------------ */
+
+/* Per-codeword statistics of an assignment: counts[g,k] = number of tokens with codes[t,g] = k,
+ * sums[g,k,:] = sum of their slices x[t, g*dg:(g+1)*dg], sqerr[g] = sum_t ||x[t, slice g] - codebook[g, codes[t,g], :]||^2
+ * (the commitment term of Eq. 2 is beta times the sum of sqerr over the groups: ||X - sg(X-hat)||_2^2 written out;
+ * the stop-gradient has no effect on the value).  K-means and the EMA update are built on counts and sums. */
+int oracle_codebook_stats(const float* x, const int32_t* codes, const float* codebook, int64_t T, int D, int G, int K,
+                          int64_t* counts, double* sums, double* sqerr) {
+    if (T < 0 || D <= 0 || G <= 0 || K <= 0 || D % G != 0) return -1;
+    const int dg = D / G;
+    memset(counts, 0, sizeof(int64_t) * (size_t)G * K);
+    for (int64_t i = 0; i < (int64_t)G * K * dg; ++i) sums[i] = 0.0;
+    for (int g = 0; g < G; ++g) sqerr[g] = 0.0;
+    for (int64_t t = 0; t < T; ++t)
+        for (int g = 0; g < G; ++g) {
+            const int32_t k = codes[t * G + g];
+            if (k < 0 || k >= K) return -2;
+            const float* xs = x + t * (int64_t)D + (int64_t)g * dg;
+            const float* c = codebook + ((int64_t)g * K + k) * dg;
+            double* s = sums + ((int64_t)g * K + k) * dg;
+            counts[(int64_t)g * K + k] += 1;
+            for (int j = 0; j < dg; ++j) {
+                s[j] += (double)xs[j];
+                const double d = (double)xs[j] - (double)c[j];
+                sqerr[g] += d * d;
+            }
+        }
+    return 0;
+}
+
+/* Codebook update from statistics.  EMA (gamma in [0, 1)):  N' = gamma N + (1 - gamma) counts,
+ * M' = gamma M + (1 - gamma) sums, codeword = M' / N' where N' > 0, else the old codeword.  gamma = 0 is one
+ * K-means (Lloyd) centroid step: codeword = sums / counts, an empty cluster keeps its codeword.
+ * ema_n [G,K], ema_m [G,K,dg] are updated in place (both may be NULL when gamma == 0). */
+int oracle_codebook_update(const int64_t* counts, const double* sums, double gamma, double* ema_n, double* ema_m,
+                           const float* codebook_old, int G, int K, int dg, double* codebook_new) {
+    if (G <= 0 || K <= 0 || dg <= 0 || !(gamma >= 0.0 && gamma < 1.0)) return -1;
+    if (gamma > 0.0 && (!ema_n || !ema_m)) return -1;
+    for (int64_t i = 0; i < (int64_t)G * K; ++i) {
+        double n = (double)counts[i];
+        if (ema_n) { n = gamma * ema_n[i] + (1.0 - gamma) * (double)counts[i]; ema_n[i] = n; }
+        for (int j = 0; j < dg; ++j) {
+            double m = sums[i * dg + j];
+            if (ema_m) { m = gamma * ema_m[i * dg + j] + (1.0 - gamma) * sums[i * dg + j]; ema_m[i * dg + j] = m; }
+            codebook_new[i * dg + j] = n > 0.0 ? m / n : (double)codebook_old[i * dg + j];
+        }
+    }
+    return 0;
+}
+
+/* NAVQ (Sec. 3.3): X-tilde = X-hat + lambda * xi, xi ~ N(mu, Sigma) fitted to the quantisation residuals.  With
+ * Sigma = L L^T and standard normal draws z [T, D] passed in (the method's random numbers are inputs):
+ * xi[t] = mu + L z[t].  l_factor [D, D] row-major (any factor with L L^T = Sigma; the lower Cholesky factor in the
+ * tests).  x_tilde [T, D]. */
+int oracle_navq(const int32_t* codes, const float* codebook, int64_t T, int D, int G, int K,
+                const float* mu, const float* l_factor, const float* z, double lambda, double* x_tilde) {
+    float* xh = (float*)malloc(sizeof(float) * ((size_t)T * D + 1));
+    int rc = oracle_vq_decode(codes, T, D, G, K, codebook, xh);
+    for (int64_t t = 0; t < T && !rc; ++t)
+        for (int i = 0; i < D; ++i) {
+            double xi = (double)mu[i];
+            for (int j = 0; j < D; ++j) xi += (double)l_factor[(int64_t)i * D + j] * (double)z[t * (int64_t)D + j];
+            x_tilde[t * (int64_t)D + i] = (double)xh[t * (int64_t)D + i] + lambda * xi;
+        }
+    free(xh);
     return rc;
 }

@@ -60,7 +60,7 @@ def main():
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the measurements outside the timed region (matrix-core probe, stand-alone decode, other ranks)")
     ap.add_argument("--extras", default="all",
-                    help="comma list of the measurements outside the timed region to run: ranks, lost, block, stack (needs block), kv, kvcache, decode, probe (default all)")
+                    help="comma list of the measurements outside the timed region to run: ranks, lost, block, stack (needs block), kv, kvcache, train, decode, probe (default all)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the warm-up, run one plain elementwise copy kernel reading and writing this many MiB "
                          "(fp32): the reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -199,7 +199,7 @@ def main():
     per_step = sorted(ev.elapsed_ms(0, 4) for ev in events)
     result["gpu_ms_per_step_events_p10_p50_p90"] = [per_step[int(q * (len(per_step) - 1))] for q in (0.1, 0.5, 0.9)]
 
-    extras = set() if args.no_extras else set(("ranks,lost,block,stack,kv,kvcache,decode,probe" if args.extras == "all" else args.extras).split(","))
+    extras = set() if args.no_extras else set(("ranks,lost,block,stack,kv,kvcache,train,decode,probe" if args.extras == "all" else args.extras).split(","))
     if extras:
         def timed(fn, n, warm=0):
             for _ in range(1 + warm):      # after host-side set-up the chip is idle: bring it back to its steady clock
@@ -352,6 +352,32 @@ def main():
             result["decode_step_index_kv_cache"] = {"G_kv": gk, "steps": steps_out,
                                                     "what": "astra_decode_attention: one query over full-precision local K/V plus code streams; "
                                                             "bytes = cache + both codebooks + q + out"}
+        # one codebook-learning step on a training-sized batch (Sec. 3.2: K-means initialisation / EMA updates with the
+        # commitment sum of Eq. 2): encode, per-codeword statistics, update; 16384 tokens of this workload's width
+        if "train" in extras:
+            tt = 16384
+            tgen = torch.Generator(device=dev).manual_seed(cfg.seed + 80)
+            tdt = torch.bfloat16 if dt == "bf16" else torch.float32
+            eb = 2 if dt == "bf16" else 4
+            xt = torch.randn((tt, D), generator=tgen, device=dev, dtype=torch.float32).to(tdt)
+            ct = torch.empty((tt, G), dtype=code_t, device=dev)
+            cnt = torch.empty((G, K), dtype=torch.int32, device=dev)
+            sm = torch.empty((G, K, cfg.group_dim), dtype=torch.float32, device=dev)
+            sq = torch.empty(G, dtype=torch.float32, device=dev)
+            en, em = torch.ones((G, K), dtype=torch.float32, device=dev), torch.zeros((G, K, cfg.group_dim), dtype=torch.float32, device=dev)
+            cb2 = torch.empty_like(codebook)
+            tws = torch.empty(max(B.astra_codebook_stats_workspace_bytes(vq, tt), 256), dtype=torch.uint8, device=dev)
+            ms_e = timed(lambda: B.astra_vq_encode(vq, xt, tt, codebook, cnorm, ct), 30, warm=5)
+            ms_s = timed(lambda: B.astra_codebook_stats(vq, xt, ct, tt, codebook, cnt, sm, sq, tws), 30, warm=5)
+            ms_u = timed(lambda: B.astra_codebook_update(vq, cnt, sm, 0.99, en, em, codebook, cb2), 30, warm=5)
+            stat_bytes = tt * D * eb + 2 * tt * G * ct.element_size() + G * K * cfg.group_dim * (eb + 4) + G * K * 4
+            result["codebook_learning_step"] = {
+                "tokens": tt, "encode_us": ms_e * 1e3, "encode_tflops": 2.0 * tt * K * D / (ms_e * 1e-3) / 1e12,
+                "stats_us": ms_s * 1e3, "stats_algorithmic_bytes": stat_bytes, "stats_GBps": stat_bytes / (ms_s * 1e-3) / 1e9,
+                "stats_frac_of_hbm_8TBps": stat_bytes / (ms_s * 1e-3) / 8e12, "update_us": ms_u * 1e3,
+                "what": "astra_vq_encode + astra_codebook_stats (deterministic: counting sort by code, rows added in token order) + "
+                        "astra_codebook_update (EMA)"}
+            del xt, ct, sm, em, cb2, tws
         # (2) the decode as a kernel of its own (inside the layer it is fused into the projection's operand load):
         #     the HBM-bound step; algorithmic bytes = codes + codebook + rebuilt rows
         t_v = view["n_before"] if cfg.causal else tn

@@ -313,6 +313,39 @@ int astra_stack_forward(const astra_block_desc* desc, int32_t n_layers, const as
                         float* x_out, void* const* codes_local_out,
                         void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- training-side operations of the VQ module (forward arithmetic only) ---------------------------
+ * Sec. 3.2: the codebook is initialised by K-means over token embeddings and updated by exponential moving average
+ * during fine-tuning, with the commitment term beta * ||X - sg(X-hat)||_2^2 of Eq. 2 in the loss; Sec. 3.3: NAVQ adds
+ * noise fitted to the quantisation residuals to the quantised embeddings during training.  Gradients are not part of
+ * this library.  All results are independent of the run (tokens are sorted by code, rows added in token order). */
+
+/* Statistics of an assignment codes [T, G] (astra_vq_encode's output for x [T, D]):
+ *   counts_out [G, K] int32   tokens per codeword
+ *   sums_out   [G, K, dg] fp32   sum of the slices x[t, g*dg:(g+1)*dg] assigned to the codeword
+ *   sqerr_out  [G] fp32       sum_t ||x[t, slice g] - codebook[g, codes[t, g]]||^2; Eq. 2's commitment term is beta times
+ *                             the sum over g (the paper does not say whether it is averaged: the plain sum is returned)
+ * dg <= 256 and K <= 8192.  workspace: astra_codebook_stats_workspace_bytes(desc, n_tokens) bytes. */
+size_t astra_codebook_stats_workspace_bytes(const astra_vq_desc* desc, int64_t n_tokens);
+int astra_codebook_stats(const astra_vq_desc* desc, const void* x, const void* codes, int64_t n_tokens, const void* codebook,
+                         int32_t* counts_out, float* sums_out, float* sqerr_out,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* Codebook update from those statistics.  gamma in (0, 1): ema_n [G, K] and ema_m [G, K, dg] (fp32, in place) become
+ * gamma * old + (1 - gamma) * (counts | sums) and the codeword is ema_m / ema_n; gamma == 0: one K-means (Lloyd)
+ * centroid step, sums / counts (ema_n, ema_m ignored, may be NULL).  A codeword whose (averaged) count is zero keeps
+ * its old value (the paper gives no rule for dead codewords; no smoothing term is applied).  codebook_new_out
+ * [G, K, dg] in the element type; it may be codebook_old itself. */
+int astra_codebook_update(const astra_vq_desc* desc, const int32_t* counts, const float* sums, float gamma,
+                          float* ema_n, float* ema_m, const void* codebook_old, void* codebook_new_out, void* stream);
+
+/* NAVQ (Sec. 3.3): x_tilde = X-hat + lambda * xi, xi ~ N(mu, Sigma).  The standard normal draws z [T, D] are an input
+ * (element type), and so is the factor: noise_factor [D, D] (element type, row-major) = lambda * L with L L^T = Sigma,
+ * so that x_tilde_out[t] = codebook rows selected by codes[t] + lambda * mu + noise_factor . z[t]   (fp32 [T, D]).
+ * mu [D] fp32.  bf16 needs D to be a multiple of 64. */
+int astra_navq_forward(const astra_vq_desc* desc, const void* codes, int64_t n_tokens, const void* codebook,
+                       const float* mu, float lambda, const void* z, const void* noise_factor,
+                       float* x_tilde_out, void* stream);
+
 /* Measurement probe, not part of the method: n_blocks workgroups of 512 threads each run `iters` rounds of
  * four independent 32x32x16 bf16 MFMAs per wavefront on register operands (no memory traffic in the loop)
  * and store one float per thread to out [n_blocks * 512] (device).  Work = n_blocks * 8 * iters * 4 * 32768

@@ -19,6 +19,7 @@ EXPORTS = ("astra_vq_prepare", "astra_vq_encode", "astra_vq_decode", "astra_mixe
            "astra_block_workspace_bytes", "astra_block_forward", "astra_stack_forward",
            "astra_layer_kv_workspace_bytes", "astra_layer_forward_kv",
            "astra_decode_attention_workspace_bytes", "astra_decode_attention",
+           "astra_codebook_stats_workspace_bytes", "astra_codebook_stats", "astra_codebook_update", "astra_navq_forward",
            "astra_probe_mfma_bf16", "astra_status_string", "astra_version")
 ASTRA_NORM_LAYER, ASTRA_NORM_RMS = 0, 1
 ASTRA_MLP_GELU_TANH, ASTRA_MLP_GELU_ERF, ASTRA_MLP_SWIGLU = 0, 1, 2
@@ -107,6 +108,14 @@ def load(build_if_missing: bool = True):
     lib.astra_decode_attention_workspace_bytes.restype = ctypes.c_size_t
     lib.astra_decode_attention.argtypes = [ctypes.POINTER(DecodeDesc)] + [vp] * 11 + [ctypes.c_size_t, vp]
     lib.astra_decode_attention.restype = ctypes.c_int
+    lib.astra_codebook_stats_workspace_bytes.argtypes = [ctypes.POINTER(VqDesc), i64]
+    lib.astra_codebook_stats_workspace_bytes.restype = ctypes.c_size_t
+    lib.astra_codebook_stats.argtypes = [ctypes.POINTER(VqDesc), vp, vp, i64, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.astra_codebook_stats.restype = ctypes.c_int
+    lib.astra_codebook_update.argtypes = [ctypes.POINTER(VqDesc), vp, vp, ctypes.c_float, vp, vp, vp, vp, vp]
+    lib.astra_codebook_update.restype = ctypes.c_int
+    lib.astra_navq_forward.argtypes = [ctypes.POINTER(VqDesc), vp, i64, vp, vp, ctypes.c_float, vp, vp, vp, vp]
+    lib.astra_navq_forward.restype = ctypes.c_int
     pp = ctypes.POINTER(ctypes.c_void_p)
     lib.astra_stack_forward.argtypes = [ctypes.POINTER(BlockDesc), ctypes.c_int32, ctypes.POINTER(BlockWeights), vp, pp, pp, vp, pp,
                                         vp, ctypes.c_size_t, vp]
@@ -242,6 +251,26 @@ def astra_decode_attention(desc: DecodeDesc, q, k_cache, v_cache, codes_k, codes
     _check(load().astra_decode_attention(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(codes_k), _ptr(codes_v),
                                          _ptr(valid_bits), _ptr(codebook_k), _ptr(codebook_v), _ptr(out), _ptr(lse_out),
                                          _ptr(workspace), nbytes, _stream()), "astra_decode_attention")
+
+
+def astra_codebook_stats_workspace_bytes(desc: VqDesc, n_tokens: int) -> int:
+    return int(load().astra_codebook_stats_workspace_bytes(ctypes.byref(desc), n_tokens))
+
+
+def astra_codebook_stats(desc: VqDesc, x, codes, n_tokens: int, codebook, counts_out, sums_out, sqerr_out, workspace):
+    nbytes = workspace.numel() * workspace.element_size()
+    _check(load().astra_codebook_stats(ctypes.byref(desc), _ptr(x), _ptr(codes), n_tokens, _ptr(codebook), _ptr(counts_out),
+                                       _ptr(sums_out), _ptr(sqerr_out), _ptr(workspace), nbytes, _stream()), "astra_codebook_stats")
+
+
+def astra_codebook_update(desc: VqDesc, counts, sums, gamma: float, ema_n, ema_m, codebook_old, codebook_new_out):
+    _check(load().astra_codebook_update(ctypes.byref(desc), _ptr(counts), _ptr(sums), gamma, _ptr(ema_n), _ptr(ema_m),
+                                        _ptr(codebook_old), _ptr(codebook_new_out), _stream()), "astra_codebook_update")
+
+
+def astra_navq_forward(desc: VqDesc, codes, n_tokens: int, codebook, mu, lam: float, z, noise_factor, x_tilde_out):
+    _check(load().astra_navq_forward(ctypes.byref(desc), _ptr(codes), n_tokens, _ptr(codebook), _ptr(mu), lam, _ptr(z),
+                                     _ptr(noise_factor), _ptr(x_tilde_out), _stream()), "astra_navq_forward")
 
 
 def _ptr_array(tensors):

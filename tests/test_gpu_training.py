@@ -1,0 +1,148 @@
+"""GPU parity: training-side VQ operations (Sec. 3.2: K-means / EMA codebook learning, commitment term of Eq. 2;
+Sec. 3.3: NAVQ) through astra_codebook_stats, astra_codebook_update and astra_navq_forward against the CPU oracle.
+Bars: counts bit-exact; sums and squared errors within 1e-5 relative of the scale (fp32 sums of at most a few
+thousand fp32 terms against fp64); updated codebook fp32 within 1e-6 relative, bf16 equal to the oracle's value
+rounded to bf16 except a counted few elements one step away; NAVQ within 1e-4 (fp32 accumulation of a D-long
+product of values that are exact on both sides); repeated calls bit-identical."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2505_19342_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def setup(cfg):
+    import torch
+    from gpu_util import to_dev, codes_to_dev, DEV
+    from paper_2505_19342_amd import binding as B
+    data = wl.generate(cfg)
+    x, cb = data["x"], data["codebook"]
+    codes = oracle.vq_encode(x, cb)
+    G, K, dg = cb.shape
+    desc = B.vq_desc(cfg.dtype, cfg.d_model, G, K)
+    T = x.shape[0]
+    dev = dict(x=to_dev(x, cfg.dtype), codes=codes_to_dev(codes, K), cb=to_dev(cb, cfg.dtype),
+               counts=torch.empty((G, K), dtype=torch.int32, device=DEV), sums=torch.empty((G, K, dg), dtype=torch.float32, device=DEV),
+               sqerr=torch.empty(G, dtype=torch.float32, device=DEV),
+               ws=torch.empty(max(B.astra_codebook_stats_workspace_bytes(desc, T), 256), dtype=torch.uint8, device=DEV))
+    return data, x, cb, codes, desc, dev
+
+
+def run_stats(desc, dev, T):
+    import torch
+    from paper_2505_19342_amd import binding as B
+    B.astra_codebook_stats(desc, dev["x"], dev["codes"], T, dev["cb"], dev["counts"], dev["sums"], dev["sqerr"], dev["ws"])
+    torch.cuda.synchronize()
+    return dev["counts"].cpu().numpy(), dev["sums"].cpu().numpy(), dev["sqerr"].cpu().numpy()
+
+
+@pytest.mark.parametrize("name", ["tiny_vit_f32", "vit_base_bf16", "gpt2_small_bf16", "llama3_8b_bf16"])
+def test_stats_and_update(name):
+    import torch
+    from gpu_util import to_host, empty_like_dtype, DEV
+    from paper_2505_19342_amd import binding as B
+    cfg = wl.CONFIGS[name]
+    data, x, cb, codes, desc, dev = setup(cfg)
+    T = x.shape[0]
+    counts, sums, sqerr = run_stats(desc, dev, T)
+    c_ref, s_ref, q_ref = oracle.codebook_stats(x, codes, cb)
+    np.testing.assert_array_equal(counts, c_ref)
+    scale = np.abs(s_ref).max()
+    assert np.abs(sums - s_ref).max() <= 1e-5 * scale
+    np.testing.assert_allclose(sqerr, q_ref, rtol=1e-5)
+    again = run_stats(desc, dev, T)
+    for a, b in zip((counts, sums, sqerr), again):
+        np.testing.assert_array_equal(a, b)
+    print(f"{name}: T {T}, sums max abs err {np.abs(sums - s_ref).max():.2e} (scale {scale:.1f}), commitment sum {q_ref.sum():.4e}, "
+          f"empty codewords {(c_ref == 0).sum()} of {c_ref.size}")
+
+    # one K-means centroid step, then an EMA step from running statistics
+    G, K, dg = cb.shape
+    new = empty_like_dtype((G, K, dg), cfg.dtype)
+    B.astra_codebook_update(desc, dev["counts"], dev["sums"], 0.0, None, None, dev["cb"], new)
+    torch.cuda.synchronize()
+    check_codebook(cfg.dtype, to_host(new), oracle.codebook_update(c_ref, s_ref, cb))
+    rng = np.random.default_rng(5)
+    n0 = (rng.random((G, K)) * 4).astype(np.float32)
+    n0[c_ref == 0] = 0.0                                     # dead codewords stay dead: they must keep their old value
+    m0 = rng.standard_normal((G, K, dg)).astype(np.float32)
+    n_d, m_d = torch.from_numpy(n0).to(DEV), torch.from_numpy(m0).to(DEV)
+    B.astra_codebook_update(desc, dev["counts"], dev["sums"], 0.9, n_d, m_d, dev["cb"], new)
+    torch.cuda.synchronize()
+    n_r, m_r = n0.astype(np.float64), m0.astype(np.float64)
+    ref = oracle.codebook_update(c_ref, s_ref, cb, gamma=0.9, ema_n=n_r, ema_m=m_r)
+    np.testing.assert_allclose(n_d.cpu().numpy(), n_r, rtol=1e-6)
+    assert np.abs(m_d.cpu().numpy() - m_r).max() <= 1e-5 * max(1.0, np.abs(m_r).max())
+    check_codebook(cfg.dtype, to_host(new), ref, loose=True)
+    dead = (c_ref == 0) & (n0 == 0)
+    np.testing.assert_array_equal(to_host(new)[dead], cb[dead])
+
+
+def check_codebook(dtype, got, ref64, loose=False):
+    if dtype == "f32":
+        np.testing.assert_allclose(got, ref64, rtol=2e-5 if loose else 2e-6, atol=1e-6)
+        return
+    ref = wl.round_to_bf16(ref64.astype(np.float32))
+    diff = got != ref
+    assert np.all(np.abs(got - ref)[diff] <= np.abs(ref)[diff] * 2.0 ** -7 + 1e-6)
+    assert diff.mean() <= (2e-2 if loose else 2e-3), f"{diff.mean():.2e} of the codewords' elements differ from the oracle's rounding"
+
+
+def test_stats_edge_cases():
+    """No tokens; fewer tokens than one pass; every token in one codeword; ragged token count."""
+    import dataclasses
+    cfg = dataclasses.replace(wl.GPT2_SMALL, name="train_ragged", seq_len=4 * 131, seed=91)
+    data, x, cb, codes, desc, dev = setup(cfg)
+    for T in (0, 1, 131, 524):
+        import torch
+        from gpu_util import codes_to_dev
+        c = codes.copy()
+        if T == 131:
+            c[:] = 7                                         # every token in codeword 7 of every group
+        dev["codes"] = codes_to_dev(c, cb.shape[1])
+        counts, sums, sqerr = run_stats(desc, dev, T)
+        c_ref, s_ref, q_ref = oracle.codebook_stats(x[:T], c[:T], cb)
+        np.testing.assert_array_equal(counts, c_ref)
+        assert np.abs(sums - s_ref).max() <= 1e-5 * max(1.0, np.abs(s_ref).max())
+        np.testing.assert_allclose(sqerr, q_ref, rtol=1e-5, atol=1e-6)
+
+
+@pytest.mark.parametrize("name", ["tiny_vit_f32", "gpt2_small_bf16"])
+def test_navq(name):
+    import torch
+    from gpu_util import to_dev, codes_to_dev, DEV
+    from paper_2505_19342_amd import binding as B
+    cfg = wl.CONFIGS[name]
+    data, x, cb, codes, desc, dev = setup(cfg)
+    T, D = 200, cfg.d_model
+    rng = np.random.default_rng(7)
+    rnd = (lambda a: wl.round_to_bf16(a.astype(np.float32))) if cfg.dtype == "bf16" else (lambda a: a.astype(np.float32))
+    z = rnd(rng.standard_normal((T, D)))
+    L = rnd(np.tril(0.05 * rng.standard_normal((D, D))))
+    mu = (0.1 * rng.standard_normal(D)).astype(np.float32)
+    lam = 0.5                                                # a power of two: lam * L is exact in the element type
+    out = torch.empty((T, D), dtype=torch.float32, device=DEV)
+    B.astra_navq_forward(desc, codes_to_dev(codes[:T], cb.shape[1]), T, dev["cb"], torch.from_numpy(mu).to(DEV), lam,
+                         to_dev(z, cfg.dtype), to_dev(lam * L, cfg.dtype), out)
+    torch.cuda.synchronize()
+    ref = oracle.navq(codes[:T], cb, mu, L, z, lam)
+    err = np.abs(out.cpu().numpy() - ref).max()
+    print(f"{name}: NAVQ max abs err {err:.2e} (|x_tilde| max {np.abs(ref).max():.2f})")
+    assert err <= 1e-4
+    assert np.abs(ref - oracle.vq_decode(codes[:T], cb)).max() > 0.05      # the noise is there
+
+
+def test_argument_errors():
+    import torch
+    from paper_2505_19342_amd import binding as B
+    desc = B.vq_desc("bf16", 768, 32, 256)
+    t = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(B.AstraError, match="workspace"):
+        B.astra_codebook_stats(desc, t, t, 100, t, t, t, t, torch.zeros(8, dtype=torch.uint8, device="cuda:0"))
+    with pytest.raises(B.AstraError, match="NULL"):
+        B.astra_codebook_update(desc, t, t, 0.5, None, None, t, t)
+    with pytest.raises(B.AstraError):
+        B.astra_codebook_update(desc, t, t, 1.0, t, t, t, t)
+    assert B.astra_codebook_stats_workspace_bytes(B.vq_desc("bf16", 768, 1, 256), 10) == 0       # 768 channels per group: no kernel

@@ -210,8 +210,8 @@ int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hi
     rc = fill_batch(batch, dtype, problems, n_problems, 128, 128, &total);
     if (rc) return rc;
     if (total == 0) return ASTRA_OK;
-    if (code16) gemm_nt_bf16_kernel<128, 128, 2, 2, true><<<total, 256, 0, s>>>(batch);
-    else gemm_nt_bf16_kernel<128, 128, 2, 2, false><<<total, 256, 0, s>>>(batch);
+    if (code16) gemm_nt_bf16_kernel<128, 128, 4, 2, true><<<total, 512, 0, s>>>(batch);
+    else gemm_nt_bf16_kernel<128, 128, 4, 2, false><<<total, 512, 0, s>>>(batch);
     return launch_status();
 }
 

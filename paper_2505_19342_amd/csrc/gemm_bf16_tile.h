@@ -98,14 +98,19 @@ int gemm_split_factor(int dtype, int64_t M, int64_t N, int64_t K);
 //   kEpiSwiGLU       bf16 store of silu(A.gate^T + b_g) * (A.up^T + b_u)
 enum { kEpiLayer = 0, kEpiResidualF32 = 1, kEpiSplit = 2, kEpiGeluTanh = 3, kEpiGeluErf = 4, kEpiSwiGLU = 5 };
 
-template <int BM, int BN, int WM, int WN, bool CODE16, bool ENC = false, int EPI = kEpiLayer>
-__global__ __launch_bounds__(64 * WM * WN) void gemm_nt_bf16_kernel(const GemmBatch batch) {
-    constexpr int THREADS = 64 * WM * WN;
+// KS = 2: two groups of WM x WN wavefronts work on the same output tile, group g contracting the k ranges
+// [128 t + 64 g, 128 t + 64 g + 64), each with its own operand buffers and the full loop below; their accumulators are
+// added through LDS at the end.  A small tile then keeps its 64 x 64 wave tiles (1 KiB of LDS reads per MFMA) and still
+// has two wavefronts per SIMD to hide each other's staging.
+template <int BM, int BN, int WM, int WN, bool CODE16, bool ENC = false, int EPI = kEpiLayer, int KS = 1>
+__global__ __launch_bounds__(64 * WM * WN * KS) void gemm_nt_bf16_kernel(const GemmBatch batch) {
+    constexpr int THREADS = 64 * WM * WN;                      // threads of one group
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;        // MFMA tiles per wavefront
     constexpr int RPP = THREADS / 8;                           // rows staged per pass
     constexpr int PA = BM / RPP, PB = BN / RPP;                // staging passes per thread
-    __shared__ u32x4 lds_a[2][BM * kBK / 8];
-    __shared__ u32x4 lds_b[2][BN * kBK / 8];
+    static_assert(KS == 1 || (KS == 2 && !ENC), "one or two contraction groups");
+    __shared__ u32x4 lds_a[2 * KS][BM * kBK / 8];              // [2 * group + buffer]
+    __shared__ u32x4 lds_b[2 * KS][BN * kBK / 8];
 
     int vt;
     if (ENC) {
@@ -149,7 +154,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_bf16_kernel(const GemmBa
     const int m0 = tm * BM, n0 = tn * BN;
     const int M = P.M, N = P.N, K = P.K;
 
-    const int tid = threadIdx.x;
+    const int kgrp = KS == 1 ? 0 : __builtin_amdgcn_readfirstlane((int)threadIdx.x / THREADS);      // contraction group (wave-uniform)
+    const int kg2 = 2 * kgrp;
+    const int tid = KS == 1 ? (int)threadIdx.x : (int)threadIdx.x % THREADS;
     const int lane = tid & 63, wave = tid >> 6;
     const int i32 = lane & 31, h = lane >> 5;
     const int wm = wave / WN, wn = wave % WN;
@@ -165,9 +172,13 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_bf16_kernel(const GemmBa
     const int dg = gather ? P.dg : 1, Kc = gather ? P.Kc : 1, G = gather ? P.G : 0;
     const uint32_t magic = gather ? (uint32_t)(0x100000000ull / (uint32_t)dg) + 1u : 0u;
     const char* __restrict__ a_base = (const char*)(gather ? P.codebook : P.a);   // plain A advances 128 bytes per tile
-    const int a_step = gather ? 0 : kBK * 2;
+    const int a_step = gather ? 0 : kBK * 2 * KS;
     const uint32_t gmask = gather ? 0xffffffffu : 0u;                           // keeps the gathered offset, or zeroes it
     const char* __restrict__ b_base = (const char*)P.b;
+    if (KS > 1) {                              // this group's first 64 of every 128 along the contraction
+        if (!gather) a_base += kgrp * kBK * 2;
+        b_base += kgrp * kBK * 2;
+    }
     if (EPI == kEpiSplit) {                    // plain A only: both operands start at this copy's slice of the contraction
         a_base += (int64_t)split * batch.k_split * 2;
         b_base += (int64_t)split * batch.k_split * 2;
@@ -196,8 +207,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_bf16_kernel(const GemmBa
         }
         boff[it] = ((uint32_t)rb * (uint32_t)K + kc * 8) * 2u;
     }
-    int k_code = kc * 8;              // contraction index of this thread's piece in the tile whose codes are fetched next
-    int k_use = kc * 8;               // ... in the tile whose operand pieces are fetched next
+    int k_code = kc * 8 + kgrp * kBK; // contraction index of this thread's piece in the tile whose codes are fetched next
+    int k_use = kc * 8 + kgrp * kBK;  // ... in the tile whose operand pieces are fetched next
     int code[PA];
     u32x4 ra[PA], rb[PB];
 
@@ -208,7 +219,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_bf16_kernel(const GemmBa
             if (CODE16) code[it] = *reinterpret_cast<const uint16_t*>(c_base + (coff[it] + g_));
             else code[it] = *reinterpret_cast<const uint8_t*>(c_base + (coff[it] + g_));
         }
-        k_code += kBK;
+        k_code += kBK * KS;
     };
     auto load_tile = [&]() {
         const uint32_t g_ = __umulhi((uint32_t)k_use, magic);
@@ -223,19 +234,19 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_bf16_kernel(const GemmBa
 #pragma unroll
         for (int it = 0; it < PB; ++it) rb[it] = *reinterpret_cast<const u32x4*>(b_base + boff[it]);
         a_base += a_step;
-        b_base += kBK * 2;
-        k_use += kBK;
+        b_base += kBK * 2 * KS;
+        k_use += kBK * KS;
     };
     auto store_tile = [&](int buf_) {
 #pragma unroll
         for (int it = 0; it < PA; ++it) {
             const int r_ = r0 + RPP * it;
-            lds_a[buf_][r_ * 8 + (kc ^ swz(r_))] = ra[it];
+            lds_a[kg2 + buf_][r_ * 8 + (kc ^ swz(r_))] = ra[it];
         }
 #pragma unroll
         for (int it = 0; it < PB; ++it) {
             const int r_ = r0 + RPP * it;
-            lds_b[buf_][r_ * 8 + (kc ^ swz(r_))] = rb[it];
+            lds_b[kg2 + buf_][r_ * 8 + (kc ^ swz(r_))] = rb[it];
         }
     };
 
@@ -247,7 +258,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_bf16_kernel(const GemmBa
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-    if (EPI == kEpiResidualF32 && P.residual != nullptr) {
+    if (EPI == kEpiResidualF32 && P.residual != nullptr && kgrp == 0) {
         // The residual is where the accumulation starts: its loads are issued here, all at once, and land while the first
         // operand tiles are fetched.  (Added in the epilogue, every load would be a round trip to memory in front of a store.)
         // Rows and columns beyond the problem are clamped: those accumulators are never stored.
@@ -281,11 +292,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_bf16_kernel(const GemmBa
     // covered by the MFMAs issued meanwhile.  Staging is spread over steps 0..2; the workgroup barrier follows step 2,
     // after which step 3 may read the first fragments of tile kt+1 from the buffer just filled, and the buffer of
     // tile kt (all of whose fragments were requested before the barrier) is free for the next iteration's staging.
-    const int n_kt = (EPI == kEpiSplit ? batch.k_split : K) / kBK;
+    const int n_kt = (EPI == kEpiSplit ? batch.k_split : K) / (kBK * KS);
     bf16x8 fa[2][TM], fb[2][TN];
     auto read_frag = [&](int buf_, int ks, int slot, int j) {
-        if (j < TM) fa[slot][j] = __builtin_bit_cast(bf16x8, lds_a[buf_][arow[j] * 8 + ((2 * ks + h) ^ swz(arow[j]))]);
-        else fb[slot][j - TM] = __builtin_bit_cast(bf16x8, lds_b[buf_][brow[j - TM] * 8 + ((2 * ks + h) ^ swz(brow[j - TM]))]);
+        if (j < TM) fa[slot][j] = __builtin_bit_cast(bf16x8, lds_a[kg2 + buf_][arow[j] * 8 + ((2 * ks + h) ^ swz(arow[j]))]);
+        else fb[slot][j - TM] = __builtin_bit_cast(bf16x8, lds_b[kg2 + buf_][brow[j - TM] * 8 + ((2 * ks + h) ^ swz(brow[j - TM]))]);
     };
     constexpr int NR = TM + TN, NM = TM * TN;
     auto tile_steps = [&](int kt, auto full_tag) {
@@ -297,7 +308,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_bf16_kernel(const GemmBa
         const uint32_t gbase_ = g_ * (uint32_t)Kc;
         auto stage_a = [&](int it) {
             const int r_ = r0 + RPP * it;
-            if (st) lds_a[buf ^ 1][r_ * 8 + (kc ^ swz(r_))] = ra[it];
+            if (st) lds_a[kg2 + (buf ^ 1)][r_ * 8 + (kc ^ swz(r_))] = ra[it];
             if (ld) {
                 const uint32_t c_ = (uint32_t)(code[it] < Kc ? code[it] : Kc - 1);
                 const uint32_t goff_ = ((gbase_ + c_) * (uint32_t)dg + j_) * 2u;
@@ -306,7 +317,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_bf16_kernel(const GemmBa
         };
         auto stage_b = [&](int it) {
             const int r_ = r0 + RPP * it;
-            if (st) lds_b[buf ^ 1][r_ * 8 + (kc ^ swz(r_))] = rb[it];
+            if (st) lds_b[kg2 + (buf ^ 1)][r_ * 8 + (kc ^ swz(r_))] = rb[it];
             if (ld) rb[it] = *reinterpret_cast<const u32x4*>(b_base + boff[it]);
         };
 #pragma unroll
@@ -338,8 +349,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_bf16_kernel(const GemmBa
         }
         if (ld) {
             a_base += a_step;
-            b_base += kBK * 2;
-            k_use += kBK;
+            b_base += kBK * 2 * KS;
+            k_use += kBK * KS;
         }
         if (FULL || kt + 3 < n_kt) load_codes();
     };
@@ -356,6 +367,29 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_bf16_kernel(const GemmBa
     int kt = 0;
     for (; kt + 3 < n_kt; ++kt) tile_steps(kt, std::true_type{});
     for (; kt < n_kt; ++kt) tile_steps(kt, std::false_type{});
+
+    if constexpr (KS == 2) {
+        // the second group hands its accumulators over through the operand buffers (all fragment reads are done)
+        static_assert(KS == 1 || sizeof(lds_a) >= sizeof(float) * BM * BN, "accumulator exchange fits the A buffers");
+        float* xch = reinterpret_cast<float*>(&lds_a[0][0]);
+        __syncthreads();
+        if (kgrp == 1) {
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < TN; ++b)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) xch[(((wave * TM + a) * TN + b) * 16 + v) * 64 + lane] = acc[a][b][v];
+        }
+        __syncthreads();
+        if (kgrp == 1) return;
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[a][b][v] += xch[(((wave * TM + a) * TN + b) * 16 + v) * 64 + lane];
+    }
 
     // epilogue.  acc[a][b][v] is C[m, n] with m = wave row base + 32a + acc_row(v, h), n = wave column base + 32b + lane % 32.
     const uint16_t* __restrict__ bias = (const uint16_t*)P.bias;

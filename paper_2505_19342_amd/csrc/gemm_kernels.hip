@@ -210,8 +210,17 @@ int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hi
     rc = fill_batch(batch, dtype, problems, n_problems, 128, 128, &total);
     if (rc) return rc;
     if (total == 0) return ASTRA_OK;
-    if (code16) gemm_nt_bf16_kernel<128, 128, 4, 2, true><<<total, 512, 0, s>>>(batch);
-    else gemm_nt_bf16_kernel<128, 128, 4, 2, false><<<total, 512, 0, s>>>(batch);
+    // one workgroup per compute unit at most: two contraction groups of four wavefronts (when every contraction is a
+    // multiple of 128); more tiles than that: eight wavefronts on one contraction, two workgroups fit a compute unit
+    bool ks2 = total <= kCus;
+    for (int i = 0; i < batch.n; ++i) ks2 = ks2 && batch.p[i].K % (2 * kBK) == 0;
+    if (ks2) {
+        if (code16) gemm_nt_bf16_kernel<128, 128, 2, 2, true, false, kEpiLayer, 2><<<total, 512, 0, s>>>(batch);
+        else gemm_nt_bf16_kernel<128, 128, 2, 2, false, false, kEpiLayer, 2><<<total, 512, 0, s>>>(batch);
+    } else {
+        if (code16) gemm_nt_bf16_kernel<128, 128, 4, 2, true><<<total, 512, 0, s>>>(batch);
+        else gemm_nt_bf16_kernel<128, 128, 4, 2, false><<<total, 512, 0, s>>>(batch);
+    }
     return launch_status();
 }
 

@@ -51,10 +51,12 @@ int launch_split_reduce(const float* part, int n_split, const GemmProblem& p, hi
 template <int EPI>
 static void launch_epi(bool big, const GemmBatch& batch, int grid, hipStream_t s) {
     if (big) gemm_nt_bf16_kernel<256, 256, 2, 4, false, false, EPI><<<grid, 512, 0, s>>>(batch);
+    else if (grid <= kCus && batch.p[0].K % (2 * kBK) == 0) gemm_nt_bf16_kernel<128, 128, 2, 2, false, false, EPI, 2><<<grid, 512, 0, s>>>(batch);
     else gemm_nt_bf16_kernel<128, 128, 4, 2, false, false, EPI><<<grid, 512, 0, s>>>(batch);
 }
 
-// big: 256 x 256 tiles, else 128 x 128, both on 512 threads; the batch was filled for that tile size.
+// big: 256 x 256 tiles, else 128 x 128 (two contraction groups when the contraction is a multiple of 128), both on 512
+// threads; the batch was filled for that tile size.
 int launch_gemm_mlp(int epi, bool big, const GemmBatch& batch, int grid, hipStream_t s) {
     if (grid <= 0) return ASTRA_OK;
     switch (epi) {

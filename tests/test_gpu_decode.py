@@ -118,7 +118,6 @@ def test_other_group_counts():
 def test_argument_errors():
     import torch
     from paper_2505_19342_amd import binding as B
-    cfg = wl.GPT2_SMALL
     desc = B.DecodeDesc(B.vq_desc("bf16", 768, 32, 256), 12, 12, 64, 10, 10, 0.0)
     t = torch.zeros(4096, dtype=torch.uint8, device="cuda:0")
     with pytest.raises(B.AstraError, match="workspace"):
@@ -129,4 +128,4 @@ def test_argument_errors():
     assert B.astra_decode_attention_workspace_bytes(bad) == 0
     odd = B.DecodeDesc(B.vq_desc("bf16", 768, 256, 256), 12, 12, 64, 10, 10, 0.0)      # groups of 3 channels
     with pytest.raises(B.AstraError, match="no kernel"):
-        B.astra_decode_attention(desc if False else odd, t, t, t, t, t, None, t, t, t, None, t)
+        B.astra_decode_attention(odd, t, t, t, t, t, None, t, t, t, None, t)

@@ -38,8 +38,12 @@ def build(force: bool = True) -> str:
 def _load():
     global _lib
     if _lib is None:
-        build(force=False)
-        lib = ctypes.CDLL(_LIB)
+        # tests/test_oracle_mutations.py points this at deliberately broken builds of the C source to show that the pins
+        # notice; nothing else sets it
+        override = os.environ.get("ASTRA_ORACLE_LIB_OVERRIDE")
+        if not override:
+            build(force=False)
+        lib = ctypes.CDLL(override or _LIB)
         lib.oracle_num_threads.restype = ctypes.c_int
         for name in ("oracle_vq_encode", "oracle_vq_decode", "oracle_linear",
                      "oracle_mixed_attention", "oracle_mixed_attention_valid",

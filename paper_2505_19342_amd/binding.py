@@ -79,6 +79,9 @@ def load(build_if_missing: bool = True):
             raise AstraError(f"{LIB_PATH} is not built; run paper_2505_19342_amd/build.py")
         from . import build as _build
         _build.build()
+    # torch brings its own HIP runtime; it has to be in the process before this library resolves its dependency on one,
+    # or two runtimes end up loaded and launches on torch's streams fail
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     vp, i64, f32p = ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p
     lib.astra_vq_prepare.argtypes = [ctypes.POINTER(VqDesc), vp, f32p, vp]

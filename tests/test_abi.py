@@ -23,6 +23,14 @@ def test_library_exports_every_declared_symbol():
         assert getattr(lib, n) is not None
 
 
+def test_loading_first_still_puts_torchs_hip_runtime_in_the_process():
+    # a library opened before torch would bind to another HIP runtime than the one torch's streams belong to
+    import subprocess
+    import sys
+    code = "from paper_2505_19342_amd import binding as B; import sys; assert 'torch' not in sys.modules; B.load(False); assert 'torch' in sys.modules"
+    subprocess.run([sys.executable, "-c", code], cwd=ROOT, check=True, timeout=300)
+
+
 def test_version_and_status_strings_run_without_a_gpu():
     lib = B.load()
     assert lib.astra_version() >= 100

@@ -116,13 +116,15 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_nt_bf16_kernel(const G
     if (ENC) {
         // The grid is the GEMM tiles plus batch.n_enc_wgs workgroups that encode the local rows (nothing in the
         // projections depends on the codes or the other way round): they fill compute units the tiles leave idle.
-        // The encode reuses the operand buffers: its ring of codebook tiles is exactly lds_a, the norms sit in lds_b.
-        static_assert(!ENC || (sizeof(lds_a) == sizeof(u32x4) * kEncBufs * kEncCbSlots && sizeof(lds_b) >= sizeof(f32x4) * kEncBufs * kEncCnSlots),
-                      "encode ring must fit the operand buffers");
+        // The encode reuses the operand buffers: its ring of codebook tiles is exactly the one of 256 rows, the norms sit in the other.
+        constexpr size_t kRing = sizeof(u32x4) * kEncBufs * kEncCbSlots, kNorms = sizeof(f32x4) * kEncBufs * kEncCnSlots;
+        constexpr bool RING_IN_A = sizeof(lds_a) == kRing;
+        static_assert(!ENC || (RING_IN_A && sizeof(lds_b) >= kNorms) || (sizeof(lds_b) == kRing && sizeof(lds_a) >= kNorms),
+                      "encode ring must be one of the operand buffers");
         const FusedId id = fused_id(blockIdx.x, gridDim.x - batch.n_enc_wgs, batch.n_enc_wgs);
         if (id.enc) {
-            u32x4* cb = &lds_a[0][0];
-            f32x4* cn = reinterpret_cast<f32x4*>(&lds_b[0][0]);
+            u32x4* cb = RING_IN_A ? &lds_a[0][0] : &lds_b[0][0];
+            f32x4* cn = reinterpret_cast<f32x4*>(RING_IN_A ? &lds_b[0][0] : &lds_a[0][0]);
             const EncodeJob& job = batch.enc;
             vq_encode_fast_zero_lds<THREADS>(cb);
             __syncthreads();                               // zero fill done before any transfer lands

@@ -178,8 +178,24 @@ int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hi
     if (rc) return rc;
     bool big = total >= 128;
     if (g_gemm_force_cfg >= 0) big = g_gemm_force_cfg >= 1;
+    // In between, 128 x 256 tiles: when they run as a single round of workgroups that fills more than half of the chip,
+    // the launch lasts one such tile (about two thirds of a 256 x 256 one), where 256 x 256 tiles would leave half of
+    // the units idle and 128 x 128 tiles would need a second workgroup per unit at a lower rate each.
+    bool mid = false;
+    if (g_gemm_force_cfg < 0 && total <= 128) {
+        GemmBatch mb{};
+        int mt = 0;
+        rc = fill_batch(mb, dtype, problems, n_problems, 128, 256, &mt);
+        if (rc) return rc;
+        if (mt > kCus / 2 && mt <= kCus) {
+            mid = true;
+            big = false;
+            batch = mb;
+            total = mt;
+        }
+    }
     // Fuse the encode into the launch when the tiles leave a good part of the last round of compute units idle.
-    if (big && enc && enc_fused && g_gemm_force_cfg < 0 && vq_encode_fast_ok(enc->K, enc->dg) && enc->n_tokens > 0) {
+    if ((big || mid) && enc && enc_fused && g_gemm_force_cfg < 0 && vq_encode_fast_ok(enc->K, enc->dg) && enc->n_tokens > 0) {
         const int rem = total % kCus;
         const int E = rem == 0 ? 0 : ((kCus - rem) & ~7);
         const int64_t n_tb = ceil_div(enc->n_tokens, 256);
@@ -190,10 +206,21 @@ int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hi
             batch.enc.n_wgs = E;
             *enc_fused = true;
             if (plan_only) return ASTRA_OK;
-            if (code16) gemm_nt_bf16_kernel<256, 256, 2, 4, true, true><<<total + E, 512, 0, s>>>(batch);
-            else gemm_nt_bf16_kernel<256, 256, 2, 4, false, true><<<total + E, 512, 0, s>>>(batch);
+            if (mid) {
+                if (code16) gemm_nt_bf16_kernel<128, 256, 2, 4, true, true><<<total + E, 512, 0, s>>>(batch);
+                else gemm_nt_bf16_kernel<128, 256, 2, 4, false, true><<<total + E, 512, 0, s>>>(batch);
+            } else {
+                if (code16) gemm_nt_bf16_kernel<256, 256, 2, 4, true, true><<<total + E, 512, 0, s>>>(batch);
+                else gemm_nt_bf16_kernel<256, 256, 2, 4, false, true><<<total + E, 512, 0, s>>>(batch);
+            }
             return launch_status();
         }
+    }
+    if (plan_only) return ASTRA_OK;
+    if (mid) {
+        if (code16) gemm_nt_bf16_kernel<128, 256, 2, 4, true><<<total, 512, 0, s>>>(batch);
+        else gemm_nt_bf16_kernel<128, 256, 2, 4, false><<<total, 512, 0, s>>>(batch);
+        return launch_status();
     }
     if (plan_only) return ASTRA_OK;
     if (big && g_gemm_force_cfg == 2) {

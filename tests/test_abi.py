@@ -63,8 +63,9 @@ def test_host_side_argument_checks_need_no_gpu():
 
 def test_encode_fusion_plan_is_host_only():
     """astra_layer_encode_fused decides from the shapes alone: the projection launch carries the encode when
-    its 256x256 tiles leave compute units idle in the last round (Llama-3-8B shape, ranks with non-local
-    rows), never for the small shapes or fp32; an invalid descriptor is an error, not a crash."""
+    its tiles leave compute units idle in the last round (Llama-3-8B shape: 192 tiles of 128x256 on the first
+    rank, 160 and 192 tiles of 256x256 on the last two; the second rank's 256 tiles of 128x256 fill the chip),
+    never for the small shapes or fp32; an invalid descriptor is an error, not a crash."""
     from paper_2505_19342_amd import workloads as wl
 
     def desc(cfg, rank):
@@ -74,7 +75,7 @@ def test_encode_fusion_plan_is_host_only():
                                        cfg.causal, rank * cfg.n_local))
 
     llama = wl.CONFIGS["llama3_8b_bf16"]
-    assert [B.astra_layer_encode_fused(desc(llama, r)) for r in range(llama.n_dev)] == [False, True, True, True]
+    assert [B.astra_layer_encode_fused(desc(llama, r)) for r in range(llama.n_dev)] == [True, False, True, True]
     for name in ("tiny_vit_f32", "vit_base_bf16", "gpt2_small_bf16"):
         cfg = wl.CONFIGS[name]
         assert not B.astra_layer_encode_fused(desc(cfg, cfg.n_dev - 1))

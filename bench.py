@@ -398,6 +398,19 @@ def main():
             result["mfma_probe"] = {"tflops": tf, "frac_of_published_peak": tf / peak,
                                     "dominant_kernel_frac_of_probe": achieved / tf,
                                     "what": "astra_probe_mfma_bf16: 32x32x16 bf16 MFMAs on register operands only"}
+            # the same loop with vector-ALU instructions of the same wavefront between the MFMAs: ns added per instruction
+            n_mfma_wave = iters * 4
+            mix = {}
+            for kind, use_exp in (("fma", False), ("exp2_mul", True)):
+                t = {nv: timed(lambda: B.astra_probe_mfma_valu_bf16(probe_out, 256, iters * 4, nv, use_exp), 3, warm=1)
+                     for nv in (0, 4, 8, 16)}
+                # 256 workgroups = one per compute unit, two wavefronts per SIMD, 4 * n_mfma_wave MFMAs per wavefront
+                per_mfma_ns = {nv: t[nv] * 1e6 / (4 * n_mfma_wave * 2) for nv in t}
+                mix[kind] = {"ns_per_mfma_per_simd": {str(nv): per_mfma_ns[nv] for nv in t},
+                             "ns_added_per_valu_step": {f"{a}->{b}": (per_mfma_ns[b] - per_mfma_ns[a]) / (b - a)
+                                                        for a, b in ((0, 4), (4, 8), (8, 16))}}
+            result["mfma_valu_probe"] = {**mix, "what": "astra_probe_mfma_valu_bf16: per SIMD, the time of one MFMA plus N vector-ALU steps "
+                                         "(fma: one instruction; exp2_mul: an exponential and a multiply) issued after it by the same wavefront"}
             del probe_out
 
     if not args.no_cpu_baseline:

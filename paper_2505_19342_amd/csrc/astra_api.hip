@@ -347,6 +347,11 @@ int astra_probe_mfma_bf16(float* out, int n_blocks, int iters, void* stream) {
     return launch_mfma_probe(out, n_blocks, iters, (hipStream_t)stream);
 }
 
+int astra_probe_mfma_valu_bf16(float* out, int n_blocks, int iters, int valu_per_mfma, int use_exp, void* stream) {
+    if (!out) return ASTRA_ERR_NULL;
+    return launch_mfma_valu_probe(out, n_blocks, iters, valu_per_mfma, use_exp, (hipStream_t)stream);
+}
+
 int astra_layer_encode_fused(const astra_layer_desc* desc) {
     int fused = 0;
     const int rc = layer_forward_impl(desc, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,

@@ -179,5 +179,6 @@ struct AttnParams {
 };
 int launch_attention(int dtype, const AttnParams& p, int head_dim, hipStream_t s);
 int launch_mfma_probe(float* out, int n_blocks, int iters, hipStream_t s);
+int launch_mfma_valu_probe(float* out, int n_blocks, int iters, int valu_per_mfma, int use_exp, hipStream_t s);
 
 }  // namespace astra

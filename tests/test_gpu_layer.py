@@ -94,27 +94,29 @@ def test_llama3_8b_shape_full_size(rank):
     run_case(wl.LLAMA3_8B, rank)
 
 
-def test_llama_dims_ragged_rows_take_the_fused_encode_path():
-    """Llama-3-8B widths with row counts that are multiples of nothing: 1000 of 3917 tokens on this device (the last
-    chunk), so the last tile of every projection and the last token block of the encode are ragged, and the tile
-    count still makes the projection launch carry the encode (the configuration bench.py times)."""
+@pytest.mark.parametrize("seq_len,lo,fused", [(3917, 2917, True), (1000, 0, True), (1900, 900, False)])
+def test_llama_dims_ragged_rows_in_every_projection_tile_shape(seq_len, lo, fused):
+    """Llama-3-8B widths with row counts that are multiples of nothing: the last 1000 of seq_len tokens on this device,
+    so the last tile of every projection and the last token block of the encode are ragged.  The three cases take
+    the three launch shapes of the projections: 256x256 tiles with the encode on the units left over (the
+    configuration bench.py times), 192 tiles of 128x256 with the encode on the units left over (no visible peers),
+    and 256 tiles of 128x256 that fill the chip (the encode then runs as a kernel of its own)."""
     from gpu_util import LayerOnGpu, compare_codes
     from paper_2505_19342_amd import binding as B
-    cfg = dataclasses.replace(wl.LLAMA3_8B, name="llama_ragged", seq_len=3917, seed=41)
+    cfg = dataclasses.replace(wl.LLAMA3_8B, name="llama_ragged", seq_len=seq_len, seed=41)
     data = wl.generate(cfg)
-    lo = 2917
     x_local, x_nl = data["x"][lo:], data["x"][:lo]
     codes_nl = oracle.vq_encode(x_nl, data["codebook"])
     y_ref, codes_ref, gap = oracle.layer_forward(x_local, codes_nl, data["codebook"], data["wq"], data["wk"], data["wv"],
                                                  data["wo"], n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, causal=True,
                                                  n_before=lo, return_gap=True)
     layer = LayerOnGpu(cfg, data, x_local, codes_nl, lo)
-    assert B.astra_layer_encode_fused(layer.desc)
+    assert B.astra_layer_encode_fused(layer.desc) == fused
     layer.run()
     y, codes = layer.results()
     n_tie = compare_codes(codes, codes_ref, gap, NEAR_TIE)
     err = np.abs(y - y_ref).max()
-    print(f"llama dims, 1000 local / 2917 non-local rows: max abs err {err:.3e}, near-tie codes {n_tie}/{codes.size}")
+    print(f"llama dims, {seq_len - lo} local / {lo} non-local rows: max abs err {err:.3e}, near-tie codes {n_tie}/{codes.size}")
     assert err <= Y_TOL["bf16"]
     assert n_tie <= max(2, codes.size // 2000)
 

@@ -60,7 +60,7 @@ def main():
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the measurements outside the timed region (matrix-core probe, stand-alone decode, other ranks)")
     ap.add_argument("--extras", default="all",
-                    help="comma list of the measurements outside the timed region to run: ranks, lost, block, stack (needs block), kv, kvcache, train, decode, probe (default all)")
+                    help="comma list of the measurements outside the timed region to run: ranks, uneven, lost, block, stack (needs block), kv, kvcache, train, decode, probe (default all)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the warm-up, run one plain elementwise copy kernel reading and writing this many MiB "
                          "(fp32): the reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -199,7 +199,7 @@ def main():
     per_step = sorted(ev.elapsed_ms(0, 4) for ev in events)
     result["gpu_ms_per_step_events_p10_p50_p90"] = [per_step[int(q * (len(per_step) - 1))] for q in (0.1, 0.5, 0.9)]
 
-    extras = set() if args.no_extras else set(("ranks,lost,block,stack,kv,kvcache,train,decode,probe" if args.extras == "all" else args.extras).split(","))
+    extras = set() if args.no_extras else set(("ranks,uneven,lost,block,stack,kv,kvcache,train,decode,probe" if args.extras == "all" else args.extras).split(","))
     if extras:
         def timed(fn, n, warm=0):
             for _ in range(1 + warm):      # after host-side set-up the chip is idle: bring it back to its steady clock
@@ -229,6 +229,33 @@ def main():
                 del xr, xn, cn
             result["per_rank_ms"] = per_rank
             result["rank_mean_tokens_per_s"] = tq / (sum(per_rank.values()) / len(per_rank) * 1e-3)
+        # an uneven split of the same sequence (App. "heterogeneous devices": token counts in proportion to device speed,
+        # FPAR = the fraction of (query, key) pairs that stay at full precision = sum_i n_i^2 / N^2): every device's call
+        if "uneven" in extras and cfg.causal and cfg.n_cls == 0 and cfg.n_dev == 4:
+            n_tot = cfg.n_dev * cfg.n_local
+            shares = [n_tot // 8, n_tot // 4, n_tot // 4, n_tot - n_tot // 8 - 2 * (n_tot // 4)]       # 1 : 2 : 2 : 3
+            xs_all = to_dev(data["x"])
+            c_all = torch.empty((n_tot, G), dtype=code_t, device=dev)
+            B.astra_vq_encode(vq, xs_all, n_tot, codebook, cnorm, c_all)
+            per_dev, lo = [], 0
+            for n_i in shares:
+                # causal: the rows before the chunk are visible as codes, the rows after it are not needed at all
+                d_i = B.LayerDesc(vq, B.attn_desc(dt, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, 0, n_i, lo, True, lo))
+                x_i = xs_all[lo:lo + n_i].contiguous()
+                cn_i = c_all[:lo].contiguous() if lo > 0 else torch.empty((0, G), dtype=code_t, device=dev)
+                y_i = torch.empty((n_i, D), dtype=torch.float32, device=dev)
+                cl_i = torch.empty((n_i, G), dtype=code_t, device=dev)
+                ws_i = torch.empty(max(B.astra_layer_workspace_bytes(d_i), 256), dtype=torch.uint8, device=dev)
+                a_i = (d_i, x_i, cn_i, codebook, cnorm, *w, None, None, None, None, y_i, cl_i, ws_i)
+                per_dev.append(timed(lambda: B.astra_layer_forward(*a_i), 100, warm=50))
+                lo += n_i
+                del x_i, cn_i, y_i, cl_i, ws_i
+            result["uneven_split"] = {"tokens_per_device": shares, "fpar": sum(n * n for n in shares) / float(n_tot) ** 2,
+                                      "fpar_even_split": 1.0 / cfg.n_dev, "ms_per_device": per_dev,
+                                      "slowest_device_ms": max(per_dev),
+                                      "what": "astra_layer_forward of every device of a 1:2:2:3 split of the same sequence "
+                                              "(under causal masking a device sees the codes of the rows before its chunk)"}
+            del xs_all, c_all
         # the layer with 5 % of the peers' tokens lost (Sec. 4.5, packet loss without retransmission): same launches,
         # the attention additionally masks the lost keys of every non-local tile
         if "lost" in extras and tn > 0:

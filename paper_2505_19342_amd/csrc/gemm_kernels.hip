@@ -199,7 +199,14 @@ int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hi
         const int rem = total % kCus;
         const int E = rem == 0 ? 0 : ((kCus - rem) & ~7);
         const int64_t n_tb = ceil_div(enc->n_tokens, 256);
-        if (E >= 8 && E <= kCus / 2 && n_tb * enc->G <= 0x7fffffff) {
+        // The encode workgroups must not outlast the tiles: an item (256 tokens of one group against its K codewords)
+        // takes about 1 us per 2^20 codeword elements (16.5 us measured at K = 1024, dg = 64), a 256 x 256 tile about
+        // 105 us per 4096 of contraction, a 128 x 256 tile about 70.
+        int k_max = 0;
+        for (int i = 0; i < batch.n; ++i) k_max = batch.p[i].K > k_max ? batch.p[i].K : k_max;
+        const double tile_us = (mid ? 70.0 : 105.0) * k_max / 4096.0;
+        const double enc_us = E > 0 ? (double)ceil_div(n_tb * enc->G, (int64_t)E) * 256.0 * enc->K * enc->dg / 1048576.0 : 0.0;
+        if (E >= 8 && E <= kCus / 2 && n_tb * enc->G <= 0x7fffffff && enc_us <= 1.05 * tile_us) {
             batch.n_enc_wgs = E;
             batch.enc = *enc;
             batch.enc.n_tb = (int)n_tb;

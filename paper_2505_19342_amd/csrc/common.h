@@ -147,7 +147,8 @@ struct EncodeJob;
 // launch took it (extra workgroups) or the caller still has to run it.  plan_only: decide and validate, launch nothing.
 // split_ws: optional scratch of gemm_split_workspace_bytes() for a single fp32-output problem whose contraction is cut into slices.
 int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hipStream_t s, const EncodeJob* enc = nullptr,
-                      bool* enc_fused = nullptr, bool plan_only = false, void* split_ws = nullptr, size_t split_ws_bytes = 0);
+                      bool* enc_fused = nullptr, bool plan_only = false, void* split_ws = nullptr, size_t split_ws_bytes = 0,
+                      bool may_cut = true);
 size_t gemm_split_workspace_bytes(int dtype, int64_t M, int64_t N, int64_t K);
 extern int g_gemm_force_cfg;
 extern const int g_gemm_problem_size;

@@ -127,10 +127,74 @@ static int fill_batch(GemmBatch& batch, int dtype, const GemmProblem* problems, 
     return ASTRA_OK;
 }
 
+// Tiles of a set of problems at a tile shape (0 when a problem is rejected: the caller's own pass reports the error).
+static int64_t count_tiles(const GemmProblem* problems, int n_problems, int bm, int bn) {
+    int64_t t = 0;
+    for (int i = 0; i < n_problems; ++i)
+        if (problems[i].M > 0 && problems[i].N > 0) t += ceil_div(problems[i].M, bm) * ceil_div(problems[i].N, bn);
+    return t;
+}
+
+// Rough duration (us) of one bf16 projection launch under the shape rules of launch_gemm_batch: rounds of 256 x 256 tiles
+// (about 105 us per 4096 of contraction), one round of 128 x 256 tiles (70), or 128 x 128 tiles (48 for a single round of
+// one workgroup per unit, 80 per round of two per unit).  Used only to compare ways of cutting a launch in two.
+static double estimate_launch_us(const GemmProblem* problems, int n_problems) {
+    int k_max = 0;
+    for (int i = 0; i < n_problems; ++i) k_max = problems[i].K > k_max ? problems[i].K : k_max;
+    const double kf = k_max / 4096.0;
+    const int64_t big = count_tiles(problems, n_problems, 256, 256);
+    if (big == 0) return 0.0;
+    if (big > 128) return (double)ceil_div(big, (int64_t)kCus) * 105.0 * kf + 8.0;
+    const int64_t mid = count_tiles(problems, n_problems, 128, 256);
+    if (mid > kCus / 2 && mid <= kCus) return 70.0 * kf + 8.0;
+    if (big == 128) return 105.0 * kf + 8.0;
+    const int64_t small = count_tiles(problems, n_problems, 128, 128);
+    return (small <= kCus ? 48.0 : (double)ceil_div(small, (int64_t)(2 * kCus)) * 80.0) * kf + 8.0;
+}
+
 int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hipStream_t s, const EncodeJob* enc, bool* enc_fused,
-                      bool plan_only, void* split_ws, size_t split_ws_bytes) {
+                      bool plan_only, void* split_ws, size_t split_ws_bytes, bool may_cut) {
     if (enc_fused) *enc_fused = false;
     if (n_problems > kMaxGemmProblems) return ASTRA_ERR_UNSUPPORTED;
+    // A launch whose last round of 256 x 256 tiles is nearly empty lasts a whole tile longer for a few tiles.  When the
+    // problems can be dealt into two launches that are shorter together (say one that fills its rounds and a small one
+    // on smaller tiles), run those: the launches are independent and follow each other on the stream.
+    if (dtype == ASTRA_BF16 && may_cut && n_problems >= 2 && g_gemm_force_cfg < 0) {
+        bool plain = true;
+        for (int i = 0; i < n_problems; ++i)
+            plain = plain && problems[i].c_mode != kCSwiGLU && problems[i].act == kActNone && !problems[i].residual;
+        const int64_t big = count_tiles(problems, n_problems, 256, 256);
+        if (plain && big > kCus && big % kCus != 0 && big % kCus <= 3 * kCus / 8) {
+            const double whole = estimate_launch_us(problems, n_problems);
+            double best = whole - 10.0;        // a second launch has to pay for itself with some margin
+            unsigned best_mask = 0;
+            GemmProblem a[kMaxGemmProblems], b[kMaxGemmProblems];
+            for (unsigned mask = 1; mask + 1 < (1u << n_problems); ++mask) {
+                int na = 0, nb = 0;
+                for (int i = 0; i < n_problems; ++i) ((mask >> i) & 1u ? a[na++] : b[nb++]) = problems[i];
+                const double t = estimate_launch_us(a, na) + estimate_launch_us(b, nb);
+                if (t < best) { best = t; best_mask = mask; }
+            }
+            if (best_mask != 0) {
+                int na = 0, nb = 0;
+                for (int i = 0; i < n_problems; ++i) ((best_mask >> i) & 1u ? a[na++] : b[nb++]) = problems[i];
+                bool fused_a = false, fused_b = false;
+                int rc;
+                if (!plan_only) {               // every problem is checked before the first of the two launches
+                    rc = launch_gemm_batch(dtype, a, na, s, nullptr, nullptr, true, nullptr, 0, false);
+                    if (rc) return rc;
+                    rc = launch_gemm_batch(dtype, b, nb, s, nullptr, nullptr, true, nullptr, 0, false);
+                    if (rc) return rc;
+                }
+                rc = launch_gemm_batch(dtype, a, na, s, enc, enc ? &fused_a : nullptr, plan_only, nullptr, 0, false);
+                if (rc) return rc;
+                rc = launch_gemm_batch(dtype, b, nb, s, fused_a ? nullptr : enc, enc && !fused_a ? &fused_b : nullptr, plan_only,
+                                       nullptr, 0, false);
+                if (enc_fused) *enc_fused = fused_a || fused_b;
+                return rc;
+            }
+        }
+    }
     GemmBatch batch{};
     int total = 0;
     if (dtype != ASTRA_BF16) {

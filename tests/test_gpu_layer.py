@@ -94,13 +94,14 @@ def test_llama3_8b_shape_full_size(rank):
     run_case(wl.LLAMA3_8B, rank)
 
 
-@pytest.mark.parametrize("seq_len,lo,fused", [(3917, 2917, True), (1000, 0, True), (1900, 900, False)])
+@pytest.mark.parametrize("seq_len,lo,fused", [(3917, 2917, True), (1000, 0, True), (1900, 900, False), (5100, 3070, False)])
 def test_llama_dims_ragged_rows_in_every_projection_tile_shape(seq_len, lo, fused):
-    """Llama-3-8B widths with row counts that are multiples of nothing: the last 1000 of seq_len tokens on this device,
-    so the last tile of every projection and the last token block of the encode are ragged.  The three cases take
-    the three launch shapes of the projections: 256x256 tiles with the encode on the units left over (the
-    configuration bench.py times), 192 tiles of 128x256 with the encode on the units left over (no visible peers),
-    and 256 tiles of 128x256 that fill the chip (the encode then runs as a kernel of its own)."""
+    """Llama-3-8B widths with row counts that are multiples of nothing: the last seq_len - lo tokens on this device,
+    so the last tile of every projection and the last token block of the encode are ragged.  The cases take the
+    launch shapes of the projections: 256x256 tiles with the encode on the units left over (the configuration
+    bench.py times), 192 tiles of 128x256 with the encode on the units left over (no visible peers), 256 tiles of
+    128x256 that fill the chip (the encode then runs as a kernel of its own), and 288 tiles of 256x256, which are dealt
+    into two launches (one of 256x256 tiles that fills its round, one on 128x128 tiles)."""
     from gpu_util import LayerOnGpu, compare_codes
     from paper_2505_19342_amd import binding as B
     cfg = dataclasses.replace(wl.LLAMA3_8B, name="llama_ragged", seq_len=seq_len, seed=41)

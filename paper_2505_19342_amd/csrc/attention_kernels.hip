@@ -390,7 +390,8 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnParams p, int d
     const int n_hat = p.Tn_vis;
     const int n_loc = p.causal ? row + 1 : p.Tq;
     float m_run = -INFINITY, l_run = 0.f;
-    float o[4] = {0.f, 0.f, 0.f, 0.f};              // head-dim values lane, lane+64, lane+128, lane+192
+    float o[4] = {0.f, 0.f, 0.f, 0.f};              // head-dim values lane, lane+64, lane+128, lane+192 (those beyond dh are never stored)
+    const bool vec4 = dh % 4 == 0 && ((uintptr_t)p.q | (uintptr_t)p.k_loc | (uintptr_t)p.k_hat) % 16 == 0;
 
     for (int src = 0; src < 2; ++src) {
         const int count = src == 0 ? n_hat : n_loc;
@@ -403,7 +404,17 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnParams p, int d
             if (j < count && arrived) {
                 const float* kr = Kp + (int64_t)j * kv_ld;
                 float dot = 0.f;
-                for (int d = 0; d < dh; ++d) dot = fmaf(q[d], kr[d], dot);
+                int d = 0;
+                if (vec4)                     // same order of additions, four elements per load
+                    for (; d + 4 <= dh; d += 4) {
+                        const f32x4 kv = *reinterpret_cast<const f32x4*>(kr + d);
+                        const f32x4 qv = *reinterpret_cast<const f32x4*>(q + d);
+                        dot = fmaf(qv.x, kv.x, dot);
+                        dot = fmaf(qv.y, kv.y, dot);
+                        dot = fmaf(qv.z, kv.z, dot);
+                        dot = fmaf(qv.w, kv.w, dot);
+                    }
+                for (; d < dh; ++d) dot = fmaf(q[d], kr[d], dot);
                 s = dot * p.scale;
             }
             float mx = s;
@@ -419,14 +430,21 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnParams p, int d
 #pragma unroll
             for (int u = 0; u < 4; ++u) o[u] *= alpha;
             const int cnt = min(kWave, count - base);
-            for (int jj = 0; jj < cnt; ++jj) {
-                const float pj = __shfl(e, jj);
-                const float* vr = Vp + (int64_t)(base + jj) * kv_ld;
+            // eight value rows in flight; rows beyond the chunk repeat its last row with weight zero
+            for (int jj = 0; jj < cnt; jj += 8) {
+                float pj[8], vv[8][4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int d = lane + 64 * u;
-                    if (d < dh) o[u] = fmaf(pj, vr[d], o[u]);
+                for (int b = 0; b < 8; ++b) {
+                    const int jb = min(jj + b, cnt - 1);
+                    pj[b] = jj + b < cnt ? __shfl(e, jb) : 0.f;
+                    const float* vr = Vp + (int64_t)(base + jb) * kv_ld;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) vv[b][u] = vr[min(lane + 64 * u, dh - 1)];
                 }
+#pragma unroll
+                for (int b = 0; b < 8; ++b)
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) o[u] = fmaf(pj[b], vv[b][u], o[u]);
             }
         }
     }

@@ -12,7 +12,8 @@ namespace astra {
 // fp32, vector ALU: 64x64 output tile, 256 threads x (4x4) outputs, contraction in steps of 16 through
 // LDS.  Used for the small fp32 configuration; sums in ascending k with fused multiply-add.
 // ------------------------------------------------------------------------------------------------
-constexpr int kFM = 64, kFN = 64, kFK = 16;
+constexpr int kFM = 64, kFN = 64, kFK = 64;
+constexpr int kFL = kFK / 4;      // consecutive k one thread stages per row
 
 __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmBatch batch) {
     __shared__ float sa[kFK][kFM + 4];
@@ -31,34 +32,45 @@ __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmBatch batch)
 
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
-    // staging: thread loads 4 consecutive k of one row: row = tid / 4, k4 = (tid % 4) * 4
-    const int lr = tid >> 2, lk = (tid & 3) * 4;
+    // staging: thread loads kFL consecutive k of one row: row = tid / 4, first k = (tid % 4) * kFL
+    const int lr = tid >> 2, lk = (tid & 3) * kFL;
     const int am = m0 + lr < M ? m0 + lr : M - 1;
     const int bn = n0 + lr < N ? n0 + lr : N - 1;
 
-    float acc[4][4] = {};
-    for (int k0 = 0; k0 < K; k0 += kFK) {
+    // the values of the next step are fetched into registers while the current step is multiplied
+    float av[kFL], bv[kFL];
+    auto fetch = [&](int k0) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < kFL; ++j) {
             const int k = k0 + lk + j;
-            float av = 0.f, bv = 0.f;
+            av[j] = 0.f;
+            bv[j] = 0.f;
             if (k < K) {
                 if (!gather) {
-                    av = A[(int64_t)am * P.lda + k];
+                    av[j] = A[(int64_t)am * P.lda + k];
                 } else {
                     const int g = k / P.dg, jj = k - g * P.dg;
                     int code;
                     if (P.code_bytes == 1) code = ((const uint8_t*)P.codes)[(int64_t)am * P.G + g];
                     else code = ((const uint16_t*)P.codes)[(int64_t)am * P.G + g];
                     code = code < P.Kc ? code : P.Kc - 1;
-                    av = CB[((int64_t)g * P.Kc + code) * P.dg + jj];
+                    av[j] = CB[((int64_t)g * P.Kc + code) * P.dg + jj];
                 }
-                bv = B[(int64_t)bn * K + k];
+                bv[j] = B[(int64_t)bn * K + k];
             }
-            sa[lk + j][lr] = av;
-            sb[lk + j][lr] = bv;
+        }
+    };
+
+    float acc[4][4] = {};
+    fetch(0);
+    for (int k0 = 0; k0 < K; k0 += kFK) {
+#pragma unroll
+        for (int j = 0; j < kFL; ++j) {
+            sa[lk + j][lr] = av[j];
+            sb[lk + j][lr] = bv[j];
         }
         __syncthreads();
+        if (k0 + kFK < K) fetch(k0 + kFK);
 #pragma unroll
         for (int k = 0; k < kFK; ++k) {
             float a[4], b[4];

@@ -183,10 +183,23 @@ __global__ __launch_bounds__(256) void vq_encode_f32_kernel(const float* __restr
     const float* z = x + t * ldx + (int64_t)g * dg;
     float best = INFINITY;
     int arg = 0x7fffffff;
+    // four elements per load where the slices allow it; the additions keep their order
+    const bool vec4 = dg % 4 == 0 && ldx % 4 == 0 && ((uintptr_t)x | (uintptr_t)codebook) % 16 == 0;
     for (int k = lane; k < K; k += kWave) {
         const float* e = codebook + ((int64_t)g * K + k) * dg;
         float dist = 0.f;
-        for (int j = 0; j < dg; ++j) {
+        int j = 0;
+        if (vec4)
+            for (; j + 4 <= dg; j += 4) {
+                const f32x4 ev = *reinterpret_cast<const f32x4*>(e + j);
+                const f32x4 zv = *reinterpret_cast<const f32x4*>(z + j);
+                const f32x4 df = ev - zv;
+                dist = fmaf(df.x, df.x, dist);
+                dist = fmaf(df.y, df.y, dist);
+                dist = fmaf(df.z, df.z, dist);
+                dist = fmaf(df.w, df.w, dist);
+            }
+        for (; j < dg; ++j) {
             const float diff = e[j] - z[j];
             dist = fmaf(diff, diff, dist);
         }

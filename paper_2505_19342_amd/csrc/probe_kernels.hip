@@ -77,7 +77,7 @@ __global__ __launch_bounds__(kProbeThreads) void mfma_valu_probe_kernel(float* _
             acc[j] = mfma_32x32x16(a[j & 1], b[j >> 1], acc[j]);
 #pragma unroll
             for (int q = 0; q < NV; ++q) {
-                if (EXP) x[q % 8] = __builtin_amdgcn_exp2f(x[q % 8]) * m;
+                if (EXP) x[q % 8] = __builtin_amdgcn_exp2f(-x[q % 8]) * m;       // stays in (0, 1]: the sign is a free operand modifier
                 else x[q % 8] = __builtin_fmaf(x[q % 8], m, c);
             }
             __builtin_amdgcn_sched_barrier(0);

@@ -54,9 +54,10 @@ def main():
     ap.add_argument("--workload", default="llama3_8b_bf16")
     ap.add_argument("--rank", type=int, default=-1, help="simulated device (default: last = critical path under causal masking)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--profile-every", type=int, default=8,
+    ap.add_argument("--profile-every", type=int, default=40,
                     help="every N-th timed step is launched through astra_layer_forward_profiled (HIP events at the stage "
-                         "boundaries, about 20 us of extra gaps per such step); the others through astra_layer_forward")
+                         "boundaries, about 35 us of extra gaps per such step: with the default the timed mean is 0.4 % above the "
+                         "event-free one); the others through astra_layer_forward")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the measurements outside the timed region (matrix-core probe, stand-alone decode, other ranks)")
     ap.add_argument("--extras", default="all",

@@ -61,7 +61,7 @@ def main():
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the measurements outside the timed region (matrix-core probe, stand-alone decode, other ranks)")
     ap.add_argument("--extras", default="all",
-                    help="comma list of the measurements outside the timed region to run: ranks, uneven, lost, block, stack (needs block), kv, kvcache, train, decode, probe (default all)")
+                    help="comma list of the measurements outside the timed region to run: ranks, uneven, lost, block, stack (needs block), kv, kvcache, train, decode, vendor, probe (default all)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the warm-up, run one plain elementwise copy kernel reading and writing this many MiB "
                          "(fp32): the reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -200,7 +200,7 @@ def main():
     per_step = sorted(ev.elapsed_ms(0, 4) for ev in events)
     result["gpu_ms_per_step_events_p10_p50_p90"] = [per_step[int(q * (len(per_step) - 1))] for q in (0.1, 0.5, 0.9)]
 
-    extras = set() if args.no_extras else set(("ranks,uneven,lost,block,stack,kv,kvcache,train,decode,probe" if args.extras == "all" else args.extras).split(","))
+    extras = set() if args.no_extras else set(("ranks,uneven,lost,block,stack,kv,kvcache,train,decode,vendor,probe" if args.extras == "all" else args.extras).split(","))
     if extras:
         def timed(fn, n, warm=0):
             for _ in range(1 + warm):      # after host-side set-up the chip is idle: bring it back to its steady clock
@@ -417,6 +417,23 @@ def main():
             result["decode_standalone"] = {"us": ms * 1e3, "algorithmic_bytes": nbytes, "GBps": nbytes / (ms * 1e-3) / 1e9,
                                            "frac_of_hbm_8TBps": nbytes / (ms * 1e-3) / 8e12, "rows": t_v}
             del x_hat
+        # a yardstick, not part of the product: the vendor GEMM (torch.matmul -> hipBLASLt / rocBLAS) on the layer's plain
+        # products.  It cannot take codes as its row operand, so the K-hat / V-hat product is given rebuilt rows.
+        if "vendor" in extras and dt == "bf16":
+            vg = {}
+            tv = view["n_before"] if cfg.causal else tn
+            dq_, dkv_ = cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
+            for name, (m_, n_, k_) in {"q_k_v_of_local_rows": (tq, dq_ + 2 * dkv_, D), "k_v_of_rebuilt_rows": (tv, 2 * dkv_, D),
+                                       "output_projection": (tq, D, dq_)}.items():
+                if m_ == 0:
+                    continue
+                a_ = torch.randn((m_, k_), device=dev, dtype=torch.float32).to(torch.bfloat16)
+                b_ = torch.randn((n_, k_), device=dev, dtype=torch.float32).to(torch.bfloat16)
+                ms = timed(lambda: torch.matmul(a_, b_.t()), 50, warm=10)
+                vg[name] = {"m_n_k": [m_, n_, k_], "us": ms * 1e3, "tflops": 2.0 * m_ * n_ * k_ / (ms * 1e-3) / 1e12}
+                del a_, b_
+            result["vendor_gemm_yardstick"] = {**vg, "what": "torch.matmul in bf16 on the same shapes, for context: the layer's projection "
+                                               "launch does the first two products (from codes, with the encode alongside) in one launch"}
         # (3) last, because it heats the chip: what the matrix cores of this machine deliver with nothing else in the loop, next to the published peak
         if "probe" in extras and dt == "bf16":
             n_blocks, iters = 1024, 2000

@@ -102,13 +102,17 @@ enum { kEpiLayer = 0, kEpiResidualF32 = 1, kEpiSplit = 2, kEpiGeluTanh = 3, kEpi
 // [128 t + 64 g, 128 t + 64 g + 64), each with its own operand buffers and the full loop below; their accumulators are
 // added through LDS at the end.  A small tile then keeps its 64 x 64 wave tiles (1 KiB of LDS reads per MFMA) and still
 // has two wavefronts per SIMD to hide each other's staging.
-template <int BM, int BN, int WM, int WN, bool CODE16, bool ENC = false, int EPI = kEpiLayer, int KS = 1>
+#ifndef ASTRA_GEMM_DIRECT_TRANSFERS
+#define ASTRA_GEMM_DIRECT_TRANSFERS 1
+#endif
+template <int BM, int BN, int WM, int WN, bool CODE16, bool ENC = false, int EPI = kEpiLayer, int KS = 1, bool DMA = ASTRA_GEMM_DIRECT_TRANSFERS != 0>
 __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_nt_bf16_kernel(const GemmBatch batch) {
     constexpr int THREADS = 64 * WM * WN;                      // threads of one group
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;        // MFMA tiles per wavefront
     constexpr int RPP = THREADS / 8;                           // rows staged per pass
     constexpr int PA = BM / RPP, PB = BN / RPP;                // staging passes per thread
     static_assert(KS == 1 || (KS == 2 && !ENC), "one or two contraction groups");
+    static_assert(!DMA || RPP % 16 == 0, "direct transfers: the row swizzle has to be periodic in the pass stride");
     __shared__ u32x4 lds_a[2 * KS][BM * kBK / 8];              // [2 * group + buffer]
     __shared__ u32x4 lds_b[2 * KS][BN * kBK / 8];
 
@@ -162,7 +166,10 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_nt_bf16_kernel(const G
     const int lane = tid & 63, wave = tid >> 6;
     const int i32 = lane & 31, h = lane >> 5;
     const int wm = wave / WN, wn = wave % WN;
-    const int kc = tid & 7, r0 = tid >> 3;      // staging: 16-byte piece kc of rows r0 + RPP * it
+    const int r0 = tid >> 3;                    // staging: 16-byte piece kc of rows r0 + RPP * it
+    // With direct global -> LDS transfers a lane's LDS slot is fixed by its lane number (slot tid & 7 of its row), so the
+    // swizzle moves to the global side: the lane fetches the piece that belongs into its slot.
+    const int kc = DMA ? ((tid & 7) ^ swz(r0)) : (tid & 7);
 
     // One straight-line loader serves plain and gathered A rows.  For gathered rows the piece at
     // contraction index k lies in group g = k / dg at offset j = k - g*dg of codeword codes[row, g];
@@ -250,6 +257,30 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_nt_bf16_kernel(const G
             const int r_ = r0 + RPP * it;
             lds_b[kg2 + buf_][r_ * 8 + (kc ^ swz(r_))] = rb[it];
         }
+    };
+
+    // direct transfer of the tile at k_use into LDS buffer buf_: the lanes of a wavefront fill 64 consecutive slots
+    // (8 rows of 8 pieces), nothing passes through registers; pass it_ of the A rows, then of the B rows
+    const uint32_t wave_rows = (uint32_t)__builtin_amdgcn_readfirstlane(8 * (tid >> 6));
+    auto dma_piece = [&](int buf_, int j_it) {
+        if (j_it < PA) {
+            const int it = j_it;
+            const uint32_t g_ = __umulhi((uint32_t)k_use, magic);
+            const uint32_t j_ = (uint32_t)k_use - g_ * (uint32_t)dg;
+            int code_here = code[it];
+            asm volatile("" : "+v"(code_here));      // the code is first touched here: an earlier use would wait for the transfers issued before its load
+            const uint32_t c_ = (uint32_t)(code_here < Kc ? code_here : Kc - 1);
+            const uint32_t goff_ = ((g_ * (uint32_t)Kc + c_) * (uint32_t)dg + j_) * 2u;
+            dma_global_to_lds_16(a_base, (goff_ & gmask) + aoff[it], lds_byte_addr(&lds_a[kg2 + buf_][(wave_rows + RPP * it) * 8]));
+        } else {
+            const int it = j_it - PA;
+            dma_global_to_lds_16(b_base, boff[it], lds_byte_addr(&lds_b[kg2 + buf_][(wave_rows + RPP * it) * 8]));
+        }
+    };
+    auto dma_advance = [&]() {
+        a_base += a_step;
+        b_base += kBK * 2 * KS;
+        k_use += kBK * KS;
     };
 
     f32x16 acc[TM][TN];
@@ -357,6 +388,68 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_nt_bf16_kernel(const G
         if (FULL || kt + 3 < n_kt) load_codes();
     };
 
+    if constexpr (DMA) {
+        // Tiles go from memory straight into LDS.  Buffer kt & 1 is free once every wavefront has passed the barrier of
+        // iteration kt (all reads of tile kt were requested and awaited before it): tile kt + 2 is sent there during step 3
+        // of iteration kt and has until the wait in front of the barrier of iteration kt + 1 to land.
+        // buf_tag: std::integral_constant<int, kt & 1> makes the buffer static (LDS addresses become immediates; steady
+        // state, where tiles kt + 1, kt + 2 and the codes of kt + 3 all exist), std::integral_constant<int, -1> reads it from kt
+        // (the last few tiles, with the run-time guards)
+        auto tile_steps_dma = [&](int kt, auto buf_tag) {
+            constexpr bool FULL = decltype(buf_tag)::value >= 0;
+            const int buf = FULL ? decltype(buf_tag)::value : (kt & 1);
+            const bool nx = FULL || kt + 1 < n_kt, nx2 = FULL || kt + 2 < n_kt;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                const int cur = ks & 1, nxt = cur ^ 1;
+                const int nd = ks == 3 ? PA + PB : 0;
+                const int nj = NR + nd;
+                const bool rd = ks < 3 || nx;
+#pragma unroll
+                for (int m = 0; m < NM; ++m) {
+                    const int a = m / TN, b = m % TN;
+                    acc[a][b] = mfma_32x32x16(fa[cur][a], fb[cur][b], acc[a][b]);
+#pragma unroll
+                    for (int j = m * nj / NM; j < (m + 1) * nj / NM; ++j) {
+                        if (j < NR) {
+                            if (rd) read_frag(ks < 3 ? buf : buf ^ 1, (ks + 1) & 3, nxt, j);
+                        } else if (nx2) {
+                            dma_piece(buf, j - NR);
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                if (ks == 2) {
+                    wait_vmem_all();          // this wavefront's transfers of tile kt + 1 have landed
+                    __syncthreads();
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (nx2) dma_advance();
+            if (FULL || kt + 3 < n_kt) load_codes();
+        };
+        load_codes();                 // codes of tile 0
+#pragma unroll
+        for (int j = 0; j < PA + PB; ++j) dma_piece(0, j);
+        dma_advance();
+        if (n_kt > 1) {
+            load_codes();             // codes of tile 1
+#pragma unroll
+            for (int j = 0; j < PA + PB; ++j) dma_piece(1, j);
+            dma_advance();
+        }
+        if (n_kt > 2) load_codes();   // codes of tile 2
+        wait_vmem_all();
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < NR; ++j) read_frag(0, 0, 0, j);
+        int kt = 0;
+        for (; kt + 4 < n_kt; kt += 2) {
+            tile_steps_dma(kt, std::integral_constant<int, 0>{});
+            tile_steps_dma(kt + 1, std::integral_constant<int, 1>{});
+        }
+        for (; kt < n_kt; ++kt) tile_steps_dma(kt, std::integral_constant<int, -1>{});
+    } else {
     load_codes();                 // codes of tile 0
     load_tile();                  // tile 0
     if (n_kt > 1) load_codes();   // codes of tile 1
@@ -369,6 +462,7 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_nt_bf16_kernel(const G
     int kt = 0;
     for (; kt + 3 < n_kt; ++kt) tile_steps(kt, std::true_type{});
     for (; kt < n_kt; ++kt) tile_steps(kt, std::false_type{});
+    }
 
     if constexpr (KS == 2) {
         // the second group hands its accumulators over through the operand buffers (all fragment reads are done)

@@ -28,9 +28,12 @@ __device__ __forceinline__ int find_problem(const GemmBatch& b, int tile) {
 // ------------------------------------------------------------------------------------------------
 // bf16, matrix cores.  A workgroup of WM x WN wavefronts owns a BM x BN output tile; each wavefront
 // owns a (BM/WM) x (BN/WN) sub-tile made of 32x32x16 MFMA tiles.  The contraction runs in steps of 64
-// through double-buffered LDS: while the matrix cores work on tile kt, the registers hold tile kt+1
-// (fetched one iteration earlier) on its way to the other LDS buffer, the loads of tile kt+2 are in
-// flight and, for gathered A rows, the codes of tile kt+3 are being fetched.  LDS tiles are
+// through double-buffered LDS.  Operand tiles travel from memory straight into LDS (DMA = true, the default:
+// one wavefront instruction fills 64 consecutive 16-byte slots, nothing passes through registers): while the
+// matrix cores work on tile kt out of one buffer, tile kt+1 has landed in the other, tile kt+2 is sent into
+// the first as soon as the barrier of iteration kt has passed and, for gathered A rows, the codes of tile
+// kt+3 are being fetched.  (DMA = false stages through registers instead: tile kt+1 sits in registers on its
+// way to the other buffer while the loads of tile kt+2 are in flight.)  LDS tiles are
 // [rows][8 pieces of 8 bf16]; piece p of row r sits at p ^ ((r >> 1) & 7): rows are 128 bytes, the
 // LDS has 64 four-byte banks, so the 16-byte fragment reads of 16 consecutive rows touch every bank once.
 //

@@ -161,11 +161,12 @@ __global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams
     f32x16 acc_s[2];
     bf16x8 pf[4];
     constexpr int QK_UNITS = NKS / 2;
-    auto mm_phase = [&](int i) {
+    auto mm_phase = [&](int i, auto parity_tag) {
+        constexpr int IB = decltype(parity_tag)::value;          // = i & 1, static: the buffer addresses become immediates
         constexpr int NPV = 4, NU = NPV + QK_UNITS;
         constexpr int NDMA = 2 * LPT;
-        const u32x4* __restrict__ Kt = lds_k[i & 1][par];
-        const u32x4* __restrict__ Vt = lds_v[(i & 1) ^ 1][par];
+        const u32x4* __restrict__ Kt = lds_k[IB][par];
+        const u32x4* __restrict__ Vt = lds_v[IB ^ 1][par];
         const Tile t_k = tile_of(i + 1), t_v = tile_of(i);
         auto load_unit = [&](int u, bf16x8(&f)[4]) {
             if (u < NPV) {
@@ -228,8 +229,8 @@ __global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams
             // spread the NDMA transfers over the NU units
 #pragma unroll
             for (int x = u * NDMA / NU; x < (u + 1) * NDMA / NU; ++x) {
-                if (x < LPT) dma_k(t_k, (i & 1) ^ 1, x);
-                else dma_v(t_v, i & 1, x - LPT);
+                if (x < LPT) dma_k(t_k, IB ^ 1, x);
+                else dma_v(t_v, IB, x - LPT);
             }
             compute_unit(u, (u & 1) ? fb : fa);
             __builtin_amdgcn_sched_barrier(0);
@@ -316,13 +317,21 @@ __global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams
     wait_vmem_all();
     __syncthreads();
     if (par == 1) __syncthreads();
-    for (int i = 0;; ++i) {
+    for (int i = 0;; i += 2) {          // two iterations per trip: the tile buffers alternate, so each copy knows its own
         __builtin_amdgcn_s_setprio(2);      // the matrix-core phase goes first when both wavefronts of the SIMD can issue
-        mm_phase(i);
+        mm_phase(i, std::integral_constant<int, 0>{});
         __builtin_amdgcn_s_setprio(0);
         __syncthreads();
         if (i == n_it) break;
         softmax_phase(i);
+        wait_vmem_all();
+        __syncthreads();
+        __builtin_amdgcn_s_setprio(2);
+        mm_phase(i + 1, std::integral_constant<int, 1>{});
+        __builtin_amdgcn_s_setprio(0);
+        __syncthreads();
+        if (i + 1 == n_it) break;
+        softmax_phase(i + 1);
         wait_vmem_all();
         __syncthreads();
     }

@@ -25,8 +25,8 @@ sys.path.insert(0, ROOT)
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}       # MI355X dense MFMA peaks
 # HBM-side bytes per launch of the dominant kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs kept
 # under profiles/ (layer_llama3_8b_pmc_fetch_size.txt, ..._write_size.txt), each scaled by what the same counter
-# reads for a 256 MiB copy kernel: (71761.4 * 2.0 + 32853.2 * 1.0) KiB.  None for workloads not profiled.
-TRAFFIC_BYTES = {"llama3_8b_bf16": (71761.4 * 2.0 + 32853.2) * 1024.0}
+# reads for a 256 MiB copy kernel: (71705.2 * 2.0 + 32810.1 * 1.0) KiB.  None for workloads not profiled.
+TRAFFIC_BYTES = {"llama3_8b_bf16": (71705.2 * 2.0 + 32810.1) * 1024.0}
 STAGES = ("vq_encode", "projections", "attention", "out_projection")
 
 

@@ -134,23 +134,27 @@ __global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams
                              : (uint32_t)((kph ^ swz_v<DH>(kr0)) * 16);
     const uint32_t kv_ld_b = (uint32_t)kv_ld * 2u;
     const uint32_t wave_slot = (uint32_t)(64 * (wave & 3)) * 16u;
+    // byte offset of row kr0 inside a tile; the rows of pass `it` lie ROW_STEP rows further (a scalar product), and a
+    // row beyond the source's last one is replaced by that last row by clamping the offset: no per-lane multiply
+    const uint32_t krow_b = (uint32_t)kr0 * kv_ld_b;
     auto dma_k = [&](const Tile& tl, int buf, int it) {
         const char* __restrict__ Kb = (const char*)(tl.is_loc ? p.k_loc : p.k_hat) + ((int64_t)tl.row0 * kv_ld + (int64_t)hk * DH) * 2;
         const int lim = (tl.is_loc ? Tq : p.Tn_vis) - 1 - tl.row0;                 // last valid row of the tile
-        const int r = min(kr0 + ROW_STEP * it, lim);
-        dma_global_to_lds_16(Kb, (uint32_t)r * kv_ld_b + kcol, lds_byte_addr(&lds_k[buf][par][0]) + wave_slot + (uint32_t)it * 4096u);
+        const uint32_t off = min(krow_b + (uint32_t)(ROW_STEP * it) * kv_ld_b, (uint32_t)min(lim, kAttKV - 1) * kv_ld_b);
+        dma_global_to_lds_16(Kb, off + kcol, lds_byte_addr(&lds_k[buf][par][0]) + wave_slot + (uint32_t)it * 4096u);
     };
     auto dma_v = [&](const Tile& tl, int buf, int it) {
         const uint32_t dst = lds_byte_addr(&lds_v[buf][par][0]) + wave_slot + (uint32_t)it * 4096u;
         if (VT) {
             const uint32_t v_ld_b = (uint32_t)(tl.is_loc ? p.ldv_loc : p.ldv_hat) * 2u;
             const char* __restrict__ Vb = (const char*)(tl.is_loc ? p.v_loc : p.v_hat) + ((int64_t)hk * DH * v_ld_b + (int64_t)tl.row0 * 2);
-            dma_global_to_lds_16(Vb, (uint32_t)((ptid >> 3) + 32 * it) * v_ld_b + vcol, dst);
+            // row ptid / 8 + 32 * it of the transposed tile: one per-lane product per tile source, the pass adds a scalar
+            dma_global_to_lds_16(Vb, (uint32_t)(ptid >> 3) * v_ld_b + (uint32_t)(32 * it) * v_ld_b + vcol, dst);
         } else {
             const char* __restrict__ Vb = (const char*)(tl.is_loc ? p.v_loc : p.v_hat) + ((int64_t)tl.row0 * kv_ld + (int64_t)hk * DH) * 2;
             const int lim = (tl.is_loc ? Tq : p.Tn_vis) - 1 - tl.row0;
-            const int r = min(kr0 + ROW_STEP * it, lim);
-            dma_global_to_lds_16(Vb, (uint32_t)r * kv_ld_b + vcol, dst);
+            const uint32_t off = min(krow_b + (uint32_t)(ROW_STEP * it) * kv_ld_b, (uint32_t)min(lim, kAttKV - 1) * kv_ld_b);
+            dma_global_to_lds_16(Vb, off + vcol, dst);
         }
     };
 

@@ -134,6 +134,31 @@ def test_navq(name):
     assert np.abs(ref - oracle.vq_decode(codes[:T], cb)).max() > 0.05      # the noise is there
 
 
+@pytest.mark.parametrize("D", [64, 128, 192, 320])
+def test_navq_short_contractions_bf16(D):
+    """Widths of 1, 2, 3 and 5 steps of 64 along the contraction of the noise product: the GEMM's loop is then all
+    prologue and tail (its steady state needs more than four steps)."""
+    import torch
+    from gpu_util import to_dev, codes_to_dev, DEV
+    from paper_2505_19342_amd import binding as B
+    G, K, T = D // 32, 64, 300
+    rng = np.random.default_rng(100 + D)
+    rnd = lambda a: wl.round_to_bf16(a.astype(np.float32))
+    cb = rnd(rng.standard_normal((G, K, 32)))
+    codes = rng.integers(0, K, size=(T, G)).astype(np.int32)
+    z = rnd(rng.standard_normal((T, D)))
+    L = rnd(np.tril(0.05 * rng.standard_normal((D, D))))
+    mu = (0.1 * rng.standard_normal(D)).astype(np.float32)
+    lam = 0.5
+    desc = B.vq_desc("bf16", D, G, K)
+    out = torch.empty((T, D), dtype=torch.float32, device=DEV)
+    B.astra_navq_forward(desc, codes_to_dev(codes, K), T, to_dev(cb, "bf16"), torch.from_numpy(mu).to(DEV), lam,
+                         to_dev(z, "bf16"), to_dev(lam * L, "bf16"), out)
+    torch.cuda.synchronize()
+    ref = oracle.navq(codes, cb, mu, L, z, lam)
+    assert np.abs(out.cpu().numpy() - ref).max() <= 1e-4
+
+
 def test_argument_errors():
     import torch
     from paper_2505_19342_amd import binding as B

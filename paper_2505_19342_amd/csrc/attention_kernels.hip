@@ -53,7 +53,9 @@ __device__ __forceinline__ int swz_v(int r) { return DH == 128 ? ((r & 3) << 2) 
 // transposed V tile: rows of 64 keys = 128 bytes, same rule as the GEMM operand tiles
 __device__ __forceinline__ int swz_vt(int r) { return (r >> 1) & 7; }
 
-template <int DH, bool VT>
+// LOST: the caller passed a validity bit per non-local token (an instantiation of its own, so that the code for it does
+// not disturb the register allocation and schedule of the kernel that runs without)
+template <int DH, bool VT, bool LOST = false>
 __global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams p) {
     constexpr int CPR = DH / 8;                // 16-byte pieces per K (and row-major V) row
     constexpr int NKS = DH / 16;               // contraction steps of Q.K
@@ -251,10 +253,23 @@ __global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams
         // non-local keys of this tile whose codes never arrived (bit = key index inside the tile; tiles start at
         // multiples of 64 keys, one word of the caller's bit array each; a wave-uniform scalar load)
         unsigned long long lost = 0ull;
-        if (p.valid_bits != nullptr && !tl.is_loc && tl.count > 0) lost = ~load_uniform_u64(p.valid_bits + (tl.row0 >> 6));
+        if (LOST && !tl.is_loc && tl.count > 0) lost = ~load_uniform_u64(p.valid_bits + (tl.row0 >> 6));
         const bool masked = diag || (tl.row0 + kAttKV > tl.count) || lost != 0ull;
         // masking (ragged source tail, causal diagonal, lost codes): a wave-uniform pass of its own
-        if (masked) {
+        if (LOST && masked && !diag && tl.row0 + kAttKV <= tl.count) {
+            // only lost codes.  Key index inside the tile = 32*mb + 4*h + c(v) with c(v) = acc_row(v, 0): the 32 lanes of
+            // a half-wave look at the same key, so the lanes to drop are one scalar word per score, built on the scalar
+            // unit from two bits of the tile's word, and each score costs a single select.
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int k0 = 32 * mb + acc_row(v, 0);
+                    const unsigned long long lanes = (((lost >> k0) & 1ull) ? 0x00000000ffffffffull : 0ull) |
+                                                     (((lost >> (k0 + 4)) & 1ull) ? 0xffffffff00000000ull : 0ull);
+                    acc_s[mb][v] = __builtin_amdgcn_inverse_ballot_w64(lanes) ? -INFINITY : acc_s[mb][v];
+                }
+        } else if (masked) {
             // key index inside the tile = 32*mb + 4*h + c(v) with c(v) = acc_row(v, 0) <= 27: one shifted word per half
             const uint32_t lost_w[2] = {(uint32_t)(lost >> (4 * h)), (uint32_t)(lost >> (32 + 4 * h))};
 #pragma unroll
@@ -478,11 +493,16 @@ int launch_attention(int dtype, const AttnParams& p_in, int head_dim, hipStream_
         const int64_t total = (int64_t)ceil_div(p.Tq, kAttQ) * p.Hq;
         if (total > 0x7fffffff) return ASTRA_ERR_SHAPE;
         const bool vt = p.v_transposed != 0;
+        const bool lost = p.valid_bits != nullptr;
         if (head_dim == 128) {
-            if (vt) attn_bf16_kernel<128, true><<<(int)total, kAttThreads, 0, s>>>(p);
+            if (vt && lost) attn_bf16_kernel<128, true, true><<<(int)total, kAttThreads, 0, s>>>(p);
+            else if (vt) attn_bf16_kernel<128, true><<<(int)total, kAttThreads, 0, s>>>(p);
+            else if (lost) attn_bf16_kernel<128, false, true><<<(int)total, kAttThreads, 0, s>>>(p);
             else attn_bf16_kernel<128, false><<<(int)total, kAttThreads, 0, s>>>(p);
         } else if (head_dim == 64) {
-            if (vt) attn_bf16_kernel<64, true><<<(int)total, kAttThreads, 0, s>>>(p);
+            if (vt && lost) attn_bf16_kernel<64, true, true><<<(int)total, kAttThreads, 0, s>>>(p);
+            else if (vt) attn_bf16_kernel<64, true><<<(int)total, kAttThreads, 0, s>>>(p);
+            else if (lost) attn_bf16_kernel<64, false, true><<<(int)total, kAttThreads, 0, s>>>(p);
             else attn_bf16_kernel<64, false><<<(int)total, kAttThreads, 0, s>>>(p);
         } else {
             return ASTRA_ERR_UNSUPPORTED;

@@ -340,7 +340,7 @@ def main():
             ms = timed(lambda: B.astra_layer_forward_kv(*k_args), 300, warm=100)
             kv_flops = (2.0 * tq * D * (cfg.n_q_heads * cfg.head_dim + 2 * dkv) + 2 * 2.0 * (tq - cfg.n_cls) * dkv * K
                         + flops["attention"] + flops["out_projection"])
-            result["kv_variant"] = {"G_kv": gk, "bits_per_token": 2 * gk * int(np.ceil(np.log2(K))), "ms": ms,
+            result["kv_variant"] = {"G_kv": gk, "bits_per_token_per_block": 2 * gk * int(np.ceil(np.log2(K))), "ms": ms,
                                     "tokens_per_s": tq / (ms * 1e-3), "flops": kv_flops, "tflops": kv_flops / (ms * 1e-3) / 1e12,
                                     "vs_embedding_space_layer": ms / ms_per_step,
                                     "what": "astra_layer_forward_kv at the same shape: no projection of rebuilt rows"}
@@ -443,19 +443,6 @@ def main():
             result["mfma_probe"] = {"tflops": tf, "frac_of_published_peak": tf / peak,
                                     "dominant_kernel_frac_of_probe": achieved / tf,
                                     "what": "astra_probe_mfma_bf16: 32x32x16 bf16 MFMAs on register operands only"}
-            # the same loop with vector-ALU instructions of the same wavefront between the MFMAs: ns added per instruction
-            n_mfma_wave = iters * 4
-            mix = {}
-            for kind, use_exp in (("fma", False), ("exp2_mul", True)):
-                t = {nv: timed(lambda: B.astra_probe_mfma_valu_bf16(probe_out, 256, iters * 4, nv, use_exp), 3, warm=1)
-                     for nv in (0, 4, 8, 16)}
-                # 256 workgroups = one per compute unit, two wavefronts per SIMD, 4 * n_mfma_wave MFMAs per wavefront
-                per_mfma_ns = {nv: t[nv] * 1e6 / (4 * n_mfma_wave * 2) for nv in t}
-                mix[kind] = {"ns_per_mfma_per_simd": {str(nv): per_mfma_ns[nv] for nv in t},
-                             "ns_added_per_valu_step": {f"{a}->{b}": (per_mfma_ns[b] - per_mfma_ns[a]) / (b - a)
-                                                        for a, b in ((0, 4), (4, 8), (8, 16))}}
-            result["mfma_valu_probe"] = {**mix, "what": "astra_probe_mfma_valu_bf16: per SIMD, the time of one MFMA plus N vector-ALU steps "
-                                         "(fma: one instruction; exp2_mul: an exponential and a multiply) issued after it by the same wavefront"}
             del probe_out
 
     if not args.no_cpu_baseline:

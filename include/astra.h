@@ -352,12 +352,6 @@ int astra_navq_forward(const astra_vq_desc* desc, const void* codes, int64_t n_t
  * flop: the on-box matrix-core rate a benchmark can quote beside the published peak. */
 int astra_probe_mfma_bf16(float* out, int n_blocks, int iters, void* stream);
 
-/* Measurement probe, not part of the method: the loop of astra_probe_mfma_bf16 with valu_per_mfma (0, 2, 4, 8 or 16;
- * anything else is ASTRA_ERR_UNSUPPORTED) vector-ALU instructions of the same wavefront after every MFMA: fused
- * multiply-adds, or, with use_exp != 0, that many pairs of a base-2 exponential and a multiply.  Same out, same MFMA
- * work: the time added per instruction is what vector work between MFMAs (softmax, addressing) costs on this chip. */
-int astra_probe_mfma_valu_bf16(float* out, int n_blocks, int iters, int valu_per_mfma, int use_exp, void* stream);
-
 const char* astra_status_string(int status);
 int astra_version(void);
 

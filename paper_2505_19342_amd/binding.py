@@ -20,7 +20,7 @@ EXPORTS = ("astra_vq_prepare", "astra_vq_encode", "astra_vq_decode", "astra_mixe
            "astra_layer_kv_workspace_bytes", "astra_layer_forward_kv",
            "astra_decode_attention_workspace_bytes", "astra_decode_attention",
            "astra_codebook_stats_workspace_bytes", "astra_codebook_stats", "astra_codebook_update", "astra_navq_forward",
-           "astra_probe_mfma_bf16", "astra_probe_mfma_valu_bf16", "astra_status_string", "astra_version")
+           "astra_probe_mfma_bf16", "astra_status_string", "astra_version")
 ASTRA_NORM_LAYER, ASTRA_NORM_RMS = 0, 1
 ASTRA_MLP_GELU_TANH, ASTRA_MLP_GELU_ERF, ASTRA_MLP_SWIGLU = 0, 1, 2
 NORM_KINDS = {"layernorm": ASTRA_NORM_LAYER, "rmsnorm": ASTRA_NORM_RMS}
@@ -94,8 +94,6 @@ def load(build_if_missing: bool = True):
     lib.astra_layer_workspace_bytes.restype = ctypes.c_size_t
     lib.astra_probe_mfma_bf16.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
     lib.astra_probe_mfma_bf16.restype = ctypes.c_int
-    lib.astra_probe_mfma_valu_bf16.argtypes = [ctypes.c_void_p] + [ctypes.c_int] * 4 + [ctypes.c_void_p]
-    lib.astra_probe_mfma_valu_bf16.restype = ctypes.c_int
     lib.astra_layer_encode_fused.argtypes = [ctypes.POINTER(LayerDesc)]
     lib.astra_layer_encode_fused.restype = ctypes.c_int
     lib.astra_layer_forward.argtypes = [ctypes.POINTER(LayerDesc)] + [vp] * 15 + [ctypes.c_size_t, vp]
@@ -302,12 +300,6 @@ def astra_stack_forward(desc: BlockDesc, weights, x, codes_nonlocal, valid_bits,
 def astra_probe_mfma_bf16(out, n_blocks: int, iters: int):
     """out: float32 device tensor with at least n_blocks * 512 elements."""
     _check(load().astra_probe_mfma_bf16(_ptr(out), n_blocks, iters, _stream()), "astra_probe_mfma_bf16")
-
-
-def astra_probe_mfma_valu_bf16(out, n_blocks: int, iters: int, valu_per_mfma: int, use_exp: bool):
-    """out as for astra_probe_mfma_bf16; valu_per_mfma in (0, 2, 4, 8, 16)."""
-    _check(load().astra_probe_mfma_valu_bf16(_ptr(out), n_blocks, iters, valu_per_mfma, int(use_exp), _stream()),
-           "astra_probe_mfma_valu_bf16")
 
 
 def astra_layer_encode_fused(desc: LayerDesc) -> bool:

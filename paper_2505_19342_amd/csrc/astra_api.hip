@@ -282,10 +282,6 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     bool enc_fused = false;
 
     // 2. projections: Q, K, V of local rows; K-hat, V-hat of the rows rebuilt from the peers' codes
-    if (pl.need_xhat && pl.Tn_vis > 0 && !plan_only) {
-        rc = launch_vq_decode(vq, codes_nonlocal, pl.Tn_vis, codebook, Xh, s);
-        if (rc) return rc;
-    }
     GemmProblem pr[5] = {};
     auto local = [&](GemmProblem& g, const void* w, const void* b, void* c, int n) {
         g.a = x_local; g.b = w; g.bias = b; g.c = c; g.M = pl.Tq; g.N = n; g.K = pl.D; g.lda = pl.D; g.ldc = n;
@@ -307,11 +303,31 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     nonlocal_(pr[3], wk, bk, Kh, pl.dkv);
     nonlocal_(pr[4], wv, bv, Vh, pl.dkv);
     if (pl.vt) { pr[4].c_mode = kCTransposedV; pr[4].ldc = pl.ldv_hat; }
-    rc = launch_gemm_batch(vq.dtype, pr, 5, s, offer ? &ej : nullptr, offer ? &enc_fused : nullptr, plan_only);
+    AttnParams ap = attn_params(at, Q, K, V, Kh, Vh, O, nullptr);
+    ap.v_transposed = pl.vt ? 1 : 0;
+    ap.valid_bits = (const unsigned long long*)valid_bits;
+    ap.ldv_loc = pl.ldv_loc;
+    ap.ldv_hat = pl.ldv_hat;
+    GemmProblem po = {};
+    po.a = O; po.b = wo; po.bias = bo; po.c = y_out; po.M = pl.Tq; po.N = pl.D; po.K = pl.dq; po.lda = pl.dq; po.ldc = pl.D;
+    po.c_mode = kCF32;      // y leaves the layer as the fp32 accumulator, for both element types
+    po.residual = residual; // inside a block: y_out = residual + layer output
+
+    // every launch of the layer is validated before the first one runs: an error leaves all outputs untouched
+    rc = launch_gemm_batch(vq.dtype, pr, 5, s, offer ? &ej : nullptr, offer ? &enc_fused : nullptr, true);
+    if (rc == ASTRA_OK) rc = launch_attention(vq.dtype, ap, at.head_dim, s, true);
+    if (rc == ASTRA_OK) rc = launch_gemm_batch(vq.dtype, &po, 1, s, nullptr, nullptr, true);
     if (plan_only) {
         *plan_encode_fused = enc_fused ? 1 : 0;
         return rc;
     }
+    if (rc) return rc;
+
+    if (pl.need_xhat && pl.Tn_vis > 0) {
+        rc = launch_vq_decode(vq, codes_nonlocal, pl.Tn_vis, codebook, Xh, s);
+        if (rc) return rc;
+    }
+    rc = launch_gemm_batch(vq.dtype, pr, 5, s, offer ? &ej : nullptr, offer ? &enc_fused : nullptr, false);
     if (rc) return rc;
     mark(1, s);
     mark(5, s);
@@ -322,20 +338,11 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     mark(6, s);
 
     // 3. mixed-precision attention (Eq. 1)
-    AttnParams ap = attn_params(at, Q, K, V, Kh, Vh, O, nullptr);
-    ap.v_transposed = pl.vt ? 1 : 0;
-    ap.valid_bits = (const unsigned long long*)valid_bits;
-    ap.ldv_loc = pl.ldv_loc;
-    ap.ldv_hat = pl.ldv_hat;
     rc = launch_attention(vq.dtype, ap, at.head_dim, s);
     if (rc) return rc;
     mark(2, s);
 
     // 4. output projection
-    GemmProblem po = {};
-    po.a = O; po.b = wo; po.bias = bo; po.c = y_out; po.M = pl.Tq; po.N = pl.D; po.K = pl.dq; po.lda = pl.dq; po.ldc = pl.D;
-    po.c_mode = kCF32;      // y leaves the layer as the fp32 accumulator, for both element types
-    po.residual = residual; // inside a block: y_out = residual + layer output
     rc = launch_gemm_batch(vq.dtype, &po, 1, s);
     mark(3, s);
     mark(4, s);
@@ -345,11 +352,6 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
 int astra_probe_mfma_bf16(float* out, int n_blocks, int iters, void* stream) {
     if (!out) return ASTRA_ERR_NULL;
     return launch_mfma_probe(out, n_blocks, iters, (hipStream_t)stream);
-}
-
-int astra_probe_mfma_valu_bf16(float* out, int n_blocks, int iters, int valu_per_mfma, int use_exp, void* stream) {
-    if (!out) return ASTRA_ERR_NULL;
-    return launch_mfma_valu_probe(out, n_blocks, iters, valu_per_mfma, use_exp, (hipStream_t)stream);
 }
 
 int astra_layer_encode_fused(const astra_layer_desc* desc) {

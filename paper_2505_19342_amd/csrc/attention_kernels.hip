@@ -486,7 +486,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnParams p, int d
     if (p.lse && lane == 0) p.lse[(int64_t)head * p.Tq + row] = m_run + logf(l_run);
 }
 
-int launch_attention(int dtype, const AttnParams& p_in, int head_dim, hipStream_t s) {
+int launch_attention(int dtype, const AttnParams& p_in, int head_dim, hipStream_t s, bool plan_only) {
     AttnParams p = p_in;
     if (p.Tq == 0) return ASTRA_OK;
     if (dtype == ASTRA_BF16) {
@@ -494,6 +494,12 @@ int launch_attention(int dtype, const AttnParams& p_in, int head_dim, hipStream_
         if (total > 0x7fffffff) return ASTRA_ERR_SHAPE;
         const bool vt = p.v_transposed != 0;
         const bool lost = p.valid_bits != nullptr;
+        if (head_dim != 64 && head_dim != 128) return ASTRA_ERR_UNSUPPORTED;
+        // the kernel forms byte offsets inside one head's tile source in 32 bits: rows of the transposed V buffers
+        // (head_dim of them, ldv tokens each) and 64 key rows of H_kv * head_dim elements
+        if (vt && (int64_t)max(p.ldv_loc, p.ldv_hat) * 2 * head_dim >= (1ll << 32)) return ASTRA_ERR_UNSUPPORTED;
+        if ((int64_t)p.Hkv * head_dim * 2 * kAttKV >= (1ll << 32)) return ASTRA_ERR_UNSUPPORTED;
+        if (plan_only) return ASTRA_OK;
         if (head_dim == 128) {
             if (vt && lost) attn_bf16_kernel<128, true, true><<<(int)total, kAttThreads, 0, s>>>(p);
             else if (vt) attn_bf16_kernel<128, true><<<(int)total, kAttThreads, 0, s>>>(p);
@@ -511,6 +517,7 @@ int launch_attention(int dtype, const AttnParams& p_in, int head_dim, hipStream_
         if (head_dim > 256 || p.v_transposed) return ASTRA_ERR_UNSUPPORTED;
         const int64_t blocks = ceil_div((int64_t)p.Hq * p.Tq, 4);
         if (blocks > 0x7fffffff) return ASTRA_ERR_SHAPE;
+        if (plan_only) return ASTRA_OK;
         attn_f32_kernel<<<(int)blocks, 256, 0, s>>>(p, head_dim);
     }
     return launch_status();

@@ -57,14 +57,14 @@ __device__ __forceinline__ uint32_t lds_byte_addr(const void* p) {
 // wait_vmem_all() and then synchronises the workgroup before any wavefront reads the data.
 __device__ __forceinline__ void dma_global_to_lds_16(const void* gptr, uint32_t lds_base) {
     const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base), "v"(gptr) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base), "v"(gptr) : "memory", "m0");
 }
 // Same, with the global address split into a wave-uniform base (scalar registers) and a 32-bit byte
 // offset per lane.
 __device__ __forceinline__ void dma_global_to_lds_16(const void* gbase_uniform, uint32_t byte_off, uint32_t lds_base) {
     const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(base), "v"(byte_off), "s"(gbase_uniform)
-                 : "memory");
+                 : "memory", "m0");
 }
 // The waits are emitted through the compiler's own s_waitcnt builtin (gfx9 encoding: vmcnt in bits 3:0 and
 // 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their maxima = no wait), not as inline assembly: the compiler's
@@ -178,8 +178,8 @@ struct AttnParams {
     // dropped from the key/value set
     const unsigned long long* valid_bits;
 };
-int launch_attention(int dtype, const AttnParams& p, int head_dim, hipStream_t s);
+// plan_only: validate the launch (shape limits, kernel availability) and launch nothing
+int launch_attention(int dtype, const AttnParams& p, int head_dim, hipStream_t s, bool plan_only = false);
 int launch_mfma_probe(float* out, int n_blocks, int iters, hipStream_t s);
-int launch_mfma_valu_probe(float* out, int n_blocks, int iters, int valu_per_mfma, int use_exp, hipStream_t s);
 
 }  // namespace astra

@@ -28,12 +28,10 @@ __device__ __forceinline__ int find_problem(const GemmBatch& b, int tile) {
 // ------------------------------------------------------------------------------------------------
 // bf16, matrix cores.  A workgroup of WM x WN wavefronts owns a BM x BN output tile; each wavefront
 // owns a (BM/WM) x (BN/WN) sub-tile made of 32x32x16 MFMA tiles.  The contraction runs in steps of 64
-// through double-buffered LDS.  Operand tiles travel from memory straight into LDS (DMA = true, the default:
-// one wavefront instruction fills 64 consecutive 16-byte slots, nothing passes through registers): while the
-// matrix cores work on tile kt out of one buffer, tile kt+1 has landed in the other, tile kt+2 is sent into
-// the first as soon as the barrier of iteration kt has passed and, for gathered A rows, the codes of tile
-// kt+3 are being fetched.  (DMA = false stages through registers instead: tile kt+1 sits in registers on its
-// way to the other buffer while the loads of tile kt+2 are in flight.)  LDS tiles are
+// through double-buffered LDS.  Operand tiles travel from memory straight into LDS (one wavefront instruction
+// fills 64 consecutive 16-byte slots, nothing passes through registers): while the matrix cores work on tile kt
+// out of one buffer, tile kt+1 has landed in the other, tile kt+2 is sent into the first as soon as the barrier
+// of iteration kt has passed and, for gathered A rows, the codes of tile kt+3 are being fetched.  LDS tiles are
 // [rows][8 pieces of 8 bf16]; piece p of row r sits at p ^ ((r >> 1) & 7): rows are 128 bytes, the
 // LDS has 64 four-byte banks, so the 16-byte fragment reads of 16 consecutive rows touch every bank once.
 //
@@ -105,17 +103,14 @@ enum { kEpiLayer = 0, kEpiResidualF32 = 1, kEpiSplit = 2, kEpiGeluTanh = 3, kEpi
 // [128 t + 64 g, 128 t + 64 g + 64), each with its own operand buffers and the full loop below; their accumulators are
 // added through LDS at the end.  A small tile then keeps its 64 x 64 wave tiles (1 KiB of LDS reads per MFMA) and still
 // has two wavefronts per SIMD to hide each other's staging.
-#ifndef ASTRA_GEMM_DIRECT_TRANSFERS
-#define ASTRA_GEMM_DIRECT_TRANSFERS 1
-#endif
-template <int BM, int BN, int WM, int WN, bool CODE16, bool ENC = false, int EPI = kEpiLayer, int KS = 1, bool DMA = ASTRA_GEMM_DIRECT_TRANSFERS != 0>
+template <int BM, int BN, int WM, int WN, bool CODE16, bool ENC = false, int EPI = kEpiLayer, int KS = 1>
 __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_nt_bf16_kernel(const GemmBatch batch) {
     constexpr int THREADS = 64 * WM * WN;                      // threads of one group
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;        // MFMA tiles per wavefront
     constexpr int RPP = THREADS / 8;                           // rows staged per pass
     constexpr int PA = BM / RPP, PB = BN / RPP;                // staging passes per thread
     static_assert(KS == 1 || (KS == 2 && !ENC), "one or two contraction groups");
-    static_assert(!DMA || RPP % 16 == 0, "direct transfers: the row swizzle has to be periodic in the pass stride");
+    static_assert(RPP % 16 == 0, "direct transfers: the row swizzle has to be periodic in the pass stride");
     __shared__ u32x4 lds_a[2 * KS][BM * kBK / 8];              // [2 * group + buffer]
     __shared__ u32x4 lds_b[2 * KS][BN * kBK / 8];
 
@@ -172,7 +167,7 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_nt_bf16_kernel(const G
     const int r0 = tid >> 3;                    // staging: 16-byte piece kc of rows r0 + RPP * it
     // With direct global -> LDS transfers a lane's LDS slot is fixed by its lane number (slot tid & 7 of its row), so the
     // swizzle moves to the global side: the lane fetches the piece that belongs into its slot.
-    const int kc = DMA ? ((tid & 7) ^ swz(r0)) : (tid & 7);
+    const int kc = (tid & 7) ^ swz(r0);
 
     // One straight-line loader serves plain and gathered A rows.  For gathered rows the piece at
     // contraction index k lies in group g = k / dg at offset j = k - g*dg of codeword codes[row, g];
@@ -222,7 +217,6 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_nt_bf16_kernel(const G
     int k_code = kc * 8 + kgrp * kBK; // contraction index of this thread's piece in the tile whose codes are fetched next
     int k_use = kc * 8 + kgrp * kBK;  // ... in the tile whose operand pieces are fetched next
     int code[PA];
-    u32x4 ra[PA], rb[PB];
 
     auto load_codes = [&]() {
         const uint32_t g_ = __umulhi((uint32_t)k_code, magic) * (CODE16 ? 2u : 1u);
@@ -233,35 +227,6 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_nt_bf16_kernel(const G
         }
         k_code += kBK * KS;
     };
-    auto load_tile = [&]() {
-        const uint32_t g_ = __umulhi((uint32_t)k_use, magic);
-        const uint32_t j_ = (uint32_t)k_use - g_ * (uint32_t)dg;
-        const uint32_t gbase_ = g_ * (uint32_t)Kc;
-#pragma unroll
-        for (int it = 0; it < PA; ++it) {
-            const uint32_t c_ = (uint32_t)(code[it] < Kc ? code[it] : Kc - 1);
-            const uint32_t goff_ = ((gbase_ + c_) * (uint32_t)dg + j_) * 2u;
-            ra[it] = *reinterpret_cast<const u32x4*>(a_base + ((goff_ & gmask) + aoff[it]));
-        }
-#pragma unroll
-        for (int it = 0; it < PB; ++it) rb[it] = *reinterpret_cast<const u32x4*>(b_base + boff[it]);
-        a_base += a_step;
-        b_base += kBK * 2 * KS;
-        k_use += kBK * KS;
-    };
-    auto store_tile = [&](int buf_) {
-#pragma unroll
-        for (int it = 0; it < PA; ++it) {
-            const int r_ = r0 + RPP * it;
-            lds_a[kg2 + buf_][r_ * 8 + (kc ^ swz(r_))] = ra[it];
-        }
-#pragma unroll
-        for (int it = 0; it < PB; ++it) {
-            const int r_ = r0 + RPP * it;
-            lds_b[kg2 + buf_][r_ * 8 + (kc ^ swz(r_))] = rb[it];
-        }
-    };
-
     // direct transfer of the tile at k_use into LDS buffer buf_: the lanes of a wavefront fill 64 consecutive slots
     // (8 rows of 8 pieces), nothing passes through registers; pass it_ of the A rows, then of the B rows
     const uint32_t wave_rows = (uint32_t)__builtin_amdgcn_readfirstlane(8 * (tid >> 6));
@@ -322,12 +287,10 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_nt_bf16_kernel(const G
 
     // ---- main loop.  One tile of 64 along the contraction is four MFMA steps of 16.  Per step a wavefront
     // issues TM*TN MFMAs on fragments it requested from LDS one step earlier (two fragment slots), and between those
-    // MFMAs, in program order, the "side jobs" of the step: the TM+TN fragment reads of the next step and a slice of
-    // the staging work (registers holding tile kt+1 -> other LDS buffer, refilled at once with the global loads of
-    // tile kt+2).  Nothing else is needed to keep a single wavefront per SIMD busy: LDS and global latencies are
-    // covered by the MFMAs issued meanwhile.  Staging is spread over steps 0..2; the workgroup barrier follows step 2,
-    // after which step 3 may read the first fragments of tile kt+1 from the buffer just filled, and the buffer of
-    // tile kt (all of whose fragments were requested before the barrier) is free for the next iteration's staging.
+    // MFMAs, in program order, the "side jobs" of the step: the TM+TN fragment reads of the next step and, in step 3,
+    // the transfers of tile kt+2.  LDS and global latencies are covered by the MFMAs issued meanwhile.  The workgroup
+    // barrier follows step 2, after which step 3 may read the first fragments of tile kt+1 from the other buffer, and
+    // the buffer of tile kt (all of whose fragments were requested before the barrier) is free for the transfers.
     const int n_kt = (EPI == kEpiSplit ? batch.k_split : K) / (kBK * KS);
     bf16x8 fa[2][TM], fb[2][TN];
     auto read_frag = [&](int buf_, int ks, int slot, int j) {
@@ -335,63 +298,7 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_nt_bf16_kernel(const G
         else fb[slot][j - TM] = __builtin_bit_cast(bf16x8, lds_b[kg2 + buf_][brow[j - TM] * 8 + ((2 * ks + h) ^ swz(brow[j - TM]))]);
     };
     constexpr int NR = TM + TN, NM = TM * TN;
-    auto tile_steps = [&](int kt, auto full_tag) {
-        constexpr bool FULL = decltype(full_tag)::value;       // steady state: tiles kt+1, kt+2 and codes kt+3 all exist
-        const int buf = kt & 1;
-        const bool st = FULL || kt + 1 < n_kt, ld = FULL || kt + 2 < n_kt;
-        const uint32_t g_ = __umulhi((uint32_t)k_use, magic);
-        const uint32_t j_ = (uint32_t)k_use - g_ * (uint32_t)dg;
-        const uint32_t gbase_ = g_ * (uint32_t)Kc;
-        auto stage_a = [&](int it) {
-            const int r_ = r0 + RPP * it;
-            if (st) lds_a[kg2 + (buf ^ 1)][r_ * 8 + (kc ^ swz(r_))] = ra[it];
-            if (ld) {
-                const uint32_t c_ = (uint32_t)(code[it] < Kc ? code[it] : Kc - 1);
-                const uint32_t goff_ = ((gbase_ + c_) * (uint32_t)dg + j_) * 2u;
-                ra[it] = *reinterpret_cast<const u32x4*>(a_base + ((goff_ & gmask) + aoff[it]));
-            }
-        };
-        auto stage_b = [&](int it) {
-            const int r_ = r0 + RPP * it;
-            if (st) lds_b[kg2 + (buf ^ 1)][r_ * 8 + (kc ^ swz(r_))] = rb[it];
-            if (ld) rb[it] = *reinterpret_cast<const u32x4*>(b_base + boff[it]);
-        };
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const int cur = ks & 1, nxt = cur ^ 1;
-            // side jobs of this step: NR fragment reads, then (steps 0..2) the staging slice
-            const int a_lo = ks < 3 ? ks * PA / 3 : PA, a_hi = ks < 3 ? (ks + 1) * PA / 3 : PA;
-            const int b_lo = ks < 3 ? ks * PB / 3 : PB, b_hi = ks < 3 ? (ks + 1) * PB / 3 : PB;
-            const int nj = NR + (a_hi - a_lo) + (b_hi - b_lo);
-            const bool rd = ks < 3 || st;                     // step 3 reads the next tile, if there is one
-#pragma unroll
-            for (int m = 0; m < NM; ++m) {
-                const int a = m / TN, b = m % TN;
-                acc[a][b] = mfma_32x32x16(fa[cur][a], fb[cur][b], acc[a][b]);
-#pragma unroll
-                for (int j = m * nj / NM; j < (m + 1) * nj / NM; ++j) {
-                    if (j < NR) {
-                        if (rd) read_frag(ks < 3 ? buf : buf ^ 1, (ks + 1) & 3, nxt, j);
-                    } else if (j - NR < a_hi - a_lo) {
-                        stage_a(a_lo + j - NR);
-                    } else {
-                        stage_b(b_lo + j - NR - (a_hi - a_lo));
-                    }
-                }
-                __builtin_amdgcn_sched_barrier(0);        // keep this order: the compiler would bunch the memory operations
-            }
-            if (ks == 2) __syncthreads();
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if (ld) {
-            a_base += a_step;
-            b_base += kBK * 2 * KS;
-            k_use += kBK * KS;
-        }
-        if (FULL || kt + 3 < n_kt) load_codes();
-    };
-
-    if constexpr (DMA) {
+    {
         // Tiles go from memory straight into LDS.  Buffer kt & 1 is free once every wavefront has passed the barrier of
         // iteration kt (all reads of tile kt were requested and awaited before it): tile kt + 2 is sent there during step 3
         // of iteration kt and has until the wait in front of the barrier of iteration kt + 1 to land.
@@ -452,19 +359,6 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_nt_bf16_kernel(const G
             tile_steps_dma(kt + 1, std::integral_constant<int, 1>{});
         }
         for (; kt < n_kt; ++kt) tile_steps_dma(kt, std::integral_constant<int, -1>{});
-    } else {
-    load_codes();                 // codes of tile 0
-    load_tile();                  // tile 0
-    if (n_kt > 1) load_codes();   // codes of tile 1
-    store_tile(0);
-    if (n_kt > 1) load_tile();    // tile 1
-    if (n_kt > 2) load_codes();   // codes of tile 2
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < NR; ++j) read_frag(0, 0, 0, j);
-    int kt = 0;
-    for (; kt + 3 < n_kt; ++kt) tile_steps(kt, std::true_type{});
-    for (; kt < n_kt; ++kt) tile_steps(kt, std::false_type{});
     }
 
     if constexpr (KS == 2) {

@@ -197,7 +197,7 @@ __global__ __launch_bounds__(kTrThreads) void stats_sqerr_kernel(const float* __
 template <typename T>
 __global__ __launch_bounds__(kTrThreads) void codebook_update_kernel(const int32_t* __restrict__ counts, const float* __restrict__ sums,
                                                                      float gamma, float* ema_n, float* ema_m,
-                                                                     const T* __restrict__ cb_old, int64_t n_cw, int dg, T* __restrict__ cb_new) {
+                                                                     const T* cb_old, int64_t n_cw, int dg, T* cb_new) {   // cb_new may be cb_old: no restrict
     const int64_t i = (int64_t)blockIdx.x * kTrThreads + threadIdx.x;          // (codeword, channel)
     if (i >= n_cw * dg) return;
     const int64_t cw = i / dg;

@@ -215,8 +215,9 @@ KV_GROUPS = {"tiny_vit_f32": 4, "vit_base_bf16": 16, "gpt2_small_bf16": 32, "lla
 def generate_kv(cfg: LayerConfig, n_groups_kv: int | None = None) -> dict:
     """generate(cfg) plus the two codebooks of the KV-space variant, codebook_k and codebook_v [G_kv, K, dkv / G_kv]
     ~ N(0, 1.3^2) (the scale of K = X W_k for unit-variance rows and N(0, 0.02^2) weights at D = 4096); the X-space
-    codebook of generate() stays in the dict but is not used by that variant.  Llama: G_kv = 32, K = 1024, i.e. the
-    640 bits per token of the paper's Llama results."""
+    codebook of generate() stays in the dict but is not used by that variant.  Llama: G_kv = 32, K = 1024, i.e.
+    2 * 32 * 10 = 640 bits per token PER BLOCK (20 480 over the 32 blocks: the G = 32 row of the paper's Llama table; the
+    640 that table prints for G = 1 is 32 blocks x 2 codebooks x 10 bits)."""
     out = generate(cfg)
     g = n_groups_kv if n_groups_kv is not None else KV_GROUPS.get(cfg.name, cfg.n_groups)
     dkv = cfg.n_kv_heads * cfg.head_dim

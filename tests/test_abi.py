@@ -61,7 +61,6 @@ def test_host_side_argument_checks_need_no_gpu():
     assert lib.astra_vq_encode(ctypes.byref(good.vq), None, -1, None, None, None, None) == -2
     # the measurement probes check their arguments before anything is launched
     assert lib.astra_probe_mfma_bf16(None, 1, 1, None) == -1
-    assert lib.astra_probe_mfma_valu_bf16(None, 1, 1, 4, 0, None) == -1
 
 
 def test_encode_fusion_plan_is_host_only():

@@ -238,6 +238,21 @@ int astra_decode_attention(const astra_decode_desc* desc, const void* q, const v
                            const void* codebook_k, const void* codebook_v, void* out, float* lse_out,
                            void* workspace, size_t workspace_bytes, void* stream);
 
+/* astra_decode_attention for callers that cannot allocate device memory or pass a workspace (work recorded under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation): the table and the per-chunk partial
+ * results live in a scratch array that is part of the library's device image, astra_decode_attention_static_max_bytes()
+ * = 8 MiB per GPU, held by every GPU the library runs on until the process ends.  Same arguments, kernels and results
+ * as astra_decode_attention; the call allocates and frees nothing.  A shape whose
+ * astra_decode_attention_workspace_bytes exceeds the array returns ASTRA_ERR_WORKSPACE before anything is launched
+ * (the Llama-3-8B shapes of a 128 K-token cache need about 2.6 MiB).  The array's device address is looked up once
+ * per device, on the first call with that device current; a failed lookup returns ASTRA_ERR_HIP.  Nothing in the array
+ * has to start at zero (every call writes what it reads), but all calls on one GPU share it: calls that overlap on one
+ * GPU (different streams or threads) race; calls that follow each other on one stream do not. */
+size_t astra_decode_attention_static_max_bytes(void);
+int astra_decode_attention_static(const astra_decode_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                                  const void* codes_k, const void* codes_v, const uint64_t* valid_bits,
+                                  const void* codebook_k, const void* codebook_v, void* out, float* lse_out, void* stream);
+
 /* ---- one whole Transformer block on one device -------------------------------------------------
  * Sec. 3.1: per block, a device quantises its local token embeddings, exchanges indices, attends with
  * the mixed-precision layer and then runs the position-wise MLP locally, without communication.  The

@@ -19,6 +19,7 @@ EXPORTS = ("astra_vq_prepare", "astra_vq_encode", "astra_vq_decode", "astra_mixe
            "astra_block_workspace_bytes", "astra_block_forward", "astra_stack_forward",
            "astra_layer_kv_workspace_bytes", "astra_layer_forward_kv",
            "astra_decode_attention_workspace_bytes", "astra_decode_attention",
+           "astra_decode_attention_static_max_bytes", "astra_decode_attention_static",
            "astra_codebook_stats_workspace_bytes", "astra_codebook_stats", "astra_codebook_update", "astra_navq_forward",
            "astra_probe_mfma_bf16", "astra_status_string", "astra_version")
 ASTRA_NORM_LAYER, ASTRA_NORM_RMS = 0, 1
@@ -111,6 +112,10 @@ def load(build_if_missing: bool = True):
     lib.astra_decode_attention_workspace_bytes.restype = ctypes.c_size_t
     lib.astra_decode_attention.argtypes = [ctypes.POINTER(DecodeDesc)] + [vp] * 11 + [ctypes.c_size_t, vp]
     lib.astra_decode_attention.restype = ctypes.c_int
+    lib.astra_decode_attention_static_max_bytes.argtypes = []
+    lib.astra_decode_attention_static_max_bytes.restype = ctypes.c_size_t
+    lib.astra_decode_attention_static.argtypes = [ctypes.POINTER(DecodeDesc)] + [vp] * 11
+    lib.astra_decode_attention_static.restype = ctypes.c_int
     lib.astra_codebook_stats_workspace_bytes.argtypes = [ctypes.POINTER(VqDesc), i64]
     lib.astra_codebook_stats_workspace_bytes.restype = ctypes.c_size_t
     lib.astra_codebook_stats.argtypes = [ctypes.POINTER(VqDesc), vp, vp, i64, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -254,6 +259,17 @@ def astra_decode_attention(desc: DecodeDesc, q, k_cache, v_cache, codes_k, codes
     _check(load().astra_decode_attention(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(codes_k), _ptr(codes_v),
                                          _ptr(valid_bits), _ptr(codebook_k), _ptr(codebook_v), _ptr(out), _ptr(lse_out),
                                          _ptr(workspace), nbytes, _stream()), "astra_decode_attention")
+
+
+def astra_decode_attention_static_max_bytes() -> int:
+    return int(load().astra_decode_attention_static_max_bytes())
+
+
+def astra_decode_attention_static(desc: DecodeDesc, q, k_cache, v_cache, codes_k, codes_v, valid_bits, codebook_k, codebook_v, out,
+                                  lse_out):
+    _check(load().astra_decode_attention_static(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(codes_k),
+                                                _ptr(codes_v), _ptr(valid_bits), _ptr(codebook_k), _ptr(codebook_v), _ptr(out),
+                                                _ptr(lse_out), _stream()), "astra_decode_attention_static")
 
 
 def astra_codebook_stats_workspace_bytes(desc: VqDesc, n_tokens: int) -> int:

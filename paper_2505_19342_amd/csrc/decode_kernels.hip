@@ -16,6 +16,7 @@
 #include "common.h"
 
 #include <algorithm>
+#include <mutex>
 #include <type_traits>
 
 namespace astra {
@@ -541,10 +542,34 @@ size_t astra_decode_attention_workspace_bytes(const astra_decode_desc* desc) {
     return pl.total;
 }
 
-int astra_decode_attention(const astra_decode_desc* desc, const void* q, const void* k_cache, const void* v_cache,
-                           const void* codes_k, const void* codes_v, const uint64_t* valid_bits, const void* codebook_k,
-                           const void* codebook_v, void* out, float* lse_out, void* workspace, size_t workspace_bytes,
-                           void* stream) {
+// Scratch of astra_decode_attention_static: one copy per GPU, held until the process ends.  In host code the array's
+// name is only a handle for hipGetSymbolAddress; kernels and the entry point use the per-device address kept below.
+constexpr size_t kDecodeStaticBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kDecodeStaticBytes];
+constexpr int kMaxDevices = 64;
+static void* g_scratch_addr[kMaxDevices];          // device address of `scratch` on device i, looked up on first use
+static std::mutex g_scratch_mutex;
+
+static int decode_static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return ASTRA_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_addr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return ASTRA_ERR_HIP;
+        }
+        g_scratch_addr[dev] = ptr;
+    }
+    *out = g_scratch_addr[dev];
+    return ASTRA_OK;
+}
+
+static int decode_attention_impl(const astra_decode_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                                 const void* codes_k, const void* codes_v, const uint64_t* valid_bits, const void* codebook_k,
+                                 const void* codebook_v, void* out, float* lse_out, void* workspace, size_t workspace_bytes,
+                                 bool library_scratch, void* stream) {
     if (!desc) return ASTRA_ERR_NULL;
     DecodePlan pl;
     int rc = make_decode_plan(*desc, &pl);
@@ -552,7 +577,13 @@ int astra_decode_attention(const astra_decode_desc* desc, const void* q, const v
     if (!q || !out) return ASTRA_ERR_NULL;
     if (desc->n_local > 0 && (!k_cache || !v_cache)) return ASTRA_ERR_NULL;
     if (desc->n_nonlocal > 0 && (!codes_k || !codes_v || !codebook_k || !codebook_v)) return ASTRA_ERR_NULL;
-    if (!workspace || workspace_bytes < pl.total) return ASTRA_ERR_WORKSPACE;
+    if (library_scratch) {
+        if (pl.total > kDecodeStaticBytes) return ASTRA_ERR_WORKSPACE;
+        rc = decode_static_scratch(&workspace);
+        if (rc) return rc;
+    } else if (!workspace || workspace_bytes < pl.total) {
+        return ASTRA_ERR_WORKSPACE;
+    }
     DecodeParams p{};
     p.q = q; p.k_loc = k_cache; p.v_loc = v_cache; p.codes_k = codes_k; p.codes_v = codes_v;
     p.valid_bits = (const unsigned long long*)valid_bits;
@@ -568,6 +599,23 @@ int astra_decode_attention(const astra_decode_desc* desc, const void* q, const v
     p.scale = desc->scale != 0.f ? desc->scale : 1.f / sqrtf((float)desc->head_dim);
     if (desc->vq.dtype == ASTRA_BF16) return run_decode<uint16_t>(p, pl, (hipStream_t)stream);
     return run_decode<float>(p, pl, (hipStream_t)stream);
+}
+
+int astra_decode_attention(const astra_decode_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                           const void* codes_k, const void* codes_v, const uint64_t* valid_bits, const void* codebook_k,
+                           const void* codebook_v, void* out, float* lse_out, void* workspace, size_t workspace_bytes,
+                           void* stream) {
+    return decode_attention_impl(desc, q, k_cache, v_cache, codes_k, codes_v, valid_bits, codebook_k, codebook_v, out, lse_out,
+                                 workspace, workspace_bytes, false, stream);
+}
+
+size_t astra_decode_attention_static_max_bytes(void) { return kDecodeStaticBytes; }
+
+int astra_decode_attention_static(const astra_decode_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                                  const void* codes_k, const void* codes_v, const uint64_t* valid_bits, const void* codebook_k,
+                                  const void* codebook_v, void* out, float* lse_out, void* stream) {
+    return decode_attention_impl(desc, q, k_cache, v_cache, codes_k, codes_v, valid_bits, codebook_k, codebook_v, out, lse_out,
+                                 nullptr, 0, true, stream);
 }
 
 }  // extern "C"

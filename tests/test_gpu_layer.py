@@ -64,9 +64,15 @@ def test_biases_f32_and_bf16():
     run_case(wl.VIT_BASE, 1, biases=True)
 
 
-@pytest.mark.parametrize("i_g,i_k,i_dev", [(0, 2, 0), (1, 1, 1), (2, 0, 2), (3, 1, 1), (3, 2, 2)])
+@pytest.mark.parametrize("i_dev", [0, 1, 2])
+@pytest.mark.parametrize("i_k", [0, 1, 2])
+@pytest.mark.parametrize("i_g", [0, 1, 2, 3])
 def test_sweep_points(i_g, i_k, i_dev):
-    run_case(wl.sweep_config(i_g, i_k, i_dev), 1)
+    """Every point of the sweep on the ViT-Base shape: G in {1, 4, 16, 64} x K in {16, 256, 1024} x {2, 4, 8} devices
+    (group widths 768, 192, 48 and 12: the last is not a multiple of the 16-byte operand piece, so the peers' rows are
+    rebuilt by the decode kernel instead of inside the projection's operand loader)."""
+    cfg = wl.sweep_config(i_g, i_k, i_dev)
+    run_case(cfg, cfg.n_dev - 1 if i_g == i_k else 1)
 
 
 def test_uneven_split_and_ragged_shapes():

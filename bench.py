@@ -22,12 +22,9 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}       # MI355X dense MFMA peaks
-# HBM-side bytes per launch of the dominant kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs kept
-# under profiles/ (layer_llama3_8b_pmc_fetch_size.txt, ..._write_size.txt), each scaled by what the same counter
-# reads for a 256 MiB copy kernel: (71705.2 * 2.0 + 32810.1 * 1.0) KiB.  None for workloads not profiled.
-TRAFFIC_BYTES = {"llama3_8b_bf16": (71705.2 * 2.0 + 32810.1) * 1024.0}
+PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}       # MI355X: dense bf16 MFMA peak; fp32 vector-ALU peak
 STAGES = ("vq_encode", "projections", "attention", "out_projection")
+N_EVENT_CALLS = 24      # calls that carry stage events, run after the timed region, whatever --steps is
 
 
 def layer_flops(cfg, n_before):
@@ -44,24 +41,129 @@ def layer_flops(cfg, n_before):
     }
 
 
+def counter_from_profile(path, counter, kernel_substr):
+    """Mean value per dispatch of `counter` for the first kernel whose name contains kernel_substr, read from a summary
+    that paper_2505_19342_amd.rocprof_summary wrote under profiles/ (None when the file or the line is missing)."""
+    try:
+        lines = open(path).read().splitlines()
+    except OSError:
+        return None
+    for ln in lines:
+        parts = ln.split(None, 2)
+        if len(parts) == 3 and parts[0] == counter and kernel_substr in parts[2]:
+            try:
+                return float(parts[1])
+            except ValueError:
+                return None
+    return None
+
+
+def traffic_from_profiles(stem, kernel_substr, copy_kib=262144.0):
+    """HBM-side bytes per dispatch of a kernel from the two rocprofv3 --pmc summaries profiles/<stem>_pmc_fetch_size.txt and
+    ..._write_size.txt (KiB per dispatch), each scaled by what the same counter reads for the plain 256 MiB copy kernel the
+    same run launched (torch's AUnaryFunctor elementwise kernel: reads and writes copy_kib KiB)."""
+    total = 0.0
+    for kind in ("fetch", "write"):
+        path = os.path.join(ROOT, "profiles", f"{stem}_pmc_{kind}_size.txt")
+        name = "FETCH_SIZE" if kind == "fetch" else "WRITE_SIZE"
+        v, cal = counter_from_profile(path, name, kernel_substr), counter_from_profile(path, name, "AUnaryFunctor")
+        if v is None or not cal:
+            return None
+        total += v * (copy_kib / cal) * 1024.0
+    return total
+
+
+def make_layer_call(cfg, rank, data=None):
+    """Device-resident tensors of one astra_layer_forward call of a workload on simulated device `rank`; the peers' codes are
+    produced by the library's own encode of their rows (what they would have transmitted)."""
+    import torch
+    from paper_2505_19342_amd import binding as B
+    from paper_2505_19342_amd import workloads as wl
+    dev = "cuda:0"
+    data = wl.generate(cfg) if data is None else data
+    view = wl.device_view(cfg, data, rank)
+    dt = cfg.dtype
+    G, K, D = cfg.n_groups, cfg.codebook_size, cfg.d_model
+
+    def to_dev(a):
+        a = np.ascontiguousarray(a, dtype=np.float32)
+        if dt == "bf16":
+            return torch.from_numpy(wl.bf16_bits(a).view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(a).to(dev)
+
+    code_t = torch.uint8 if K <= 256 else torch.int16
+    vq = B.vq_desc(dt, D, G, K)
+    codebook = to_dev(data["codebook"])
+    cnorm = torch.empty((G, K), dtype=torch.float32, device=dev)
+    B.astra_vq_prepare(vq, codebook, cnorm)
+    x_nl = to_dev(view["x_nonlocal"])
+    tn = x_nl.shape[0]
+    codes_nl = torch.empty((tn, G), dtype=code_t, device=dev)
+    B.astra_vq_encode(vq, x_nl, tn, codebook, cnorm, codes_nl)
+    del x_nl
+    x_local = to_dev(view["x_local"])
+    tq = x_local.shape[0]
+    desc = B.LayerDesc(vq, B.attn_desc(dt, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n_cls, tq - cfg.n_cls, tn,
+                                       cfg.causal, view["n_before"]))
+    w = [to_dev(np.ascontiguousarray(data[n].T)) for n in ("wq", "wk", "wv", "wo")]
+    y = torch.empty((tq, D), dtype=torch.float32, device=dev)
+    codes_local = torch.empty((tq - cfg.n_cls, G), dtype=code_t, device=dev)
+    ws = torch.empty(max(B.astra_layer_workspace_bytes(desc), 256), dtype=torch.uint8, device=dev)
+    call_args = (desc, x_local, codes_nl, codebook, cnorm, *w, None, None, None, None, y, codes_local, ws)
+    return {"cfg": cfg, "rank": rank, "data": data, "view": view, "to_dev": to_dev, "code_t": code_t, "vq": vq, "codebook": codebook,
+            "cnorm": cnorm, "codes_nl": codes_nl, "x_local": x_local, "tq": tq, "tn": tn, "desc": desc, "w": w, "y": y,
+            "codes_local": codes_local, "ws": ws, "call_args": call_args}
+
+
+def preheat(fn, min_ms, sync):
+    """Calls fn back to back for at least min_ms of wall clock (in runs of 64 calls, each followed by a synchronisation, so
+    the host never gets far ahead): after host-side set-up the chip sits at an idle clock and needs a few hundred
+    milliseconds of load to settle at the clock it holds under this work.  Returns (calls made, seconds)."""
+    t0, n = time.perf_counter(), 0
+    while (time.perf_counter() - t0) * 1e3 < min_ms:
+        for _ in range(64):
+            fn()
+        n += 64
+        sync()
+    return n, time.perf_counter() - t0
+
+
+def stage_times(lc, n_calls):
+    """Per-stage HIP-event spans (ms) of n_calls back-to-back astra_layer_forward_profiled calls: median and mean per stage,
+    and the sorted whole-call spans.  Events: 0 entry, 1 projection launch done, 5/6 around the encode if it ran as a kernel of
+    its own (otherwise it ran inside the projection launch and 5..6 is empty), 2 attention done, 3 output projection done,
+    4 exit.  Back to back, a span starts when the previous kernel ends, so it is the kernel's duration plus one launch gap."""
+    import torch
+    from paper_2505_19342_amd import binding as B
+    evs = [B.HipEvents(7) for _ in range(n_calls)]
+    for _ in range(8):
+        B.astra_layer_forward(*lc["call_args"])
+    for ev in evs:
+        B.astra_layer_forward_profiled(*lc["call_args"], ev.handles)
+    torch.cuda.synchronize()
+    spans = {"vq_encode": (5, 6), "projections": (0, 1), "attention": (6, 2), "out_projection": (2, 3)}
+    per = {s: [ev.elapsed_ms(*spans[s]) for ev in evs] for s in STAGES}
+    whole = sorted(ev.elapsed_ms(0, 4) for ev in evs)
+    return {s: float(np.median(v)) for s, v in per.items()}, {s: float(np.mean(v)) for s, v in per.items()}, whole
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
-    ap.add_argument("--warmup", type=int, default=200,
-                    help="untimed calls before the timed region; the chip needs some tens of milliseconds of load to reach its "
-                         "steady clock after the host-side set-up, during which it sat idle")
+    ap.add_argument("--warmup", type=int, default=200, help="untimed calls right before the timed region")
+    ap.add_argument("--preheat-ms", type=float, default=400.0,
+                    help="before the --warmup calls, run the same call back to back for at least this long: after the host-side "
+                         "set-up the chip needs some hundred milliseconds of load to reach the clock it holds under this work, "
+                         "and a warm-up given as a call count alone would make the result depend on --steps / --warmup")
     ap.add_argument("--workload", default="llama3_8b_bf16")
     ap.add_argument("--rank", type=int, default=-1, help="simulated device (default: last = critical path under causal masking)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--profile-every", type=int, default=40,
-                    help="every N-th timed step is launched through astra_layer_forward_profiled (HIP events at the stage "
-                         "boundaries, about 35 us of extra gaps per such step: with the default the timed mean is 0.4 % above the "
-                         "event-free one); the others through astra_layer_forward")
     ap.add_argument("--no-extras", action="store_true",
-                    help="skip the measurements outside the timed region (matrix-core probe, stand-alone decode, other ranks)")
+                    help="skip the measurements outside the timed region")
     ap.add_argument("--extras", default="all",
-                    help="comma list of the measurements outside the timed region to run: ranks, uneven, lost, block, stack (needs block), kv, kvcache, train, decode, vendor, probe (default all)")
+                    help="comma list of the measurements outside the timed region to run: ranks, workloads, sweep, uneven, lost, block, "
+                         "stack (needs block), kv, kvcache, train, decode, gather, vendor, probe (default all)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the warm-up, run one plain elementwise copy kernel reading and writing this many MiB "
                          "(fp32): the reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -82,37 +184,12 @@ def main():
     dev = "cuda:0"
     cfg = wl.CONFIGS[args.workload]
     rank = args.rank if args.rank >= 0 else cfg.n_dev - 1
-    data = wl.generate(cfg)
-    view = wl.device_view(cfg, data, rank)
+    lc = make_layer_call(cfg, rank)
+    data, view, to_dev, code_t, vq = lc["data"], lc["view"], lc["to_dev"], lc["code_t"], lc["vq"]
+    codebook, cnorm, codes_nl, x_local, tq, tn = lc["codebook"], lc["cnorm"], lc["codes_nl"], lc["x_local"], lc["tq"], lc["tn"]
+    desc, w, y, codes_local, ws, call_args = lc["desc"], lc["w"], lc["y"], lc["codes_local"], lc["ws"], lc["call_args"]
     dt = cfg.dtype
     G, K, D = cfg.n_groups, cfg.codebook_size, cfg.d_model
-
-    def to_dev(a):
-        a = np.ascontiguousarray(a, dtype=np.float32)
-        if dt == "bf16":
-            return torch.from_numpy(wl.bf16_bits(a).view(np.int16)).to(dev).view(torch.bfloat16)
-        return torch.from_numpy(a).to(dev)
-
-    code_t = torch.uint8 if K <= 256 else torch.int16
-    vq = B.vq_desc(dt, D, G, K)
-    codebook = to_dev(data["codebook"])
-    cnorm = torch.empty((G, K), dtype=torch.float32, device=dev)
-    B.astra_vq_prepare(vq, codebook, cnorm)
-    # the peers' codes: encode their rows with the library itself (what they would have transmitted)
-    x_nl = to_dev(view["x_nonlocal"])
-    tn = x_nl.shape[0]
-    codes_nl = torch.empty((tn, G), dtype=code_t, device=dev)
-    B.astra_vq_encode(vq, x_nl, tn, codebook, cnorm, codes_nl)
-    del x_nl
-    x_local = to_dev(view["x_local"])
-    tq = x_local.shape[0]
-    desc = B.LayerDesc(vq, B.attn_desc(dt, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n_cls, tq - cfg.n_cls, tn,
-                                       cfg.causal, view["n_before"]))
-    w = [to_dev(np.ascontiguousarray(data[n].T)) for n in ("wq", "wk", "wv", "wo")]
-    y = torch.empty((tq, D), dtype=torch.float32, device=dev)
-    codes_local = torch.empty((tq - cfg.n_cls, G), dtype=code_t, device=dev)
-    ws = torch.empty(max(B.astra_layer_workspace_bytes(desc), 256), dtype=torch.uint8, device=dev)
-    call_args = (desc, x_local, codes_nl, codebook, cnorm, *w, None, None, None, None, y, codes_local, ws)
 
     if args.calibration_copy_mib > 0:
         n = args.calibration_copy_mib * (1 << 20) // 4
@@ -123,31 +200,34 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    step = lambda: B.astra_layer_forward(*call_args)
+    preheat_calls, preheat_s = preheat(step, args.preheat_ms, torch.cuda.synchronize) if args.preheat_ms > 0 else (0, 0.0)
     for _ in range(args.warmup):
-        B.astra_layer_forward(*call_args)
+        step()
     torch.cuda.synchronize()
 
-    # ---- timed region: exactly `steps` calls; on a sample of them the stage boundaries are marked with HIP
-    # events on the launch stream (the events cost idle gaps between the kernels, so not on every step)
-    every = max(1, args.profile_every)
-    sampled = [i for i in range(args.steps) if i % every == every - 1] or [args.steps - 1]
-    events = {i: B.HipEvents(7) for i in sampled}
+    # ---- timed region: exactly `steps` calls of astra_layer_forward, back to back, wall clock between two synchronisations.
+    # Up to ten torch events on the launch stream cut the region into blocks of equal length (an event record between two
+    # calls costs no measurable gap): the spread of the per-call time over the region.
+    n_blocks = min(10, args.steps)
+    edges = [round(i * args.steps / n_blocks) for i in range(n_blocks + 1)]
+    marks = [torch.cuda.Event(enable_timing=True) for _ in edges]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    nxt = 0
     for i in range(args.steps):
-        if i in events:
-            B.astra_layer_forward_profiled(*call_args, events[i].handles)
-        else:
-            B.astra_layer_forward(*call_args)
+        if i == edges[nxt]:
+            marks[nxt].record()
+            nxt += 1
+        step()
+    marks[-1].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    events = list(events.values())
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    # events: 0 entry, 1 projection launch done, 5/6 around the encode if it ran as a kernel of its own (otherwise
-    # it ran inside the projection launch and 5..6 is empty), 2 attention done, 3 output projection done, 4 exit
-    spans = {"vq_encode": (5, 6), "projections": (0, 1), "attention": (6, 2), "out_projection": (2, 3)}
-    stage_ms = {s: float(np.mean([ev.elapsed_ms(*spans[s]) for ev in events])) for s in STAGES}
-    gpu_ms = float(np.mean([ev.elapsed_ms(0, 4) for ev in events]))
+    block_ms = sorted(marks[i].elapsed_time(marks[i + 1]) / (edges[i + 1] - edges[i]) for i in range(n_blocks))
+
+    # ---- stage times: a fixed number of event-carrying calls after the timed region
+    stage_ms, stage_ms_mean, per_step = stage_times(lc, N_EVENT_CALLS)
 
     flops = layer_flops(cfg, view["n_before"])
     total_flops = sum(flops.values())
@@ -158,17 +238,23 @@ def main():
     enc_fused = B.astra_layer_encode_fused(desc)
     dom_flops = flops[dom] + (flops["vq_encode"] if enc_fused else 0.0)
     achieved = dom_flops / (stage_ms[dom] * 1e-3) / 1e12
-    if enc_fused:
-        # no span of its own inside the layer: time the same encode once as a kernel of its own, for reference
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        x_enc = x_local[cfg.n_cls:]
-        B.astra_vq_encode(vq, x_enc, tq - cfg.n_cls, codebook, cnorm, codes_local)
-        e0.record()
-        for _ in range(10):
-            B.astra_vq_encode(vq, x_enc, tq - cfg.n_cls, codebook, cnorm, codes_local)
-        e1.record()
+
+    def timed(fn, n, warm=0):
+        for _ in range(1 + warm):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(n):
+            fn()
+        b.record()
         torch.cuda.synchronize()
-        stage_ms["vq_encode"] = e0.elapsed_time(e1) / 10
+        return a.elapsed_time(b) / n          # ms
+
+    if enc_fused:
+        # no span of its own inside the layer: time the same encode as a kernel of its own, for reference
+        x_enc = x_local[cfg.n_cls:]
+        stage_ms["vq_encode"] = timed(lambda: B.astra_vq_encode(vq, x_enc, tq - cfg.n_cls, codebook, cnorm, codes_local), 20, warm=5)
+    is_bench_shape = cfg.name == "llama3_8b_bf16" and rank == cfg.n_dev - 1
     result = {
         "metric": "tokens/sec per layer (VQ encode + mixed attention) and % of MFMA roofline",
         "value": tq / (ms_per_step * 1e-3),
@@ -181,38 +267,33 @@ def main():
                    "visible_nonlocal_rows": view["n_before"] if cfg.causal else tn, "d_model": D,
                    "heads": [cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim], "vq": {"G": G, "K": K, "dg": cfg.group_dim},
                    "causal": cfg.causal, "seed": cfg.seed},
+        "preheat": {"ms_requested": args.preheat_ms, "calls": preheat_calls, "seconds": preheat_s,
+                    "what": "the same call back to back before the --warmup calls, so that the timed region runs at the clock "
+                            "the chip holds under this work"},
         "layer_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
         "layer_mfma_frac": total_flops / (ms_per_step * 1e-3) / 1e12 / peak,
-        "gpu_ms_per_step_events": gpu_ms, "steps_with_events": len(events),
+        "ms_per_step_blocks_p10_p50_p90": [block_ms[int(q * (len(block_ms) - 1))] for q in (0.1, 0.5, 0.9)],
+        "steps_with_events": N_EVENT_CALLS,
+        "gpu_ms_per_step_events_p10_p50_p90": [per_step[int(q * (len(per_step) - 1))] for q in (0.1, 0.5, 0.9)],
         "encode_fused_into_projection_launch": bool(enc_fused),
         "stage_us": {s: stage_ms[s] * 1e3 for s in STAGES},
+        "stage_us_mean": {s: stage_ms_mean[s] * 1e3 for s in STAGES},
         "stage_tflops": {s: (dom_flops if s == dom else flops[s]) / (stage_ms[s] * 1e-3) / 1e12 for s in STAGES},
+        "stage_mfma_frac": {s: (dom_flops if s == dom else flops[s]) / (stage_ms[s] * 1e-3) / 1e12 / peak for s in STAGES},
         "roofline": {"kernel": ("gemm_nt_bf16_kernel (grouped Q/K/V/K-hat/V-hat projections" +
                                 (" + VQ encode of the local rows as extra workgroups)" if enc_fused else ")")) if dt == "bf16"
                      else "gemm_nt_f32_kernel (grouped projections)",
                      "bound": "mfma" if dt == "bf16" else "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak,
-                     "traffic": TRAFFIC_BYTES.get(cfg.name) if rank == cfg.n_dev - 1 else None,
-                     "flops_per_launch": dom_flops, "us_per_launch": stage_ms[dom] * 1e3},
+                     # HBM-side bytes per launch from the rocprofv3 --pmc summaries kept under profiles/
+                     "traffic": traffic_from_profiles("layer_llama3_8b", "gemm_nt_bf16_kernel<256, 256") if is_bench_shape else None,
+                     "flops_per_launch": dom_flops, "us_per_launch": stage_ms[dom] * 1e3,
+                     "how": f"median HIP-event span (entry of the call to the end of the launch) over {N_EVENT_CALLS} back-to-back calls "
+                            "after the timed region"},
     }
 
-    # percentiles of the GPU time of one call over the steps that carry events (events 0..4)
-    per_step = sorted(ev.elapsed_ms(0, 4) for ev in events)
-    result["gpu_ms_per_step_events_p10_p50_p90"] = [per_step[int(q * (len(per_step) - 1))] for q in (0.1, 0.5, 0.9)]
-
-    extras = set() if args.no_extras else set(("ranks,uneven,lost,block,stack,kv,kvcache,train,decode,vendor,probe" if args.extras == "all" else args.extras).split(","))
+    extras = set() if args.no_extras else set(("ranks,workloads,sweep,uneven,lost,block,stack,kv,kvcache,train,decode,gather,vendor,probe" if args.extras == "all" else args.extras).split(","))
     if extras:
-        def timed(fn, n, warm=0):
-            for _ in range(1 + warm):      # after host-side set-up the chip is idle: bring it back to its steady clock
-                fn()
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            for _ in range(n):
-                fn()
-            b.record()
-            torch.cuda.synchronize()
-            return a.elapsed_time(b) / n          # ms
-
         # (1) the other simulated devices (under causal masking they see fewer non-local rows)
         if "ranks" in extras and cfg.causal and args.rank < 0:
             per_rank = {}
@@ -230,6 +311,78 @@ def main():
                 del xr, xn, cn
             result["per_rank_ms"] = per_rank
             result["rank_mean_tokens_per_s"] = tq / (sum(per_rank.values()) / len(per_rank) * 1e-3)
+        # (1b) the other named workloads (tiny ViT fp32, ViT-Base bf16 with class rows, GPT-2-small bf16 causal): per layer call on the
+        # last simulated device, tokens/s, TFLOP/s, fraction of the peak of their arithmetic, and the oracle timed beside them
+        def oracle_layer_seconds(lcw, budget_s, max_calls):
+            import oracle
+            c, d, v = lcw["cfg"], lcw["data"], lcw["view"]
+            ch = lcw["codes_nl"].cpu().numpy()
+            ch = (ch.view(np.uint16) if c.codebook_size > 256 else ch).astype(np.int32)
+            oracle.num_threads()
+            n, c0 = 0, time.perf_counter()
+            while n < max_calls and (n == 0 or time.perf_counter() - c0 < budget_s):
+                oracle.layer_forward(v["x_local"], ch, d["codebook"], d["wq"], d["wk"], d["wv"], d["wo"], n_q_heads=c.n_q_heads,
+                                     n_kv_heads=c.n_kv_heads, n_cls=c.n_cls, causal=c.causal, n_before=v["n_before"])
+                n += 1
+            return (time.perf_counter() - c0) / n, n, oracle.num_threads()
+
+        def measure_layer(lcw, n=300, warm=100):
+            c = lcw["cfg"]
+            ms = timed(lambda: B.astra_layer_forward(*lcw["call_args"]), n, warm=warm)
+            fl = layer_flops(c, lcw["view"]["n_before"])
+            tot = sum(fl.values())
+            return ms, fl, tot
+
+        if "workloads" in extras and args.workload == "llama3_8b_bf16":
+            out_w = {}
+            for name in ("tiny_vit_f32", "vit_base_bf16", "gpt2_small_bf16"):
+                c = wl.CONFIGS[name]
+                lcw = make_layer_call(c, c.n_dev - 1)
+                ms, fl, tot = measure_layer(lcw)
+                st_med, _, _ = stage_times(lcw, N_EVENT_CALLS)
+                x_enc = lcw["x_local"][c.n_cls:]
+                enc_ms = timed(lambda: B.astra_vq_encode(lcw["vq"], x_enc, lcw["tq"] - c.n_cls, lcw["codebook"], lcw["cnorm"],
+                                                         lcw["codes_local"]), 100, warm=20)
+                pk = PEAK_TFLOPS[c.dtype]
+                entry = {"rank": c.n_dev - 1, "local_rows": lcw["tq"], "nonlocal_rows": lcw["tn"], "dtype": c.dtype, "us_per_call": ms * 1e3,
+                         "tokens_per_s": lcw["tq"] / (ms * 1e-3), "flops": tot, "tflops": tot / (ms * 1e-3) / 1e12,
+                         "peak_tflops": pk, "frac_of_peak": tot / (ms * 1e-3) / 1e12 / pk,
+                         "bound": "mfma" if c.dtype == "bf16" else "alu",
+                         "encode_fused_into_projection_launch": bool(B.astra_layer_encode_fused(lcw["desc"])),
+                         "stage_us_with_events": {s_: st_med[s_] * 1e3 for s_ in STAGES},
+                         "encode_standalone_us": enc_ms * 1e3, "encode_tflops": fl["vq_encode"] / (enc_ms * 1e-3) / 1e12}
+                if not args.no_cpu_baseline:
+                    sec, n_or, cores = oracle_layer_seconds(lcw, 2.0, 20)
+                    entry["cpu_oracle"] = {"s_per_call": sec, "tokens_per_s": lcw["tq"] / sec, "cores": cores, "calls": n_or}
+                out_w[name] = entry
+                del lcw
+            result["workloads"] = {**out_w, "what": "astra_layer_forward of the other named workloads, last simulated device, "
+                                   "300 back-to-back calls after 100 warm-up calls; stage_us_with_events are HIP-event spans "
+                                   "(each includes one launch gap)"}
+        # (1c) the sweep on the ViT-Base shape: G x K x simulated devices (36 points): time per layer call and the encode alone;
+        # the oracle timed at the three device counts for G = 16, K = 256
+        if "sweep" in extras and args.workload == "llama3_8b_bf16":
+            pts = []
+            for i_dev in range(len(wl.SWEEP_DEVICES)):
+                for i_g in range(len(wl.SWEEP_GROUPS)):
+                    for i_k in range(len(wl.SWEEP_CODEBOOK_SIZES)):
+                        c = wl.sweep_config(i_g, i_k, i_dev)
+                        lcw = make_layer_call(c, c.n_dev - 1)
+                        ms, fl, tot = measure_layer(lcw, n=100, warm=30)
+                        x_enc = lcw["x_local"]
+                        enc_ms = timed(lambda: B.astra_vq_encode(lcw["vq"], x_enc, lcw["tq"], lcw["codebook"], lcw["cnorm"],
+                                                                 lcw["codes_local"]), 50, warm=10)
+                        pt = {"G": c.n_groups, "K": c.codebook_size, "n_dev": c.n_dev, "local_rows": lcw["tq"], "us_per_call": ms * 1e3,
+                              "tokens_per_s": lcw["tq"] / (ms * 1e-3), "tflops": tot / (ms * 1e-3) / 1e12,
+                              "frac_of_peak": tot / (ms * 1e-3) / 1e12 / PEAK_TFLOPS["bf16"],
+                              "encode_us": enc_ms * 1e3, "encode_tflops": fl["vq_encode"] / (enc_ms * 1e-3) / 1e12}
+                        if not args.no_cpu_baseline and c.n_groups == 16 and c.codebook_size == 256:
+                            sec, n_or, cores = oracle_layer_seconds(lcw, 1.0, 10)
+                            pt["cpu_oracle"] = {"s_per_call": sec, "tokens_per_s": lcw["tq"] / sec, "cores": cores, "calls": n_or}
+                        pts.append(pt)
+                        del lcw
+            result["sweep"] = {"points": pts, "what": "ViT-Base shape (D 768, 12 heads of 64, N 1024, non-causal, bf16), last simulated "
+                               "device; codes of the peers from the library's own encode; 100 back-to-back calls each"}
         # an uneven split of the same sequence (App. "heterogeneous devices": token counts in proportion to device speed,
         # FPAR = the fraction of (query, key) pairs that stay at full precision = sum_i n_i^2 / N^2): every device's call
         if "uneven" in extras and cfg.causal and cfg.n_cls == 0 and cfg.n_dev == 4:
@@ -417,6 +570,44 @@ def main():
             result["decode_standalone"] = {"us": ms * 1e3, "algorithmic_bytes": nbytes, "GBps": nbytes / (ms * 1e-3) / 1e9,
                                            "frac_of_hbm_8TBps": nbytes / (ms * 1e-3) / 8e12, "rows": t_v}
             del x_hat
+        # (2b) the same decode over buffers that rotate through more than the 256 MB last-level cache: every call reads its own copy
+        #      of the codes and of the codebook and writes its own output, so that the rate is an HBM rate
+        if "gather" in extras and t_v > 0:
+            eb = 2 if dt == "bf16" else 4
+            per_call = t_v * G * codes_nl.element_size() + G * K * cfg.group_dim * eb + t_v * D * eb
+            n_sets = max(4, int(np.ceil(768e6 / per_call)))
+            sets = [(codes_nl[:t_v].clone(), codebook.clone(), torch.empty((t_v, D), dtype=x_local.dtype, device=dev)) for _ in range(n_sets)]
+            state = {"i": 0}
+
+            def rot():
+                c_, cb_, o_ = sets[state["i"] % n_sets]
+                state["i"] += 1
+                B.astra_vq_decode(vq, c_, t_v, cb_, o_)
+            ms = timed(rot, 10 * n_sets, warm=2 * n_sets)
+            gather = {"us": ms * 1e3, "algorithmic_bytes": per_call, "GBps": per_call / (ms * 1e-3) / 1e9,
+                      "frac_of_hbm_8TBps": per_call / (ms * 1e-3) / 8e12, "rows": t_v, "buffer_sets": n_sets,
+                      "rotating_bytes": n_sets * per_call,
+                      "what": "astra_vq_decode, each call on its own copy of codes, codebook and output (the working set exceeds the "
+                              "256 MB last-level cache)"}
+            if is_bench_shape:
+                tr = traffic_from_profiles("vq_decode_llama3_8b", "vq_decode_kernel")
+                gather["traffic_bytes_from_counters"] = tr
+                # the kernel's average duration in the kernel trace kept under profiles/, and the HBM rate that goes with the counters
+                us_prof = None
+                try:
+                    for ln in open(os.path.join(ROOT, "profiles", "vq_decode_llama3_8b_kernel_trace.txt")):
+                        f_ = ln.split()
+                        if len(f_) >= 6 and "vq_decode_kernel" in ln and f_[0].isdigit():
+                            us_prof = float(f_[1])
+                            break
+                except OSError:
+                    pass
+                gather["kernel_us_in_profile"] = us_prof
+                if tr and us_prof:
+                    gather["hbm_GBps_from_counters"] = tr / (us_prof * 1e-6) / 1e9
+                    gather["hbm_frac_from_counters"] = tr / (us_prof * 1e-6) / 8e12
+            result["decode_rotating_buffers"] = gather
+            del sets
         # a yardstick, not part of the product: the vendor GEMM (torch.matmul -> hipBLASLt / rocBLAS) on the layer's plain
         # products.  It cannot take codes as its row operand, so the K-hat / V-hat product is given rebuilt rows.
         if "vendor" in extras and dt == "bf16":

@@ -122,6 +122,38 @@ def linear(x, w, bias=None):
     return out
 
 
+def project_codebook(codebook, w):
+    """Pre-projected codebooks: P[g, k, :] = codebook[g, k, :] @ w[g*dg:(g+1)*dg, :], fp64 [G, K, D_out].  Written as the
+    definition it comes from: the projection (linear) of the row that holds codeword k in slice g and zeros elsewhere,
+    i.e. that codeword's share of the projection of any rebuilt row (Sec. 3.2: X-hat is rebuilt from the indices and
+    projected with the same weights as the local rows)."""
+    codebook = _f32(codebook)
+    w = _f32(w)
+    G, K, dg = codebook.shape
+    assert w.shape[0] == G * dg
+    out = np.empty((G, K, w.shape[1]), dtype=np.float64)
+    for g in range(G):
+        rows = np.zeros((K, G * dg), dtype=np.float32)
+        rows[:, g * dg:(g + 1) * dg] = codebook[g]
+        out[g] = linear(rows, w)
+    return out
+
+
+def gather_sum(codes, p, bias=None):
+    """out[t, :] = bias + sum_g p[g, codes[t, g], :], fp64 (groups added in ascending order)."""
+    codes = _i32(codes)
+    p = _f64(p)
+    G, K, n = p.shape
+    T = codes.shape[0]
+    assert codes.shape == (T, G) and (T == 0 or (codes.min() >= 0 and codes.max() < K))
+    out = np.zeros((T, n), dtype=np.float64)
+    if bias is not None:
+        out += _f64(bias)[None, :]
+    for g in range(G):
+        out += p[g, codes[:, g], :]
+    return out
+
+
 def _u8(a):
     return None if a is None else np.ascontiguousarray(np.asarray(a) != 0, dtype=np.uint8)
 

@@ -162,7 +162,7 @@ def main():
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the measurements outside the timed region")
     ap.add_argument("--extras", default="all",
-                    help="comma list of the measurements outside the timed region to run: ranks, workloads, sweep, uneven, lost, block, "
+                    help="comma list of the measurements outside the timed region to run: ranks, preprojected, workloads, sweep, uneven, lost, block, "
                          "stack (needs block), kv, kvcache, train, decode, gather, vendor, probe (default all)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the warm-up, run one plain elementwise copy kernel reading and writing this many MiB "
@@ -292,7 +292,7 @@ def main():
                             "after the timed region"},
     }
 
-    extras = set() if args.no_extras else set(("ranks,workloads,sweep,uneven,lost,block,stack,kv,kvcache,train,decode,gather,vendor,probe" if args.extras == "all" else args.extras).split(","))
+    extras = set() if args.no_extras else set(("ranks,preprojected,workloads,sweep,uneven,lost,block,stack,kv,kvcache,train,decode,gather,vendor,probe" if args.extras == "all" else args.extras).split(","))
     if extras:
         # (1) the other simulated devices (under causal masking they see fewer non-local rows)
         if "ranks" in extras and cfg.causal and args.rank < 0:
@@ -333,6 +333,40 @@ def main():
             tot = sum(fl.values())
             return ms, fl, tot
 
+        def preprojected_tables(lcw):
+            c = lcw["cfg"]
+            dkv_ = c.n_kv_heads * c.head_dim
+            pk = torch.empty((c.n_groups, c.codebook_size, dkv_), dtype=torch.float32, device=dev)
+            pv = torch.empty_like(pk)
+            B.astra_vq_project_codebook(lcw["vq"], lcw["codebook"], lcw["w"][1], dkv_, pk)
+            B.astra_vq_project_codebook(lcw["vq"], lcw["codebook"], lcw["w"][2], dkv_, pv)
+            return pk, pv
+
+        # (1a) the benchmark shape with one or two groups (the paper's strongest compression, G = 1): the layer with K-hat, V-hat
+        # projected from rebuilt rows, and with K-hat, V-hat looked up in pre-projected codebooks
+        if "preprojected" in extras and args.workload == "llama3_8b_bf16":
+            import dataclasses
+            out_p = []
+            for g_ in (1, 2):
+                c = dataclasses.replace(cfg, name=f"llama3_8b_bf16_G{g_}", n_groups=g_)
+                d_ = dict(data)
+                d_["codebook"] = wl.round_to_bf16(np.random.default_rng(cfg.seed + 900 + g_).standard_normal(
+                    (g_, c.codebook_size, c.group_dim), dtype=np.float32))
+                lcw = make_layer_call(c, rank, data=d_)
+                ms_gemm = timed(lambda: B.astra_layer_forward(*lcw["call_args"]), 100, warm=30)
+                pk, pv = preprojected_tables(lcw)
+                a_ = lcw["call_args"]
+                pa = (a_[0], a_[1], a_[2], None, a_[3], a_[4], pk, pv, *a_[5:])
+                ms_pre = timed(lambda: B.astra_layer_forward_preprojected(*pa), 100, warm=30)
+                x_enc = lcw["x_local"]
+                ms_enc = timed(lambda: B.astra_vq_encode(lcw["vq"], x_enc, lcw["tq"], lcw["codebook"], lcw["cnorm"], lcw["codes_local"]), 20, warm=5)
+                ms_tab = timed(lambda: preprojected_tables(lcw), 5, warm=1)
+                out_p.append({"G": g_, "K": c.codebook_size, "dg": c.group_dim, "ms_projecting_rebuilt_rows": ms_gemm, "ms_preprojected": ms_pre,
+                              "encode_alone_ms": ms_enc, "tables_once_ms": ms_tab, "table_bytes": 2 * pk.numel() * 4,
+                              "tokens_per_s_preprojected": lcw["tq"] / (ms_pre * 1e-3)})
+                del pk, pv, lcw
+            result["preprojected_codebooks"] = {"cases": out_p, "what": "the benchmark shape with G = 1 and G = 2 (K 1024): astra_layer_forward against "
+                                                "astra_layer_forward_preprojected (K-hat, V-hat = sums of G rows of tables built once per codebook and weights)"}
         if "workloads" in extras and args.workload == "llama3_8b_bf16":
             out_w = {}
             for name in ("tiny_vit_f32", "vit_base_bf16", "gpt2_small_bf16"):
@@ -376,6 +410,13 @@ def main():
                               "tokens_per_s": lcw["tq"] / (ms * 1e-3), "tflops": tot / (ms * 1e-3) / 1e12,
                               "frac_of_peak": tot / (ms * 1e-3) / 1e12 / PEAK_TFLOPS["bf16"],
                               "encode_us": enc_ms * 1e3, "encode_tflops": fl["vq_encode"] / (enc_ms * 1e-3) / 1e12}
+                        if c.group_dim % 64 == 0:
+                            # K-hat / V-hat from pre-projected codebooks (tables built once, outside the timed calls)
+                            pk, pv = preprojected_tables(lcw)
+                            a_ = lcw["call_args"]
+                            pa = (a_[0], a_[1], a_[2], None, a_[3], a_[4], pk, pv, *a_[5:])
+                            pt["us_per_call_preprojected"] = timed(lambda: B.astra_layer_forward_preprojected(*pa), 100, warm=30) * 1e3
+                            del pk, pv
                         if not args.no_cpu_baseline and c.n_groups == 16 and c.codebook_size == 256:
                             sec, n_or, cores = oracle_layer_seconds(lcw, 1.0, 10)
                             pt["cpu_oracle"] = {"s_per_call": sec, "tokens_per_s": lcw["tq"] / sec, "cores": cores, "calls": n_or}

@@ -160,6 +160,32 @@ int astra_layer_forward_valid(const astra_layer_desc* desc, const void* x_local,
                               void* y_out, void* codes_local_out,
                               void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- the peers' K-hat, V-hat from pre-projected codebooks --------------------------------------------
+ * A rebuilt row is a concatenation of codewords (Sec. 3.2, "Vector-Quantized Non-Local Tokens"), so its projection with the
+ * shared W_k, W_v (text under Eq. 1) is a sum of per-group products that do not depend on the token:
+ *     (X-hat W)[t, :] = sum_g codebook[g, codes[t, g], :] . W[g*dg:(g+1)*dg, :] = sum_g P[g, codes[t, g], :].
+ * astra_vq_project_codebook computes P once per (codebook, weights); the layer then only gathers and adds G rows of P per
+ * token and matrix.  With the paper's strongest compression, G = 1 (Tables 1, 3, 6), K-hat and V-hat are pure lookups and
+ * the largest product of the layer disappears; the gather reads G * n_out * 4 bytes per token, so it pays for one or two groups.
+ *   w       [n_out, D] in the element type (stored [out, in] like every weight); n_out a multiple of 8
+ *   p_out   [G, K, n_out] fp32 (the unrounded accumulators; bias is not included)
+ * bf16 needs dg = D / G to be a multiple of 64. */
+int astra_vq_project_codebook(const astra_vq_desc* desc, const void* codebook, const void* w, int32_t n_out, float* p_out,
+                              void* stream);
+
+/* astra_layer_forward_valid with K-hat, V-hat taken from p_k, p_v = astra_vq_project_codebook(codebook, wk | wv)
+ * [G, K, H_kv*dh] instead of projecting rebuilt rows: K-hat[t] = bk + sum_g p_k[g, codes_nonlocal[t, g]] (groups added in
+ * ascending order in fp32, rounded once to the element type), V-hat likewise.  Everything else (encode of the local rows,
+ * Q/K/V of the local rows, Eq. 1, W_o, the arguments, the workspace size) is as in astra_layer_forward_valid; wk, wv are still
+ * needed for the local rows.  The caller keeps p_k, p_v consistent with codebook, wk, wv. */
+int astra_layer_forward_preprojected(const astra_layer_desc* desc, const void* x_local, const void* codes_nonlocal,
+                                     const uint64_t* valid_nonlocal_bits, const void* codebook, const float* cnorm,
+                                     const float* p_k, const float* p_v,
+                                     const void* wq, const void* wk, const void* wv, const void* wo,
+                                     const void* bq, const void* bk, const void* bv, const void* bo,
+                                     void* y_out, void* codes_local_out,
+                                     void* workspace, size_t workspace_bytes, void* stream);
+
 /* astra_layer_forward with stage timing for benchmarks: identical work and results, and in addition
  * seven hipEvent_t (created by the caller with timing enabled, passed as void*; a NULL entry is skipped)
  * are recorded on `stream`: [0] at entry, [1] after the launch that computes the Q/K/V/K-hat/V-hat

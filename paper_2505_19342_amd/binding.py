@@ -15,6 +15,7 @@ _lib = None
 
 EXPORTS = ("astra_vq_prepare", "astra_vq_encode", "astra_vq_decode", "astra_mixed_attention",
            "astra_mixed_attention_valid", "astra_layer_forward_valid",
+           "astra_vq_project_codebook", "astra_layer_forward_preprojected",
            "astra_layer_workspace_bytes", "astra_layer_encode_fused", "astra_layer_forward", "astra_layer_forward_profiled",
            "astra_block_workspace_bytes", "astra_block_forward", "astra_stack_forward",
            "astra_layer_kv_workspace_bytes", "astra_layer_forward_kv",
@@ -91,6 +92,10 @@ def load(build_if_missing: bool = True):
     lib.astra_mixed_attention.argtypes = [ctypes.POINTER(AttnDesc)] + [vp] * 8
     lib.astra_mixed_attention_valid.argtypes = [ctypes.POINTER(AttnDesc)] + [vp] * 9
     lib.astra_layer_forward_valid.argtypes = [ctypes.POINTER(LayerDesc)] + [vp] * 16 + [ctypes.c_size_t, vp]
+    lib.astra_vq_project_codebook.argtypes = [ctypes.POINTER(VqDesc), vp, vp, ctypes.c_int32, vp, vp]
+    lib.astra_vq_project_codebook.restype = ctypes.c_int
+    lib.astra_layer_forward_preprojected.argtypes = [ctypes.POINTER(LayerDesc)] + [vp] * 18 + [ctypes.c_size_t, vp]
+    lib.astra_layer_forward_preprojected.restype = ctypes.c_int
     lib.astra_layer_workspace_bytes.argtypes = [ctypes.POINTER(LayerDesc)]
     lib.astra_layer_workspace_bytes.restype = ctypes.c_size_t
     lib.astra_probe_mfma_bf16.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
@@ -193,6 +198,21 @@ def astra_layer_forward_valid(desc: LayerDesc, x_local, codes_nonlocal, valid_bi
                                             _ptr(codebook), _ptr(cnorm), _ptr(wq), _ptr(wk), _ptr(wv), _ptr(wo),
                                             _ptr(bq), _ptr(bk), _ptr(bv), _ptr(bo), _ptr(y_out), _ptr(codes_local_out),
                                             _ptr(workspace), nbytes, _stream()), "astra_layer_forward_valid")
+
+
+def astra_vq_project_codebook(desc: VqDesc, codebook, w, n_out: int, p_out):
+    _check(load().astra_vq_project_codebook(ctypes.byref(desc), _ptr(codebook), _ptr(w), n_out, _ptr(p_out), _stream()),
+           "astra_vq_project_codebook")
+
+
+def astra_layer_forward_preprojected(desc: LayerDesc, x_local, codes_nonlocal, valid_bits, codebook, cnorm, p_k, p_v, wq, wk, wv, wo,
+                                     bq, bk, bv, bo, y_out, codes_local_out, workspace):
+    nbytes = workspace.numel() * workspace.element_size()
+    _check(load().astra_layer_forward_preprojected(ctypes.byref(desc), _ptr(x_local), _ptr(codes_nonlocal), _ptr(valid_bits),
+                                                   _ptr(codebook), _ptr(cnorm), _ptr(p_k), _ptr(p_v), _ptr(wq), _ptr(wk), _ptr(wv),
+                                                   _ptr(wo), _ptr(bq), _ptr(bk), _ptr(bv), _ptr(bo), _ptr(y_out),
+                                                   _ptr(codes_local_out), _ptr(workspace), nbytes, _stream()),
+           "astra_layer_forward_preprojected")
 
 
 def pack_valid_bits(valid):

@@ -17,7 +17,7 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
 # softmax / argmin arithmetic).  Not for the GEMM: its 256x256 tile on four wavefronts holds 256 accumulator
 # registers per lane, which only fit next to the operands when they live in the accumulation registers.
 VGPR_FORM_FLAGS = ["-mllvm", "-amdgpu-mfma-vgpr-form"]
-ACC_REGISTER_FILES = ("gemm_kernels.hip", "gemm_mlp_kernels.hip")
+ACC_REGISTER_FILES = ("gemm_kernels.hip", "gemm_mlp_kernels.hip", "vq_encode_wide_kernels.hip")
 
 
 def build(verbose: bool = False) -> str:

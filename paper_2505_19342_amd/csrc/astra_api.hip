@@ -239,7 +239,7 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
                               const void* bq, const void* bk, const void* bv, const void* bo,
                               void* y_out, void* codes_local_out, void* workspace, size_t workspace_bytes, void* stream,
                               void* const* ev, int* plan_encode_fused = nullptr, const uint64_t* valid_bits = nullptr,
-                              const float* residual = nullptr) {
+                              const float* residual = nullptr, const float* pre_k = nullptr, const float* pre_v = nullptr) {
     // plan_encode_fused: validate the shapes and report whether the projection launch would carry the encode;
     // nothing is launched and no pointer is dereferenced
     const bool plan_only = plan_encode_fused != nullptr;
@@ -300,9 +300,14 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     local(pr[1], wk, bk, K, pl.dkv);
     local(pr[2], wv, bv, V, pl.dkv);
     if (pl.vt) { pr[2].c_mode = kCTransposedV; pr[2].ldc = pl.ldv_loc; }
+    const bool preprojected = pre_k != nullptr;       // K-hat, V-hat come from pre-projected codebooks: no product of rebuilt rows
     nonlocal_(pr[3], wk, bk, Kh, pl.dkv);
     nonlocal_(pr[4], wv, bv, Vh, pl.dkv);
     if (pl.vt) { pr[4].c_mode = kCTransposedV; pr[4].ldc = pl.ldv_hat; }
+    if (preprojected) {
+        if (pl.dkv % 8 != 0 || (pl.vt && pl.dkv % 64 != 0)) return ASTRA_ERR_UNSUPPORTED;
+        pr[3].M = pr[4].M = 0;
+    }
     AttnParams ap = attn_params(at, Q, K, V, Kh, Vh, O, nullptr);
     ap.v_transposed = pl.vt ? 1 : 0;
     ap.valid_bits = (const unsigned long long*)valid_bits;
@@ -323,12 +328,20 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     }
     if (rc) return rc;
 
-    if (pl.need_xhat && pl.Tn_vis > 0) {
+    if (pl.need_xhat && pl.Tn_vis > 0 && !preprojected) {
         rc = launch_vq_decode(vq, codes_nonlocal, pl.Tn_vis, codebook, Xh, s);
         if (rc) return rc;
     }
     rc = launch_gemm_batch(vq.dtype, pr, 5, s, offer ? &ej : nullptr, offer ? &enc_fused : nullptr, false);
     if (rc) return rc;
+    if (preprojected && pl.Tn_vis > 0) {
+        rc = launch_preproj_gather(vq.dtype, vq.code_type, codes_nonlocal, pre_k, bk, pl.Tn_vis, vq.n_groups, vq.codebook_size, pl.dkv,
+                                   Kh, pl.dkv, false, s);
+        if (rc) return rc;
+        rc = launch_preproj_gather(vq.dtype, vq.code_type, codes_nonlocal, pre_v, bv, pl.Tn_vis, vq.n_groups, vq.codebook_size, pl.dkv,
+                                   Vh, pl.vt ? pl.ldv_hat : pl.dkv, pl.vt, s);
+        if (rc) return rc;
+    }
     mark(1, s);
     mark(5, s);
     if (!enc_fused && at.n_local > 0) {
@@ -347,6 +360,46 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     mark(3, s);
     mark(4, s);
     return rc;
+}
+
+int astra_vq_project_codebook(const astra_vq_desc* desc, const void* codebook, const void* w, int32_t n_out, float* p_out,
+                              void* stream) {
+    int rc = check_vq_desc(desc);
+    if (rc) return rc;
+    if (n_out <= 0 || n_out % 8 != 0) return ASTRA_ERR_SHAPE;
+    if (!codebook || !w || !p_out) return ASTRA_ERR_NULL;
+    const int G = desc->n_groups, K = desc->codebook_size, D = desc->d_model, dg = D / G;
+    const int eb = elem_bytes(desc->dtype);
+    // one product per group: P_g [K, n_out] = C_g [K, dg] . (w[:, g*dg:(g+1)*dg])^T, the weight slice read in place through
+    // its row stride D; fp32 out.  All launches are validated before the first.
+    for (int pass = 0; pass < 2; ++pass) {
+        for (int g0 = 0; g0 < G; g0 += kMaxGemmProblems) {
+            GemmProblem pr[kMaxGemmProblems] = {};
+            const int n = G - g0 < kMaxGemmProblems ? G - g0 : kMaxGemmProblems;
+            for (int i = 0; i < n; ++i) {
+                const int g = g0 + i;
+                pr[i].a = (const char*)codebook + (size_t)g * K * dg * eb;
+                pr[i].b = (const char*)w + (size_t)g * dg * eb;
+                pr[i].c = p_out + (size_t)g * K * n_out;
+                pr[i].M = K; pr[i].N = n_out; pr[i].K = dg; pr[i].lda = dg; pr[i].ldb = D; pr[i].ldc = n_out;
+                pr[i].c_mode = kCF32;
+            }
+            rc = launch_gemm_batch(desc->dtype, pr, n, (hipStream_t)stream, nullptr, nullptr, pass == 0, nullptr, 0, false);
+            if (rc) return rc;
+        }
+    }
+    return ASTRA_OK;
+}
+
+int astra_layer_forward_preprojected(const astra_layer_desc* desc, const void* x_local, const void* codes_nonlocal,
+                                     const uint64_t* valid_nonlocal_bits, const void* codebook, const float* cnorm,
+                                     const float* p_k, const float* p_v,
+                                     const void* wq, const void* wk, const void* wv, const void* wo,
+                                     const void* bq, const void* bk, const void* bv, const void* bo,
+                                     void* y_out, void* codes_local_out, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!p_k || !p_v) return ASTRA_ERR_NULL;
+    return layer_forward_impl(desc, x_local, codes_nonlocal, codebook, cnorm, wq, wk, wv, wo, bq, bk, bv, bo, y_out, codes_local_out,
+                              workspace, workspace_bytes, stream, nullptr, nullptr, valid_nonlocal_bits, nullptr, p_k, p_v);
 }
 
 int astra_probe_mfma_bf16(float* out, int n_blocks, int iters, void* stream) {

@@ -112,11 +112,20 @@ int check_attn_desc(const astra_attn_desc* d);
 int launch_vq_prepare(const astra_vq_desc& d, const void* codebook, float* cnorm, hipStream_t s);
 int launch_vq_encode(const astra_vq_desc& d, const void* x, int64_t ldx, int64_t n_tokens, const void* codebook,
                      const float* cnorm, void* codes, hipStream_t s);
+// wide groups (dg a multiple of 64 above 64), bf16
+bool vq_encode_wide_ok(int K, int dg, int64_t ldx);
+int launch_vq_encode_wide(const astra_vq_desc& d, const void* x, int64_t ldx, int64_t n_tokens, const void* codebook,
+                          const float* cnorm, void* codes, hipStream_t s);
 int launch_vq_decode(const astra_vq_desc& d, const void* codes, int64_t n_tokens, const void* codebook,
                      void* x_hat, hipStream_t s);
 
 int launch_vt_pack(const astra_vq_desc& d, const void* src, int64_t ld_src, const void* codes, const void* codebook, int T, int C,
                    void* dst, int ldv, hipStream_t s);
+
+// out[t, n] = bias[n] + sum_g P[g, codes[t, g], n] with P fp32 [G, K, N]: row-major [T, ld] in the element type, or (transposed,
+// bf16) [N, ld] in the attention kernel's V^T layout
+int launch_preproj_gather(int dtype, int code_type, const void* codes, const float* P, const void* bias, int T, int G, int K, int N,
+                          void* dst, int ld, bool transposed, hipStream_t s);
 
 // One C[M,N] = A[M,K] . B[N,K]^T (+ bias[N]) problem of a grouped launch.  When `codes` is set the
 // rows of A are not read from `a` but rebuilt on the fly: A[m, g*dg + j] = codebook[g, codes[m, g], j].
@@ -136,6 +145,7 @@ struct GemmProblem {
     const void* codebook;
     int32_t M, N, K;
     int32_t lda, ldc;
+    int32_t ldb;        // row stride of B in elements; 0 = K (dense rows)
     int32_t G, Kc, dg, code_bytes;
     int32_t c_mode;     // how C is stored (bf16 problems; fp32 problems always store fp32 row-major)
     int32_t act;        // kAct*

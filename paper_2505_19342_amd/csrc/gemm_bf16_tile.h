@@ -212,7 +212,7 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_nt_bf16_kernel(const G
             col = col < Fh ? col : Fh - 1;
             rb = (b_r >= TN / 2 ? Fh : 0) + col;
         }
-        boff[it] = ((uint32_t)rb * (uint32_t)K + kc * 8) * 2u;
+        boff[it] = ((uint32_t)rb * (uint32_t)(P.ldb ? P.ldb : K) + kc * 8) * 2u;
     }
     int k_code = kc * 8 + kgrp * kBK; // contraction index of this thread's piece in the tile whose codes are fetched next
     int k_use = kc * 8 + kgrp * kBK;  // ... in the tile whose operand pieces are fetched next

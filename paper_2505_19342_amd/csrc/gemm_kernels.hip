@@ -56,7 +56,7 @@ __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmBatch batch)
                     code = code < P.Kc ? code : P.Kc - 1;
                     av[j] = CB[((int64_t)g * P.Kc + code) * P.dg + jj];
                 }
-                bv[j] = B[(int64_t)bn * K + k];
+                bv[j] = B[(int64_t)bn * (P.ldb ? P.ldb : K) + k];
             }
         }
     };
@@ -119,7 +119,8 @@ static int fill_batch(GemmBatch& batch, int dtype, const GemmProblem* problems, 
             if (p.residual && (p.c_mode != kCF32 || p.act != kActNone || (int64_t)p.M * p.ldc * 4 >= lim)) return ASTRA_ERR_UNSUPPORTED;
             if ((p.c_mode == kCTransposedV || p.c_mode == kCSwiGLU) && p.act != kActNone) return ASTRA_ERR_UNSUPPORTED;
             // operands are addressed with 32-bit byte offsets from their base
-            if ((int64_t)p.M * p.lda * 2 >= lim || (int64_t)p.N * p.K * 2 >= lim) return ASTRA_ERR_UNSUPPORTED;
+            if (p.ldb != 0 && (p.ldb < p.K || p.ldb % 8 != 0)) return ASTRA_ERR_UNSUPPORTED;
+            if ((int64_t)p.M * p.lda * 2 >= lim || (int64_t)p.N * (p.ldb ? p.ldb : p.K) * 2 >= lim) return ASTRA_ERR_UNSUPPORTED;
             if (p.codes && ((int64_t)p.G * p.Kc * p.dg * 2 >= lim || (int64_t)p.M * p.G * 2 >= lim)) return ASTRA_ERR_UNSUPPORTED;
         } else if (p.c_mode != kCF32) {
             return ASTRA_ERR_UNSUPPORTED;

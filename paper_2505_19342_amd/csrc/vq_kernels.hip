@@ -167,6 +167,110 @@ int launch_vt_pack(const astra_vq_desc& d, const void* src, int64_t ld_src, cons
 }
 
 // ------------------------------------------------------------------------------------------------
+// Projections of the peers' tokens from pre-projected codebooks.  A rebuilt row is a concatenation of codewords, so its
+// projection is a sum of per-group products that do not depend on the token (paper Sec. 3.2: X-hat is rebuilt from the
+// indices and projected with the same W_k, W_v as the local rows):
+//     (X-hat W)[t, :] = sum_g C_g[codes[t, g], :] . W[g*dg:(g+1)*dg, :] = sum_g P[g, codes[t, g], :],
+// with P [G, K, N] fp32 computed once per (codebook, weights) by astra_vq_project_codebook.  out[t, n] = bias[n] +
+// sum_g P[g, codes[t, g], n], groups added in ascending order in fp32 and rounded once to the element type.  It reads
+// G * N * 4 bytes per token and matrix where the product costs 2 * D * N flops: it pays for one or two groups.
+// A workgroup owns 64 tokens x 64 channels (a thread: 8 channels of a token, twice).  TRANSPOSED (bf16): the tile goes
+// through LDS into the [N, ld] layout with permuted token positions that the attention kernel reads V in (vt_pack_kernel).
+// ------------------------------------------------------------------------------------------------
+template <typename CodeT, typename ElemT, bool TRANSPOSED>
+__global__ __launch_bounds__(256) void preproj_gather_kernel(const CodeT* __restrict__ codes, const float* __restrict__ P,
+                                                             const ElemT* __restrict__ bias, int T, int G, int K, int N,
+                                                             ElemT* __restrict__ dst, int ld) {
+    __shared__ __attribute__((aligned(16))) uint16_t tile[TRANSPOSED ? 64 * kVtStride : 8];
+    const int t0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int piece = tid + 256 * it;
+        const int tl = piece >> 3, pc = piece & 7;
+        const int t = t0 + tl, c = c0 + 8 * pc;
+        float acc[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+        const bool live = t < T && c < N;
+        if (live) {
+            if (bias) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    if constexpr (sizeof(ElemT) == 2) acc[i] = bf16_bits_to_f32(((const uint16_t*)bias)[c + i]);
+                    else acc[i] = ((const float*)bias)[c + i];
+                }
+            }
+            for (int g = 0; g < G; ++g) {
+                int code = (int)codes[(int64_t)t * G + g];
+                code = code < K ? code : K - 1;
+                const float* __restrict__ row = P + ((int64_t)g * K + code) * N + c;
+                const f32x4 lo = *reinterpret_cast<const f32x4*>(row), hi = *reinterpret_cast<const f32x4*>(row + 4);
+                acc[0] += lo.x; acc[1] += lo.y; acc[2] += lo.z; acc[3] += lo.w;
+                acc[4] += hi.x; acc[5] += hi.y; acc[6] += hi.z; acc[7] += hi.w;
+            }
+        }
+        if constexpr (sizeof(ElemT) == 2) {
+            u32x4 v;
+            v.x = pack_bf16x2(acc[0], acc[1]);
+            v.y = pack_bf16x2(acc[2], acc[3]);
+            v.z = pack_bf16x2(acc[4], acc[5]);
+            v.w = pack_bf16x2(acc[6], acc[7]);
+            if constexpr (TRANSPOSED) *reinterpret_cast<u32x4*>(&tile[tl * kVtStride + 8 * pc]) = v;      // zeros beyond T
+            else if (live) *reinterpret_cast<u32x4*>((uint16_t*)dst + (int64_t)t * ld + c) = v;
+        } else if (live) {
+            float* o = (float*)dst + (int64_t)t * ld + c;
+            *reinterpret_cast<f32x4*>(o) = f32x4{acc[0], acc[1], acc[2], acc[3]};
+            *reinterpret_cast<f32x4*>(o + 4) = f32x4{acc[4], acc[5], acc[6], acc[7]};
+        }
+    }
+    if constexpr (TRANSPOSED) {
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int q = tid & 7;                      // which run of 8 positions of the 64 tokens
+            const int c = (tid >> 3) + 32 * it;
+            const int blk = q >> 1, half = q & 1;
+            uint16_t e[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int p = 8 * half + i;
+                const int o = (((p >> 2) & 1) << 3) | ((p >> 3) << 2) | (p & 3);
+                e[i] = tile[(16 * blk + o) * kVtStride + c];
+            }
+            u32x4 w;
+            w.x = e[0] | ((uint32_t)e[1] << 16);
+            w.y = e[2] | ((uint32_t)e[3] << 16);
+            w.z = e[4] | ((uint32_t)e[5] << 16);
+            w.w = e[6] | ((uint32_t)e[7] << 16);
+            *reinterpret_cast<u32x4*>((uint16_t*)dst + (int64_t)(c0 + c) * ld + t0 + 8 * q) = w;
+        }
+    }
+}
+
+// out [T, ld] row-major in the element type, or (transposed, bf16 only) [N, ld] with ld the padded token count.
+int launch_preproj_gather(int dtype, int code_type, const void* codes, const float* P, const void* bias, int T, int G, int K, int N,
+                          void* dst, int ld, bool transposed, hipStream_t s) {
+    if (T < 0 || G <= 0 || K <= 0 || N <= 0 || N % 8 != 0) return ASTRA_ERR_UNSUPPORTED;
+    if (transposed && (dtype != ASTRA_BF16 || N % 64 != 0 || ld % 64 != 0 || ld < T)) return ASTRA_ERR_UNSUPPORTED;
+    if (!transposed && ld < N) return ASTRA_ERR_SHAPE;
+    const int64_t bt = transposed ? ld / 64 : ceil_div(T, 64);
+    if (bt == 0) return ASTRA_OK;
+    if (bt > 0x7fffffff || ceil_div(N, 64) > 65535) return ASTRA_ERR_SHAPE;
+    const dim3 grid((unsigned)bt, (unsigned)ceil_div(N, 64));
+    const bool c16 = code_type == ASTRA_CODE_U16;
+#define ASTRA_GATHER(CT, ET, TR) preproj_gather_kernel<CT, ET, TR><<<grid, 256, 0, s>>>((const CT*)codes, P, (const ET*)bias, T, G, K, N, (ET*)dst, ld)
+    if (dtype == ASTRA_BF16) {
+        if (transposed) { if (c16) ASTRA_GATHER(uint16_t, uint16_t, true); else ASTRA_GATHER(uint8_t, uint16_t, true); }
+        else { if (c16) ASTRA_GATHER(uint16_t, uint16_t, false); else ASTRA_GATHER(uint8_t, uint16_t, false); }
+    } else {
+        if (c16) ASTRA_GATHER(uint16_t, float, false); else ASTRA_GATHER(uint8_t, float, false);
+    }
+#undef ASTRA_GATHER
+    return launch_status();
+}
+
+// ------------------------------------------------------------------------------------------------
 // Encode, fp32: one wavefront per (token, group).  Lanes stride over the codewords and evaluate the
 // definition sum_j (x_j - c_j)^2 directly; the wavefront then reduces (distance, index)
 // lexicographically so that the lowest index wins a tie.
@@ -373,8 +477,9 @@ int launch_vq_encode(const astra_vq_desc& d, const void* x, int64_t ldx, int64_t
             else vq_encode_bf16_fast_kernel<uint16_t><<<total, 256, 0, s>>>(job);
             return launch_status();
         }
-        dim3 grid((unsigned)n_tb, (unsigned)G);
         if (G > 65535) return ASTRA_ERR_SHAPE;
+        if (vq_encode_wide_ok(K, dg, ldx)) return launch_vq_encode_wide(d, x, ldx, n_tokens, codebook, cnorm, codes, s);
+        dim3 grid((unsigned)n_tb, (unsigned)G);
         if (d.code_type == ASTRA_CODE_U8)
             vq_encode_bf16_kernel<uint8_t><<<grid, 256, 0, s>>>((const uint16_t*)x, ldx, (int)n_tokens, (const uint16_t*)codebook,
                                                                 cnorm, (uint8_t*)codes, G, K, dg);

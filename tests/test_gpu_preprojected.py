@@ -1,0 +1,126 @@
+"""GPU parity: K-hat / V-hat of the peers' tokens from pre-projected codebooks (a rebuilt row is a concatenation of
+codewords, Sec. 3.2, so its projection is a sum of per-group table rows; with the paper's G = 1 setting the peers' keys
+and values are pure lookups).  astra_vq_project_codebook against oracle.project_codebook (fp32 accumulation of exact
+products: 1e-5 relative to the table's scale); astra_layer_forward_preprojected against the oracle's LAYER (the path
+must reproduce the layer itself) under the layer's bars: codes bit-exact except near-ties, y within 1e-4 (fp32) / 2e-2
+(bf16); and against the GPU's own product path, which it may differ from only by bf16 rounding boundaries of K-hat / V-hat."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2505_19342_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+Y_TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def tables_on_gpu(layer, data, cfg):
+    import torch
+    from gpu_util import DEV
+    from paper_2505_19342_amd import binding as B
+    G, K = cfg.n_groups, cfg.codebook_size
+    dkv = cfg.n_kv_heads * cfg.head_dim
+    pk = torch.empty((G, K, dkv), dtype=torch.float32, device=DEV)
+    pv = torch.empty((G, K, dkv), dtype=torch.float32, device=DEV)
+    B.astra_vq_project_codebook(layer.desc.vq, layer.codebook, layer.w[1], dkv, pk)
+    B.astra_vq_project_codebook(layer.desc.vq, layer.codebook, layer.w[2], dkv, pv)
+    return pk, pv
+
+
+def run_case(cfg, rank, biases=False, valid=None, check_tables=True):
+    import torch
+    from gpu_util import LayerOnGpu, compare_codes, to_host, valid_bits_to_dev
+    from paper_2505_19342_amd import binding as B
+    data = wl.generate(cfg)
+    view = wl.device_view(cfg, data, rank)
+    codes_nl = oracle.vq_encode(view["x_nonlocal"], data["codebook"])
+    b = None
+    if biases:
+        rng = np.random.default_rng(98)
+        dq, dkv = cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
+        b = [(0.1 * rng.standard_normal(n)).astype(np.float32) for n in (dq, dkv, dkv, cfg.d_model)]
+        if cfg.dtype == "bf16":
+            b = [wl.round_to_bf16(v) for v in b]
+    kw = {} if b is None else dict(bq=b[0], bk=b[1], bv=b[2], bo=b[3])
+    y_ref, codes_ref, gap = oracle.layer_forward(
+        view["x_local"], codes_nl, data["codebook"], data["wq"], data["wk"], data["wv"], data["wo"],
+        n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, n_cls=cfg.n_cls, causal=cfg.causal,
+        n_before=view["n_before"], return_gap=True, valid_nonlocal=valid, **kw)
+    layer = LayerOnGpu(cfg, data, view["x_local"], codes_nl, view["n_before"], biases=b)
+    pk, pv = tables_on_gpu(layer, data, cfg)
+    if check_tables:
+        for got, wname in ((pk, "wk"), (pv, "wv")):
+            ref = oracle.project_codebook(data["codebook"], data[wname])
+            err = np.abs(got.cpu().numpy() - ref).max()
+            assert err <= 1e-5 * max(1.0, np.abs(ref).max()), f"table of {wname}: {err:.3e}"
+    vb = None if valid is None else valid_bits_to_dev(valid)
+    B.astra_layer_forward_preprojected(layer.desc, layer.x_local, layer.codes_nonlocal, vb, layer.codebook, layer.cnorm, pk, pv,
+                                       *layer.w, *layer.b, layer.y, layer.codes_local, layer.workspace)
+    y, codes = layer.results()
+    n_tie = compare_codes(codes, codes_ref, gap, 1e-5)
+    err = np.abs(y - y_ref).max()
+    # the product path on the same inputs: same K-hat / V-hat up to bf16 rounding boundaries
+    layer.y.zero_()
+    layer.run(valid)
+    y_gemm, codes_gemm = layer.results()
+    np.testing.assert_array_equal(codes, codes_gemm)
+    d = np.abs(y - y_gemm).max()
+    print(f"{cfg.name} rank {rank}: max abs err {err:.3e} vs oracle, {d:.3e} vs the product path (|y| max {np.abs(y_ref).max():.3f}), "
+          f"near-tie codes {n_tie}/{codes.size}")
+    assert err <= Y_TOL[cfg.dtype]
+    assert d <= Y_TOL[cfg.dtype] / 4
+    assert n_tie <= max(2, codes.size // 2000)
+
+
+@pytest.mark.parametrize("i_dev", [0, 1, 2])
+@pytest.mark.parametrize("i_k", [0, 1, 2])
+def test_one_group_sweep_points(i_k, i_dev):
+    """The paper's G = 1 setting on the ViT-Base shape: K in {16, 256, 1024} x {2, 4, 8} devices."""
+    run_case(wl.sweep_config(0, i_k, i_dev), 1)
+
+
+def test_two_and_four_groups():
+    run_case(dataclasses.replace(wl.VIT_BASE, name="vit_g2", n_groups=2, seed=71), 2)                  # class row, dg 384
+    run_case(dataclasses.replace(wl.GPT2_SMALL, name="gpt2_g4", n_groups=4, seed=72), 3, biases=True)  # causal, dg 192, biases
+
+
+def test_tiny_vit_f32_and_lost_codes():
+    run_case(dataclasses.replace(wl.TINY_VIT, name="tiny_g1", n_groups=1, seed=73), 1)
+    run_case(wl.TINY_VIT, 2, biases=True)                                                             # G 4, dg 48, fp32
+    cfg = dataclasses.replace(wl.GPT2_SMALL, name="gpt2_g1_lost", n_groups=1, seed=74)
+    valid = (np.random.default_rng(8).random(cfg.n_nonlocal) > 0.1).astype(np.uint8)
+    run_case(cfg, 3, valid=valid)
+
+
+@pytest.mark.parametrize("G,rank", [(1, 3), (2, 1)])
+def test_llama_width(G, rank):
+    """Llama-3-8B widths (D 4096, 32 / 8 heads of 128, K 1024, 16-bit codes, causal) with one and two groups, 1200-token
+    sequence on 4 devices (300 local rows, ragged against every tile)."""
+    cfg = dataclasses.replace(wl.LLAMA3_8B, name=f"llama_g{G}", n_groups=G, seq_len=1200, seed=75 + G)
+    run_case(cfg, rank, check_tables=(G == 1))
+
+
+def test_argument_errors():
+    import torch
+    from gpu_util import DEV, LayerOnGpu
+    from paper_2505_19342_amd import binding as B
+    cfg = wl.VIT_BASE                                           # G 16: groups of 48 values
+    data = wl.generate(cfg)
+    view = wl.device_view(cfg, data, 0)
+    layer = LayerOnGpu(cfg, data, view["x_local"], np.zeros((cfg.n_nonlocal, cfg.n_groups), np.int32), 0)
+    p = torch.empty((cfg.n_groups, cfg.codebook_size, 768), dtype=torch.float32, device=DEV)
+    with pytest.raises(B.AstraError, match="no kernel"):        # bf16 tables need whole 64-wide contraction tiles per group
+        B.astra_vq_project_codebook(layer.desc.vq, layer.codebook, layer.w[1], 768, p)
+    with pytest.raises(B.AstraError, match="NULL"):
+        B.astra_vq_project_codebook(layer.desc.vq, layer.codebook, None, 768, p)
+    with pytest.raises(B.AstraError):
+        B.astra_vq_project_codebook(layer.desc.vq, layer.codebook, layer.w[1], 770, p)
+    layer.y.fill_(-5.0)
+    with pytest.raises(B.AstraError, match="NULL"):
+        B.astra_layer_forward_preprojected(layer.desc, layer.x_local, layer.codes_nonlocal, None, layer.codebook, layer.cnorm, p, None,
+                                           *layer.w, *layer.b, layer.y, layer.codes_local, layer.workspace)
+    torch.cuda.synchronize()
+    assert bool((layer.y == -5.0).all())

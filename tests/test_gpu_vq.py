@@ -35,6 +35,12 @@ ENCODE_CASES = [
     (200, 4, 1024, 192, "bf16", "normal"),        # sweep: dg spans 3 LDS tiles
     (140, 1, 1024, 768, "bf16", "normal"),        # vanilla VQ (G = 1), dg = 768
     (257, 5, 100, 40, "bf16", "normal"),          # K not a multiple of 32, dg not a multiple of 16
+    # wide groups (dg a multiple of 64 above 64): the kernel that streams both operands over dg
+    (300, 1, 1024, 4096, "bf16", "rms_normal"),   # Llama width with the paper's G = 1; ragged token tail
+    (1024, 2, 1024, 2048, "bf16", "rms_normal"),  # G = 2, full row count
+    (37, 3, 1001, 128, "bf16", "normal"),         # K odd: scalar norm loads, last pass ragged against the 32-codeword blocks
+    (65, 2, 2500, 320, "bf16", "normal"),         # three passes over the codewords, odd number of 64-chunks
+    (5, 6, 16, 64 * 3, "bf16", "normal"),         # K below one block of a single wavefront
 ]
 
 
@@ -65,6 +71,25 @@ def test_encode_codewords_and_exact_ties(dtype):
     assert np.array_equal(got, expect)
     assert np.array_equal(got, oracle.vq_encode(x, cb))
     assert np.array_equal(gpu_vq_decode(got, cb, dtype), x)          # decode(encode(c)) == c
+
+
+def test_wide_group_encode_exact_ties_across_wavefronts_and_passes():
+    """Duplicate codewords that land in different half-waves, wavefronts and passes of the wide-group kernel: the lowest
+    index must win every time."""
+    from gpu_util import gpu_vq_encode
+    rng = np.random.default_rng(17)
+    G, K, dg = 2, 2304, 128
+    cb = wl.round_to_bf16(rng.standard_normal((G, K, dg), dtype=np.float32))
+    dup = {5: 4, 200: 9, 1030: 3, 2050: 1029, 2303: 131, 36: 32}        # later index -> the earlier codeword it copies
+    for later, first in dup.items():
+        cb[:, later] = cb[:, first]
+    x = np.concatenate([cb[g] for g in range(G)], axis=1)                   # token k is codeword k in both groups
+    got = gpu_vq_encode(x, cb, "bf16")
+    expect = np.repeat(np.arange(K)[:, None], G, axis=1)
+    for later, first in dup.items():
+        expect[later] = first
+    assert np.array_equal(got, expect)
+    assert np.array_equal(got, oracle.vq_encode(x, cb))
 
 
 DECODE_CASES = [(192, 4, 256, 48, "f32"), (768, 16, 256, 48, "bf16"), (777, 32, 256, 24, "bf16"),

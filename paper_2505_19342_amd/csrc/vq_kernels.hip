@@ -37,14 +37,48 @@ int launch_vq_prepare(const astra_vq_desc& d, const void* codebook, float* cnorm
 }
 
 // ------------------------------------------------------------------------------------------------
-// Decode: a pure gather.  One thread copies one CHUNK-byte piece of one (token, group) row.
-// Consecutive threads write consecutive addresses of x_hat; the lanes of one group row read the same
-// code (a broadcast) and consecutive pieces of one codeword.
+// Decode: a pure gather.  One CHUNK-byte piece of one (token, group) row per thread and pass, kDecUnroll passes per
+// thread a whole grid apart: consecutive threads write consecutive addresses of x_hat; the lanes of one group row read
+// the same code (a broadcast) and consecutive pieces of one codeword.  The passes' code reads, codeword reads and stores
+// are issued as three batches, so that every thread has kDecUnroll independent chains in flight (the step is bound by
+// memory latency times bytes in flight, not by arithmetic); piece -> (token, group, offset) uses multiply-high divisions.
 // ------------------------------------------------------------------------------------------------
+constexpr int kDecUnroll = 4;
+
 template <typename ChunkT, typename CodeT>
-__global__ void vq_decode_kernel(const CodeT* __restrict__ codes, const ChunkT* __restrict__ codebook,
-                                 ChunkT* __restrict__ x_hat, int64_t n_chunks, int chunks_per_token,
-                                 int chunks_per_group, int G, int K) {
+__global__ __launch_bounds__(256) void vq_decode_kernel(const CodeT* __restrict__ codes, const ChunkT* __restrict__ codebook,
+                                                        ChunkT* __restrict__ x_hat, uint32_t n_chunks, uint32_t chunks_per_token,
+                                                        uint32_t chunks_per_group, uint32_t magic_token, uint32_t magic_group, int G, int K) {
+    const uint32_t stride = gridDim.x * 256u;
+    const uint32_t first = blockIdx.x * 256u + threadIdx.x;
+    uint32_t idx[kDecUnroll], src[kDecUnroll];
+    int code[kDecUnroll];
+#pragma unroll
+    for (int u = 0; u < kDecUnroll; ++u) {
+        idx[u] = first + (uint32_t)u * stride;
+        const uint32_t i = idx[u] < n_chunks ? idx[u] : n_chunks - 1;       // clamped, not guarded: the store below is the only guard
+        const uint32_t t = __umulhi(i, magic_token);
+        const uint32_t c = i - t * chunks_per_token;
+        const uint32_t g = __umulhi(c, magic_group);
+        src[u] = g * (uint32_t)K * chunks_per_group + (c - g * chunks_per_group);
+        code[u] = (int)codes[(uint64_t)t * (uint32_t)G + g];
+    }
+    ChunkT v[kDecUnroll];
+#pragma unroll
+    for (int u = 0; u < kDecUnroll; ++u) {
+        const int cd = code[u] < K ? code[u] : K - 1;
+        v[u] = codebook[(uint64_t)src[u] + (uint64_t)cd * chunks_per_group];
+    }
+#pragma unroll
+    for (int u = 0; u < kDecUnroll; ++u)
+        if (idx[u] < n_chunks) x_hat[idx[u]] = v[u];
+}
+
+// one thread per piece, 64-bit indices: shapes beyond 2^31 pieces
+template <typename ChunkT, typename CodeT>
+__global__ void vq_decode_big_kernel(const CodeT* __restrict__ codes, const ChunkT* __restrict__ codebook,
+                                     ChunkT* __restrict__ x_hat, int64_t n_chunks, int chunks_per_token,
+                                     int chunks_per_group, int G, int K) {
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= n_chunks) return;
     const int64_t t = idx / chunks_per_token;
@@ -56,6 +90,19 @@ __global__ void vq_decode_kernel(const CodeT* __restrict__ codes, const ChunkT* 
     x_hat[idx] = codebook[((int64_t)g * K + code) * chunks_per_group + r];
 }
 
+// floor(n / d) == umulhi(n, magic) with magic = floor(2^32 / d) + 1 for every n <= n_max as long as
+// n_max * (magic * d - 2^32) < 2^32 (the estimate's excess stays below 1 / d); false when that cannot be guaranteed or d < 2
+// (the caller then runs the kernel with 64-bit divisions)
+static bool magic_div(uint32_t d, uint64_t n_max, uint32_t* magic) {
+    if (d < 2) return false;
+    const uint64_t m = ((uint64_t)1 << 32) / d + 1;
+    // error of the estimate: n * (m * d - 2^32) / (2^32 * d) must stay below 1 / d  <=>  n * (m * d - 2^32) < 2^32
+    const uint64_t e = m * d - ((uint64_t)1 << 32);
+    if (m > 0xffffffffull || n_max * e >= ((uint64_t)1 << 32)) return false;
+    *magic = (uint32_t)m;
+    return true;
+}
+
 template <typename ChunkT>
 static int decode_dispatch(const astra_vq_desc& d, const void* codes, int64_t n_tokens, const void* codebook,
                            void* x_hat, hipStream_t s) {
@@ -65,13 +112,28 @@ static int decode_dispatch(const astra_vq_desc& d, const void* codes, int64_t n_
     const int cpt = cpg * d.n_groups;
     const int64_t n_chunks = n_tokens * cpt;
     const int threads = 256;
+    uint32_t magic_t = 0, magic_g = 0;
+    const int64_t cb_chunks = (int64_t)d.n_groups * d.codebook_size * cpg;
+    if (n_chunks < ((int64_t)1 << 31) && cb_chunks < ((int64_t)1 << 32) && magic_div((uint32_t)cpt, (uint64_t)n_chunks, &magic_t) &&
+        magic_div((uint32_t)cpg, (uint64_t)cpt, &magic_g)) {
+        const int64_t blocks = ceil_div(n_chunks, threads * kDecUnroll);
+        if (d.code_type == ASTRA_CODE_U8)
+            vq_decode_kernel<ChunkT, uint8_t><<<(int)blocks, threads, 0, s>>>(
+                (const uint8_t*)codes, (const ChunkT*)codebook, (ChunkT*)x_hat, (uint32_t)n_chunks, (uint32_t)cpt, (uint32_t)cpg, magic_t,
+                magic_g, d.n_groups, d.codebook_size);
+        else
+            vq_decode_kernel<ChunkT, uint16_t><<<(int)blocks, threads, 0, s>>>(
+                (const uint16_t*)codes, (const ChunkT*)codebook, (ChunkT*)x_hat, (uint32_t)n_chunks, (uint32_t)cpt, (uint32_t)cpg, magic_t,
+                magic_g, d.n_groups, d.codebook_size);
+        return launch_status();
+    }
     const int64_t blocks = ceil_div(n_chunks, threads);
     if (blocks > 0x7fffffff) return ASTRA_ERR_SHAPE;
     if (d.code_type == ASTRA_CODE_U8)
-        vq_decode_kernel<ChunkT, uint8_t><<<(int)blocks, threads, 0, s>>>(
+        vq_decode_big_kernel<ChunkT, uint8_t><<<(int)blocks, threads, 0, s>>>(
             (const uint8_t*)codes, (const ChunkT*)codebook, (ChunkT*)x_hat, n_chunks, cpt, cpg, d.n_groups, d.codebook_size);
     else
-        vq_decode_kernel<ChunkT, uint16_t><<<(int)blocks, threads, 0, s>>>(
+        vq_decode_big_kernel<ChunkT, uint16_t><<<(int)blocks, threads, 0, s>>>(
             (const uint16_t*)codes, (const ChunkT*)codebook, (ChunkT*)x_hat, n_chunks, cpt, cpg, d.n_groups, d.codebook_size);
     return launch_status();
 }

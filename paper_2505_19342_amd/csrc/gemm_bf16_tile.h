@@ -109,7 +109,7 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_nt_bf16_kernel(const G
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;        // MFMA tiles per wavefront
     constexpr int RPP = THREADS / 8;                           // rows staged per pass
     constexpr int PA = BM / RPP, PB = BN / RPP;                // staging passes per thread
-    static_assert(KS == 1 || (KS == 2 && !ENC), "one or two contraction groups");
+    static_assert(KS == 1 || KS == 2, "one or two contraction groups");
     static_assert(RPP % 16 == 0, "direct transfers: the row swizzle has to be periodic in the pass stride");
     __shared__ u32x4 lds_a[2 * KS][BM * kBK / 8];              // [2 * group + buffer]
     __shared__ u32x4 lds_b[2 * KS][BN * kBK / 8];
@@ -128,14 +128,15 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_nt_bf16_kernel(const G
             u32x4* cb = RING_IN_A ? &lds_a[0][0] : &lds_b[0][0];
             f32x4* cn = reinterpret_cast<f32x4*>(RING_IN_A ? &lds_b[0][0] : &lds_a[0][0]);
             const EncodeJob& job = batch.enc;
-            vq_encode_fast_zero_lds<THREADS>(cb);
+            constexpr int WG_THREADS = THREADS * KS;          // the encode uses every wavefront of the workgroup
+            vq_encode_fast_zero_lds<WG_THREADS>(cb);
             __syncthreads();                               // zero fill done before any transfer lands
             const int n_items = job.G * job.n_tb;
             const int chunk = (n_items + batch.n_enc_wgs - 1) / batch.n_enc_wgs;     // consecutive items share the group
             const int hi = min((id.idx + 1) * chunk, n_items);
             for (int item = id.idx * chunk; item < hi; ++item) {
-                if (job.code_bytes == 2) vq_encode_fast_body<THREADS, uint16_t>(job, item / job.n_tb, item % job.n_tb, cb, cn);
-                else vq_encode_fast_body<THREADS, uint8_t>(job, item / job.n_tb, item % job.n_tb, cb, cn);
+                if (job.code_bytes == 2) vq_encode_fast_body<WG_THREADS, uint16_t>(job, item / job.n_tb, item % job.n_tb, cb, cn);
+                else vq_encode_fast_body<WG_THREADS, uint8_t>(job, item / job.n_tb, item % job.n_tb, cb, cn);
                 __syncthreads();                           // all reads of this item's tiles done before the next item's transfers
             }
             return;

@@ -300,20 +300,20 @@ int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hi
             return launch_status();
         }
     }
-    if (plan_only) return ASTRA_OK;
     if (mid) {
+        if (plan_only) return ASTRA_OK;
         if (code16) gemm_nt_bf16_kernel<128, 256, 2, 4, true><<<total, 512, 0, s>>>(batch);
         else gemm_nt_bf16_kernel<128, 256, 2, 4, false><<<total, 512, 0, s>>>(batch);
         return launch_status();
     }
-    if (plan_only) return ASTRA_OK;
     if (big && g_gemm_force_cfg == 2) {
+        if (plan_only) return ASTRA_OK;
         if (code16) gemm_nt_bf16_kernel<256, 256, 2, 2, true><<<total, 256, 0, s>>>(batch);
         else gemm_nt_bf16_kernel<256, 256, 2, 2, false><<<total, 256, 0, s>>>(batch);
         return launch_status();
     }
     if (big) {
-        if (total == 0) return ASTRA_OK;
+        if (total == 0 || plan_only) return ASTRA_OK;
         if (code16) gemm_nt_bf16_kernel<256, 256, 2, 4, true><<<total, 512, 0, s>>>(batch);
         else gemm_nt_bf16_kernel<256, 256, 2, 4, false><<<total, 512, 0, s>>>(batch);
         return launch_status();
@@ -326,9 +326,33 @@ int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hi
     bool ks2 = total <= kCus;
     for (int i = 0; i < batch.n; ++i) ks2 = ks2 && batch.p[i].K % (2 * kBK) == 0;
     if (ks2) {
+        // a single round that leaves compute units idle: they take the encode of the local rows, as in the large-tile launches
+        // (an item = 256 tokens of one group; about 1 us per 2^20 codeword elements; a 128 x 128 tile about 48 us per 4096 of
+        // contraction plus 8 us of fixed cost)
+        if (enc && enc_fused && g_gemm_force_cfg < 0 && vq_encode_fast_ok(enc->K, enc->dg) && enc->n_tokens > 0) {
+            const int E = (kCus - total) & ~7;
+            const int64_t n_tb = ceil_div(enc->n_tokens, 256);
+            int k_max = 0;
+            for (int i = 0; i < batch.n; ++i) k_max = batch.p[i].K > k_max ? batch.p[i].K : k_max;
+            const double tile_us = 48.0 * k_max / 4096.0 + 8.0;
+            const double enc_us = E > 0 ? (double)ceil_div(n_tb * enc->G, (int64_t)E) * 256.0 * enc->K * enc->dg / 1048576.0 + 4.0 : 0.0;
+            if (E >= 8 && n_tb * enc->G <= 0x7fffffff && enc_us <= tile_us) {
+                batch.n_enc_wgs = E;
+                batch.enc = *enc;
+                batch.enc.n_tb = (int)n_tb;
+                batch.enc.n_wgs = E;
+                *enc_fused = true;
+                if (plan_only) return ASTRA_OK;
+                if (code16) gemm_nt_bf16_kernel<128, 128, 2, 2, true, true, kEpiLayer, 2><<<total + E, 512, 0, s>>>(batch);
+                else gemm_nt_bf16_kernel<128, 128, 2, 2, false, true, kEpiLayer, 2><<<total + E, 512, 0, s>>>(batch);
+                return launch_status();
+            }
+        }
+        if (plan_only) return ASTRA_OK;
         if (code16) gemm_nt_bf16_kernel<128, 128, 2, 2, true, false, kEpiLayer, 2><<<total, 512, 0, s>>>(batch);
         else gemm_nt_bf16_kernel<128, 128, 2, 2, false, false, kEpiLayer, 2><<<total, 512, 0, s>>>(batch);
     } else {
+        if (plan_only) return ASTRA_OK;
         if (code16) gemm_nt_bf16_kernel<128, 128, 4, 2, true><<<total, 512, 0, s>>>(batch);
         else gemm_nt_bf16_kernel<128, 128, 4, 2, false><<<total, 512, 0, s>>>(batch);
     }

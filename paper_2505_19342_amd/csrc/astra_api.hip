@@ -49,9 +49,10 @@ static AttnParams attn_params(const astra_attn_desc& d, const void* q, const voi
 struct LayerPlan {
     int Tq, Tn, Tn_vis, D, dq, dkv;
     bool need_xhat;
+    bool wide_enc;           // wide groups: the encode runs as score products + an argmin pass over scores kept in the workspace
     bool vt;                 // V, V-hat kept transposed for the attention kernel (bf16)
     int ldv_loc, ldv_hat;    // padded token counts of the transposed V buffers
-    size_t off_q, off_k, off_v, off_kh, off_vh, off_o, off_xhat, total;
+    size_t off_q, off_k, off_v, off_kh, off_vh, off_o, off_xhat, off_scores, total;
 };
 
 static int make_plan(const astra_layer_desc* desc, LayerPlan* pl) {
@@ -84,6 +85,11 @@ static int make_plan(const astra_layer_desc* desc, LayerPlan* pl) {
     pl->off_vh = take((size_t)(pl->vt ? pl->ldv_hat : pl->Tn_vis) * pl->dkv * eb);
     pl->off_o = take((size_t)pl->Tq * pl->dq * eb);
     pl->off_xhat = take(pl->need_xhat ? (size_t)pl->Tn_vis * pl->D * eb : 0);
+    // scores [T_l, G, K] fp32 of the wide-group encode (few groups: the buffer is T_l * G * K * 4 bytes, capped at 256 MiB)
+    pl->wide_enc = desc->vq.dtype == ASTRA_BF16 && vq_encode_wide_ok(desc->vq.codebook_size, dg, pl->D) && a.n_local > 0 &&
+                   desc->vq.codebook_size % 8 == 0 &&
+                   (size_t)a.n_local * desc->vq.n_groups * desc->vq.codebook_size * 4 <= ((size_t)256 << 20);
+    pl->off_scores = take(pl->wide_enc ? (size_t)a.n_local * desc->vq.n_groups * desc->vq.codebook_size * 4 : 0);
     pl->total = off > 0 ? off : 256;
     return ASTRA_OK;
 }
@@ -282,7 +288,8 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     bool enc_fused = false;
 
     // 2. projections: Q, K, V of local rows; K-hat, V-hat of the rows rebuilt from the peers' codes
-    GemmProblem pr[5] = {};
+    GemmProblem pr[kMaxGemmProblems] = {};
+    int n_pr = 5;
     auto local = [&](GemmProblem& g, const void* w, const void* b, void* c, int n) {
         g.a = x_local; g.b = w; g.bias = b; g.c = c; g.M = pl.Tq; g.N = n; g.K = pl.D; g.lda = pl.D; g.ldc = n;
         g.c_mode = vq.dtype == ASTRA_BF16 ? kCBf16 : kCF32;
@@ -308,6 +315,23 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
         if (pl.dkv % 8 != 0 || (pl.vt && pl.dkv % 64 != 0)) return ASTRA_ERR_UNSUPPORTED;
         pr[3].M = pr[4].M = 0;
     }
+    // Wide groups (few groups of 128 values or more, down to the paper's G = 1): the distance matrix of a group is a product of
+    // its own, scores[t, g, k] = x[t, slice g] . codebook[g, k, :] (fp32, workspace), followed by one argmin pass over
+    // ||c||^2 - 2 score.  With one group the product rides in the projection launch as a sixth problem (its tiles land on compute
+    // units the projections leave idle); with more it is launched on its own, up to six groups at a time.
+    float* scores = (float*)(ws + pl.off_scores);
+    const int Kc = vq.codebook_size, dg_ = pl.D / vq.n_groups;
+    auto score_problem = [&](GemmProblem& g, int grp) {
+        g = GemmProblem{};
+        g.a = (const char*)ej.x + (size_t)grp * dg_ * eb; g.lda = pl.D;
+        g.b = (const char*)codebook + (size_t)grp * Kc * dg_ * eb; g.ldb = dg_;
+        g.c = scores + (size_t)grp * Kc; g.ldc = vq.n_groups * Kc;
+        g.M = at.n_local; g.N = Kc; g.K = dg_; g.c_mode = kCF32;
+    };
+    const bool scores_in_projection_launch = pl.wide_enc && vq.n_groups == 1;
+    if (scores_in_projection_launch) score_problem(pr[n_pr++], 0);
+    const bool offer_fused = offer && !pl.wide_enc;
+
     AttnParams ap = attn_params(at, Q, K, V, Kh, Vh, O, nullptr);
     ap.v_transposed = pl.vt ? 1 : 0;
     ap.valid_bits = (const unsigned long long*)valid_bits;
@@ -319,7 +343,15 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     po.residual = residual; // inside a block: y_out = residual + layer output
 
     // every launch of the layer is validated before the first one runs: an error leaves all outputs untouched
-    rc = launch_gemm_batch(vq.dtype, pr, 5, s, offer ? &ej : nullptr, offer ? &enc_fused : nullptr, true);
+    rc = launch_gemm_batch(vq.dtype, pr, n_pr, s, offer_fused ? &ej : nullptr, offer_fused ? &enc_fused : nullptr, true);
+    if (rc == ASTRA_OK && pl.wide_enc && !scores_in_projection_launch) {
+        for (int g0 = 0; g0 < vq.n_groups && rc == ASTRA_OK; g0 += kMaxGemmProblems) {
+            GemmProblem sp[kMaxGemmProblems];
+            const int n = vq.n_groups - g0 < kMaxGemmProblems ? vq.n_groups - g0 : kMaxGemmProblems;
+            for (int i = 0; i < n; ++i) score_problem(sp[i], g0 + i);
+            rc = launch_gemm_batch(vq.dtype, sp, n, s, nullptr, nullptr, true, nullptr, 0, false);
+        }
+    }
     if (rc == ASTRA_OK) rc = launch_attention(vq.dtype, ap, at.head_dim, s, true);
     if (rc == ASTRA_OK) rc = launch_gemm_batch(vq.dtype, &po, 1, s, nullptr, nullptr, true);
     if (plan_only) {
@@ -332,7 +364,7 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
         rc = launch_vq_decode(vq, codes_nonlocal, pl.Tn_vis, codebook, Xh, s);
         if (rc) return rc;
     }
-    rc = launch_gemm_batch(vq.dtype, pr, 5, s, offer ? &ej : nullptr, offer ? &enc_fused : nullptr, false);
+    rc = launch_gemm_batch(vq.dtype, pr, n_pr, s, offer_fused ? &ej : nullptr, offer_fused ? &enc_fused : nullptr, false);
     if (rc) return rc;
     if (preprojected && pl.Tn_vis > 0) {
         rc = launch_preproj_gather(vq.dtype, vq.code_type, codes_nonlocal, pre_k, bk, pl.Tn_vis, vq.n_groups, vq.codebook_size, pl.dkv,
@@ -344,7 +376,19 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     }
     mark(1, s);
     mark(5, s);
-    if (!enc_fused && at.n_local > 0) {
+    if (pl.wide_enc) {
+        if (!scores_in_projection_launch) {
+            for (int g0 = 0; g0 < vq.n_groups; g0 += kMaxGemmProblems) {
+                GemmProblem sp[kMaxGemmProblems];
+                const int n = vq.n_groups - g0 < kMaxGemmProblems ? vq.n_groups - g0 : kMaxGemmProblems;
+                for (int i = 0; i < n; ++i) score_problem(sp[i], g0 + i);
+                rc = launch_gemm_batch(vq.dtype, sp, n, s, nullptr, nullptr, false, nullptr, 0, false);
+                if (rc) return rc;
+            }
+        }
+        rc = launch_vq_argmin_scores(vq, scores, cnorm, at.n_local, codes_local_out, s);
+        if (rc) return rc;
+    } else if (!enc_fused && at.n_local > 0) {
         rc = launch_vq_encode(vq, ej.x, pl.D, at.n_local, codebook, cnorm, codes_local_out, s);
         if (rc) return rc;
     }

@@ -116,6 +116,8 @@ int launch_vq_encode(const astra_vq_desc& d, const void* x, int64_t ldx, int64_t
 bool vq_encode_wide_ok(int K, int dg, int64_t ldx);
 int launch_vq_encode_wide(const astra_vq_desc& d, const void* x, int64_t ldx, int64_t n_tokens, const void* codebook,
                           const float* cnorm, void* codes, hipStream_t s);
+// codes[t, g] = argmin_k cnorm[g, k] - 2 scores[t, g, k] (lowest k on ties); scores fp32 [T, G, K]
+int launch_vq_argmin_scores(const astra_vq_desc& d, const float* scores, const float* cnorm, int64_t n_tokens, void* codes, hipStream_t s);
 int launch_vq_decode(const astra_vq_desc& d, const void* codes, int64_t n_tokens, const void* codebook,
                      void* x_hat, hipStream_t s);
 

@@ -155,4 +155,48 @@ int launch_vq_encode_wide(const astra_vq_desc& d, const void* x, int64_t ldx, in
     return launch_status();
 }
 
+// The second half of the encode when the distance products were run as matrix products of their own (wide groups inside the
+// layer): one wavefront per (token, group) walks the K scores x.c, forms ||c||^2 - 2 x.c in fp32 and keeps the smallest, lowest
+// index first (strict '<' in ascending order per lane, lanes merged by (distance, index)).
+template <typename CodeT>
+__global__ __launch_bounds__(256) void vq_argmin_scores_kernel(const float* __restrict__ scores, const float* __restrict__ cnorm,
+                                                               CodeT* __restrict__ codes, int64_t n_rows, int G, int K) {
+    const int64_t row = ((int64_t)blockIdx.x * 256 + threadIdx.x) / kWave;        // (token, group)
+    if (row >= n_rows) return;
+    const int lane = lane_id();
+    const int g = (int)(row % G);
+    const float* __restrict__ sr = scores + row * K;
+    const float* __restrict__ cn = cnorm + (int64_t)g * K;
+    float best = INFINITY;
+    int arg = 0x7fffffff;
+    for (int k0 = 4 * lane; k0 < K; k0 += 4 * kWave) {                         // K is a multiple of 4
+        const f32x4 sv = *reinterpret_cast<const f32x4*>(sr + k0);
+        const f32x4 cv = *reinterpret_cast<const f32x4*>(cn + k0);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float d = fmaf(-2.f, sv[e], cv[e]);
+            if (d < best) { best = d; arg = k0 + e; }
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        const float ob = __shfl_xor(best, off);
+        const int oa = __shfl_xor(arg, off);
+        if (ob < best || (ob == best && oa < arg)) { best = ob; arg = oa; }
+    }
+    if (lane == 0) codes[row] = (CodeT)arg;
+}
+
+int launch_vq_argmin_scores(const astra_vq_desc& d, const float* scores, const float* cnorm, int64_t n_tokens, void* codes, hipStream_t s) {
+    if (n_tokens == 0) return ASTRA_OK;
+    if (d.codebook_size % 4 != 0) return ASTRA_ERR_UNSUPPORTED;
+    const int64_t rows = n_tokens * d.n_groups;
+    const int64_t blocks = ceil_div(rows, 4);
+    if (blocks > 0x7fffffff) return ASTRA_ERR_SHAPE;
+    if (d.code_type == ASTRA_CODE_U8)
+        vq_argmin_scores_kernel<uint8_t><<<(int)blocks, 256, 0, s>>>(scores, cnorm, (uint8_t*)codes, rows, d.n_groups, d.codebook_size);
+    else
+        vq_argmin_scores_kernel<uint16_t><<<(int)blocks, 256, 0, s>>>(scores, cnorm, (uint16_t*)codes, rows, d.n_groups, d.codebook_size);
+    return launch_status();
+}
+
 }  // namespace astra

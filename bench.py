@@ -406,6 +406,13 @@ def main():
                         x_enc = lcw["x_local"]
                         enc_ms = timed(lambda: B.astra_vq_encode(lcw["vq"], x_enc, lcw["tq"], lcw["codebook"], lcw["cnorm"],
                                                                  lcw["codes_local"]), 50, warm=10)
+                        need_ws = B.astra_vq_encode_workspace_bytes(lcw["vq"], lcw["tq"])
+                        if need_ws > 256:
+                            # wide groups: the encode with a workspace (score products + an argmin pass) is the one the layer itself runs
+                            ews = torch.empty(need_ws, dtype=torch.uint8, device=dev)
+                            enc_ms = timed(lambda: B.astra_vq_encode_ws(lcw["vq"], x_enc, lcw["tq"], lcw["codebook"], lcw["cnorm"],
+                                                                        lcw["codes_local"], ews), 50, warm=10)
+                            del ews
                         pt = {"G": c.n_groups, "K": c.codebook_size, "n_dev": c.n_dev, "local_rows": lcw["tq"], "us_per_call": ms * 1e3,
                               "tokens_per_s": lcw["tq"] / (ms * 1e-3), "tflops": tot / (ms * 1e-3) / 1e12,
                               "frac_of_peak": tot / (ms * 1e-3) / 1e12 / PEAK_TFLOPS["bf16"],

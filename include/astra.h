@@ -94,6 +94,17 @@ int astra_vq_prepare(const astra_vq_desc* desc, const void* codebook, float* cno
 int astra_vq_encode(const astra_vq_desc* desc, const void* x, int64_t n_tokens, const void* codebook,
                     const float* cnorm, void* codes_out, void* stream);
 
+/* astra_vq_encode with scratch memory.  For wide groups in bf16 (dg = D / G a multiple of 64 above 64, K a multiple of 8: few
+ * groups, down to the vanilla VQ of Sec. 2 with G = 1, the setting of the paper's strongest compression) the distance matrix
+ * of a group is a matrix product of its own: scores[t, g, k] = x[t, slice g] . codebook[g, k, :] run on the projection tile
+ * kernel into workspace (fp32, n_tokens * G * K * 4 bytes), followed by one pass that picks argmin_k ||c||^2 - 2 score, lowest k
+ * on ties (used when a group's codebook has at least 2^17 elements; smaller ones are faster in astra_vq_encode's kernels).
+ * Same results as astra_vq_encode under the same near-tie rule; other shapes run astra_vq_encode's kernels and ignore the
+ * workspace.  astra_vq_encode_workspace_bytes: the size needed (256 when unused; 0 on an invalid descriptor). */
+size_t astra_vq_encode_workspace_bytes(const astra_vq_desc* desc, int64_t n_tokens);
+int astra_vq_encode_ws(const astra_vq_desc* desc, const void* x, int64_t n_tokens, const void* codebook, const float* cnorm,
+                       void* codes_out, void* workspace, size_t workspace_bytes, void* stream);
+
 /* VQ decode (Sec. 3.2, "Vector-Quantized Non-Local Tokens"): x_hat_out[t, g*dg:(g+1)*dg] =
  * codebook[g, codes[t, g], :], a bit-exact copy.  A code >= K is a caller error; it is read as K-1
  * so that no access leaves the codebook. */

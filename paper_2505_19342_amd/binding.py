@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libastra_hip.so")
 _lib = None
 
-EXPORTS = ("astra_vq_prepare", "astra_vq_encode", "astra_vq_decode", "astra_mixed_attention",
+EXPORTS = ("astra_vq_prepare", "astra_vq_encode", "astra_vq_encode_workspace_bytes", "astra_vq_encode_ws", "astra_vq_decode", "astra_mixed_attention",
            "astra_mixed_attention_valid", "astra_layer_forward_valid",
            "astra_vq_project_codebook", "astra_layer_forward_preprojected",
            "astra_layer_workspace_bytes", "astra_layer_encode_fused", "astra_layer_forward", "astra_layer_forward_profiled",
@@ -92,6 +92,10 @@ def load(build_if_missing: bool = True):
     lib.astra_mixed_attention.argtypes = [ctypes.POINTER(AttnDesc)] + [vp] * 8
     lib.astra_mixed_attention_valid.argtypes = [ctypes.POINTER(AttnDesc)] + [vp] * 9
     lib.astra_layer_forward_valid.argtypes = [ctypes.POINTER(LayerDesc)] + [vp] * 16 + [ctypes.c_size_t, vp]
+    lib.astra_vq_encode_workspace_bytes.argtypes = [ctypes.POINTER(VqDesc), i64]
+    lib.astra_vq_encode_workspace_bytes.restype = ctypes.c_size_t
+    lib.astra_vq_encode_ws.argtypes = [ctypes.POINTER(VqDesc), vp, i64, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.astra_vq_encode_ws.restype = ctypes.c_int
     lib.astra_vq_project_codebook.argtypes = [ctypes.POINTER(VqDesc), vp, vp, ctypes.c_int32, vp, vp]
     lib.astra_vq_project_codebook.restype = ctypes.c_int
     lib.astra_layer_forward_preprojected.argtypes = [ctypes.POINTER(LayerDesc)] + [vp] * 18 + [ctypes.c_size_t, vp]
@@ -198,6 +202,16 @@ def astra_layer_forward_valid(desc: LayerDesc, x_local, codes_nonlocal, valid_bi
                                             _ptr(codebook), _ptr(cnorm), _ptr(wq), _ptr(wk), _ptr(wv), _ptr(wo),
                                             _ptr(bq), _ptr(bk), _ptr(bv), _ptr(bo), _ptr(y_out), _ptr(codes_local_out),
                                             _ptr(workspace), nbytes, _stream()), "astra_layer_forward_valid")
+
+
+def astra_vq_encode_workspace_bytes(desc: VqDesc, n_tokens: int) -> int:
+    return int(load().astra_vq_encode_workspace_bytes(ctypes.byref(desc), n_tokens))
+
+
+def astra_vq_encode_ws(desc: VqDesc, x, n_tokens: int, codebook, cnorm, codes_out, workspace):
+    nbytes = workspace.numel() * workspace.element_size()
+    _check(load().astra_vq_encode_ws(ctypes.byref(desc), _ptr(x), n_tokens, _ptr(codebook), _ptr(cnorm), _ptr(codes_out),
+                                     _ptr(workspace), nbytes, _stream()), "astra_vq_encode_ws")
 
 
 def astra_vq_project_codebook(desc: VqDesc, codebook, w, n_out: int, p_out):

@@ -86,8 +86,11 @@ static int make_plan(const astra_layer_desc* desc, LayerPlan* pl) {
     pl->off_o = take((size_t)pl->Tq * pl->dq * eb);
     pl->off_xhat = take(pl->need_xhat ? (size_t)pl->Tn_vis * pl->D * eb : 0);
     // scores [T_l, G, K] fp32 of the wide-group encode (few groups: the buffer is T_l * G * K * 4 bytes, capped at 256 MiB)
+    // (with one group the product rides in the projection launch for free; with more it is launches of its own, which pay once
+    // a group's codebook has 2^17 elements or more: below that the kernel that streams the codebook per 32 tokens is faster)
     pl->wide_enc = desc->vq.dtype == ASTRA_BF16 && vq_encode_wide_ok(desc->vq.codebook_size, dg, pl->D) && a.n_local > 0 &&
                    desc->vq.codebook_size % 8 == 0 &&
+                   (desc->vq.n_groups == 1 || (int64_t)desc->vq.codebook_size * dg >= (1 << 17)) &&
                    (size_t)a.n_local * desc->vq.n_groups * desc->vq.codebook_size * 4 <= ((size_t)256 << 20);
     pl->off_scores = take(pl->wide_enc ? (size_t)a.n_local * desc->vq.n_groups * desc->vq.codebook_size * 4 : 0);
     pl->total = off > 0 ? off : 256;
@@ -202,6 +205,50 @@ int astra_vq_encode(const astra_vq_desc* desc, const void* x, int64_t n_tokens, 
     if (n_tokens == 0) return ASTRA_OK;
     if (!x || !codebook || !cnorm || !codes_out) return ASTRA_ERR_NULL;
     return launch_vq_encode(*desc, x, desc->d_model, n_tokens, codebook, cnorm, codes_out, (hipStream_t)stream);
+}
+
+// wide groups with a workspace: score products (up to six groups per launch) + one argmin pass
+static bool encode_ws_applies(const astra_vq_desc& d, int64_t n_tokens) {
+    const int dg = d.d_model / d.n_groups;
+    // the products pay once a group's codebook has 2^17 elements or more; below that the kernel that streams it per 32 tokens wins
+    return d.dtype == ASTRA_BF16 && vq_encode_wide_ok(d.codebook_size, dg, d.d_model) && d.codebook_size % 8 == 0 && n_tokens > 0 &&
+           n_tokens <= 0x7fffffff && (int64_t)d.codebook_size * dg >= (1 << 17);
+}
+
+size_t astra_vq_encode_workspace_bytes(const astra_vq_desc* desc, int64_t n_tokens) {
+    if (check_vq_desc(desc) != ASTRA_OK || n_tokens < 0) return 0;
+    if (!encode_ws_applies(*desc, n_tokens)) return 256;
+    return align_up((size_t)n_tokens * desc->n_groups * desc->codebook_size * sizeof(float), 256);
+}
+
+int astra_vq_encode_ws(const astra_vq_desc* desc, const void* x, int64_t n_tokens, const void* codebook, const float* cnorm,
+                       void* codes_out, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_vq_desc(desc);
+    if (rc) return rc;
+    if (n_tokens < 0) return ASTRA_ERR_SHAPE;
+    if (n_tokens == 0) return ASTRA_OK;
+    if (!x || !codebook || !cnorm || !codes_out) return ASTRA_ERR_NULL;
+    hipStream_t s = (hipStream_t)stream;
+    if (!encode_ws_applies(*desc, n_tokens)) return launch_vq_encode(*desc, x, desc->d_model, n_tokens, codebook, cnorm, codes_out, s);
+    if (!workspace || workspace_bytes < astra_vq_encode_workspace_bytes(desc, n_tokens)) return ASTRA_ERR_WORKSPACE;
+    const int G = desc->n_groups, K = desc->codebook_size, D = desc->d_model, dg = D / G;
+    float* scores = (float*)workspace;
+    for (int pass = 0; pass < 2; ++pass) {           // every launch is validated before the first one runs
+        for (int g0 = 0; g0 < G; g0 += kMaxGemmProblems) {
+            GemmProblem sp[kMaxGemmProblems] = {};
+            const int n = G - g0 < kMaxGemmProblems ? G - g0 : kMaxGemmProblems;
+            for (int i = 0; i < n; ++i) {
+                const int g = g0 + i;
+                sp[i].a = (const char*)x + (size_t)g * dg * 2; sp[i].lda = D;
+                sp[i].b = (const char*)codebook + (size_t)g * K * dg * 2; sp[i].ldb = dg;
+                sp[i].c = scores + (size_t)g * K; sp[i].ldc = G * K;
+                sp[i].M = (int)n_tokens; sp[i].N = K; sp[i].K = dg; sp[i].c_mode = kCF32;
+            }
+            rc = launch_gemm_batch(desc->dtype, sp, n, s, nullptr, nullptr, pass == 0, nullptr, 0, false);
+            if (rc) return rc;
+        }
+    }
+    return launch_vq_argmin_scores(*desc, scores, cnorm, n_tokens, codes_out, s);
 }
 
 int astra_vq_decode(const astra_vq_desc* desc, const void* codes, int64_t n_tokens, const void* codebook,

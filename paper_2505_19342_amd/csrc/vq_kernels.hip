@@ -91,10 +91,15 @@ __global__ void vq_decode_big_kernel(const CodeT* __restrict__ codes, const Chun
 }
 
 // floor(n / d) == umulhi(n, magic) with magic = floor(2^32 / d) + 1 for every n <= n_max as long as
-// n_max * (magic * d - 2^32) < 2^32 (the estimate's excess stays below 1 / d); false when that cannot be guaranteed or d < 2
+// n_max * (magic * d - 2^32) < 2^32 (the estimate's excess stays below 1 / d; for a power of two magic = 2^32 / d is exact);
+// false when that cannot be guaranteed or d < 2
 // (the caller then runs the kernel with 64-bit divisions)
 static bool magic_div(uint32_t d, uint64_t n_max, uint32_t* magic) {
     if (d < 2) return false;
+    if ((((uint64_t)1 << 32) % d) == 0) {           // a power of two: 2^32 / d is exact for every 32-bit n
+        *magic = (uint32_t)(((uint64_t)1 << 32) / d);
+        return true;
+    }
     const uint64_t m = ((uint64_t)1 << 32) / d + 1;
     // error of the estimate: n * (m * d - 2^32) / (2^32 * d) must stay below 1 / d  <=>  n * (m * d - 2^32) < 2^32
     const uint64_t e = m * d - ((uint64_t)1 << 32);

@@ -73,6 +73,36 @@ def test_encode_codewords_and_exact_ties(dtype):
     assert np.array_equal(gpu_vq_decode(got, cb, dtype), x)          # decode(encode(c)) == c
 
 
+@pytest.mark.parametrize("T,G,K,dg", [(300, 1, 1024, 4096), (257, 2, 1000, 384), (100, 7, 1024, 128), (64, 4, 16, 192), (33, 16, 256, 48)])
+def test_encode_with_workspace_matches_oracle_and_the_plain_entry_point(T, G, K, dg):
+    """astra_vq_encode_ws: wide groups run as score products + an argmin pass (seven groups: two launches of products);
+    the last two shapes (a small codebook per group, narrow groups) must fall through to astra_vq_encode's kernels."""
+    import torch
+    from gpu_util import DEV, codes_to_host, compare_codes, empty_codes, gpu_vq_encode, to_dev
+    from paper_2505_19342_amd import binding as B
+    x, cb = make(300 + T + G, T, G, K, dg, "bf16", "normal")
+    ref, gap = oracle.vq_encode(x, cb, return_gap=True)
+    desc = B.vq_desc("bf16", G * dg, G, K)
+    cbd, xd = to_dev(cb, "bf16"), to_dev(x, "bf16")
+    cnorm = torch.empty((G, K), dtype=torch.float32, device=DEV)
+    B.astra_vq_prepare(desc, cbd, cnorm)
+    need = B.astra_vq_encode_workspace_bytes(desc, T)
+    uses_ws = dg % 64 == 0 and dg > 64 and K * dg >= 1 << 17
+    assert need >= (T * G * K * 4 if uses_ws else 256)
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    codes = empty_codes(T, G, K)
+    B.astra_vq_encode_ws(desc, xd, T, cbd, cnorm, codes, ws)
+    torch.cuda.synchronize()
+    got = codes_to_host(codes, K)
+    n_tie = compare_codes(got, ref, gap, NEAR_TIE)
+    assert n_tie <= max(2, ref.size // 2000)
+    plain = gpu_vq_encode(x, cb, "bf16")
+    assert (got != plain).sum() <= max(2, ref.size // 2000)        # both obey the near-tie rule; they may differ only there
+    if uses_ws:
+        with pytest.raises(B.AstraError, match="workspace"):
+            B.astra_vq_encode_ws(desc, xd, T, cbd, cnorm, codes, torch.empty(256, dtype=torch.uint8, device=DEV))
+
+
 def test_wide_group_encode_exact_ties_across_wavefronts_and_passes():
     """Duplicate codewords that land in different half-waves, wavefronts and passes of the wide-group kernel: the lowest
     index must win every time."""

@@ -163,7 +163,7 @@ def main():
                     help="skip the measurements outside the timed region")
     ap.add_argument("--extras", default="all",
                     help="comma list of the measurements outside the timed region to run: ranks, preprojected, workloads, sweep, uneven, lost, block, "
-                         "stack (needs block), kv, kvcache, train, decode, gather, vendor, probe (default all)")
+                         "stack (needs block), kv, kvcache, train, decode, gather, gather_x8, vendor, probe (default all)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the warm-up, run one plain elementwise copy kernel reading and writing this many MiB "
                          "(fp32): the reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -292,7 +292,7 @@ def main():
                             "after the timed region"},
     }
 
-    extras = set() if args.no_extras else set(("ranks,preprojected,workloads,sweep,uneven,lost,block,stack,kv,kvcache,train,decode,gather,vendor,probe" if args.extras == "all" else args.extras).split(","))
+    extras = set() if args.no_extras else set(("ranks,preprojected,workloads,sweep,uneven,lost,block,stack,kv,kvcache,train,decode,gather,gather_x8,vendor,probe" if args.extras == "all" else args.extras).split(","))
     if extras:
         # (1) the other simulated devices (under causal masking they see fewer non-local rows)
         if "ranks" in extras and cfg.causal and args.rank < 0:
@@ -655,6 +655,10 @@ def main():
                     gather["hbm_GBps_from_counters"] = tr / (us_prof * 1e-6) / 1e9
                     gather["hbm_frac_from_counters"] = tr / (us_prof * 1e-6) / 8e12
             del sets
+            result["decode_rotating_buffers"] = gather
+        if "gather_x8" in extras and t_v > 0:
+            eb = 2 if dt == "bf16" else 4
+            gather = result.setdefault("decode_rotating_buffers", {})
             # the same kernel on 8 times the rows (one call moves more than the last-level cache holds): its streaming rate
             # without the fixed cost of a launch that a 10-microsecond kernel is dominated by
             t_big = 8 * t_v
@@ -665,7 +669,6 @@ def main():
             gather["rows_x8"] = {"rows": t_big, "us": ms_big * 1e3, "algorithmic_bytes": big_bytes, "GBps": big_bytes / (ms_big * 1e-3) / 1e9,
                                  "frac_of_hbm_8TBps": big_bytes / (ms_big * 1e-3) / 8e12}
             del codes_big, out_big
-            result["decode_rotating_buffers"] = gather
         # a yardstick, not part of the product: the vendor GEMM (torch.matmul -> hipBLASLt / rocBLAS) on the layer's plain
         # products.  It cannot take codes as its row operand, so the K-hat / V-hat product is given rebuilt rows.
         if "vendor" in extras and dt == "bf16":

@@ -8,31 +8,35 @@
 namespace astra {
 
 // ------------------------------------------------------------------------------------------------
-// ||c||^2 per codeword, fp32.
+// ||c||^2 per codeword, fp32.  Sixteen lanes per codeword read its values in consecutive 16-lane strides (coalesced for wide
+// groups, where one thread per codeword would walk thousands of values alone); each lane adds its values in ascending
+// order with fused multiply-adds, the sixteen partial sums are then added pairwise across lanes: a fixed order.
 // ------------------------------------------------------------------------------------------------
 template <typename T>
-__global__ void vq_cnorm_kernel(const T* __restrict__ codebook, float* __restrict__ cnorm, int64_t n_codewords, int dg) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n_codewords) return;
-    const T* c = codebook + i * dg;
+__global__ __launch_bounds__(256) void vq_cnorm_kernel(const T* __restrict__ codebook, float* __restrict__ cnorm, int64_t n_codewords, int dg) {
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 4;
+    const int sub = threadIdx.x & 15;
+    const int64_t ic = i < n_codewords ? i : n_codewords - 1;         // clamped: every lane takes part in the shuffles
+    const T* c = codebook + ic * dg;
     float s = 0.f;
-    for (int j = 0; j < dg; ++j) {
+    for (int j = sub; j < dg; j += 16) {
         float v;
         if constexpr (sizeof(T) == 2) v = bf16_bits_to_f32(c[j]); else v = c[j];
         s = fmaf(v, v, s);
     }
-    cnorm[i] = s;
+    for (int off = 8; off > 0; off >>= 1) s += __shfl_xor(s, off);
+    if (sub == 0 && i < n_codewords) cnorm[i] = s;
 }
 
 int launch_vq_prepare(const astra_vq_desc& d, const void* codebook, float* cnorm, hipStream_t s) {
     const int64_t n = (int64_t)d.n_groups * d.codebook_size;
     const int dg = d.d_model / d.n_groups;
-    const int threads = 256;
-    const int blocks = (int)ceil_div(n, threads);
+    const int64_t blocks = ceil_div(n * 16, 256);
+    if (blocks > 0x7fffffff) return ASTRA_ERR_SHAPE;
     if (d.dtype == ASTRA_BF16)
-        vq_cnorm_kernel<uint16_t><<<blocks, threads, 0, s>>>((const uint16_t*)codebook, cnorm, n, dg);
+        vq_cnorm_kernel<uint16_t><<<(int)blocks, 256, 0, s>>>((const uint16_t*)codebook, cnorm, n, dg);
     else
-        vq_cnorm_kernel<float><<<blocks, threads, 0, s>>>((const float*)codebook, cnorm, n, dg);
+        vq_cnorm_kernel<float><<<(int)blocks, 256, 0, s>>>((const float*)codebook, cnorm, n, dg);
     return launch_status();
 }
 

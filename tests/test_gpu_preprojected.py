@@ -85,6 +85,7 @@ def test_one_group_sweep_points(i_k, i_dev):
 def test_two_and_four_groups():
     run_case(dataclasses.replace(wl.VIT_BASE, name="vit_g2", n_groups=2, seed=71), 2)                  # class row, dg 384
     run_case(dataclasses.replace(wl.GPT2_SMALL, name="gpt2_g4", n_groups=4, seed=72), 3, biases=True)  # causal, dg 192, biases
+    run_case(dataclasses.replace(wl.GPT2_SMALL, name="gpt2_g4", n_groups=4, seed=72), 0)               # first rank: no visible peer
 
 
 def test_tiny_vit_f32_and_lost_codes():

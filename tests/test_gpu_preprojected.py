@@ -104,6 +104,15 @@ def test_llama_width(G, rank):
     run_case(cfg, rank, check_tables=(G == 1))
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_tables_for_eight_groups_take_two_grouped_launches(dtype):
+    """Eight groups of 128 values: the per-group products run six to a launch (two launches); tables against the oracle's,
+    and the gather-sum over all eight groups through the layer."""
+    cfg = dataclasses.replace(wl.GPT2_SMALL, name=f"g8_{dtype}", dtype=dtype, d_model=1024, n_q_heads=16, n_kv_heads=4, head_dim=64,
+                              n_groups=8, codebook_size=64, seq_len=400, seed=79)
+    run_case(cfg, 2, biases=True)
+
+
 def test_argument_errors():
     import torch
     from gpu_util import DEV, LayerOnGpu

@@ -103,6 +103,34 @@ def test_encode_with_workspace_matches_oracle_and_the_plain_entry_point(T, G, K,
             B.astra_vq_encode_ws(desc, xd, T, cbd, cnorm, codes, torch.empty(256, dtype=torch.uint8, device=DEV))
 
 
+def test_wide_group_encodes_on_seeded_random_shapes():
+    """Twelve seeded shapes with wide groups (token counts, codebook sizes and group widths that are multiples of nothing
+    in particular beyond what the kernels need): astra_vq_encode and astra_vq_encode_ws against the oracle."""
+    import torch
+    from gpu_util import DEV, codes_to_host, compare_codes, empty_codes, gpu_vq_encode, to_dev
+    from paper_2505_19342_amd import binding as B
+    rng = np.random.default_rng(2024)
+    for case in range(12):
+        T = int(rng.integers(1, 400))
+        G = int(rng.integers(1, 5))
+        dg = 64 * int(rng.integers(2, 9))
+        K = 8 * int(rng.integers(1, 330))
+        x, cb = make(900 + case, T, G, K, dg, "bf16", "normal")
+        ref, gap = oracle.vq_encode(x, cb, return_gap=True)
+        got = gpu_vq_encode(x, cb, "bf16")
+        compare_codes(got, ref, gap, NEAR_TIE)
+        desc = B.vq_desc("bf16", G * dg, G, K)
+        cbd, xd = to_dev(cb, "bf16"), to_dev(x, "bf16")
+        cnorm = torch.empty((G, K), dtype=torch.float32, device=DEV)
+        B.astra_vq_prepare(desc, cbd, cnorm)
+        ws = torch.empty(B.astra_vq_encode_workspace_bytes(desc, T), dtype=torch.uint8, device=DEV)
+        codes = empty_codes(T, G, K)
+        B.astra_vq_encode_ws(desc, xd, T, cbd, cnorm, codes, ws)
+        torch.cuda.synchronize()
+        n_tie = compare_codes(codes_to_host(codes, K), ref, gap, NEAR_TIE)
+        print(f"case {case}: T {T} G {G} K {K} dg {dg}: ok ({n_tie} near-ties)")
+
+
 def test_wide_group_encode_exact_ties_across_wavefronts_and_passes():
     """Duplicate codewords that land in different half-waves, wavefronts and passes of the wide-group kernel: the lowest
     index must win every time."""

@@ -282,7 +282,9 @@ int astra_decode_attention(const astra_decode_desc* desc, const void* q, const v
  * as astra_decode_attention; the call allocates and frees nothing.  A shape whose
  * astra_decode_attention_workspace_bytes exceeds the array returns ASTRA_ERR_WORKSPACE before anything is launched
  * (the Llama-3-8B shapes of a 128 K-token cache need about 2.6 MiB).  The array's device address is looked up once
- * per device, on the first call with that device current; a failed lookup returns ASTRA_ERR_HIP.  Nothing in the array
+ * per device, on the first call with that device current (a caller that records calls into a HIP graph makes one call on
+ * the device before it starts capturing, so that the lookup and the kernels' one-time set-up are not part of the capture);
+ * a failed lookup returns ASTRA_ERR_HIP.  Nothing in the array
  * has to start at zero (every call writes what it reads), but all calls on one GPU share it: calls that overlap on one
  * GPU (different streams or threads) race; calls that follow each other on one stream do not. */
 size_t astra_decode_attention_static_max_bytes(void);

@@ -129,14 +129,15 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_nt_bf16_kernel(const G
             f32x4* cn = reinterpret_cast<f32x4*>(RING_IN_A ? &lds_b[0][0] : &lds_a[0][0]);
             const EncodeJob& job = batch.enc;
             constexpr int WG_THREADS = THREADS * KS;          // the encode uses every wavefront of the workgroup
-            vq_encode_fast_zero_lds<WG_THREADS>(cb);
-            __syncthreads();                               // zero fill done before any transfer lands
+            if (vq_encode_fast_needs_zero(job.dg)) {
+                vq_encode_fast_zero_lds<WG_THREADS>(cb);
+                __syncthreads();                           // zero fill done before any transfer lands
+            }
             const int n_items = job.G * job.n_tb;
             const int chunk = (n_items + batch.n_enc_wgs - 1) / batch.n_enc_wgs;     // consecutive items share the group
             const int hi = min((id.idx + 1) * chunk, n_items);
             for (int item = id.idx * chunk; item < hi; ++item) {
-                if (job.code_bytes == 2) vq_encode_fast_body<WG_THREADS, uint16_t>(job, item / job.n_tb, item % job.n_tb, cb, cn);
-                else vq_encode_fast_body<WG_THREADS, uint8_t>(job, item / job.n_tb, item % job.n_tb, cb, cn);
+                vq_encode_fast_body<WG_THREADS>(job, item / job.n_tb, item % job.n_tb, cb, cn);
                 __syncthreads();                           // all reads of this item's tiles done before the next item's transfers
             }
             return;

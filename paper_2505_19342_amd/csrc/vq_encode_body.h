@@ -37,8 +37,12 @@ struct EncodeJob {
 //     doubled (exact in bf16), and the accumulator is preloaded with ||c||^2 straight from LDS, so no
 //     vector-ALU work is spent on forming the score; the argmin costs a compare and two selects per value.
 //   - Codebook tiles and their norms go from global memory straight into a ring of four LDS buffers,
-//     three tiles ahead of the one being multiplied.  Pieces beyond dg are never transferred: those LDS
-//     slots are zeroed once (vq_encode_fast_zero_lds) and meet zero token values.
+//     three tiles ahead of the one being multiplied.  Pieces beyond dg are never transferred; the one such
+//     slot a contraction step can read (dg an odd multiple of 8) is zeroed once by the caller
+//     (vq_encode_fast_zero_lds, when vq_encode_fast_needs_zero) and meets zero token values.
+//   - NKS, the number of contraction steps of 16 (ceil(dg / 16)), is a compile-time value: the tile's work is then
+//     one basic block, and every LDS read of a tile (16 of norms, 4 NKS of codeword fragments) is requested before
+//     its first MFMA, so a wavefront waits for the LDS once per tile, not once per pair of MFMAs.
 // cb_lds: kEncBufs * kEncCbSlots slots, cn_lds: kEncBufs * kEncCnSlots slots.  Ends with every wavefront
 // past its last LDS read only after the caller's next barrier: callers that run several items in a row
 // put a barrier between them.
@@ -47,9 +51,10 @@ template <int THREADS>
 __device__ __forceinline__ void vq_encode_fast_zero_lds(u32x4* cb_lds) {
     for (int i = threadIdx.x; i < kEncBufs * kEncCbSlots; i += THREADS) cb_lds[i] = u32x4{0u, 0u, 0u, 0u};
 }
+__device__ __forceinline__ bool vq_encode_fast_needs_zero(int dg) { return (dg & 8) != 0; }
 
-template <int THREADS, typename CodeT>
-__device__ __forceinline__ void vq_encode_fast_body(const EncodeJob& job, int g, int tb, u32x4* cb_lds, f32x4* cn_lds) {
+template <int THREADS, int NKS>
+__device__ __forceinline__ void vq_encode_fast_body_nks(const EncodeJob& job, int g, int tb, u32x4* cb_lds, f32x4* cn_lds) {
     constexpr int WAVES = THREADS / 64;
     constexpr int TOKENS = WAVES * 32;                  // tokens per workgroup
     constexpr int ITS = kEncCbSlots / THREADS;          // codebook transfers per thread per tile
@@ -60,22 +65,6 @@ __device__ __forceinline__ void vq_encode_fast_body(const EncodeJob& job, int g,
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i32 = lane & 31, h = lane >> 5;
     const int n_pieces = dg >> 3;                       // valid 16-byte pieces per codeword
-    const int n_ks = (dg + 15) >> 4;                    // contraction steps of 16
-
-    // this lane's token (N side), as -2x so that the MFMA accumulates ||c||^2 - 2 x.c
-    const int tok = tb * TOKENS + wave * 32 + i32;
-    const int tok_ld = tok < n_tokens ? tok : n_tokens - 1;
-    const uint16_t* xrow = (const uint16_t*)job.x + (int64_t)tok_ld * job.ldx + (int64_t)g * dg;
-    bf16x8 xfrag[4];
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-        const int k = 16 * ks + 8 * h;
-        u32x4 raw = u32x4{0u, 0u, 0u, 0u};
-        if (k < dg) raw = *reinterpret_cast<const u32x4*>(xrow + k);
-        const bf16x8 xv = __builtin_bit_cast(bf16x8, raw);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) xfrag[ks][e] = (__bf16)(-2.f * (float)xv[e]);
-    }
 
     const char* __restrict__ cb_g = (const char*)((const uint16_t*)job.codebook + (int64_t)g * K * dg);
     const char* __restrict__ cn_g = (const char*)(job.cnorm + (int64_t)g * K);
@@ -89,21 +78,45 @@ __device__ __forceinline__ void vq_encode_fast_body(const EncodeJob& job, int g,
     const int cw_l = tid >> 3;
     const int piece = (tid & 7) ^ enc_swz(cw_l);
     const bool piece_ok = piece < n_pieces;
+    // byte offsets of this thread's pieces in tile 0; a tile further on is a wave-uniform step, and offsets past the
+    // group's last codeword are clamped to its row K-1 (the last tile of a K that is no multiple of 128)
+    uint32_t cb_off[ITS];
+#pragma unroll
+    for (int it = 0; it < ITS; ++it) cb_off[it] = (uint32_t)(cw_l + (THREADS / 8) * it) * row_b + (uint32_t)piece * 16u;
+    const uint32_t cb_off_max = (uint32_t)(K - 1) * row_b + (uint32_t)piece * 16u;
+    const uint32_t cn_off = (uint32_t)(4 * NORM_LANES * wave + 4 * lane) * 4u, cn_off_max = (uint32_t)(K - 4) * 4u;
     auto issue_tile = [&](int t) {
         const int buf = t % kEncBufs;
-        const int cw0 = t * kEncCw;
         const uint32_t base = lds_byte_addr(cb_lds + buf * kEncCbSlots);
+        const uint32_t tile_b = (uint32_t)t * (uint32_t)kEncCw * row_b;
+        if (piece_ok) {
 #pragma unroll
-        for (int it = 0; it < ITS; ++it) {
-            const int cw = min(cw0 + cw_l + (THREADS / 8) * it, K - 1);
-            if (piece_ok)
-                dma_global_to_lds_16(cb_g, (uint32_t)cw * row_b + (uint32_t)piece * 16u, base + (uint32_t)(64 * (wave + WAVES * it)) * 16u);
+            for (int it = 0; it < ITS; ++it)
+                dma_global_to_lds_16(cb_g, min(cb_off[it] + tile_b, cb_off_max), base + (uint32_t)(64 * (wave + WAVES * it)) * 16u);
         }
-        if (lane < NORM_LANES) {                        // 128 norms = WAVES x NORM_LANES lanes x 16 bytes
-            const int cwn = min(cw0 + 4 * NORM_LANES * wave + 4 * lane, K - 4);
-            dma_global_to_lds_16(cn_g, (uint32_t)cwn * 4u, lds_byte_addr(cn_lds + buf * kEncCnSlots) + (uint32_t)wave * (16u * NORM_LANES));
-        }
+        if (lane < NORM_LANES)                          // 128 norms = WAVES x NORM_LANES lanes x 16 bytes
+            dma_global_to_lds_16(cn_g, min(cn_off + (uint32_t)t * (uint32_t)(kEncCw * 4), cn_off_max),
+                                 lds_byte_addr(cn_lds + buf * kEncCnSlots) + (uint32_t)wave * (16u * NORM_LANES));
     };
+    // the first tiles are on their way before the token values are asked for: the two latencies overlap
+#pragma unroll
+    for (int t = 0; t < kEncBufs - 1; ++t)
+        if (t < n_tiles) issue_tile(t);
+
+    // this lane's token (N side), as -2x so that the MFMA accumulates ||c||^2 - 2 x.c
+    const int tok = tb * TOKENS + wave * 32 + i32;
+    const int tok_ld = tok < n_tokens ? tok : n_tokens - 1;
+    const uint16_t* xrow = (const uint16_t*)job.x + (int64_t)tok_ld * job.ldx + (int64_t)g * dg;
+    bf16x8 xfrag[NKS];
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+        const int k = 16 * ks + 8 * h;
+        u32x4 raw = u32x4{0u, 0u, 0u, 0u};
+        if (k < dg) raw = *reinterpret_cast<const u32x4*>(xrow + k);
+        const bf16x8 xv = __builtin_bit_cast(bf16x8, raw);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) xfrag[ks][e] = (__bf16)(-2.f * (float)xv[e]);
+    }
 
     // Running argmin of this lane.  The winner is remembered as (tile, slot) with slot = mb*16 + v, a
     // small compile-time constant per accumulator value, so the loop spends exactly a compare and two
@@ -117,26 +130,31 @@ __device__ __forceinline__ void vq_encode_fast_body(const EncodeJob& job, int g,
         const int cw0 = t * kEncCw;
         const u32x4* __restrict__ cb = cb_lds + buf * kEncCbSlots;
         const f32x4* __restrict__ cnb = cn_lds + buf * kEncCnSlots;
+        // all LDS reads of the tile, in the order the MFMAs use them
         f32x16 acc[4];
+        bf16x8 a[NKS][4];
 #pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
+        for (int mb = 0; mb < 4; ++mb) {
 #pragma unroll
             for (int vq = 0; vq < 4; ++vq) {
                 const f32x4 cn = cnb[mb * 8 + 2 * vq + h];             // rows 32*mb + 8*vq + 4*h .. +3
 #pragma unroll
                 for (int e = 0; e < 4; ++e) acc[mb][4 * vq + e] = cn[e];
             }
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            if (ks < n_ks) {
-#pragma unroll
-                for (int mb = 0; mb < 4; ++mb) {
-                    const int row = mb * 32 + i32;
-                    const bf16x8 a = __builtin_bit_cast(bf16x8, cb[row * 8 + ((2 * ks + h) ^ enc_swz(row))]);
-                    acc[mb] = mfma_32x32x16(a, xfrag[ks], acc[mb]);
-                }
-            }
+            const int row = mb * 32 + i32;
+            a[0][mb] = __builtin_bit_cast(bf16x8, cb[row * 8 + (h ^ enc_swz(row))]);
         }
+#pragma unroll
+        for (int ks = 1; ks < NKS; ++ks)
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb) {
+                const int row = mb * 32 + i32;
+                a[ks][mb] = __builtin_bit_cast(bf16x8, cb[row * 8 + ((2 * ks + h) ^ enc_swz(row))]);
+            }
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks)
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb) acc[mb] = mfma_32x32x16(a[ks][mb], xfrag[ks], acc[mb]);
         const float best_in = best;
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb)
@@ -151,9 +169,6 @@ __device__ __forceinline__ void vq_encode_fast_body(const EncodeJob& job, int g,
         arg_tile = best < best_in ? t : arg_tile;
     };
 
-#pragma unroll
-    for (int t = 0; t < kEncBufs - 1; ++t)
-        if (t < n_tiles) issue_tile(t);
     const int n_full = K / kEncCw;                      // tiles without codewords past K
     for (int t = 0; t < n_tiles; ++t) {
         // tile t has landed once at most the transfers of the (up to two) younger tiles are outstanding
@@ -171,7 +186,20 @@ __device__ __forceinline__ void vq_encode_fast_body(const EncodeJob& job, int g,
     const float ob = __shfl_xor(best, 32);
     const int oa = __shfl_xor(arg, 32);
     if (ob < best || (ob == best && oa < arg)) { best = ob; arg = oa; }
-    if (h == 0 && tok < n_tokens) ((CodeT*)job.codes)[(int64_t)tok * job.G + g] = (CodeT)arg;
+    if (h == 0 && tok < n_tokens) {
+        if (job.code_bytes == 2) ((uint16_t*)job.codes)[(int64_t)tok * job.G + g] = (uint16_t)arg;
+        else ((uint8_t*)job.codes)[(int64_t)tok * job.G + g] = (uint8_t)arg;
+    }
+}
+
+template <int THREADS>
+__device__ __forceinline__ void vq_encode_fast_body(const EncodeJob& job, int g, int tb, u32x4* cb_lds, f32x4* cn_lds) {
+    switch ((job.dg + 15) >> 4) {
+        case 1: vq_encode_fast_body_nks<THREADS, 1>(job, g, tb, cb_lds, cn_lds); break;
+        case 2: vq_encode_fast_body_nks<THREADS, 2>(job, g, tb, cb_lds, cn_lds); break;
+        case 3: vq_encode_fast_body_nks<THREADS, 3>(job, g, tb, cb_lds, cn_lds); break;
+        default: vq_encode_fast_body_nks<THREADS, 4>(job, g, tb, cb_lds, cn_lds); break;
+    }
 }
 
 // true when the fast body handles this configuration

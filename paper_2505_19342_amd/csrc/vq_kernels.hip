@@ -515,7 +515,6 @@ __global__ __launch_bounds__(256) void vq_encode_bf16_kernel(const uint16_t* __r
 // (group, block of 128 tokens).  Workgroup ids are remapped so that all token blocks of a group run on the
 // same XCD and find the group's codebook in that XCD's L2.
 // ------------------------------------------------------------------------------------------------
-template <typename CodeT>
 __global__ __launch_bounds__(256) void vq_encode_bf16_fast_kernel(const EncodeJob job) {
     __shared__ u32x4 cb_lds[kEncBufs * kEncCbSlots];    // 4 x 16 KiB: [128 codewords][8 pieces of 8 bf16], swizzled
     __shared__ f32x4 cn_lds[kEncBufs * kEncCnSlots];    // 4 x 512 B
@@ -523,9 +522,11 @@ __global__ __launch_bounds__(256) void vq_encode_bf16_fast_kernel(const EncodeJo
     const int total = gridDim.x;
     const int q = total / 8, rr = total % 8, xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
     const int vid = xcd < rr ? xcd * (q + 1) + slot : rr * (q + 1) + (xcd - rr) * q + slot;
-    vq_encode_fast_zero_lds<256>(cb_lds);
-    __syncthreads();                                   // zero fill done before any transfer lands
-    vq_encode_fast_body<256, CodeT>(job, vid / job.n_tb, vid % job.n_tb, cb_lds, cn_lds);
+    if (vq_encode_fast_needs_zero(job.dg)) {
+        vq_encode_fast_zero_lds<256>(cb_lds);
+        __syncthreads();                               // zero fill done before any transfer lands
+    }
+    vq_encode_fast_body<256>(job, vid / job.n_tb, vid % job.n_tb, cb_lds, cn_lds);
 }
 
 int launch_vq_encode(const astra_vq_desc& d, const void* x, int64_t ldx, int64_t n_tokens, const void* codebook,
@@ -544,8 +545,7 @@ int launch_vq_encode(const astra_vq_desc& d, const void* x, int64_t ldx, int64_t
             job.n_tokens = (int)n_tokens; job.G = G; job.K = K; job.dg = dg;
             job.code_bytes = d.code_type == ASTRA_CODE_U8 ? 1 : 2;
             job.n_tb = (int)n_tb; job.n_wgs = total;
-            if (d.code_type == ASTRA_CODE_U8) vq_encode_bf16_fast_kernel<uint8_t><<<total, 256, 0, s>>>(job);
-            else vq_encode_bf16_fast_kernel<uint16_t><<<total, 256, 0, s>>>(job);
+            vq_encode_bf16_fast_kernel<<<total, 256, 0, s>>>(job);
             return launch_status();
         }
         if (G > 65535) return ASTRA_ERR_SHAPE;

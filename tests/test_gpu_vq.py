@@ -35,6 +35,11 @@ ENCODE_CASES = [
     (200, 4, 1024, 192, "bf16", "normal"),        # sweep: dg spans 3 LDS tiles
     (140, 1, 1024, 768, "bf16", "normal"),        # vanilla VQ (G = 1), dg = 768
     (257, 5, 100, 40, "bf16", "normal"),          # K not a multiple of 32, dg not a multiple of 16
+    # every contraction-step count of the fast body (dg <= 64), with and without the zero-filled odd piece, ragged K
+    (200, 8, 512, 32, "bf16", "normal"),          # two steps, every slot transferred
+    (150, 3, 260, 56, "bf16", "normal"),          # four steps, the last piece zero-filled; K = 2 tiles + 4 codewords
+    (100, 5, 132, 16, "bf16", "normal"),          # one step; second tile holds 4 codewords
+    (70, 2, 1024, 8, "bf16", "normal"),           # one step, upper half of it zero-filled
     # wide groups (dg a multiple of 64 above 64): the kernel that streams both operands over dg
     (300, 1, 1024, 4096, "bf16", "rms_normal"),   # Llama width with the paper's G = 1; ragged token tail
     (1024, 2, 1024, 2048, "bf16", "rms_normal"),  # G = 2, full row count

@@ -604,7 +604,7 @@ def main():
                 "tokens": tt, "encode_us": ms_e * 1e3, "encode_tflops": 2.0 * tt * K * D / (ms_e * 1e-3) / 1e12,
                 "stats_us": ms_s * 1e3, "stats_algorithmic_bytes": stat_bytes, "stats_GBps": stat_bytes / (ms_s * 1e-3) / 1e9,
                 "stats_frac_of_hbm_8TBps": stat_bytes / (ms_s * 1e-3) / 8e12, "update_us": ms_u * 1e3,
-                "what": "astra_vq_encode + astra_codebook_stats (deterministic: counting sort by code, rows added in token order) + "
+                "what": "astra_vq_encode + astra_codebook_stats (deterministic: counting sort by code, rows added in a fixed order) + "
                         "astra_codebook_update (EMA)"}
             del xt, ct, sm, em, cb2, tws
         # (2) the decode as a kernel of its own (inside the layer it is fused into the projection's operand load):

@@ -49,7 +49,8 @@ def _load():
                      "oracle_mixed_attention", "oracle_mixed_attention_valid",
                      "oracle_layer_forward", "oracle_layer_forward_valid",
                      "oracle_norm", "oracle_mlp", "oracle_block_forward", "oracle_layer_forward_kv",
-                     "oracle_decode_attention", "oracle_codebook_stats", "oracle_codebook_update", "oracle_navq"):
+                     "oracle_decode_attention", "oracle_codebook_stats", "oracle_codebook_update", "oracle_navq",
+                     "oracle_rope", "oracle_layer_forward_rope", "oracle_block_forward_rope"):
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -192,11 +193,12 @@ def mixed_attention(q, k_loc, v_loc, k_hat, v_hat, *, n_cls=0, causal=False, n_b
 
 def layer_forward(x_local, codes_nonlocal, codebook, wq, wk, wv, wo, *, n_q_heads, n_kv_heads,
                   n_cls=0, causal=False, n_before=0, scale=0.0,
-                  bq=None, bk=None, bv=None, bo=None, return_gap=False, valid_nonlocal=None):
+                  bq=None, bk=None, bv=None, bo=None, return_gap=False, valid_nonlocal=None, rope_base=0.0):
     """One device's layer (Sec. 3.1).  Weights in the paper's orientation
     ``[D_in, D_out]``.  Returns (y [T_q, D] fp64, codes_local [T_l, G] int32
     [, gap [T_l, G]]).  valid_nonlocal (optional, [T_n] of 0/1): rows whose codes never
-    arrived (0) are neither looked up nor attended to."""
+    arrived (0) are neither looked up nor attended to.  rope_base > 0 (optional, outside the paper):
+    Q, K and K-hat are rotated by `rope` at their positions in the whole sequence."""
     x_local = _f32(x_local)
     codebook = _f32(codebook)
     codes_nonlocal = _i32(codes_nonlocal)
@@ -215,15 +217,29 @@ def layer_forward(x_local, codes_nonlocal, codebook, wq, wk, wv, wo, *, n_q_head
     gap = np.empty((n_local, G), dtype=np.float64) if return_gap else None
     valid_nonlocal = _u8(valid_nonlocal)
     assert valid_nonlocal is None or valid_nonlocal.shape == (Tn,)
-    rc = _load().oracle_layer_forward_valid(
+    rc = _load().oracle_layer_forward_rope(
         _p(x_local), _p(codes_nonlocal), _p(valid_nonlocal), _p(codebook), D, G, K,
         _p(wq), _p(wk), _p(wv), _p(wo), _p(bq), _p(bk), _p(bv), _p(bo),
         n_q_heads, n_kv_heads, dh, int(n_cls), n_local, Tn,
-        int(bool(causal)), int(n_before), ctypes.c_double(scale),
+        int(bool(causal)), int(n_before), ctypes.c_double(scale), ctypes.c_double(rope_base),
         _p(y), _p(codes_local), _p(gap))
     if rc:
         raise ValueError(f"oracle_layer_forward failed ({rc})")
     return (y, codes_local, gap) if return_gap else (y, codes_local)
+
+
+def rope(mat, pos, n_heads, base=10000.0):
+    """Rotary position embedding (Su et al., RoFormer, Eq. 34, interleaved pairs; not part of the paper): mat [rows,
+    n_heads * head_dim] rotated row by row at the positions pos [rows] (a negative position leaves the row as it is).
+    Returns a new fp64 array."""
+    out = _f64(mat).copy()
+    rows, width = out.shape
+    pos = np.ascontiguousarray(pos, dtype=np.int64)
+    assert pos.shape == (rows,) and width % n_heads == 0
+    rc = _load().oracle_rope(_p(out), ctypes.c_int64(rows), int(n_heads), width // n_heads, _p(pos), ctypes.c_double(base))
+    if rc:
+        raise ValueError(f"oracle_rope failed ({rc})")
+    return out
 
 
 NORM_KINDS = {"layernorm": 0, "rmsnorm": 1}
@@ -259,8 +275,9 @@ def mlp(h, kind, w1, w2, b1=None, b2=None):
 
 def block_forward(x, codes_nonlocal, codebook, wq, wk, wv, wo, *, norm_kind, eps, g1, g2, be1=None, be2=None,
                   mlp_kind, w1, w2, b1=None, b2=None, n_q_heads, n_kv_heads, n_cls=0, causal=False, n_before=0,
-                  scale=0.0, bq=None, bk=None, bv=None, bo=None, valid_nonlocal=None, h_is_bf16=False):
+                  scale=0.0, bq=None, bk=None, bv=None, bo=None, valid_nonlocal=None, h_is_bf16=False, rope_base=0.0):
     """One Transformer block on one device (Sec. 3.1): out = r + mlp(norm2(r)), r = x + layer(norm1(x)).
+    rope_base > 0: the layer rotates Q, K and K-hat (see layer_forward).
     x [T_q, D] is the fp64 residual stream.  Returns (x_out [T_q, D] fp64, codes_local [T_l, G] int32,
     gap [T_l, G], h [T_q, D] fp32 = the normalised tensor that was quantised and projected)."""
     x = _f64(x)
@@ -284,20 +301,20 @@ def block_forward(x, codes_nonlocal, codebook, wq, wk, wv, wo, *, norm_kind, eps
     gap = np.empty((n_local, G), dtype=np.float64)
     valid_nonlocal = _u8(valid_nonlocal)
     assert valid_nonlocal is None or valid_nonlocal.shape == (Tn,)
-    rc = _load().oracle_block_forward(
+    rc = _load().oracle_block_forward_rope(
         _p(x), _p(codes_nonlocal), _p(valid_nonlocal), _p(codebook), D, G, K,
         NORM_KINDS[norm_kind], ctypes.c_double(eps), _p(g1), _p(be1), _p(g2), _p(be2),
         _p(wq), _p(wk), _p(wv), _p(wo), _p(bq), _p(bk), _p(bv), _p(bo),
         MLP_KINDS[mlp_kind], d_ff, _p(w1), _p(b1), _p(w2), _p(b2),
         n_q_heads, n_kv_heads, dh, int(n_cls), n_local, Tn, int(bool(causal)), int(n_before), ctypes.c_double(scale),
-        int(bool(h_is_bf16)), _p(x_out), _p(codes_local), _p(gap), _p(h))
+        int(bool(h_is_bf16)), ctypes.c_double(rope_base), _p(x_out), _p(codes_local), _p(gap), _p(h))
     if rc:
         raise ValueError(f"oracle_block_forward failed ({rc})")
     return x_out, codes_local, gap, h
 
 
 def model_forward(x_all, layers, *, n_dev, n_q_heads, n_kv_heads, norm_kind, eps, mlp_kind, causal=False, cls=None,
-                  h_is_bf16=False, lost=None):
+                  h_is_bf16=False, lost=None, rope_base=0.0):
     """The whole multi-device procedure of Sec. 3.1 simulated on the CPU: the sequence x_all [N, D] (fp64 residual
     stream entering block 0) is cut into n_dev contiguous chunks; per block every device normalises and quantises its
     chunk, the codes are exchanged, and every device runs block_forward on its chunk with the others' codes
@@ -305,11 +322,13 @@ def model_forward(x_all, layers, *, n_dev, n_q_heads, n_kv_heads, norm_kind, eps
     row, never quantised; after the last block the replicas are averaged (Sec. 3.3).
     layers: list of dicts with codebook, wq, wk, wv, wo, g1, g2, w1, w2 and optionally be1, be2, bq, bk, bv, bo, b1, b2.
     lost (optional): lost[l][d] = 0/1 array over device d's non-local tokens at block l (1 = arrived).
+    rope_base > 0 (optional, causal models only, where n_before places every chunk): rotary positions inside every layer.
     Returns dict: x [n_dev][T_q, D] final streams, codes [L][n_dev] (what each device sent), codes_nonlocal [L][n_dev]
     (what each device received), cls_pooled [D] or None."""
     x_all = _f64(x_all)
     N = x_all.shape[0]
     assert N % n_dev == 0
+    assert not rope_base or causal
     tl = N // n_dev
     n_cls = 0 if cls is None else 1
     streams = []
@@ -336,7 +355,7 @@ def model_forward(x_all, layers, *, n_dev, n_q_heads, n_kv_heads, norm_kind, eps
                 g1=p["g1"], g2=p["g2"], be1=opt["be1"], be2=opt["be2"], mlp_kind=mlp_kind, w1=p["w1"], w2=p["w2"],
                 b1=opt["b1"], b2=opt["b2"], n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, n_cls=n_cls, causal=causal,
                 n_before=d * tl if causal else 0, bq=opt["bq"], bk=opt["bk"], bv=opt["bv"], bo=opt["bo"],
-                valid_nonlocal=None if lost is None else lost[l][d], h_is_bf16=h_is_bf16)
+                valid_nonlocal=None if lost is None else lost[l][d], h_is_bf16=h_is_bf16, rope_base=rope_base)
             assert np.array_equal(c_loc, codes[d])          # the block quantises the same tensor phase 1 did
             nxt.append(out)
             rec.append(nl)

@@ -20,6 +20,7 @@
  *   oracle_mixed_attention  Sec. 3.2 Eq. 1, sigma(Q [K | K-hat]^T / sqrt(d_k)) [V | V-hat]
  *   oracle_layer_forward    Sec. 3.1 (per-block procedure on one device)
  *   oracle_block_forward    Sec. 3.1, the whole block: norms, residuals and the local MLP around the layer
+ *   oracle_rope, *_rope     optional rotary position embedding (outside the paper; Su et al., RoFormer, Eq. 34)
  *   oracle_layer_forward_kv the layer with K and V quantised after projection (App. memory cost: C = 2, d = 1024)
  *   oracle_decode_attention one decoding step over a KV cache whose non-local part is VQ indices (App. memory cost)
  *   oracle_codebook_stats / oracle_codebook_update / oracle_navq   training-side VQ operations (Sec. 3.2, Eq. 2, Sec. 3.3)
@@ -215,6 +216,30 @@ int oracle_mixed_attention(const double* q, const double* k_loc, const double* v
                                         n_cls, n_local, n_nonlocal, causal, n_before, scale, out, lse, probs);
 }
 
+/* Rotary position embedding (not part of the paper, which never says how its Llama-shaped model encodes positions; the
+ * published definition of Su et al., "RoFormer", Sec. 3.2.2, Eq. 34, in its original interleaved pairing): every head's
+ * vector x of head_dim values at sequence position m is rotated pair by pair,
+ *     (x[2i], x[2i+1]) -> (x[2i] cos(m t_i) - x[2i+1] sin(m t_i),  x[2i] sin(m t_i) + x[2i+1] cos(m t_i)),   t_i = base^(-2i / head_dim).
+ * mat [rows, n_heads * head_dim] in place; pos[r] = position of row r, a negative value leaves the row as it is. */
+int oracle_rope(double* mat, int64_t rows, int n_heads, int head_dim, const int64_t* pos, double base) {
+    if (head_dim <= 0 || head_dim % 2 != 0 || n_heads <= 0 || !(base > 0.0)) return -1;
+    for (int64_t r = 0; r < rows; ++r) {
+        if (pos[r] < 0) continue;
+        for (int h = 0; h < n_heads; ++h) {
+            double* x = mat + (r * n_heads + h) * head_dim;
+            for (int i = 0; i < head_dim / 2; ++i) {
+                const double theta = pow(base, -2.0 * (double)i / (double)head_dim);
+                const double a = (double)pos[r] * theta;
+                const double c = cos(a), sn = sin(a);
+                const double x0 = x[2 * i], x1 = x[2 * i + 1];
+                x[2 * i] = x0 * c - x1 * sn;
+                x[2 * i + 1] = x0 * sn + x1 * c;
+            }
+        }
+    }
+    return 0;
+}
+
 /* One Astra attention layer on one device (Sec. 3.1):
  *   codes_local = encode(content rows of x_local)        -> what this device transmits
  *   X-hat       = decode(codes_nonlocal)                  -> what it rebuilds from its peers
@@ -222,15 +247,18 @@ int oracle_mixed_attention(const double* q, const double* k_loc, const double* v
  *   K-hat,V-hat = X-hat W_k, X-hat W_v                     (same weights)
  *   Y           = Attn(Q, K, K-hat, V, V-hat) W_o
  * x_local [T_q, D] with the class row (if any) first; weights [D_in, D_out];
- * biases nullable.  y [T_q, D] double, codes_local [n_local, G], gap nullable. */
-int oracle_layer_forward_valid(const float* x_local, const int32_t* codes_nonlocal, const uint8_t* valid_nonlocal,
-                               const float* codebook, int D, int G, int K,
-                         const float* wq, const float* wk, const float* wv, const float* wo,
-                         const float* bq, const float* bk, const float* bv, const float* bo,
-                         int n_q_heads, int n_kv_heads, int head_dim,
-                         int n_cls, int n_local, int n_nonlocal,
-                         int causal, int n_before, double scale,
-                         double* y, int32_t* codes_local, double* gap_local) {
+ * biases nullable.  y [T_q, D] double, codes_local [n_local, G], gap nullable.
+ * rope_base > 0 (optional, outside the paper): Q, K and K-hat are rotated by oracle_rope before the attention, every row
+ * at its position in the whole sequence: local content row i at n_before + i, non-local row j at j when it precedes the
+ * local chunk (j < n_before) and at j + n_local otherwise; a class row has no position and is not rotated. */
+int oracle_layer_forward_rope(const float* x_local, const int32_t* codes_nonlocal, const uint8_t* valid_nonlocal,
+                              const float* codebook, int D, int G, int K,
+                              const float* wq, const float* wk, const float* wv, const float* wo,
+                              const float* bq, const float* bk, const float* bv, const float* bo,
+                              int n_q_heads, int n_kv_heads, int head_dim,
+                              int n_cls, int n_local, int n_nonlocal,
+                              int causal, int n_before, double scale, double rope_base,
+                              double* y, int32_t* codes_local, double* gap_local) {
     const int Tq = n_cls + n_local, Tn = n_nonlocal;
     const int dq = n_q_heads * head_dim, dkv = n_kv_heads * head_dim;
     int rc = oracle_vq_encode(x_local + (int64_t)n_cls * D, n_local, D, G, K, codebook,
@@ -265,12 +293,36 @@ int oracle_layer_forward_valid(const float* x_local, const int32_t* codes_nonloc
     oracle_linear(xl, Tq, D, dkv, wv, bv, Vl);
     oracle_linear(xh, Tn, D, dkv, wk, bk, Kh);
     oracle_linear(xh, Tn, D, dkv, wv, bv, Vh);
-    rc = oracle_mixed_attention_valid(Q, Kl, Vl, Kh, Vh, valid_nonlocal, n_q_heads, n_kv_heads, head_dim,
-                                      n_cls, n_local, n_nonlocal, causal, n_before, scale,
-                                      O, NULL, NULL);
+    if (rope_base > 0.0) {
+        int64_t* pos = (int64_t*)malloc(sizeof(int64_t) * ((int64_t)Tq + Tn + 1));
+        for (int i = 0; i < Tq; ++i) pos[i] = i < n_cls ? -1 : (int64_t)n_before + (i - n_cls);
+        for (int j = 0; j < Tn; ++j) pos[Tq + j] = j < n_before ? j : (int64_t)j + n_local;
+        rc = oracle_rope(Q, Tq, n_q_heads, head_dim, pos, rope_base);
+        if (!rc) rc = oracle_rope(Kl, Tq, n_kv_heads, head_dim, pos, rope_base);
+        if (!rc) rc = oracle_rope(Kh, Tn, n_kv_heads, head_dim, pos + Tq, rope_base);
+        free(pos);
+    }
+    if (!rc)
+        rc = oracle_mixed_attention_valid(Q, Kl, Vl, Kh, Vh, valid_nonlocal, n_q_heads, n_kv_heads, head_dim,
+                                          n_cls, n_local, n_nonlocal, causal, n_before, scale,
+                                          O, NULL, NULL);
     if (!rc) oracle_linear(O, Tq, dq, D, wo, bo, y);
     free(x_hat); free(xl); free(xh); free(Q); free(Kl); free(Vl); free(Kh); free(Vh); free(O);
     return rc;
+}
+
+/* The layer as the paper states it (no positional rotation). */
+int oracle_layer_forward_valid(const float* x_local, const int32_t* codes_nonlocal, const uint8_t* valid_nonlocal,
+                               const float* codebook, int D, int G, int K,
+                         const float* wq, const float* wk, const float* wv, const float* wo,
+                         const float* bq, const float* bk, const float* bv, const float* bo,
+                         int n_q_heads, int n_kv_heads, int head_dim,
+                         int n_cls, int n_local, int n_nonlocal,
+                         int causal, int n_before, double scale,
+                         double* y, int32_t* codes_local, double* gap_local) {
+    return oracle_layer_forward_rope(x_local, codes_nonlocal, valid_nonlocal, codebook, D, G, K, wq, wk, wv, wo, bq, bk, bv, bo,
+                                     n_q_heads, n_kv_heads, head_dim, n_cls, n_local, n_nonlocal, causal, n_before, scale, 0.0,
+                                     y, codes_local, gap_local);
 }
 
 /* The layer with every non-local code present. */
@@ -362,16 +414,16 @@ int oracle_mlp(const double* h, int64_t T, int D, int d_ff, int mlp_kind,
  * element type the layer's inputs have (h_is_bf16: bf16, round to nearest even; else fp32) before it enters the
  * layer: an argmin is decided on it, and both sides must take that decision on the same values.  h_out (nullable)
  * returns that tensor, which is what this device's peers would receive the codes of. */
-int oracle_block_forward(const double* x, const int32_t* codes_nonlocal, const uint8_t* valid_nonlocal,
-                         const float* codebook, int D, int G, int K,
-                         int norm_kind, double eps, const float* g1, const float* be1, const float* g2, const float* be2,
-                         const float* wq, const float* wk, const float* wv, const float* wo,
-                         const float* bq, const float* bk, const float* bv, const float* bo,
-                         int mlp_kind, int d_ff, const float* w1, const float* b1, const float* w2, const float* b2,
-                         int n_q_heads, int n_kv_heads, int head_dim,
-                         int n_cls, int n_local, int n_nonlocal, int causal, int n_before, double scale,
-                         int h_is_bf16,
-                         double* x_out, int32_t* codes_local, double* gap_local, float* h_out) {
+int oracle_block_forward_rope(const double* x, const int32_t* codes_nonlocal, const uint8_t* valid_nonlocal,
+                              const float* codebook, int D, int G, int K,
+                              int norm_kind, double eps, const float* g1, const float* be1, const float* g2, const float* be2,
+                              const float* wq, const float* wk, const float* wv, const float* wo,
+                              const float* bq, const float* bk, const float* bv, const float* bo,
+                              int mlp_kind, int d_ff, const float* w1, const float* b1, const float* w2, const float* b2,
+                              int n_q_heads, int n_kv_heads, int head_dim,
+                              int n_cls, int n_local, int n_nonlocal, int causal, int n_before, double scale,
+                              int h_is_bf16, double rope_base,
+                              double* x_out, int32_t* codes_local, double* gap_local, float* h_out) {
     const int Tq = n_cls + n_local;
     const int64_t n = (int64_t)Tq * D;
     double* h = (double*)malloc(sizeof(double) * (n + 1));
@@ -394,9 +446,9 @@ int oracle_block_forward(const double* x, const int32_t* codes_nonlocal, const u
             hf[i] = f;
         }
         if (h_out) memcpy(h_out, hf, sizeof(float) * n);
-        rc = oracle_layer_forward_valid(hf, codes_nonlocal, valid_nonlocal, codebook, D, G, K, wq, wk, wv, wo, bq, bk, bv, bo,
-                                        n_q_heads, n_kv_heads, head_dim, n_cls, n_local, n_nonlocal, causal, n_before,
-                                        scale, y, codes_local, gap_local);
+        rc = oracle_layer_forward_rope(hf, codes_nonlocal, valid_nonlocal, codebook, D, G, K, wq, wk, wv, wo, bq, bk, bv, bo,
+                                       n_q_heads, n_kv_heads, head_dim, n_cls, n_local, n_nonlocal, causal, n_before,
+                                       scale, rope_base, y, codes_local, gap_local);
     }
     if (!rc) {
         for (int64_t i = 0; i < n; ++i) r[i] = x[i] + y[i];
@@ -407,6 +459,23 @@ int oracle_block_forward(const double* x, const int32_t* codes_nonlocal, const u
         for (int64_t i = 0; i < n; ++i) x_out[i] = r[i] + m[i];
     free(h); free(hf); free(y); free(r); free(m);
     return rc;
+}
+
+/* The block as the paper states it (no positional rotation inside the layer). */
+int oracle_block_forward(const double* x, const int32_t* codes_nonlocal, const uint8_t* valid_nonlocal,
+                         const float* codebook, int D, int G, int K,
+                         int norm_kind, double eps, const float* g1, const float* be1, const float* g2, const float* be2,
+                         const float* wq, const float* wk, const float* wv, const float* wo,
+                         const float* bq, const float* bk, const float* bv, const float* bo,
+                         int mlp_kind, int d_ff, const float* w1, const float* b1, const float* w2, const float* b2,
+                         int n_q_heads, int n_kv_heads, int head_dim,
+                         int n_cls, int n_local, int n_nonlocal, int causal, int n_before, double scale,
+                         int h_is_bf16,
+                         double* x_out, int32_t* codes_local, double* gap_local, float* h_out) {
+    return oracle_block_forward_rope(x, codes_nonlocal, valid_nonlocal, codebook, D, G, K, norm_kind, eps, g1, be1, g2, be2,
+                                     wq, wk, wv, wo, bq, bk, bv, bo, mlp_kind, d_ff, w1, b1, w2, b2, n_q_heads, n_kv_heads, head_dim,
+                                     n_cls, n_local, n_nonlocal, causal, n_before, scale, h_is_bf16, 0.0,
+                                     x_out, codes_local, gap_local, h_out);
 }
 
 /* ------------------------------------------------------------------------------------------------

@@ -48,6 +48,13 @@ MUTATIONS = [
      "codebook_new[i * dg + j] = n > 0.0 ? m / n : 0.0;", "dead codewords are zeroed"),
     ("test_oracle_training.py", "xi += (double)l_factor[(int64_t)i * D + j] * (double)z[t * (int64_t)D + j];",
      "xi += (double)l_factor[(int64_t)j * D + i] * (double)z[t * (int64_t)D + j];", "NAVQ multiplies by the transposed factor"),
+    ("test_oracle_rope.py", "x[2 * i + 1] = x0 * sn + x1 * c;", "x[2 * i + 1] = x1 * c - x0 * sn;", "rotation turns the other way in the second component"),
+    ("test_oracle_rope.py", "const double theta = pow(base, -2.0 * (double)i / (double)head_dim);",
+     "const double theta = pow(base, -(double)i / (double)head_dim);", "angle exponent i/d instead of 2i/d"),
+    ("test_oracle_rope.py", "pos[Tq + j] = j < n_before ? j : (int64_t)j + n_local;", "pos[Tq + j] = j;", "non-local rows after the chunk keep their list index as position"),
+    ("test_oracle_rope.py", "pos[i] = i < n_cls ? -1 : (int64_t)n_before + (i - n_cls);", "pos[i] = i < n_cls ? -1 : (int64_t)(i - n_cls);",
+     "local rows counted from the start of the chunk"),
+    ("test_oracle_rope.py", "if (!rc) rc = oracle_rope(Kh, Tn, n_kv_heads, head_dim, pos + Tq, rope_base);", "", "rebuilt keys are not rotated"),
 ]
 
 

@@ -493,6 +493,11 @@ def main():
                                "flops": total_flops + mlp_flops, "tflops": (total_flops + mlp_flops) / (ms * 1e-3) / 1e12,
                                "mfma_frac": (total_flops + mlp_flops) / (ms * 1e-3) / 1e12 / peak,
                                "mlp_and_norms_ms": ms - ms_per_step, "mlp_tflops": mlp_flops / ((ms - ms_per_step) * 1e-3) / 1e12}
+            if cfg.causal:
+                # the same block with rotary positions inside the layer (optional, outside the paper): three in-place passes
+                rdesc = B.block_desc(desc, bcfg.norm_kind, bcfg.mlp_kind, bcfg.d_ff, bcfg.eps, 500000.0)
+                ms_r = timed(lambda: B.astra_block_forward(rdesc, *b_args[1:]), 200, warm=100)
+                result["block"]["with_rotary_positions_ms"] = ms_r
             # L such blocks in sequence = this device's share of the whole model's prefill (12 blocks for the ViT-Base and
             # GPT-2 shapes, 32 for Llama-3-8B): distinct random weights and codes per block, generated on the device
             if "stack" in extras:

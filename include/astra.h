@@ -308,7 +308,12 @@ int astra_decode_attention_static(const astra_decode_desc* desc, const void* q, 
  *            ASTRA_MLP_SWIGLU:    down(silu(gate(v)) * up(v)), silu(a) = a / (1 + exp(-a)); w1 holds the gate
  *                                 rows first, then the up rows
  * The residual stream (x, x_out) is fp32 for both element types; h, the MLP's hidden rows and everything
- * inside the layer use the element type (products accumulate in fp32).  No positional encoding is applied. */
+ * inside the layer use the element type (products accumulate in fp32).
+ * rope_base  0: no positional encoding is applied (the paper names none).  > 0 (optional; causal layers only, head_dim
+ *            even): rotary position embedding inside the layer (Su et al., "RoFormer", Eq. 34, interleaved pairs): before
+ *            Eq. 1, every head's vector of Q, K and K-hat at sequence position m has its pairs (v[2i], v[2i+1]) turned by
+ *            the angle m * rope_base^(-2i / head_dim); a local content row i sits at position n_nonlocal_before + i, a visible
+ *            non-local row j at position j; a class row is not turned, values never are. */
 enum { ASTRA_NORM_LAYER = 0, ASTRA_NORM_RMS = 1 };
 enum { ASTRA_MLP_GELU_TANH = 0, ASTRA_MLP_GELU_ERF = 1, ASTRA_MLP_SWIGLU = 2 };
 
@@ -318,6 +323,7 @@ typedef struct {
     int32_t mlp_kind;
     int32_t d_ff;               /* hidden width of the MLP; a multiple of 64 for bf16 */
     float eps;                  /* >= 0, inside the square root of both norms */
+    float rope_base;            /* 0 = none; e.g. 10000 or 500000 */
 } astra_block_desc;
 
 /* Device pointers, owned by the caller.  Matrices and their biases are in the element type and stored

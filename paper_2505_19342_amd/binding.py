@@ -60,7 +60,7 @@ class DecodeDesc(ctypes.Structure):
 
 class BlockDesc(ctypes.Structure):
     _fields_ = [("layer", LayerDesc), ("norm_kind", ctypes.c_int32), ("mlp_kind", ctypes.c_int32), ("d_ff", ctypes.c_int32),
-                ("eps", ctypes.c_float)]
+                ("eps", ctypes.c_float), ("rope_base", ctypes.c_float)]
 
 
 _BLOCK_WEIGHT_NAMES = ("codebook", "cnorm", "wq", "wk", "wv", "wo", "bq", "bk", "bv", "bo",
@@ -423,5 +423,5 @@ def attn_desc(dtype: str, n_q_heads: int, n_kv_heads: int, head_dim: int, n_cls:
                     n_nonlocal, int(bool(causal)), n_before if causal else 0, scale)
 
 
-def block_desc(layer: LayerDesc, norm_kind: str, mlp_kind: str, d_ff: int, eps: float) -> BlockDesc:
-    return BlockDesc(layer, NORM_KINDS[norm_kind], MLP_KINDS[mlp_kind], d_ff, eps)
+def block_desc(layer: LayerDesc, norm_kind: str, mlp_kind: str, d_ff: int, eps: float, rope_base: float = 0.0) -> BlockDesc:
+    return BlockDesc(layer, NORM_KINDS[norm_kind], MLP_KINDS[mlp_kind], d_ff, eps, rope_base)

@@ -152,6 +152,9 @@ static int make_block_plan(const astra_block_desc* desc, BlockPlan* bp) {
     if (desc->mlp_kind != ASTRA_MLP_GELU_TANH && desc->mlp_kind != ASTRA_MLP_GELU_ERF && desc->mlp_kind != ASTRA_MLP_SWIGLU)
         return ASTRA_ERR_SHAPE;
     if (desc->d_ff <= 0 || desc->d_ff > (1 << 24) || !(desc->eps >= 0.f)) return ASTRA_ERR_SHAPE;
+    if (!(desc->rope_base >= 0.f) || desc->rope_base > 1e30f) return ASTRA_ERR_SHAPE;
+    // rotary positions need every row's place in the sequence: given for causal layers (contiguous chunks, n_before)
+    if (desc->rope_base > 0.f && (!desc->layer.attn.causal || desc->layer.attn.head_dim % 2 != 0)) return ASTRA_ERR_UNSUPPORTED;
     const int dtype = desc->layer.vq.dtype;
     if (dtype == ASTRA_BF16 && desc->d_ff % 64 != 0) return ASTRA_ERR_UNSUPPORTED;     // d_ff is a contraction length
     const int eb = elem_bytes(dtype);
@@ -292,7 +295,8 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
                               const void* bq, const void* bk, const void* bv, const void* bo,
                               void* y_out, void* codes_local_out, void* workspace, size_t workspace_bytes, void* stream,
                               void* const* ev, int* plan_encode_fused = nullptr, const uint64_t* valid_bits = nullptr,
-                              const float* residual = nullptr, const float* pre_k = nullptr, const float* pre_v = nullptr) {
+                              const float* residual = nullptr, const float* pre_k = nullptr, const float* pre_v = nullptr,
+                              float rope_base = 0.f) {
     // plan_encode_fused: validate the shapes and report whether the projection launch would carry the encode;
     // nothing is launched and no pointer is dereferenced
     const bool plan_only = plan_encode_fused != nullptr;
@@ -440,6 +444,15 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
         if (rc) return rc;
     }
     mark(6, s);
+
+    // optional rotary positions (a block's choice, outside the paper): Q and K of the local rows (content row i at n_before + i,
+    // class rows untouched) and K-hat of the visible non-local rows (row j at j; the layer is causal, so they all precede the chunk)
+    if (rope_base > 0.f) {
+        rc = launch_rope(vq.dtype, Q, pl.dq, pl.Tq, at.n_q_heads, at.head_dim, at.n_cls, 0, 0, at.n_nonlocal_before - at.n_cls, rope_base, s);
+        if (rc == ASTRA_OK) rc = launch_rope(vq.dtype, K, pl.dkv, pl.Tq, at.n_kv_heads, at.head_dim, at.n_cls, 0, 0, at.n_nonlocal_before - at.n_cls, rope_base, s);
+        if (rc == ASTRA_OK) rc = launch_rope(vq.dtype, Kh, pl.dkv, pl.Tn_vis, at.n_kv_heads, at.head_dim, 0, at.n_nonlocal_before, 0, at.n_local, rope_base, s);
+        if (rc) return rc;
+    }
 
     // 3. mixed-precision attention (Eq. 1)
     rc = launch_attention(vq.dtype, ap, at.head_dim, s);
@@ -665,7 +678,8 @@ static int block_forward_impl(const astra_block_desc* desc, const astra_block_we
     if (rc) return rc;
     // r = x + layer(h), written to x_out by the output projection's epilogue
     rc = layer_forward_impl(&desc->layer, h, codes_nonlocal, w->codebook, w->cnorm, w->wq, w->wk, w->wv, w->wo, w->bq, w->bk, w->bv,
-                            w->bo, x_out, codes_local_out, workspace, pl.total, stream, nullptr, nullptr, valid_nonlocal_bits, x);
+                            w->bo, x_out, codes_local_out, workspace, pl.total, stream, nullptr, nullptr, valid_nonlocal_bits, x,
+                            nullptr, nullptr, desc->rope_base);
     if (rc) return rc;
     rc = launch_norm(dtype, desc->norm_kind, x_out, pl.Tq, pl.D, desc->eps, w->norm2_gain, w->norm2_bias, h2, s);
     if (rc) return rc;

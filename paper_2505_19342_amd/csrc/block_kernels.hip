@@ -137,4 +137,82 @@ int launch_swiglu_f32(const float* a, int64_t T, int F, float* out, hipStream_t 
     return launch_status();
 }
 
+// ---- optional rotary position embedding (not part of the paper; Su et al., "RoFormer", Eq. 34, interleaved pairs), in
+// place on a [rows, n_heads * head_dim] matrix of the element type with row stride ld: pair i of every head's vector at
+// position m is turned by m * base^(-2i / head_dim).  Row r has position r + add_lo when r < split and r + add_hi
+// otherwise; rows below `skip` have no position and are left alone.  The angle is formed in fp64 and reduced to a
+// fraction of a turn before it is rounded (positions reach 10^5, the cosine of an fp32 product would be off by 10^-3);
+// the frequencies of a head are computed once per workgroup.  A thread turns PAIRS consecutive pairs of a row.
+constexpr int kRopeThreads = 256;
+
+template <typename T, int PAIRS>
+__global__ __launch_bounds__(kRopeThreads) void rope_kernel(T* __restrict__ mat, int64_t ld, int rows, int width, int head_dim, int skip,
+                                                            int split, int add_lo, int add_hi, float base) {
+    extern __shared__ double theta[];                    // [head_dim / 2]
+    const int half = head_dim >> 1;
+    for (int i = threadIdx.x; i < half; i += kRopeThreads) theta[i] = exp2(-2.0 * (double)i / (double)head_dim * log2((double)base));
+    __syncthreads();
+    const int per_row = width / (2 * PAIRS);
+    const int64_t id = (int64_t)blockIdx.x * kRopeThreads + threadIdx.x;
+    if (id >= (int64_t)rows * per_row) return;
+    const int r = (int)(id / per_row), c = (int)(id - (int64_t)r * per_row) * 2 * PAIRS;       // first column of this thread
+    if (r < skip) return;
+    const double m = (double)(r < split ? r + add_lo : r + add_hi);
+    T* __restrict__ p = mat + (int64_t)r * ld + c;
+    float v[2 * PAIRS];
+    if constexpr (sizeof(T) == 2 && PAIRS == 4) {
+        const u32x4 w = *reinterpret_cast<const u32x4*>(p);
+        const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            v[2 * e] = __uint_as_float(ww[e] << 16);
+            v[2 * e + 1] = __uint_as_float(ww[e] & 0xffff0000u);
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 2 * PAIRS; ++e) {
+            if constexpr (sizeof(T) == 2) v[e] = bf16_bits_to_f32(p[e]);
+            else v[e] = p[e];
+        }
+    }
+    const int i0 = (c % head_dim) >> 1;
+#pragma unroll
+    for (int e = 0; e < PAIRS; ++e) {
+        double turns = m * theta[i0 + e] * 0.15915494309189535;       // angle / 2 pi
+        turns -= floor(turns);
+        const float a = (float)(turns * 6.283185307179586);
+        const float cs = cosf(a), sn = sinf(a);
+        const float x0 = v[2 * e], x1 = v[2 * e + 1];
+        v[2 * e] = x0 * cs - x1 * sn;
+        v[2 * e + 1] = x0 * sn + x1 * cs;
+    }
+    if constexpr (sizeof(T) == 2 && PAIRS == 4) {
+        u32x4 w;
+        w.x = pack_bf16x2(v[0], v[1]);
+        w.y = pack_bf16x2(v[2], v[3]);
+        w.z = pack_bf16x2(v[4], v[5]);
+        w.w = pack_bf16x2(v[6], v[7]);
+        *reinterpret_cast<u32x4*>(p) = w;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 2 * PAIRS; ++e) store_elem<T>(p + e, v[e]);
+    }
+}
+
+int launch_rope(int dtype, void* mat, int64_t ld, int rows, int n_heads, int head_dim, int skip, int split, int add_lo, int add_hi,
+                float base, hipStream_t s) {
+    if (rows <= 0) return ASTRA_OK;
+    if (head_dim <= 0 || head_dim % 2 != 0 || !(base > 0.f)) return ASTRA_ERR_SHAPE;
+    const int width = n_heads * head_dim;
+    const size_t lds = (size_t)(head_dim / 2) * sizeof(double);
+    const bool vec = dtype == ASTRA_BF16 && head_dim % 8 == 0 && ld % 8 == 0;
+    const int64_t n = (int64_t)rows * (width / (vec ? 8 : 2));
+    const int64_t blocks = ceil_div(n, kRopeThreads);
+    if (blocks > 0x7fffffff) return ASTRA_ERR_SHAPE;
+    if (vec) rope_kernel<uint16_t, 4><<<(int)blocks, kRopeThreads, lds, s>>>((uint16_t*)mat, ld, rows, width, head_dim, skip, split, add_lo, add_hi, base);
+    else if (dtype == ASTRA_BF16) rope_kernel<uint16_t, 1><<<(int)blocks, kRopeThreads, lds, s>>>((uint16_t*)mat, ld, rows, width, head_dim, skip, split, add_lo, add_hi, base);
+    else rope_kernel<float, 1><<<(int)blocks, kRopeThreads, lds, s>>>((float*)mat, ld, rows, width, head_dim, skip, split, add_lo, add_hi, base);
+    return launch_status();
+}
+
 }  // namespace astra

@@ -167,6 +167,8 @@ extern const int g_gemm_problem_size;
 
 // Row-wise LayerNorm (kind 0) / RMSNorm (kind 1) of the fp32 residual stream x [T, D] into the element type of the layer
 // (out [T, D]); gain, bias fp32 [D], nullable.
+int launch_rope(int dtype, void* mat, int64_t ld, int rows, int n_heads, int head_dim, int skip, int split, int add_lo, int add_hi,
+                float base, hipStream_t s);
 int launch_norm(int dtype, int kind, const float* x, int64_t T, int D, float eps, const float* gain, const float* bias, void* out,
                 hipStream_t s);
 // out[t, f] = silu(a[t, f]) * a[t, F + f] for fp32 a [T, 2F]

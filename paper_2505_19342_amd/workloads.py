@@ -152,6 +152,7 @@ class BlockConfig:
     d_ff: int
     eps: float
     biases: bool          # linear layers carry biases (ViT, GPT-2) or not (Llama)
+    rope_base: float = 0.0  # > 0: rotary positions inside the layer (optional, causal layers; the paper names no positional encoding)
 
 
 TINY_VIT_BLOCK = BlockConfig("tiny_vit_block_f32", TINY_VIT, "layernorm", "gelu_erf", 768, 1e-6, True)

@@ -150,7 +150,7 @@ class BlockOnGpu:
         layer = B.LayerDesc(
             B.vq_desc(dt, cfg.d_model, G, K),
             B.attn_desc(dt, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n_cls, Tq - cfg.n_cls, Tn, cfg.causal, n_before))
-        self.desc = B.block_desc(layer, bcfg.norm_kind, bcfg.mlp_kind, bcfg.d_ff, bcfg.eps)
+        self.desc = B.block_desc(layer, bcfg.norm_kind, bcfg.mlp_kind, bcfg.d_ff, bcfg.eps, bcfg.rope_base)
         f32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(DEV)
         self.x = f32(x_local)
         self.codes_nonlocal = codes_to_dev(codes_nonlocal, K) if Tn > 0 else None

@@ -91,7 +91,7 @@ def test_block_kv_and_decode_planning_is_host_only():
     """Workspace sizes and argument checks of the entry points around the layer are decided on the host: the sizes
     cover the buffers the calls need, invalid descriptors give 0 / an error code, NULL pointers are reported."""
     lib = B.load()
-    assert ctypes.sizeof(B.BlockDesc) == 76 and ctypes.sizeof(B.LayerKvDesc) == 64 and ctypes.sizeof(B.DecodeDesc) == 44
+    assert ctypes.sizeof(B.BlockDesc) == 80 and ctypes.sizeof(B.LayerKvDesc) == 64 and ctypes.sizeof(B.DecodeDesc) == 44
     assert ctypes.sizeof(B.BlockWeights) == 18 * ctypes.sizeof(ctypes.c_void_p)
     layer = B.LayerDesc(B.vq_desc("bf16", 4096, 64, 1024), B.attn_desc("bf16", 32, 8, 128, 0, 1024, 3072, True, 3072))
     blk = B.block_desc(layer, "rmsnorm", "swiglu", 14336, 1e-5)

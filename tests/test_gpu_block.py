@@ -44,7 +44,7 @@ def run_case(bcfg, rank, in_place=False, valid=None):
         norm_kind=bcfg.norm_kind, eps=bcfg.eps, g1=data["g1"], g2=data["g2"], be1=data["be1"], be2=data["be2"],
         mlp_kind=bcfg.mlp_kind, w1=data["w1"], w2=data["w2"], n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads,
         n_cls=cfg.n_cls, causal=cfg.causal, n_before=view["n_before"], valid_nonlocal=valid,
-        h_is_bf16=cfg.dtype == "bf16", **{n: data.get(n) for n in names})
+        h_is_bf16=cfg.dtype == "bf16", rope_base=bcfg.rope_base, **{n: data.get(n) for n in names})
     blk = BlockOnGpu(bcfg, data, view["x_local"], codes_nl, view["n_before"], in_place=in_place)
     blk.run(valid)
     out, codes, h = blk.results()
@@ -126,6 +126,41 @@ def test_block_with_lost_codes():
 
 def test_llama3_8b_block_full_size():
     run_case(wl.LLAMA3_8B_BLOCK, 3)
+
+
+@pytest.mark.parametrize("rank", [0, 1, 3])
+def test_llama_width_block_with_rotary_positions(rank):
+    """Optional rotary positions (outside the paper): Q, K and K-hat turned at their sequence positions before Eq. 1;
+    rank 0 has no visible non-local rows, rank 3 the most."""
+    a = run_case(dataclasses.replace(small_llama(seed=56), rope_base=500000.0), rank)
+    b = run_case(small_llama(seed=56), rank)
+    assert np.abs(a - b).max() > 1e-3          # the rotation matters
+
+
+def test_rotary_positions_fp32_and_head_dim_64():
+    """The fp32 path (a pair per thread) on a causal variant of the tiny model, and the bf16 path with 64-wide heads."""
+    layer = dataclasses.replace(wl.TINY_VIT, name="tiny_causal_f32", n_cls=0, causal=True, seed=57)
+    run_case(dataclasses.replace(wl.TINY_VIT_BLOCK, name="tiny_causal_block_f32", layer=layer, rope_base=10000.0), 2)
+    run_case(dataclasses.replace(wl.GPT2_SMALL_BLOCK, name="gpt2_small_rope_block", rope_base=10000.0), 2)
+
+
+def test_rotary_positions_need_a_causal_layer():
+    """A layer that is not causal carries no row positions: the descriptor is refused (no workspace size, no launch)."""
+    import torch
+    from gpu_util import BlockOnGpu
+    from paper_2505_19342_amd import binding as B
+    bcfg = wl.TINY_VIT_BLOCK
+    data = wl.generate_block(bcfg)
+    view = wl.device_view(bcfg.layer, data, 0)
+    codes_nl = peer_codes(bcfg, data, view["x_nonlocal"])
+    blk = BlockOnGpu(bcfg, data, view["x_local"], codes_nl, view["n_before"])
+    bad = B.block_desc(blk.desc.layer, bcfg.norm_kind, bcfg.mlp_kind, bcfg.d_ff, bcfg.eps, 10000.0)
+    assert B.astra_block_workspace_bytes(bad) == 0
+    blk.x_out.fill_(-7.0)
+    with pytest.raises(B.AstraError):
+        B.astra_block_forward(bad, blk.weights, blk.x, blk.codes_nonlocal, None, blk.x_out, blk.codes_local, blk.h, blk.workspace)
+    torch.cuda.synchronize()
+    assert bool((blk.x_out == -7.0).all())
 
 
 def test_block_argument_errors_launch_nothing():

@@ -28,7 +28,7 @@ def run_stack(bcfg, n_layers, rank):
     data = wl.generate_stack(bcfg, n_layers)
     sim = oracle.model_forward(data["x"], data["layers"], n_dev=cfg.n_dev, n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads,
                                norm_kind=bcfg.norm_kind, eps=bcfg.eps, mlp_kind=bcfg.mlp_kind, causal=cfg.causal,
-                               cls=data.get("cls"), h_is_bf16=cfg.dtype == "bf16")
+                               cls=data.get("cls"), h_is_bf16=cfg.dtype == "bf16", rope_base=bcfg.rope_base)
     view = wl.device_view(cfg, data, rank)
     received = [sim["codes_nonlocal"][l][rank] for l in range(n_layers)]
     st = StackOnGpu(bcfg, data["layers"], view["x_local"], received, view["n_before"])
@@ -47,7 +47,7 @@ def run_stack(bcfg, n_layers, rank):
         view["x_local"], received[0], p0["codebook"], p0["wq"], p0["wk"], p0["wv"], p0["wo"], norm_kind=bcfg.norm_kind,
         eps=bcfg.eps, g1=p0["g1"], g2=p0["g2"], be1=p0.get("be1"), be2=p0.get("be2"), mlp_kind=bcfg.mlp_kind, w1=p0["w1"],
         w2=p0["w2"], n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, n_cls=cfg.n_cls, causal=cfg.causal,
-        n_before=view["n_before"], h_is_bf16=cfg.dtype == "bf16", **{n: p0.get(n) for n in names})
+        n_before=view["n_before"], h_is_bf16=cfg.dtype == "bf16", rope_base=bcfg.rope_base, **{n: p0.get(n) for n in names})
     np.testing.assert_array_equal(codes_ref, sim["codes"][0][rank])
     b0 = BlockOnGpu(bcfg, p0, view["x_local"], received[0], view["n_before"])
     b0.run()
@@ -88,6 +88,12 @@ def test_llama_width_four_blocks_rmsnorm_swiglu_grouped_query_heads():
     and a narrower MLP, four blocks deep, on a middle rank of the causal split."""
     layer = dataclasses.replace(wl.LLAMA3_8B, name="llama_stack", seq_len=1148, seed=61)
     run_stack(dataclasses.replace(wl.LLAMA3_8B_BLOCK, name="llama_stack_block", layer=layer, d_ff=1792), 4, 2)
+
+
+def test_llama_width_three_blocks_with_rotary_positions():
+    """The same widths with rotary positions inside every layer (optional, outside the paper), last rank of the causal split."""
+    layer = dataclasses.replace(wl.LLAMA3_8B, name="llama_rope_stack", seq_len=1148, seed=62)
+    run_stack(dataclasses.replace(wl.LLAMA3_8B_BLOCK, name="llama_rope_stack_block", layer=layer, d_ff=1792, rope_base=500000.0), 3, 3)
 
 
 def test_stack_argument_errors_launch_nothing():

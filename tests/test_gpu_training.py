@@ -91,16 +91,20 @@ def check_codebook(dtype, got, ref64, loose=False):
 
 
 def test_stats_edge_cases():
-    """No tokens; fewer tokens than one pass; every token in one codeword; ragged token count."""
+    """No tokens; fewer tokens than one pass; every token in one codeword; ragged token count; three codewords only, so that
+    every codeword's run of the sorted sequence spans several 32-position units (more than the four a thread of the
+    fix-up pass keeps in flight) and starts and ends inside a unit."""
     import dataclasses
     cfg = dataclasses.replace(wl.GPT2_SMALL, name="train_ragged", seq_len=4 * 131, seed=91)
     data, x, cb, codes, desc, dev = setup(cfg)
-    for T in (0, 1, 131, 524):
+    for T in (0, 1, 131, 524, 523):
         import torch
         from gpu_util import codes_to_dev
         c = codes.copy()
         if T == 131:
             c[:] = 7                                         # every token in codeword 7 of every group
+        if T == 523:
+            c = np.random.default_rng(3).choice([2, 9, 200], size=c.shape, p=[0.5, 0.3, 0.2]).astype(c.dtype)
         dev["codes"] = codes_to_dev(c, cb.shape[1])
         counts, sums, sqerr = run_stats(desc, dev, T)
         c_ref, s_ref, q_ref = oracle.codebook_stats(x[:T], c[:T], cb)

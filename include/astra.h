@@ -377,7 +377,8 @@ int astra_stack_forward(const astra_block_desc* desc, int32_t n_layers, const as
  * Sec. 3.2: the codebook is initialised by K-means over token embeddings and updated by exponential moving average
  * during fine-tuning, with the commitment term beta * ||X - sg(X-hat)||_2^2 of Eq. 2 in the loss; Sec. 3.3: NAVQ adds
  * noise fitted to the quantisation residuals to the quantised embeddings during training.  Gradients are not part of
- * this library.  All results are independent of the run (tokens are sorted by code, rows added in token order). */
+ * this library.  All results are independent of the run (tokens are sorted by code with a stable sort, rows added in a fixed order: no
+ * floating-point atomics). */
 
 /* Statistics of an assignment codes [T, G] (astra_vq_encode's output for x [T, D]):
  *   counts_out [G, K] int32   tokens per codeword

@@ -20,7 +20,9 @@ namespace astra {
 // group w & 3 and walks only the key/value tiles of parity w >> 2; the two wavefronts that share a query
 // group merge their (max, sum, O) triples through LDS at the end.  The two wavefronts of a SIMD have
 // different parities and are kept in opposite phases (see the schedule below): one runs its softmax on
-// the vector ALU while the other occupies the matrix core.  A wavefront's whole state (O^T 64, S^T 32,
+// the vector ALU while the other occupies the matrix core.  (NPAR = 4, for short sequences with 64-wide heads: 64 query
+// rows per workgroup, two query groups, and the tiles dealt to four wavefronts per group: twice the workgroups, half the
+// iterations; wavefronts 0..3 still run one phase ahead of wavefronts 4..7.)  A wavefront's whole state (O^T 64, S^T 32,
 // Q 32, P 16 registers) stays in ordinary vector registers.  Tiles of 64 keys are double-buffered in LDS
 // with XOR-swizzled 16-byte pieces and arrive by direct global->LDS transfers, issued one iteration ahead
 // by the four wavefronts that will read them.
@@ -33,10 +35,11 @@ namespace astra {
 // query heads of as few KV heads as possible, and inside a head the later (heavier under causal
 // masking) query blocks come first.
 // ------------------------------------------------------------------------------------------------
-constexpr int kAttQ = 128;       // query rows per workgroup
+constexpr int kAttQ = 128;       // query rows per workgroup (64 with four tile parities)
 constexpr int kAttKV = 64;       // key/value rows per tile
 constexpr int kAttThreads = 512;
 constexpr int kXcdsA = 8;
+constexpr int kAttCus = 256;     // compute units of the device the launch shapes are chosen for
 constexpr float kLazy = 8.f;     // base-2 units
 
 __device__ __forceinline__ int xcd_remap_attn(int wg, int total) {
@@ -55,31 +58,37 @@ __device__ __forceinline__ int swz_vt(int r) { return (r >> 1) & 7; }
 
 // LOST: the caller passed a validity bit per non-local token (an instantiation of its own, so that the code for it does
 // not disturb the register allocation and schedule of the kernel that runs without)
-template <int DH, bool VT, bool LOST = false>
+template <int DH, bool VT, bool LOST = false, int NPAR = 2>
 __global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams p) {
+    static_assert(NPAR == 2 || NPAR == 4, "two or four tile parities");
+    constexpr int NQG = 8 / NPAR;              // query groups of 32 rows (wavefronts per parity)
+    constexpr int kQRows = 32 * NQG;           // query rows per workgroup
     constexpr int CPR = DH / 8;                // 16-byte pieces per K (and row-major V) row
     constexpr int NKS = DH / 16;               // contraction steps of Q.K
     constexpr int NDB = DH / 32;               // 32-wide blocks of the head dimension
     constexpr int PIECES = kAttKV * CPR;       // pieces per tile
-    constexpr int kParThreads = kAttThreads / 2;           // threads of one key parity
+    constexpr int kParThreads = kAttThreads / NPAR;        // threads of one key parity
     constexpr int LPT = PIECES / kParThreads;  // transfers per thread per tile
     // [buffer][parity] tiles
-    __shared__ u32x4 lds_k[2][2][PIECES];
-    __shared__ u32x4 lds_v[2][2][PIECES];
+    __shared__ u32x4 lds_k[2][NPAR][PIECES];
+    __shared__ u32x4 lds_v[2][NPAR][PIECES];
+    static_assert(sizeof(lds_k) + sizeof(lds_v) <= 128 * 1024, "tile buffers");
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform: keeps the tile bookkeeping in scalar registers
     const int i32 = lane & 31, h = lane >> 5;
-    const int qg = wave & 3, par = wave >> 2;
+    // wavefronts w and w + 4 share a SIMD and run in opposite phases; the NQG wavefronts of a parity are consecutive
+    const int phase = wave >> 2;
+    const int qg = wave & (NQG - 1), par = 2 * ((wave & 3) / NQG) + phase;
     const int ptid = tid & (kParThreads - 1);
 
-    const int n_qb = (p.Tq + kAttQ - 1) / kAttQ;
+    const int n_qb = (p.Tq + kQRows - 1) / kQRows;
     const int vt_id = xcd_remap_attn(blockIdx.x, gridDim.x);
     const int head = vt_id / n_qb;
     const int qb = n_qb - 1 - (vt_id % n_qb);
     const int hk = head / (p.Hq / p.Hkv);
-    const int q0 = qb * kAttQ;
+    const int q0 = qb * kQRows;
     const int Tq = p.Tq;
     const int64_t q_ld = (int64_t)p.Hq * DH, kv_ld = (int64_t)p.Hkv * DH;
 
@@ -102,12 +111,12 @@ __global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams
     const float sl2 = p.scale * 1.4426950408889634f;       // logits in base-2 units
 
     const int n_hat_tiles = (p.Tn_vis + kAttKV - 1) / kAttKV;
-    const int loc_rows = p.causal ? min(q0 + kAttQ, Tq) : Tq;     // local keys any row of this block may see
+    const int loc_rows = p.causal ? min(q0 + kQRows, Tq) : Tq;    // local keys any row of this block may see
     const int n_tiles = n_hat_tiles + (loc_rows + kAttKV - 1) / kAttKV;
-    const int n_pairs = (n_tiles + 1) / 2;
+    const int n_pairs = (n_tiles + NPAR - 1) / NPAR;
     const int wave_q_lo = q0 + 32 * qg;
 
-    // ---- tiles of this wavefront's parity: own iteration i works on tile 2i + par of the walk (visible
+    // ---- tiles of this wavefront's parity: own iteration i works on tile NPAR * i + par of the walk (visible
     // non-local tiles first, local tiles after them).  An index past the end (odd tile count) is the last
     // tile again with every key masked, so all wavefronts run the same number of iterations.
     struct Tile {
@@ -115,7 +124,7 @@ __global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams
         int row0, count;
     };
     auto tile_of = [&](int i) {
-        const int t_in = 2 * i + par;
+        const int t_in = NPAR * i + par;
         const int t = t_in < n_tiles ? t_in : n_tiles - 1;
         Tile tl;
         tl.is_loc = t >= n_hat_tiles;
@@ -135,7 +144,8 @@ __global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams
     const uint32_t vcol = VT ? (uint32_t)(((ptid & 7) ^ swz_vt(ptid >> 3)) * 16)    // V^T: row ptid/8 + 32*it, piece ptid%8
                              : (uint32_t)((kph ^ swz_v<DH>(kr0)) * 16);
     const uint32_t kv_ld_b = (uint32_t)kv_ld * 2u;
-    const uint32_t wave_slot = (uint32_t)(64 * (wave & 3)) * 16u;
+    const uint32_t wave_slot = (uint32_t)(64 * qg) * 16u;                      // this wavefront's 64 slots inside a pass of its parity
+    constexpr uint32_t kPassBytes = (uint32_t)kParThreads * 16u;
     // byte offset of row kr0 inside a tile; the rows of pass `it` lie ROW_STEP rows further (a scalar product), and a
     // row beyond the source's last one is replaced by that last row by clamping the offset: no per-lane multiply
     const uint32_t krow_b = (uint32_t)kr0 * kv_ld_b;
@@ -143,15 +153,15 @@ __global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams
         const char* __restrict__ Kb = (const char*)(tl.is_loc ? p.k_loc : p.k_hat) + ((int64_t)tl.row0 * kv_ld + (int64_t)hk * DH) * 2;
         const int lim = (tl.is_loc ? Tq : p.Tn_vis) - 1 - tl.row0;                 // last valid row of the tile
         const uint32_t off = min(krow_b + (uint32_t)(ROW_STEP * it) * kv_ld_b, (uint32_t)min(lim, kAttKV - 1) * kv_ld_b);
-        dma_global_to_lds_16(Kb, off + kcol, lds_byte_addr(&lds_k[buf][par][0]) + wave_slot + (uint32_t)it * 4096u);
+        dma_global_to_lds_16(Kb, off + kcol, lds_byte_addr(&lds_k[buf][par][0]) + wave_slot + (uint32_t)it * kPassBytes);
     };
     auto dma_v = [&](const Tile& tl, int buf, int it) {
-        const uint32_t dst = lds_byte_addr(&lds_v[buf][par][0]) + wave_slot + (uint32_t)it * 4096u;
+        const uint32_t dst = lds_byte_addr(&lds_v[buf][par][0]) + wave_slot + (uint32_t)it * kPassBytes;
         if (VT) {
             const uint32_t v_ld_b = (uint32_t)(tl.is_loc ? p.ldv_loc : p.ldv_hat) * 2u;
             const char* __restrict__ Vb = (const char*)(tl.is_loc ? p.v_loc : p.v_hat) + ((int64_t)hk * DH * v_ld_b + (int64_t)tl.row0 * 2);
-            // row ptid / 8 + 32 * it of the transposed tile: one per-lane product per tile source, the pass adds a scalar
-            dma_global_to_lds_16(Vb, (uint32_t)(ptid >> 3) * v_ld_b + (uint32_t)(32 * it) * v_ld_b + vcol, dst);
+            // row ptid / 8 + (kParThreads / 8) * it of the transposed tile: one per-lane product per tile source, the pass adds a scalar
+            dma_global_to_lds_16(Vb, (uint32_t)(ptid >> 3) * v_ld_b + (uint32_t)((kParThreads / 8) * it) * v_ld_b + vcol, dst);
         } else {
             const char* __restrict__ Vb = (const char*)(tl.is_loc ? p.v_loc : p.v_hat) + ((int64_t)tl.row0 * kv_ld + (int64_t)hk * DH) * 2;
             const int lim = (tl.is_loc ? Tq : p.Tn_vis) - 1 - tl.row0;
@@ -335,7 +345,7 @@ __global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams
     }
     wait_vmem_all();
     __syncthreads();
-    if (par == 1) __syncthreads();
+    if (phase == 1) __syncthreads();
     for (int i = 0;; i += 2) {          // two iterations per trip: the tile buffers alternate, so each copy knows its own
         __builtin_amdgcn_s_setprio(2);      // the matrix-core phase goes first when both wavefronts of the SIMD can issue
         mm_phase(i, std::integral_constant<int, 0>{});
@@ -355,31 +365,48 @@ __global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams
         __syncthreads();
     }
     wait_vmem_all();          // transfers issued by the last matrix-core phase land in buffers the merge reuses
-    if (par == 0) __syncthreads();
+    if (phase == 0) __syncthreads();
     __syncthreads();
 
-    // ---- merge the two parities of each query group through LDS (the tile buffers are free now)
-    float* xch = reinterpret_cast<float*>(&lds_k[0][0][0]);        // NDB*16*64 floats per query group (<= 16 KiB each)
-    float* xml = reinterpret_cast<float*>(&lds_v[0][0][0]);        // m, l per (query group, lane)
+    // ---- merge the parities of each query group through LDS (the tile buffers are free now): parities 1.. hand their
+    // triples to parity 0, which adds them in ascending parity
+    float* xch = reinterpret_cast<float*>(&lds_k[0][0][0]);        // NDB*16*64 floats per (query group, parity > 0)
+    float* xml = reinterpret_cast<float*>(&lds_v[0][0][0]);        // m, l per (query group, parity > 0, lane)
+    static_assert(sizeof(lds_k) >= sizeof(float) * NQG * (NPAR - 1) * NDB * 16 * 64, "the exchange fits the key tiles");
     const float l_tot = l_run + __shfl_xor(l_run, 32);
-    if (par == 1) {
+    if (par > 0) {
+        const int sl = qg * (NPAR - 1) + par - 1;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) xch[((qg * NDB + db) * 16 + v) * 64 + lane] = acc_o[db][v];
-        xml[(qg * 2 + 0) * 64 + lane] = m_run;
-        xml[(qg * 2 + 1) * 64 + lane] = l_tot;
+            for (int v = 0; v < 16; ++v) xch[((sl * NDB + db) * 16 + v) * 64 + lane] = acc_o[db][v];
+        xml[(sl * 2 + 0) * 64 + lane] = m_run;
+        xml[(sl * 2 + 1) * 64 + lane] = l_tot;
     }
     __syncthreads();
     if (par == 0) {
-        const float m1 = xml[(qg * 2 + 0) * 64 + lane];
-        const float l1 = xml[(qg * 2 + 1) * 64 + lane];
-        const float m = fmaxf(m_run, m1);
+        float mo[NPAR - 1], lo[NPAR - 1];
+        float m = m_run;
+#pragma unroll
+        for (int q = 0; q < NPAR - 1; ++q) {
+            mo[q] = xml[((qg * (NPAR - 1) + q) * 2 + 0) * 64 + lane];
+            lo[q] = xml[((qg * (NPAR - 1) + q) * 2 + 1) * 64 + lane];
+            m = fmaxf(m, mo[q]);
+        }
         const float m_safe = m == -INFINITY ? 0.f : m;
-        const float a0 = __builtin_amdgcn_exp2f(m_run - m_safe), a1 = __builtin_amdgcn_exp2f(m1 - m_safe);
-        const float l = l_tot * a0 + l1 * a1;
+        const float a0 = __builtin_amdgcn_exp2f(m_run - m_safe);
+        float ao[NPAR - 1];
+        float l = l_tot * a0;
+#pragma unroll
+        for (int q = 0; q < NPAR - 1; ++q) {
+            ao[q] = __builtin_amdgcn_exp2f(mo[q] - m_safe);
+            l += lo[q] * ao[q];
+        }
         const float inv = l > 0.f ? 1.f / l : 0.f;
-        const float c0 = a0 * inv, c1 = a1 * inv;
+        const float c0 = a0 * inv;
+        float co[NPAR - 1];
+#pragma unroll
+        for (int q = 0; q < NPAR - 1; ++q) co[q] = ao[q] * inv;
         if (qrow < Tq) {
             uint16_t* __restrict__ O = (uint16_t*)p.out + (int64_t)qrow * q_ld + (int64_t)head * DH;
 #pragma unroll
@@ -390,7 +417,10 @@ __global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const int v = 4 * vq + e;
-                        o[e] = acc_o[db][v] * c0 + xch[((qg * NDB + db) * 16 + v) * 64 + lane] * c1;
+                        o[e] = acc_o[db][v] * c0;
+#pragma unroll
+                        for (int q = 0; q < NPAR - 1; ++q)
+                            o[e] += xch[(((qg * (NPAR - 1) + q) * NDB + db) * 16 + v) * 64 + lane] * co[q];
                     }
                     u32x2 w;
                     w.x = pack_bf16x2(o[0], o[1]);
@@ -490,8 +520,12 @@ int launch_attention(int dtype, const AttnParams& p_in, int head_dim, hipStream_
     AttnParams p = p_in;
     if (p.Tq == 0) return ASTRA_OK;
     if (dtype == ASTRA_BF16) {
-        const int64_t total = (int64_t)ceil_div(p.Tq, kAttQ) * p.Hq;
+        int64_t total = (int64_t)ceil_div(p.Tq, kAttQ) * p.Hq;
         if (total > 0x7fffffff) return ASTRA_ERR_SHAPE;
+        // short sequences with 64-wide heads: when 128-row query blocks would leave half of the compute units without a
+        // workgroup, 64-row blocks whose tiles are dealt to four wavefronts per query group (half the iterations each)
+        const bool four = head_dim == 64 && total <= kAttCus / 2;
+        if (four) total = (int64_t)ceil_div(p.Tq, kAttQ / 2) * p.Hq;
         const bool vt = p.v_transposed != 0;
         const bool lost = p.valid_bits != nullptr;
         if (head_dim != 64 && head_dim != 128) return ASTRA_ERR_UNSUPPORTED;
@@ -505,6 +539,11 @@ int launch_attention(int dtype, const AttnParams& p_in, int head_dim, hipStream_
             else if (vt) attn_bf16_kernel<128, true><<<(int)total, kAttThreads, 0, s>>>(p);
             else if (lost) attn_bf16_kernel<128, false, true><<<(int)total, kAttThreads, 0, s>>>(p);
             else attn_bf16_kernel<128, false><<<(int)total, kAttThreads, 0, s>>>(p);
+        } else if (four) {
+            if (vt && lost) attn_bf16_kernel<64, true, true, 4><<<(int)total, kAttThreads, 0, s>>>(p);
+            else if (vt) attn_bf16_kernel<64, true, false, 4><<<(int)total, kAttThreads, 0, s>>>(p);
+            else if (lost) attn_bf16_kernel<64, false, true, 4><<<(int)total, kAttThreads, 0, s>>>(p);
+            else attn_bf16_kernel<64, false, false, 4><<<(int)total, kAttThreads, 0, s>>>(p);
         } else if (head_dim == 64) {
             if (vt && lost) attn_bf16_kernel<64, true, true><<<(int)total, kAttThreads, 0, s>>>(p);
             else if (vt) attn_bf16_kernel<64, true><<<(int)total, kAttThreads, 0, s>>>(p);

@@ -35,6 +35,11 @@ CASES = [
     (1, 5, 2, 1, 128, "bf16", 0, False, 0),           # single query row
     (130, 333, 8, 2, 128, "bf16", 0, False, 0),       # GQA, ragged everywhere
     (200, 450, 8, 2, 128, "bf16", 0, True, 333),      # GQA causal, ragged, some non-local rows hidden
+    # 64-wide heads run on 64-row query blocks with four tile parities while 128-row blocks would fill at most half of the
+    # chip (every case above); beyond that on 128-row blocks with two:
+    (1500, 600, 12, 12, 64, "bf16", 1, False, 0),     # 144 blocks of 128 rows: two parities, class row, ragged
+    (1400, 650, 12, 4, 64, "bf16", 0, True, 650),     # the same kernel causal with grouped queries
+    (70, 131, 12, 12, 64, "bf16", 0, True, 131),      # four parities, three tiles + a key: dummy tiles in the last iteration
 ]
 
 

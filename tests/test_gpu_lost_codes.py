@@ -32,6 +32,7 @@ CASES = [
     (200, 450, 8, 2, 128, "bf16", True, 333, 0.05),
     (128, 256, 4, 4, 128, "bf16", False, 0, 1.0),        # everything lost: plain local attention
     (128, 320, 4, 4, 64, "bf16", False, 0, -64.0),       # one whole 64-key tile lost, the rest present
+    (1400, 700, 12, 12, 64, "bf16", True, 700, 0.1),     # 64-wide heads on 128-row query blocks (more than half a chip of them)
 ]
 
 

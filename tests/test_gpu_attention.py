@@ -40,6 +40,9 @@ CASES = [
     (1500, 600, 12, 12, 64, "bf16", 1, False, 0),     # 144 blocks of 128 rows: two parities, class row, ragged
     (1400, 650, 12, 4, 64, "bf16", 0, True, 650),     # the same kernel causal with grouped queries
     (70, 131, 12, 12, 64, "bf16", 0, True, 131),      # four parities, three tiles + a key: dummy tiles in the last iteration
+    (1, 5, 2, 1, 64, "bf16", 0, False, 0),            # four parities, a single query row and a single tile
+    (65, 1, 4, 2, 64, "bf16", 1, False, 0),           # a second query block of one row; one non-local key; class row
+    (129, 260, 4, 4, 64, "bf16", 0, True, 100),       # causal with rows of the non-local set hidden, ragged blocks
 ]
 
 

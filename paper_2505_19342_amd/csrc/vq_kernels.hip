@@ -450,29 +450,46 @@ __global__ __launch_bounds__(256) void vq_encode_bf16_kernel(const uint16_t* __r
     float best = -INFINITY;
     int arg = 0;
 
+    // The pieces of the tile after the current one are fetched into registers while the current one is multiplied (the
+    // loads are not 16-byte aligned in general, so they cannot go to LDS directly): (codeword tile, contraction tile)
+    // pairs in walking order.
+    uint4 stage[4];
+    float stage_cn = 0.f;
+    auto fetch = [&](int cw0, int kt) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int c = tid + 256 * it;
+            const int cw = c >> 3, kc = c & 7;
+            const int cwg = cw0 + cw < K ? cw0 + cw : K - 1;
+            stage[it] = load_slice_chunk(cb_g + (int64_t)cwg * dg, kt * kEncKt + kc * 8, dg, vec_ok);
+        }
+        if (kt == 0 && tid < kEncCw) {
+            const int cwg = cw0 + tid;
+            stage_cn = cwg < K ? -0.5f * cn_g[cwg] : -INFINITY;
+        }
+    };
+    fetch(0, 0);
     for (int cw0 = 0; cw0 < K; cw0 += kEncCw) {
         f32x16 acc[4];
         for (int kt = 0; kt < n_kt; ++kt) {
             __syncthreads();      // previous tile fully consumed
-            // stage codebook tile: 1024 pieces, 4 per thread
+            // the staged tile goes to LDS: 1024 pieces, 4 per thread
 #pragma unroll
             for (int it = 0; it < 4; ++it) {
                 const int c = tid + 256 * it;
                 const int cw = c >> 3, kc = c & 7;
-                const int cwg = cw0 + cw < K ? cw0 + cw : K - 1;
-                const uint4 v = load_slice_chunk(cb_g + (int64_t)cwg * dg, kt * kEncKt + kc * 8, dg, vec_ok);
-                cb_lds[cw * 8 + (kc ^ (cw & 7))] = v;
+                cb_lds[cw * 8 + (kc ^ (cw & 7))] = stage[it];
             }
-            if (kt == 0 && tid < kEncCw) {
-                const int cwg = cw0 + tid;
-                cn_lds[tid] = cwg < K ? -0.5f * cn_g[cwg] : -INFINITY;
-            }
+            if (kt == 0 && tid < kEncCw) cn_lds[tid] = stage_cn;
             if (n_kt > 1) {
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks)
                     xfrag[ks] = as_bf16x8(load_slice_chunk(xrow, kt * kEncKt + 16 * ks + 8 * h, dg, vec_ok));
             }
             __syncthreads();
+            // next pair on its way
+            if (kt + 1 < n_kt) fetch(cw0, kt + 1);
+            else if (cw0 + kEncCw < K) fetch(cw0 + kEncCw, 0);
             if (kt == 0) {
 #pragma unroll
                 for (int mb = 0; mb < 4; ++mb)

@@ -402,30 +402,39 @@ __global__ __launch_bounds__(256) void vq_encode_f32_kernel(const float* __restr
 // ------------------------------------------------------------------------------------------------
 constexpr int kEncTokens = 128;   // tokens per workgroup
 
-// 8 consecutive bf16 of a row slice of length dg starting at element k; zero beyond dg.
+// 8 consecutive bf16 of a row slice of length dg starting at element k; zero beyond dg.  Loads are never guarded
+// (a guarded load compiles to a branch with a wait of its own): addresses are clamped into the slice and the
+// values beyond it replaced afterwards.
 __device__ __forceinline__ uint4 load_slice_chunk(const uint16_t* __restrict__ row, int k, int dg, bool vec_ok) {
-    uint4 r = make_uint4(0, 0, 0, 0);
+    uint4 r;
     if (vec_ok) {
-        if (k < dg) r = *reinterpret_cast<const uint4*>(row + k);
+        r = *reinterpret_cast<const uint4*>(row + (k < dg ? k : dg - 8));
+        if (k >= dg) r = make_uint4(0, 0, 0, 0);
     } else {
-        uint16_t e[8];
+        uint32_t e[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) e[j] = (k + j < dg) ? row[k + j] : (uint16_t)0;
-        r.x = e[0] | ((uint32_t)e[1] << 16);
-        r.y = e[2] | ((uint32_t)e[3] << 16);
-        r.z = e[4] | ((uint32_t)e[5] << 16);
-        r.w = e[6] | ((uint32_t)e[7] << 16);
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t v = row[k + j < dg ? k + j : dg - 1];
+            e[j] = k + j < dg ? v : 0u;
+        }
+        r.x = e[0] | (e[1] << 16);
+        r.y = e[2] | (e[3] << 16);
+        r.z = e[4] | (e[5] << 16);
+        r.w = e[6] | (e[7] << 16);
     }
     return r;
 }
 
-template <typename CodeT>
+// DW: slices of an even length that is no multiple of 8, at most 64 values (e.g. D = 768 in 64 groups of 12).  A tile
+// of 128 codewords is then a contiguous run of 64 * dg 32-bit words: each thread fetches words tid, tid + 256, ...
+// (coalesced) and writes each into the padded LDS layout at a position worked out once; the padding is zeroed once.
+template <typename CodeT, bool DW>
 __global__ __launch_bounds__(256) void vq_encode_bf16_kernel(const uint16_t* __restrict__ x, int64_t ldx, int n_tokens,
                                                              const uint16_t* __restrict__ codebook,
                                                              const float* __restrict__ cnorm, CodeT* __restrict__ codes,
                                                              int G, int K, int dg) {
     __shared__ uint4 cb_lds[kEncCw * kEncKt / 8];     // 16 KiB: [128 codewords][8 pieces of 8 bf16], swizzled
-    __shared__ float cn_lds[kEncCw];
+    __shared__ __align__(16) float cn_lds[kEncCw];
 
     const int g = blockIdx.y;
     const int tid = threadIdx.x;
@@ -444,7 +453,10 @@ __global__ __launch_bounds__(256) void vq_encode_bf16_kernel(const uint16_t* __r
     bf16x8 xfrag[4];
     if (n_kt == 1) {
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) xfrag[ks] = as_bf16x8(load_slice_chunk(xrow, 16 * ks + 8 * h, dg, vec_ok));
+        for (int ks = 0; ks < 4; ++ks) {
+            xfrag[ks] = as_bf16x8(make_uint4(0, 0, 0, 0));
+            if (16 * ks < dg) xfrag[ks] = as_bf16x8(load_slice_chunk(xrow, 16 * ks + 8 * h, dg, vec_ok));
+        }
     }
 
     float best = -INFINITY;
@@ -453,15 +465,42 @@ __global__ __launch_bounds__(256) void vq_encode_bf16_kernel(const uint16_t* __r
     // The pieces of the tile after the current one are fetched into registers while the current one is multiplied (the
     // loads are not 16-byte aligned in general, so they cannot go to LDS directly): (codeword tile, contraction tile)
     // pairs in walking order.
+    constexpr int kDwMax = 16;                          // 64 * dg words per tile over 256 threads, dg <= 64
     uint4 stage[4];
+    uint32_t stage_dw[DW ? kDwMax : 1];
+    int dw_lds[DW ? kDwMax : 1];                        // byte position in cb_lds of word tid + 256 * n of a tile; -1: none
     float stage_cn = 0.f;
-    auto fetch = [&](int cw0, int kt) {
+    const int tile_dw = 64 * dg;                        // DW: words per full tile
+    const uint32_t* cb_dw = reinterpret_cast<const uint32_t*>(cb_g);
+    const int last_dw = (K * dg >> 1) - 1;
+    if (DW) {
+        for (int c = tid; c < kEncCw * kEncKt / 8; c += 256) cb_lds[c] = make_uint4(0, 0, 0, 0);
+        const float inv_dg = 1.0f / (float)dg;
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            const int c = tid + 256 * it;
-            const int cw = c >> 3, kc = c & 7;
-            const int cwg = cw0 + cw < K ? cw0 + cw : K - 1;
-            stage[it] = load_slice_chunk(cb_g + (int64_t)cwg * dg, kt * kEncKt + kc * 8, dg, vec_ok);
+        for (int n = 0; n < kDwMax; ++n) {
+            const int e = 2 * (tid + 256 * n);          // first of the word's two values, counted from the tile's start
+            const int cw = (int)(((float)e + 0.5f) * inv_dg);      // exact: e < 8192, dg <= 64
+            const int k = e - cw * dg;
+            dw_lds[n] = e < 2 * tile_dw ? (cw * 8 + ((k >> 3) ^ (cw & 7))) * 16 + (k & 7) * 2 : -1;
+        }
+    }
+    auto fetch = [&](int cw0, int kt) {
+        if (DW) {
+            const int first = cw0 * (dg >> 1);
+#pragma unroll
+            for (int n = 0; n < kDwMax; ++n)
+                if (256 * n < tile_dw) {                // the same for every thread
+                    const int w = first + tid + 256 * n;
+                    stage_dw[n] = cb_dw[w < last_dw ? w : last_dw];
+                }
+        } else {
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                const int c = tid + 256 * it;
+                const int cw = c >> 3, kc = c & 7;
+                const int cwg = cw0 + cw < K ? cw0 + cw : K - 1;
+                stage[it] = load_slice_chunk(cb_g + (int64_t)cwg * dg, kt * kEncKt + kc * 8, dg, vec_ok);
+            }
         }
         if (kt == 0 && tid < kEncCw) {
             const int cwg = cw0 + tid;
@@ -472,13 +511,20 @@ __global__ __launch_bounds__(256) void vq_encode_bf16_kernel(const uint16_t* __r
     for (int cw0 = 0; cw0 < K; cw0 += kEncCw) {
         f32x16 acc[4];
         for (int kt = 0; kt < n_kt; ++kt) {
-            __syncthreads();      // previous tile fully consumed
-            // the staged tile goes to LDS: 1024 pieces, 4 per thread
+            __syncthreads();      // previous tile fully consumed (DW, first pass: the zero fill is complete)
+            // the staged tile goes to LDS
+            if (DW) {
 #pragma unroll
-            for (int it = 0; it < 4; ++it) {
-                const int c = tid + 256 * it;
-                const int cw = c >> 3, kc = c & 7;
-                cb_lds[cw * 8 + (kc ^ (cw & 7))] = stage[it];
+                for (int n = 0; n < kDwMax; ++n)
+                    if (256 * n < tile_dw && dw_lds[n] >= 0)
+                        *reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(cb_lds) + dw_lds[n]) = stage_dw[n];
+            } else {
+#pragma unroll
+                for (int it = 0; it < 4; ++it) {
+                    const int c = tid + 256 * it;
+                    const int cw = c >> 3, kc = c & 7;
+                    cb_lds[cw * 8 + (kc ^ (cw & 7))] = stage[it];
+                }
             }
             if (kt == 0 && tid < kEncCw) cn_lds[tid] = stage_cn;
             if (n_kt > 1) {
@@ -494,7 +540,11 @@ __global__ __launch_bounds__(256) void vq_encode_bf16_kernel(const uint16_t* __r
 #pragma unroll
                 for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[mb][v] = cn_lds[mb * 32 + acc_row(v, h)];
+                    for (int q = 0; q < 4; ++q) {
+                        const float4 c4 = *reinterpret_cast<const float4*>(&cn_lds[mb * 32 + 8 * q + 4 * h]);
+                        acc[mb][4 * q + 0] = c4.x; acc[mb][4 * q + 1] = c4.y;
+                        acc[mb][4 * q + 2] = c4.z; acc[mb][4 * q + 3] = c4.w;
+                    }
             }
             const int k_left = dg - kt * kEncKt;
             const int n_ks = k_left >= kEncKt ? 4 : (k_left + 15) / 16;
@@ -568,12 +618,18 @@ int launch_vq_encode(const astra_vq_desc& d, const void* x, int64_t ldx, int64_t
         if (G > 65535) return ASTRA_ERR_SHAPE;
         if (vq_encode_wide_ok(K, dg, ldx)) return launch_vq_encode_wide(d, x, ldx, n_tokens, codebook, cnorm, codes, s);
         dim3 grid((unsigned)n_tb, (unsigned)G);
-        if (d.code_type == ASTRA_CODE_U8)
-            vq_encode_bf16_kernel<uint8_t><<<grid, 256, 0, s>>>((const uint16_t*)x, ldx, (int)n_tokens, (const uint16_t*)codebook,
-                                                                cnorm, (uint8_t*)codes, G, K, dg);
-        else
-            vq_encode_bf16_kernel<uint16_t><<<grid, 256, 0, s>>>((const uint16_t*)x, ldx, (int)n_tokens, (const uint16_t*)codebook,
-                                                                 cnorm, (uint16_t*)codes, G, K, dg);
+        // even slices of at most 64 values that are not whole 16-byte pieces: tiles fetched as 32-bit words
+        const bool dw = dg % 2 == 0 && dg % 8 != 0 && dg <= 64 && (int64_t)K * dg < 0x7fffffff &&
+                        reinterpret_cast<uintptr_t>(codebook) % 4 == 0;
+        const uint16_t* xb = (const uint16_t*)x;
+        const uint16_t* cb = (const uint16_t*)codebook;
+        if (d.code_type == ASTRA_CODE_U8) {
+            if (dw) vq_encode_bf16_kernel<uint8_t, true><<<grid, 256, 0, s>>>(xb, ldx, (int)n_tokens, cb, cnorm, (uint8_t*)codes, G, K, dg);
+            else vq_encode_bf16_kernel<uint8_t, false><<<grid, 256, 0, s>>>(xb, ldx, (int)n_tokens, cb, cnorm, (uint8_t*)codes, G, K, dg);
+        } else {
+            if (dw) vq_encode_bf16_kernel<uint16_t, true><<<grid, 256, 0, s>>>(xb, ldx, (int)n_tokens, cb, cnorm, (uint16_t*)codes, G, K, dg);
+            else vq_encode_bf16_kernel<uint16_t, false><<<grid, 256, 0, s>>>(xb, ldx, (int)n_tokens, cb, cnorm, (uint16_t*)codes, G, K, dg);
+        }
     } else {
         const int64_t waves = n_tokens * G;
         const int64_t blocks = ceil_div(waves, 4);

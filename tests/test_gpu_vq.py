@@ -46,6 +46,15 @@ ENCODE_CASES = [
     (37, 3, 1001, 128, "bf16", "normal"),         # K odd: scalar norm loads, last pass ragged against the 32-codeword blocks
     (65, 2, 2500, 320, "bf16", "normal"),         # three passes over the codewords, odd number of 64-chunks
     (5, 6, 16, 64 * 3, "bf16", "normal"),         # K below one block of a single wavefront
+    # even slices that are no whole 16-byte pieces (tiles fetched as 32-bit words), and odd ones (value by value)
+    (512, 64, 1024, 12, "bf16", "normal"),        # sweep corner at its largest codebook: 8 codeword tiles
+    (130, 3, 300, 2, "bf16", "normal"),           # shortest even slice; K = 2 tiles + 44 codewords
+    (77, 5, 129, 6, "bf16", "normal"),            # second tile holds one codeword
+    (140, 2, 520, 62, "bf16", "normal"),          # longest such slice: the last thread pass of a tile is ragged
+    (90, 4, 257, 36, "bf16", "student_t5"),       # three contraction steps, the third partly padding
+    (60, 7, 200, 20, "bf16", "normal"),           # 140 values per row: rows are not 16-byte multiples
+    (50, 3, 150, 7, "bf16", "normal"),            # odd slice length
+    (40, 1, 300, 33, "bf16", "normal"),           # odd, three contraction steps
 ]
 
 

@@ -491,6 +491,7 @@ int astra_codebook_update(const astra_vq_desc* desc, const int32_t* counts, cons
     hipStream_t s = (hipStream_t)stream;
     const int dg = desc->d_model / desc->n_groups;
     const int64_t n_cw = (int64_t)desc->n_groups * desc->codebook_size;
+    if (ceil_div(n_cw * dg, kTrThreads) > 0x7fffffff) return ASTRA_ERR_SHAPE;
     const int blocks = (int)ceil_div(n_cw * dg, kTrThreads);
     if (desc->dtype == ASTRA_BF16)
         codebook_update_kernel<uint16_t><<<blocks, kTrThreads, 0, s>>>(counts, sums, gamma, ema_n, ema_m, (const uint16_t*)codebook_old, n_cw,
@@ -519,6 +520,7 @@ int astra_navq_forward(const astra_vq_desc* desc, const void* codes, int64_t n_t
     rc = launch_gemm_batch(desc->dtype, &p, 1, s, nullptr, nullptr, true);
     if (rc) return rc;
     const int64_t n = n_tokens * D;
+    if (ceil_div(n, kTrThreads) > 0x7fffffff) return ASTRA_ERR_SHAPE;
     const int blocks = (int)ceil_div(n, kTrThreads);
     const int code16 = desc->code_type == ASTRA_CODE_U16 ? 1 : 0;
     if (desc->dtype == ASTRA_BF16)

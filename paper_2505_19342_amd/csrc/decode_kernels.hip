@@ -32,7 +32,7 @@ struct DecodeParams {
     const void* cb_v;
     void* out;
     float* lse;
-    float* lut;      // [H_q][n_gh][K]
+    float* lut;      // [H_kv][n_gh][K][H_q / H_kv]
     float* part;     // [n_chunks][H_q][dh + 2]: unnormalised o, then m, l
     int32_t Hq, Hkv, dh, n_local, n_nonlocal, G, K, dg, code16, n_gh, chunk_loc, chunk_nl, n_chunks_loc, n_chunks_nl;
     int32_t aux_floats;      // floats of the LDS region shared by the query floats, the table slice and the cross-phase sums
@@ -106,6 +106,33 @@ __device__ __forceinline__ void ld_seg(const T* p, float (&o)[CPL]) {
     }
 }
 
+// N consecutive elements kept as the 32-bit words they arrive in (bf16: two per word), unpacked where they are used: a
+// row in flight then costs half the registers of its floats.  The address is aligned to the whole segment.
+template <typename T, int N>
+struct Seg {
+    static constexpr int W = sizeof(T) == 2 ? N / 2 : N;
+    uint32_t w[W];
+    __device__ __forceinline__ void load(const T* p) {
+        if constexpr (W % 4 == 0) {
+#pragma unroll
+            for (int i = 0; i < W / 4; ++i) {
+                const u32x4 v = reinterpret_cast<const u32x4*>(p)[i];
+                w[4 * i] = v.x; w[4 * i + 1] = v.y; w[4 * i + 2] = v.z; w[4 * i + 3] = v.w;
+            }
+        } else if constexpr (W == 2) {
+            const u32x2 v = *reinterpret_cast<const u32x2*>(p);
+            w[0] = v.x; w[1] = v.y;
+        } else {
+#pragma unroll
+            for (int i = 0; i < W; ++i) w[i] = reinterpret_cast<const uint32_t*>(p)[i];
+        }
+    }
+    __device__ __forceinline__ float get(int i) const {
+        if constexpr (sizeof(T) == 2) return __uint_as_float((i & 1) ? (w[i >> 1] & 0xffff0000u) : (w[i >> 1] << 16));
+        else return __uint_as_float(w[i]);
+    }
+};
+
 // One workgroup: 256 consecutive codewords k of one (query head, group touching its KV head).  The head's slice of q
 // sits in LDS as floats; a thread reads its codeword's slice with up to 8 vector loads in flight.
 template <typename T>
@@ -143,7 +170,9 @@ __global__ __launch_bounds__(kDecThreads) void decode_lut_kernel(const DecodePar
             for (int c = 0; c < n; ++c) acc = fmaf(qs[c], ldf(cw + c), acc);
         }
     }
-    p.lut[((int64_t)h * p.n_gh + gi) * p.K + k] = acc * p.scale;
+    // the entries of the query heads that share a KV head sit side by side: a token's code picks all of them with one LDS read
+    const int rep = p.Hq / p.Hkv;
+    p.lut[((((int64_t)j * p.n_gh + gi) * p.K + k) * rep) + (h - j * rep)] = acc * p.scale;
 }
 
 // sum / max over each row of 16 consecutive lanes with data-parallel-primitive moves (no LDS): swap inside pairs, swap
@@ -167,29 +196,37 @@ constexpr int kDecRows = kDecThreads / 16;
 template <bool MAX, int REP>
 __device__ __forceinline__ void block_reduce_multi(float (&v)[REP], float (*red)[kDecMaxRep]) {
 #pragma unroll
-    for (int r = 0; r < REP; ++r) v[r] = row16_reduce<MAX>(v[r]);
-    __syncthreads();                                 // earlier readers of red are done
-    if ((threadIdx.x & 15) == 0)
+    for (int r = 0; r < REP; ++r) {
+        v[r] = row16_reduce<MAX>(v[r]);
+        // the four rows of the wavefront, read from their first lanes: pairs of rows, then the two halves
+        float a[4];
 #pragma unroll
-        for (int r = 0; r < REP; ++r) red[threadIdx.x >> 4][r] = v[r];
+        for (int i = 0; i < 4; ++i) a[i] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v[r]), 16 * i));
+        v[r] = MAX ? fmaxf(fmaxf(a[0], a[1]), fmaxf(a[2], a[3])) : (a[0] + a[1]) + (a[2] + a[3]);
+    }
+    __syncthreads();                                 // earlier readers of red are done
+    if ((threadIdx.x & (kWave - 1)) == 0)
+#pragma unroll
+        for (int r = 0; r < REP; ++r) red[threadIdx.x / kWave][r] = v[r];
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < REP; ++r) {
         float t = red[0][r];
 #pragma unroll
-        for (int w = 1; w < kDecRows; ++w) t = MAX ? fmaxf(t, red[w][r]) : t + red[w][r];
+        for (int w = 1; w < kDecThreads / kWave; ++w) t = MAX ? fmaxf(t, red[w][r]) : t + red[w][r];
         v[r] = t;
     }
 }
 
-constexpr int kDecSub = 256;    // tokens per pass of a workgroup (one per thread)
+constexpr int kDecSub = 256;    // tokens per pass of a workgroup over the local cache (one per thread)
+constexpr int kDecSubNl = 512;  // ... over the index cache (two per thread: half as many barriers and reductions per token)
 constexpr int kDecTok = 4;      // cached rows a 16-lane group has in flight in the score pass
 constexpr int kDecBatch = 8;    // value rows a thread has in flight in the value pass
 
 // One workgroup: KV head blockIdx.y, tokens [chunk * bx, ...) of the local cache (NL = false) or of the index
 // cache (NL = true), walked in passes of 256 tokens with a running maximum (the accumulated sums are rescaled when it
 // grows), so a chunk may be arbitrarily long while the LDS holds one pass: s[rep][256] scores then probabilities;
-// aux = the table slice [rep][n_gh][K] (index cache), at the end the cross-phase sums; cvs[256][n_gh] the value codes
+// aux = the table slice [n_gh][K][rep] (index cache), at the end the cross-phase sums; cvs[256][n_gh] the value codes
 // of the pass (index cache).
 // DH: the head dimension when it is 64 or 128 and the codewords are cut into whole octets (then a lane of the score
 // pass holds DH / 16 channels, a thread of the value pass 8, and nothing depends on the lane), or 0: any even dh <= 256,
@@ -207,9 +244,11 @@ __device__ __forceinline__ void decode_partial_body(const DecodeParams& p, const
     const int chunk = NL ? p.chunk_nl : p.chunk_loc;
     const int t0 = bx * chunk;
     const int t1 = min(t0 + chunk, NL ? p.n_nonlocal : p.n_local);
-    float* s = lds;                                  // [rep][kDecSub]
-    float* aux = lds + rep * kDecSub;
-    int* cvs = reinterpret_cast<int*>(aux + p.aux_floats);
+    constexpr int SUB = NL ? kDecSubNl : kDecSub;    // tokens per pass
+    constexpr int TPT = SUB / kDecThreads;           // tokens per thread and pass
+    float* s = lds;                                  // [rep][SUB]
+    float* aux = lds + rep * SUB;
+    uint16_t* cvs = reinterpret_cast<uint16_t*>(aux + p.aux_floats);    // [SUB][n_gh]
     const int c_head = j * dh;
     const int g_lo = c_head / p.dg, g_hi = (c_head + dh - 1) / p.dg;
 
@@ -253,23 +292,82 @@ __device__ __forceinline__ void decode_partial_body(const DecodeParams& p, const
         for (int e = 0; e < VC; ++e) acc[r][e] = 0.f;
     }
 
-    for (int b0 = t0; b0 < t1; b0 += kDecSub) {
-        const int nt = min(kDecSub, t1 - b0);
-        // ---- raw scores of this pass; thread tid ends up with those of token b0 + tid
-        float sc[REP];
+    // index cache: the codes (and the validity word) of a pass are fetched one pass ahead, while the previous pass gathers
+    // its value codewords, when at most kDecPre groups touch a head (otherwise they are loaded where they are used)
+    constexpr int kDecPre = 4;
+    const int n_g = g_hi - g_lo + 1;
+    const bool pre = NL && n_g <= kDecPre;
+    int ck_n[TPT][NL ? kDecPre : 1], cv_n[TPT][NL ? kDecPre : 1];
+    bool ok_n[TPT];
 #pragma unroll
-        for (int r = 0; r < REP; ++r) sc[r] = -INFINITY;
+    for (int q = 0; q < TPT; ++q) ok_n[q] = true;
+    // a head's codes of a token as one load when they are 4 or 8 aligned bytes (a strided 2-byte load costs the memory
+    // pipeline a cache line per lane, as the wide one does)
+    const int cb = p.code16 ? 2 : 1;
+    const int cw_bytes = n_g * cb;
+    const bool wide = NL && n_g <= kDecPre && (cw_bytes == 8 || cw_bytes == 4) && (p.G * cb) % cw_bytes == 0 && (g_lo * cb) % cw_bytes == 0;
+    auto unpack_codes = [&](const void* codes, int64_t t, int (&c)[NL ? kDecPre : 1]) {
+        const char* at = (const char*)codes + (t * p.G + g_lo) * cb;
+        uint32_t lo = 0, hi = 0;
+        if (cw_bytes == 8) {
+            const u32x2 v = *reinterpret_cast<const u32x2*>(at);
+            lo = v.x;
+            hi = v.y;
+        } else {
+            lo = *reinterpret_cast<const uint32_t*>(at);
+        }
+        if (p.code16) {
+            c[0] = lo & 0xffffu;
+            if constexpr (NL) { c[1] = lo >> 16; c[2] = hi & 0xffffu; c[3] = hi >> 16; }
+        } else {
+            c[0] = lo & 0xffu;
+            if constexpr (NL) { c[1] = (lo >> 8) & 0xffu; c[2] = (lo >> 16) & 0xffu; c[3] = lo >> 24; }
+        }
+#pragma unroll
+        for (int gi = 0; gi < (NL ? kDecPre : 1); ++gi) c[gi] = min(c[gi], p.K - 1);
+    };
+    auto fetch_codes = [&](int b0) {
+#pragma unroll
+        for (int q = 0; q < TPT; ++q) {
+            const int64_t t = min(b0 + q * kDecThreads + tid, t1 - 1);      // beyond the chunk: a repeat, unused
+            if (wide) {
+                unpack_codes(p.codes_k, t, ck_n[q]);
+                unpack_codes(p.codes_v, t, cv_n[q]);
+            } else {
+#pragma unroll
+                for (int gi = 0; gi < kDecPre; ++gi)
+                    if (gi < n_g) {                       // the same for every thread
+                        ck_n[q][gi] = load_code(p.codes_k, p.code16, t * p.G + g_lo + gi, p.K);
+                        cv_n[q][gi] = load_code(p.codes_v, p.code16, t * p.G + g_lo + gi, p.K);
+                    }
+            }
+            if (p.valid_bits) ok_n[q] = (p.valid_bits[t >> 6] >> (t & 63)) & 1ull;
+        }
+    };
+    if constexpr (NL) {
+        if (pre && t0 < t1) fetch_codes(t0);
+    }
+
+    for (int b0 = t0; b0 < t1; b0 += SUB) {
+        const int nt = min(SUB, t1 - b0);
+        // ---- raw scores of this pass; thread tid ends up with those of tokens b0 + tid (+ 256)
+        float sc[TPT][REP];
+#pragma unroll
+        for (int q = 0; q < TPT; ++q)
+#pragma unroll
+            for (int r = 0; r < REP; ++r) sc[q][r] = -INFINITY;
         if (!NL) {
             constexpr int STEP = kDecTok * kDecRows;
 #pragma unroll
             for (int tb = 0; tb < kDecSub; tb += STEP) {
-                float kf[kDecTok][CPL];
+                float kf[DH ? 1 : kDecTok][DH ? 1 : CPL];
+                Seg<T, DH ? CPL : 2> kseg[DH ? kDecTok : 1];
 #pragma unroll
                 for (int u = 0; u < kDecTok; ++u) {
                     const int t = min(tb + grp + 16 * u, nt - 1);           // rows beyond the pass repeat its last row, unused
                     const T* __restrict__ kr = (const T*)p.k_loc + (int64_t)(b0 + t) * dkv + c_head;
                     if constexpr (DH != 0) {
-                        ld_seg<T, CPL>(kr + c_lo, kf[u]);
+                        kseg[u].load(kr + c_lo);
                     } else {
 #pragma unroll
                         for (int c = 0; c < CPL; ++c) kf[u][c] = ldf(kr + min(c_lo + c, dh - 1));      // masked by the zeros in qf
@@ -282,50 +380,111 @@ __device__ __forceinline__ void decode_partial_body(const DecodeParams& p, const
                     for (int r = 0; r < REP; ++r) {
                         float v = 0.f;
 #pragma unroll
-                        for (int c = 0; c < CPL; ++c) v = fmaf(qf[r][c], kf[u][c], v);
+                        for (int c = 0; c < CPL; ++c) {
+                            if constexpr (DH != 0) v = fmaf(qf[r][c], kseg[u].get(c), v);
+                            else v = fmaf(qf[r][c], kf[u][c], v);
+                        }
                         v = row16_reduce<false>(v);
-                        s[r * kDecSub + t] = t < nt ? v : -INFINITY;      // all 16 lanes of the row store the same value: no branch
+                        s[r * SUB + t] = t < nt ? v : -INFINITY;      // all 16 lanes of the row store the same value: no branch
                     }
                 }
             }
             __syncthreads();
 #pragma unroll
-            for (int r = 0; r < REP; ++r) sc[r] = s[r * kDecSub + tid];
-        } else if (tid < nt) {
-            const int64_t t = b0 + tid;
-            bool ok = true;
-            if (p.valid_bits) ok = (p.valid_bits[t >> 6] >> (t & 63)) & 1ull;
-            float a[REP];
+            for (int r = 0; r < REP; ++r) sc[0][r] = s[r * SUB + tid];
+        } else if (pre) {
 #pragma unroll
-            for (int r = 0; r < REP; ++r) a[r] = 0.f;
-            for (int g = g_lo; g <= g_hi; ++g) {
-                const int ck = load_code(p.codes_k, p.code16, t * p.G + g, p.K);
-                cvs[tid * p.n_gh + (g - g_lo)] = load_code(p.codes_v, p.code16, t * p.G + g, p.K);
+            for (int q = 0; q < TPT; ++q) {
+                if (q * kDecThreads >= nt) break;         // a short pass: the same for every thread
+                const int slot = q * kDecThreads + tid;
+                float a[REP];
 #pragma unroll
-                for (int r = 0; r < REP; ++r) a[r] += aux[(r * p.n_gh + (g - g_lo)) * p.K + ck];
+                for (int r = 0; r < REP; ++r) a[r] = 0.f;
+#pragma unroll
+                for (int gi = 0; gi < kDecPre; ++gi)
+                    if (gi < n_g) {
+                        cvs[slot * p.n_gh + gi] = (uint16_t)cv_n[q][gi];
+#pragma unroll
+                        for (int r = 0; r < REP; ++r) a[r] += aux[(gi * p.K + ck_n[q][gi]) * REP + r];
+                    }
+#pragma unroll
+                for (int r = 0; r < REP; ++r)
+                    if (ok_n[q] && slot < nt) sc[q][r] = a[r];
             }
+        } else {
 #pragma unroll
-            for (int r = 0; r < REP; ++r)
-                if (ok) sc[r] = a[r];
+            for (int q = 0; q < TPT; ++q) {
+                const int slot = q * kDecThreads + tid;
+                if (slot < nt) {
+                    const int64_t t = b0 + slot;
+                    bool ok = true;
+                    if (p.valid_bits) ok = (p.valid_bits[t >> 6] >> (t & 63)) & 1ull;
+                    float a[REP];
+#pragma unroll
+                    for (int r = 0; r < REP; ++r) a[r] = 0.f;
+                    for (int g = g_lo; g <= g_hi; ++g) {
+                        const int ck = load_code(p.codes_k, p.code16, t * p.G + g, p.K);
+                        cvs[slot * p.n_gh + (g - g_lo)] = (uint16_t)load_code(p.codes_v, p.code16, t * p.G + g, p.K);
+#pragma unroll
+                        for (int r = 0; r < REP; ++r) a[r] += aux[((g - g_lo) * p.K + ck) * REP + r];
+                    }
+#pragma unroll
+                    for (int r = 0; r < REP; ++r)
+                        if (ok) sc[q][r] = a[r];
+                }
+            }
         }
         // ---- running maximum, probabilities, rescale
         float mx[REP];
 #pragma unroll
-        for (int r = 0; r < REP; ++r) mx[r] = sc[r];
+        for (int r = 0; r < REP; ++r) {
+            mx[r] = sc[0][r];
+#pragma unroll
+            for (int q = 1; q < TPT; ++q) mx[r] = fmaxf(mx[r], sc[q][r]);
+        }
         block_reduce_multi<true, REP>(mx, red);          // its first barrier also orders the reads of s above before the writes below
 #pragma unroll
         for (int r = 0; r < REP; ++r) {
             const float m_new = fmaxf(m_run[r], mx[r]);
             const float alpha = m_new == -INFINITY ? 1.f : __expf(m_run[r] - m_new);      // exp(-inf) = 0 for the first pass
-            const float pr = sc[r] == -INFINITY ? 0.f : __expf(sc[r] - m_new);
-            s[r * kDecSub + tid] = pr;
-            l_own[r] = l_own[r] * alpha + pr;
+            l_own[r] *= alpha;
+#pragma unroll
+            for (int q = 0; q < TPT; ++q) {
+                if (q * kDecThreads >= nt) break;
+                const float pr = sc[q][r] == -INFINITY ? 0.f : __expf(sc[q][r] - m_new);
+                s[r * SUB + q * kDecThreads + tid] = pr;
+                l_own[r] += pr;
+            }
 #pragma unroll
             for (int e = 0; e < VC; ++e) acc[r][e] *= alpha;
             m_run[r] = m_new;
         }
         __syncthreads();
+        if constexpr (NL) {
+            if (pre && b0 + SUB < t1) fetch_codes(b0 + SUB);             // on their way during the gathers below
+        }
         // ---- sum of p * value rows of this pass: kDecBatch rows in flight per thread
+        if constexpr (DH != 0) {
+            for (int tb = ph; tb < nt; tb += n_ph * kDecBatch) {
+                Seg<T, VC> raw[kDecBatch];
+#pragma unroll
+                for (int u = 0; u < kDecBatch; ++u) {
+                    const int t = min(tb + u * n_ph, nt - 1);                    // beyond the pass: a repeat with weight 0
+                    const int64_t row = NL ? (int64_t)cvs[t * p.n_gh + (gv - g_lo)] * p.dg : (int64_t)(b0 + t) * dkv;
+                    raw[u].load(vb + row);
+                }
+#pragma unroll
+                for (int u = 0; u < kDecBatch; ++u) {
+                    const int t = tb + u * n_ph;
+#pragma unroll
+                    for (int r = 0; r < REP; ++r) {
+                        const float w = t < nt ? s[r * SUB + t] : 0.f;      // 0 for a lost token, too
+#pragma unroll
+                        for (int e = 0; e < VC; ++e) acc[r][e] = fmaf(w, raw[u].get(e), acc[r][e]);
+                    }
+                }
+            }
+        } else
         for (int tb = ph; tb < nt; tb += n_ph * kDecBatch) {
             float a[kDecBatch][VC];
 #pragma unroll
@@ -339,7 +498,7 @@ __device__ __forceinline__ void decode_partial_body(const DecodeParams& p, const
                 const int t = tb + u * n_ph;
 #pragma unroll
                 for (int r = 0; r < REP; ++r) {
-                    const float w = t < nt ? s[r * kDecSub + t] : 0.f;          // 0 for a lost token, too
+                    const float w = t < nt ? s[r * SUB + t] : 0.f;          // 0 for a lost token, too
 #pragma unroll
                     for (int e = 0; e < VC; ++e) acc[r][e] = fmaf(w, a[u][e], acc[r][e]);
                 }
@@ -478,7 +637,7 @@ static int make_decode_plan(const astra_decode_desc& d, DecodePlan* pl) {
     const size_t qf = (size_t)rep * d.head_dim;
     pl->aux_floats = (int)std::max(tab, std::max(xs, qf));
     pl->lds_loc = ((size_t)rep * kDecSub + std::max(xs, qf)) * sizeof(float);
-    pl->lds_nl = ((size_t)rep * kDecSub + pl->aux_floats + (size_t)kDecSub * n_gh) * sizeof(float);
+    pl->lds_nl = ((size_t)rep * kDecSubNl + pl->aux_floats) * sizeof(float) + align_up((size_t)kDecSubNl * n_gh * sizeof(uint16_t), 16);
     if (pl->lds_nl > 150 * 1024) return ASTRA_ERR_UNSUPPORTED;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };

@@ -546,8 +546,9 @@ __device__ __forceinline__ void st_elem<float>(float* p, float v) { *p = v; }
 template <>
 __device__ __forceinline__ void st_elem<uint16_t>(uint16_t* p, float v) { *p = f32_to_bf16_bits(v); }
 
-// one workgroup per query head: the chunks' statistics are combined in parallel, then thread c sums output channel c
-// over the chunks (ascending, several loads in flight)
+// gridDim.y workgroups per query head, each with its share of the head's channels (a multiple of gridDim.y): the chunks'
+// statistics are combined in parallel (by every workgroup of the head for itself), then thread (c, part) sums output
+// channel c over the chunks part, part + n_part, ... (several loads in flight), parts added in ascending order
 template <typename T>
 __global__ __launch_bounds__(kDecThreads) void decode_reduce_kernel(const DecodeParams p) {
     extern __shared__ float w_lds[];                 // [n_chunks] weights exp(m_i - M)
@@ -574,11 +575,12 @@ __global__ __launch_bounds__(kDecThreads) void decode_reduce_kernel(const Decode
     block_reduce_multi<false, 1>(v, red);            // its barriers also publish w_lds
     const float L = v[0];
     // thread (c, part): channel c over the chunks i = part, part + n_part, ... (16 loads in flight); parts added in order
+    const int cs = p.dh / gridDim.y, c_lo = blockIdx.y * cs;      // this workgroup's channels
     int dhp = 1;
-    while (dhp < p.dh) dhp <<= 1;
-    const int n_part = kDecThreads / dhp, c = tid % dhp, part = tid / dhp;
+    while (dhp < cs) dhp <<= 1;
+    const int n_part = kDecThreads / dhp, c = c_lo + tid % dhp, part = tid / dhp;
     float o = 0.f;
-    if (c < p.dh) {
+    if (tid % dhp < cs) {
         for (int i0 = part; i0 < n_chunks; i0 += 16 * n_part) {
             float x[16];
 #pragma unroll
@@ -591,12 +593,12 @@ __global__ __launch_bounds__(kDecThreads) void decode_reduce_kernel(const Decode
     __shared__ float os[kDecThreads];
     os[tid] = o;
     __syncthreads();
-    if (tid < p.dh) {
+    if (tid < cs) {
         float t = 0.f;
         for (int q = 0; q < n_part; ++q) t += os[q * dhp + tid];
-        st_elem((T*)p.out + (int64_t)h * p.dh + tid, L > 0.f ? t / L : 0.f);
+        st_elem((T*)p.out + (int64_t)h * p.dh + c_lo + tid, L > 0.f ? t / L : 0.f);
     }
-    if (tid == 0 && p.lse) p.lse[h] = L > 0.f ? M + logf(L) : -INFINITY;
+    if (tid == 0 && blockIdx.y == 0 && p.lse) p.lse[h] = L > 0.f ? M + logf(L) : -INFINITY;
 }
 
 struct DecodePlan {
@@ -685,7 +687,9 @@ static int run_decode(const DecodeParams& p, const DecodePlan& pl, hipStream_t s
         default: return ASTRA_ERR_UNSUPPORTED;
     }
     if (rc) return rc;
-    decode_reduce_kernel<T><<<p.Hq, kDecThreads, (size_t)std::max(1, p.n_chunks_loc + p.n_chunks_nl) * sizeof(float), s>>>(p);
+    // long caches: a head's channels over four workgroups, so that each thread walks an eighth of the chunks, not half
+    const int slices = p.dh % 4 == 0 && p.n_chunks_loc + p.n_chunks_nl > 64 ? 4 : 1;
+    decode_reduce_kernel<T><<<dim3(p.Hq, slices), kDecThreads, (size_t)std::max(1, p.n_chunks_loc + p.n_chunks_nl) * sizeof(float), s>>>(p);
     return launch_status();
 }
 

@@ -433,87 +433,132 @@ __global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams
 }
 
 // ------------------------------------------------------------------------------------------------
-// fp32, vector ALU: one wavefront per (query row, head), online softmax over chunks of 64 keys (one
-// key per lane for the logits, head-dim values spread over lanes for the output).
+// fp32, vector ALU: one workgroup of four wavefronts per (query row, head).  The keys ([K-hat | K], 64 at a time: one
+// key per lane for the logits, head-dim values spread over lanes for the output) are dealt to the wavefronts chunk by
+// chunk, each wavefront runs an online softmax over its chunks, and the four partial results are merged through LDS
+// in wavefront order.  U = ceil(dh / 64) output values per lane.
 // ------------------------------------------------------------------------------------------------
+template <int U>
 __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnParams p, int dh) {
-    const int64_t wid = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
-    if (wid >= (int64_t)p.Hq * p.Tq) return;
-    const int lane = lane_id();
-    const int head = (int)(wid / p.Tq), row = (int)(wid % p.Tq);
+    constexpr int kWaves = 4;
+    constexpr int kRows = U <= 2 ? 16 : 8;           // value rows in flight
+    __shared__ float part[kWaves][U * kWave + 2];
+    const int lane = lane_id(), wave = threadIdx.x / kWave;
+    const int head = blockIdx.x / p.Tq, row = blockIdx.x % p.Tq;
     const int hk = head / (p.Hq / p.Hkv);
     const int64_t q_ld = (int64_t)p.Hq * dh, kv_ld = (int64_t)p.Hkv * dh;
     const float* __restrict__ q = (const float*)p.q + (int64_t)row * q_ld + (int64_t)head * dh;
 
     const int n_hat = p.Tn_vis;
     const int n_loc = p.causal ? row + 1 : p.Tq;
+    const int chunks_hat = (n_hat + kWave - 1) / kWave, chunks = chunks_hat + (n_loc + kWave - 1) / kWave;
     float m_run = -INFINITY, l_run = 0.f;
-    float o[4] = {0.f, 0.f, 0.f, 0.f};              // head-dim values lane, lane+64, lane+128, lane+192 (those beyond dh are never stored)
+    float o[U];                                      // head-dim values lane, lane + 64, ... (those beyond dh are never stored)
+#pragma unroll
+    for (int u = 0; u < U; ++u) o[u] = 0.f;
     const bool vec4 = dh % 4 == 0 && ((uintptr_t)p.q | (uintptr_t)p.k_loc | (uintptr_t)p.k_hat) % 16 == 0;
 
-    for (int src = 0; src < 2; ++src) {
+    for (int c = wave; c < chunks; c += kWaves) {
+        const int src = c < chunks_hat ? 0 : 1;
         const int count = src == 0 ? n_hat : n_loc;
+        const int base = (src == 0 ? c : c - chunks_hat) * kWave;
         const float* __restrict__ Kp = (const float*)(src == 0 ? p.k_hat : p.k_loc) + (int64_t)hk * dh;
         const float* __restrict__ Vp = (const float*)(src == 0 ? p.v_hat : p.v_loc) + (int64_t)hk * dh;
-        for (int base = 0; base < count; base += kWave) {
-            const int j = base + lane;
-            float s = -INFINITY;
-            const bool arrived = src != 0 || p.valid_bits == nullptr || j >= count || ((p.valid_bits[j >> 6] >> (j & 63)) & 1ull);
-            if (j < count && arrived) {
-                const float* kr = Kp + (int64_t)j * kv_ld;
-                float dot = 0.f;
-                int d = 0;
-                if (vec4)                     // same order of additions, four elements per load
-                    for (; d + 4 <= dh; d += 4) {
-                        const f32x4 kv = *reinterpret_cast<const f32x4*>(kr + d);
-                        const f32x4 qv = *reinterpret_cast<const f32x4*>(q + d);
-                        dot = fmaf(qv.x, kv.x, dot);
-                        dot = fmaf(qv.y, kv.y, dot);
-                        dot = fmaf(qv.z, kv.z, dot);
-                        dot = fmaf(qv.w, kv.w, dot);
+        const int j = base + lane;
+        float s = -INFINITY;
+        const bool arrived = src != 0 || p.valid_bits == nullptr || j >= count || ((p.valid_bits[j >> 6] >> (j & 63)) & 1ull);
+        if (j < count && arrived) {
+            const float* kr = Kp + (int64_t)j * kv_ld;
+            float dot = 0.f;
+            int d = 0;
+            if (vec4) {                   // ascending order of additions, four elements per load
+                // 32 elements at a time: the eight key loads are issued together, then consumed in ascending order
+                for (; d + 32 <= dh; d += 32) {
+                    f32x4 kv[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) kv[u] = *reinterpret_cast<const f32x4*>(kr + d + 4 * u);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const f32x4 qv = *reinterpret_cast<const f32x4*>(q + d + 4 * u);
+                        dot = fmaf(qv.x, kv[u].x, dot);
+                        dot = fmaf(qv.y, kv[u].y, dot);
+                        dot = fmaf(qv.z, kv[u].z, dot);
+                        dot = fmaf(qv.w, kv[u].w, dot);
                     }
-                for (; d < dh; ++d) dot = fmaf(q[d], kr[d], dot);
-                s = dot * p.scale;
-            }
-            float mx = s;
-            for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
-            const float m_new = fmaxf(m_run, mx);          // -inf only while every key so far was lost
-            const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-            const float alpha = expf(m_run - m_safe);
-            const float e = (j < count && arrived) ? expf(s - m_safe) : 0.f;
-            float sum = e;
-            for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
-            l_run = l_run * alpha + sum;
-            m_run = m_new;
-#pragma unroll
-            for (int u = 0; u < 4; ++u) o[u] *= alpha;
-            const int cnt = min(kWave, count - base);
-            // eight value rows in flight; rows beyond the chunk repeat its last row with weight zero
-            for (int jj = 0; jj < cnt; jj += 8) {
-                float pj[8], vv[8][4];
-#pragma unroll
-                for (int b = 0; b < 8; ++b) {
-                    const int jb = min(jj + b, cnt - 1);
-                    pj[b] = jj + b < cnt ? __shfl(e, jb) : 0.f;
-                    const float* vr = Vp + (int64_t)(base + jb) * kv_ld;
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) vv[b][u] = vr[min(lane + 64 * u, dh - 1)];
                 }
-#pragma unroll
-                for (int b = 0; b < 8; ++b)
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) o[u] = fmaf(pj[b], vv[b][u], o[u]);
+                for (; d + 4 <= dh; d += 4) {
+                    const f32x4 kv = *reinterpret_cast<const f32x4*>(kr + d);
+                    const f32x4 qv = *reinterpret_cast<const f32x4*>(q + d);
+                    dot = fmaf(qv.x, kv.x, dot);
+                    dot = fmaf(qv.y, kv.y, dot);
+                    dot = fmaf(qv.z, kv.z, dot);
+                    dot = fmaf(qv.w, kv.w, dot);
+                }
             }
+            for (; d < dh; ++d) dot = fmaf(q[d], kr[d], dot);
+            s = dot * p.scale;
+        }
+        float mx = s;
+        for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+        const float m_new = fmaxf(m_run, mx);          // -inf only while every key so far was lost
+        const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = expf(m_run - m_safe);
+        const float e = (j < count && arrived) ? expf(s - m_safe) : 0.f;
+        float sum = e;
+        for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+        l_run = l_run * alpha + sum;
+        m_run = m_new;
+#pragma unroll
+        for (int u = 0; u < U; ++u) o[u] *= alpha;
+        const int cnt = min(kWave, count - base);
+        // kRows value rows in flight; rows beyond the chunk repeat its last row with weight zero
+        for (int jj = 0; jj < cnt; jj += kRows) {
+            float pj[kRows], vv[kRows][U];
+#pragma unroll
+            for (int b = 0; b < kRows; ++b) {
+                const int jb = min(jj + b, cnt - 1);
+                pj[b] = jj + b < cnt ? __shfl(e, jb) : 0.f;
+                const float* vr = Vp + (int64_t)(base + jb) * kv_ld;
+#pragma unroll
+                for (int u = 0; u < U; ++u) vv[b][u] = vr[min(lane + 64 * u, dh - 1)];
+            }
+#pragma unroll
+            for (int b = 0; b < kRows; ++b)
+#pragma unroll
+                for (int u = 0; u < U; ++u) o[u] = fmaf(pj[b], vv[b][u], o[u]);
         }
     }
-    const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
+    // merge: wavefront w leaves (o, m, l); the first wavefront adds the four in order
+#pragma unroll
+    for (int u = 0; u < U; ++u) part[wave][u * kWave + lane] = o[u];
+    if (lane == 0) {
+        part[wave][U * kWave] = m_run;
+        part[wave][U * kWave + 1] = l_run;
+    }
+    __syncthreads();
+    if (wave != 0) return;
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) M = fmaxf(M, part[w][U * kWave]);
+    const float m_safe = M == -INFINITY ? 0.f : M;
+    float L = 0.f;
+#pragma unroll
+    for (int u = 0; u < U; ++u) o[u] = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const float wgt = expf(part[w][U * kWave] - m_safe);       // exp(-inf) = 0 for a wavefront without keys
+        L = fmaf(wgt, part[w][U * kWave + 1], L);
+#pragma unroll
+        for (int u = 0; u < U; ++u) o[u] = fmaf(wgt, part[w][u * kWave + lane], o[u]);
+    }
+    const float inv = L > 0.f ? 1.f / L : 0.f;
     float* __restrict__ out = (float*)p.out + (int64_t)row * q_ld + (int64_t)head * dh;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < U; ++u) {
         const int d = lane + 64 * u;
         if (d < dh) out[d] = o[u] * inv;
     }
-    if (p.lse && lane == 0) p.lse[(int64_t)head * p.Tq + row] = m_run + logf(l_run);
+    if (p.lse && lane == 0) p.lse[(int64_t)head * p.Tq + row] = M + logf(L);
 }
 
 int launch_attention(int dtype, const AttnParams& p_in, int head_dim, hipStream_t s, bool plan_only) {
@@ -554,10 +599,15 @@ int launch_attention(int dtype, const AttnParams& p_in, int head_dim, hipStream_
         }
     } else {
         if (head_dim > 256 || p.v_transposed) return ASTRA_ERR_UNSUPPORTED;
-        const int64_t blocks = ceil_div((int64_t)p.Hq * p.Tq, 4);
+        const int64_t blocks = (int64_t)p.Hq * p.Tq;
         if (blocks > 0x7fffffff) return ASTRA_ERR_SHAPE;
         if (plan_only) return ASTRA_OK;
-        attn_f32_kernel<<<(int)blocks, 256, 0, s>>>(p, head_dim);
+        switch ((head_dim + 63) / 64) {
+            case 1: attn_f32_kernel<1><<<(int)blocks, 256, 0, s>>>(p, head_dim); break;
+            case 2: attn_f32_kernel<2><<<(int)blocks, 256, 0, s>>>(p, head_dim); break;
+            case 3: attn_f32_kernel<3><<<(int)blocks, 256, 0, s>>>(p, head_dim); break;
+            default: attn_f32_kernel<4><<<(int)blocks, 256, 0, s>>>(p, head_dim); break;
+        }
     }
     return launch_status();
 }

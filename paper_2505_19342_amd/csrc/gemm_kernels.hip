@@ -37,26 +37,43 @@ __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmBatch batch)
     const int am = m0 + lr < M ? m0 + lr : M - 1;
     const int bn = n0 + lr < N ? n0 + lr : N - 1;
 
-    // the values of the next step are fetched into registers while the current step is multiplied
+    // the values of the next step are fetched into registers while the current step is multiplied.  No load is guarded (a
+    // guarded load compiles to a branch with a wait of its own, 32 of them in a row per step): addresses are clamped into
+    // the row and values beyond the contraction replaced by zeros afterwards; four consecutive k are one 16-byte load
+    // when every row start and the group length allow it.
     float av[kFL], bv[kFL];
+    const int64_t ldb = P.ldb ? P.ldb : K;
+    const bool vec = K % 4 == 0 && P.lda % 4 == 0 && ldb % 4 == 0 && (!gather || P.dg % 4 == 0) &&
+                     (reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B) | reinterpret_cast<uintptr_t>(CB)) % 16 == 0;
+    auto a_ptr = [&](int k) -> const float* {           // address of element (am, k), k < K
+        if (!gather) return A + (int64_t)am * P.lda + k;
+        const int g = k / P.dg, jj = k - g * P.dg;
+        int code;
+        if (P.code_bytes == 1) code = ((const uint8_t*)P.codes)[(int64_t)am * P.G + g];
+        else code = ((const uint16_t*)P.codes)[(int64_t)am * P.G + g];
+        code = code < P.Kc ? code : P.Kc - 1;
+        return CB + ((int64_t)g * P.Kc + code) * P.dg + jj;
+    };
     auto fetch = [&](int k0) {
+        if (vec) {
 #pragma unroll
-        for (int j = 0; j < kFL; ++j) {
-            const int k = k0 + lk + j;
-            av[j] = 0.f;
-            bv[j] = 0.f;
-            if (k < K) {
-                if (!gather) {
-                    av[j] = A[(int64_t)am * P.lda + k];
-                } else {
-                    const int g = k / P.dg, jj = k - g * P.dg;
-                    int code;
-                    if (P.code_bytes == 1) code = ((const uint8_t*)P.codes)[(int64_t)am * P.G + g];
-                    else code = ((const uint16_t*)P.codes)[(int64_t)am * P.G + g];
-                    code = code < P.Kc ? code : P.Kc - 1;
-                    av[j] = CB[((int64_t)g * P.Kc + code) * P.dg + jj];
-                }
-                bv[j] = B[(int64_t)bn * (P.ldb ? P.ldb : K) + k];
+            for (int j = 0; j < kFL; j += 4) {
+                const int k = k0 + lk + j;
+                const int kc = k < K ? k : K - 4;
+                const float4 a4 = *reinterpret_cast<const float4*>(a_ptr(kc));
+                const float4 b4 = *reinterpret_cast<const float4*>(B + (int64_t)bn * ldb + kc);
+                const bool in = k < K;
+                av[j] = in ? a4.x : 0.f; av[j + 1] = in ? a4.y : 0.f; av[j + 2] = in ? a4.z : 0.f; av[j + 3] = in ? a4.w : 0.f;
+                bv[j] = in ? b4.x : 0.f; bv[j + 1] = in ? b4.y : 0.f; bv[j + 2] = in ? b4.z : 0.f; bv[j + 3] = in ? b4.w : 0.f;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < kFL; ++j) {
+                const int k = k0 + lk + j;
+                const int kc = k < K ? k : K - 1;
+                const float a1 = *a_ptr(kc), b1 = B[(int64_t)bn * ldb + kc];
+                av[j] = k < K ? a1 : 0.f;
+                bv[j] = k < K ? b1 : 0.f;
             }
         }
     };

@@ -365,6 +365,22 @@ __global__ __launch_bounds__(256) void vq_encode_f32_kernel(const float* __restr
         float dist = 0.f;
         int j = 0;
         if (vec4)
+            // 32 values at a time: the eight codeword loads are issued together, then consumed in ascending order
+            for (; j + 32 <= dg; j += 32) {
+                f32x4 ev[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) ev[u] = *reinterpret_cast<const f32x4*>(e + j + 4 * u);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const f32x4 zv = *reinterpret_cast<const f32x4*>(z + j + 4 * u);
+                    const f32x4 df = ev[u] - zv;
+                    dist = fmaf(df.x, df.x, dist);
+                    dist = fmaf(df.y, df.y, dist);
+                    dist = fmaf(df.z, df.z, dist);
+                    dist = fmaf(df.w, df.w, dist);
+                }
+            }
+        if (vec4)
             for (; j + 4 <= dg; j += 4) {
                 const f32x4 ev = *reinterpret_cast<const f32x4*>(e + j);
                 const f32x4 zv = *reinterpret_cast<const f32x4*>(z + j);

@@ -12,10 +12,14 @@ namespace astra {
 // fp32, vector ALU: 64x64 output tile, 256 threads x (4x4) outputs, contraction in steps of 16 through
 // LDS.  Used for the small fp32 configuration; sums in ascending k with fused multiply-add.
 // ------------------------------------------------------------------------------------------------
-constexpr int kFM = 64, kFN = 64, kFK = 64;
-constexpr int kFL = kFK / 4;      // consecutive k one thread stages per row
+constexpr int kFK = 64;
 
+// TILE x TILE outputs per workgroup (64, or 32 for launches that would leave most of the chip without a workgroup),
+// TILE / 16 x TILE / 16 per thread
+template <int TILE>
 __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmBatch batch) {
+    constexpr int kFM = TILE, kFN = TILE, RT = TILE / 16;
+    constexpr int kFL = TILE / 4;     // consecutive k one thread stages per row: TILE rows x 64 k over 256 threads
     __shared__ float sa[kFK][kFM + 4];
     __shared__ float sb[kFK][kFN + 4];
 
@@ -32,8 +36,8 @@ __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmBatch batch)
 
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
-    // staging: thread loads kFL consecutive k of one row: row = tid / 4, first k = (tid % 4) * kFL
-    const int lr = tid >> 2, lk = (tid & 3) * kFL;
+    // staging: thread loads kFL consecutive k of one row
+    const int lr = tid / (kFK / kFL), lk = (tid % (kFK / kFL)) * kFL;
     const int am = m0 + lr < M ? m0 + lr : M - 1;
     const int bn = n0 + lr < N ? n0 + lr : N - 1;
 
@@ -78,7 +82,7 @@ __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmBatch batch)
         }
     };
 
-    float acc[4][4] = {};
+    float acc[RT][RT] = {};
     fetch(0);
     for (int k0 = 0; k0 < K; k0 += kFK) {
 #pragma unroll
@@ -90,25 +94,25 @@ __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmBatch batch)
         if (k0 + kFK < K) fetch(k0 + kFK);
 #pragma unroll
         for (int k = 0; k < kFK; ++k) {
-            float a[4], b[4];
+            float a[RT], b[RT];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) { a[i] = sa[k][ty * 4 + i]; b[i] = sb[k][tx * 4 + i]; }
+            for (int i = 0; i < RT; ++i) { a[i] = sa[k][ty * RT + i]; b[i] = sb[k][tx * RT + i]; }
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < RT; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+                for (int j = 0; j < RT; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
         }
         __syncthreads();
     }
     float* C = (float*)P.c;                               // may be the residual itself: no restrict
     const float* __restrict__ bias = (const float*)P.bias;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int m = m0 + ty * 4 + i;
+    for (int i = 0; i < RT; ++i) {
+        const int m = m0 + ty * RT + i;
         if (m >= M) continue;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int n = n0 + tx * 4 + j;
+        for (int j = 0; j < RT; ++j) {
+            const int n = n0 + tx * RT + j;
             if (n < N) {
                 const int64_t at = (int64_t)m * P.ldc + n;
                 const float r = apply_act<false>(acc[i][j] + (bias ? bias[n] : 0.f), P.act);
@@ -228,10 +232,16 @@ int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hi
     GemmBatch batch{};
     int total = 0;
     if (dtype != ASTRA_BF16) {
-        int rc = fill_batch(batch, dtype, problems, n_problems, kFM, kFN, &total);
+        int rc = fill_batch(batch, dtype, problems, n_problems, 64, 64, &total);
         if (rc) return rc;
         if (total == 0 || plan_only) return ASTRA_OK;
-        gemm_nt_f32_kernel<<<total, 256, 0, s>>>(batch);
+        if (total >= 128) {
+            gemm_nt_f32_kernel<64><<<total, 256, 0, s>>>(batch);
+        } else {
+            rc = fill_batch(batch, dtype, problems, n_problems, 32, 32, &total);
+            if (rc) return rc;
+            gemm_nt_f32_kernel<32><<<total, 256, 0, s>>>(batch);
+        }
         return launch_status();
     }
     bool code16 = false, mlp = false;

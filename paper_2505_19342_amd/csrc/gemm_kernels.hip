@@ -376,6 +376,17 @@ int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hi
             }
         }
         if (plan_only) return ASTRA_OK;
+        // a handful of tiles and no gathered rows (the output projection of a short sequence): a compute unit takes its
+        // operands in at 64 bytes per clock whatever the others do, so the launch is spread over four times as many units
+        // on 64 x 64 tiles
+        bool plain = true;
+        for (int i = 0; i < batch.n; ++i) plain = plain && batch.p[i].codes == nullptr;
+        if (plain && total <= kCus / 8 && g_gemm_force_cfg < 0) {
+            rc = fill_batch(batch, dtype, problems, n_problems, 64, 64, &total);
+            if (rc) return rc;
+            gemm_nt_bf16_kernel<64, 64, 2, 2, false, false, kEpiLayer, 2><<<total, 512, 0, s>>>(batch);
+            return launch_status();
+        }
         if (code16) gemm_nt_bf16_kernel<128, 128, 2, 2, true, false, kEpiLayer, 2><<<total, 512, 0, s>>>(batch);
         else gemm_nt_bf16_kernel<128, 128, 2, 2, false, false, kEpiLayer, 2><<<total, 512, 0, s>>>(batch);
     } else {

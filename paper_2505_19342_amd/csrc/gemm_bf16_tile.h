@@ -87,6 +87,7 @@ __device__ __forceinline__ FusedId fused_id(int wg, int T, int E) {
 __device__ __forceinline__ int vt_pos(int o) { return 8 * ((o >> 2) & 1) + (o & 3) + 4 * (o >> 3); }
 
 int launch_gemm_mlp(int epi, bool big, const GemmBatch& batch, int grid, hipStream_t s);
+int launch_gemm_mlp_small(int epi, const GemmBatch& batch, int grid, hipStream_t s);
 int launch_split_reduce(const float* part, int n_split, const GemmProblem& p, hipStream_t s);
 int gemm_split_factor(int dtype, int64_t M, int64_t N, int64_t K);
 

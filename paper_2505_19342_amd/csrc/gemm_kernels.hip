@@ -275,7 +275,13 @@ int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hi
         }
         rc = fill_batch(batch, dtype, problems, n_problems, 128, 128, &total);
         if (rc) return rc;
-        return plan_only ? ASTRA_OK : launch_gemm_mlp(epi, false, batch, total, s);
+        if (plan_only) return ASTRA_OK;
+        if (total <= kCus / 8 && epi != kEpiSwiGLU && p0.K % (2 * kBK) == 0 && g_gemm_force_cfg < 0) {      // a handful of tiles: see below
+            rc = fill_batch(batch, dtype, problems, n_problems, 64, 64, &total);
+            if (rc) return rc;
+            return launch_gemm_mlp_small(epi, batch, total, s);
+        }
+        return launch_gemm_mlp(epi, false, batch, total, s);
     }
     // Large tiles quarter the operand traffic per flop; use them once they still fill most of the chip.
     int rc = fill_batch(batch, dtype, problems, n_problems, 256, 256, &total);

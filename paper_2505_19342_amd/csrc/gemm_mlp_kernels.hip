@@ -55,6 +55,19 @@ static void launch_epi(bool big, const GemmBatch& batch, int grid, hipStream_t s
     else gemm_nt_bf16_kernel<128, 128, 4, 2, false, false, EPI><<<grid, 512, 0, s>>>(batch);
 }
 
+// 64 x 64 tiles on two contraction groups (launches of a handful of tiles: see launch_gemm_batch); the batch was filled
+// for that tile size and every contraction is a multiple of 128
+int launch_gemm_mlp_small(int epi, const GemmBatch& batch, int grid, hipStream_t s) {
+    if (grid <= 0) return ASTRA_OK;
+    switch (epi) {
+        case kEpiResidualF32: gemm_nt_bf16_kernel<64, 64, 2, 2, false, false, kEpiResidualF32, 2><<<grid, 512, 0, s>>>(batch); break;
+        case kEpiGeluTanh: gemm_nt_bf16_kernel<64, 64, 2, 2, false, false, kEpiGeluTanh, 2><<<grid, 512, 0, s>>>(batch); break;
+        case kEpiGeluErf: gemm_nt_bf16_kernel<64, 64, 2, 2, false, false, kEpiGeluErf, 2><<<grid, 512, 0, s>>>(batch); break;
+        default: return ASTRA_ERR_UNSUPPORTED;
+    }
+    return launch_status();
+}
+
 // big: 256 x 256 tiles, else 128 x 128 (two contraction groups when the contraction is a multiple of 128), both on 512
 // threads; the batch was filled for that tile size.
 int launch_gemm_mlp(int epi, bool big, const GemmBatch& batch, int grid, hipStream_t s) {

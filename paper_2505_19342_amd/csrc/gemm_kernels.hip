@@ -276,10 +276,12 @@ int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hi
         rc = fill_batch(batch, dtype, problems, n_problems, 128, 128, &total);
         if (rc) return rc;
         if (plan_only) return ASTRA_OK;
-        if (total <= kCus / 8 && epi != kEpiSwiGLU && p0.K % (2 * kBK) == 0 && g_gemm_force_cfg < 0) {      // a handful of tiles: see below
-            rc = fill_batch(batch, dtype, problems, n_problems, 64, 64, &total);
+        if (total <= kCus / 2 && epi != kEpiSwiGLU && p0.K % (2 * kBK) == 0 && g_gemm_force_cfg < 0) {      // few tiles: see below
+            GemmBatch sb{};
+            int st = 0;
+            rc = fill_batch(sb, dtype, problems, n_problems, 64, 64, &st);
             if (rc) return rc;
-            return launch_gemm_mlp_small(epi, batch, total, s);
+            if (st <= kCus) return launch_gemm_mlp_small(epi, sb, st, s);
         }
         return launch_gemm_mlp(epi, false, batch, total, s);
     }
@@ -382,16 +384,20 @@ int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hi
             }
         }
         if (plan_only) return ASTRA_OK;
-        // a handful of tiles and no gathered rows (the output projection of a short sequence): a compute unit takes its
-        // operands in at 64 bytes per clock whatever the others do, so the launch is spread over four times as many units
-        // on 64 x 64 tiles
+        // few tiles and no gathered rows (the output projection of a short sequence): a compute unit takes its operands in
+        // at 64 bytes per clock whatever the others do, so the launch is spread over four times as many units on 64 x 64
+        // tiles when those still make a single round
         bool plain = true;
         for (int i = 0; i < batch.n; ++i) plain = plain && batch.p[i].codes == nullptr;
-        if (plain && total <= kCus / 8 && g_gemm_force_cfg < 0) {
-            rc = fill_batch(batch, dtype, problems, n_problems, 64, 64, &total);
+        if (plain && total <= kCus / 2 && g_gemm_force_cfg < 0) {
+            GemmBatch sb{};
+            int st = 0;
+            rc = fill_batch(sb, dtype, problems, n_problems, 64, 64, &st);
             if (rc) return rc;
-            gemm_nt_bf16_kernel<64, 64, 2, 2, false, false, kEpiLayer, 2><<<total, 512, 0, s>>>(batch);
-            return launch_status();
+            if (st <= kCus) {                              // still a single round of workgroups
+                gemm_nt_bf16_kernel<64, 64, 2, 2, false, false, kEpiLayer, 2><<<st, 512, 0, s>>>(sb);
+                return launch_status();
+            }
         }
         if (code16) gemm_nt_bf16_kernel<128, 128, 2, 2, true, false, kEpiLayer, 2><<<total, 512, 0, s>>>(batch);
         else gemm_nt_bf16_kernel<128, 128, 2, 2, false, false, kEpiLayer, 2><<<total, 512, 0, s>>>(batch);

@@ -113,6 +113,27 @@ def test_tables_for_eight_groups_take_two_grouped_launches(dtype):
     run_case(cfg, 2, biases=True)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_tables_with_ragged_rows_and_columns(dtype):
+    """100 codewords and 72 output columns: neither a whole tile of the small-tile product (64 x 64) that such a short launch
+    takes, nor of the fp32 kernel's 32 x 32."""
+    import torch
+    from gpu_util import DEV, to_dev
+    from paper_2505_19342_amd import binding as B
+    G, K, dg, n_out = 2, 100, 128, 72
+    rng = np.random.default_rng(5)
+    cb = rng.standard_normal((G, K, dg)).astype(np.float32)
+    w = (rng.standard_normal((G * dg, n_out)) / np.sqrt(G * dg)).astype(np.float32)
+    if dtype == "bf16":
+        cb, w = wl.round_to_bf16(cb), wl.round_to_bf16(w)
+    ref = oracle.project_codebook(cb, w)
+    p = torch.full((G, K, n_out), float("nan"), dtype=torch.float32, device=DEV)
+    B.astra_vq_project_codebook(B.vq_desc(dtype, G * dg, G, K), to_dev(cb, dtype), to_dev(np.ascontiguousarray(w.T), dtype), n_out, p)
+    torch.cuda.synchronize()
+    err = np.abs(p.cpu().numpy() - ref).max()
+    assert err <= 1e-5 * max(1.0, np.abs(ref).max()), f"{err:.3e}"
+
+
 def test_argument_errors():
     import torch
     from gpu_util import DEV, LayerOnGpu

@@ -361,6 +361,27 @@ int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hi
     bool ks2 = total <= kCus;
     for (int i = 0; i < batch.n; ++i) ks2 = ks2 && batch.p[i].K % (2 * kBK) == 0;
     if (ks2) {
+        // Half-width tiles (128 x 64) when they still make a single round: a compute unit takes its operands in at 64 bytes per
+        // clock whatever the others do, and a 128 x 64 tile needs three quarters of a 128 x 128 tile's bytes per step
+        // (or 64 x 128, whichever makes fewer tiles: row counts just above a multiple of 128 waste less that way)
+        bool narrow = false, flat = false;
+        if (g_gemm_force_cfg < 0 && total <= kCus / 2) {
+            GemmBatch nb{}, fb{};
+            int nt = 0, ft = 0;
+            rc = fill_batch(nb, dtype, problems, n_problems, 128, 64, &nt);
+            if (rc) return rc;
+            rc = fill_batch(fb, dtype, problems, n_problems, 64, 128, &ft);
+            if (rc) return rc;
+            if (nt <= kCus - 8 && nt <= ft) {
+                narrow = true;
+                batch = nb;
+                total = nt;
+            } else if (ft <= kCus - 8) {
+                narrow = flat = true;
+                batch = fb;
+                total = ft;
+            }
+        }
         // a single round that leaves compute units idle: they take the encode of the local rows, as in the large-tile launches
         // (an item = 256 tokens of one group; about 1 us per 2^20 codeword elements; a 128 x 128 tile about 48 us per 4096 of
         // contraction plus 8 us of fixed cost)
@@ -369,7 +390,7 @@ int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hi
             const int64_t n_tb = ceil_div(enc->n_tokens, 256);
             int k_max = 0;
             for (int i = 0; i < batch.n; ++i) k_max = batch.p[i].K > k_max ? batch.p[i].K : k_max;
-            const double tile_us = 48.0 * k_max / 4096.0 + 8.0;
+            const double tile_us = (narrow ? 36.0 : 48.0) * k_max / 4096.0 + 8.0;
             const double enc_us = E > 0 ? (double)ceil_div(n_tb * enc->G, (int64_t)E) * 256.0 * enc->K * enc->dg / 1048576.0 + 4.0 : 0.0;
             if (E >= 8 && n_tb * enc->G <= 0x7fffffff && enc_us <= tile_us) {
                 batch.n_enc_wgs = E;
@@ -378,8 +399,16 @@ int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hi
                 batch.enc.n_wgs = E;
                 *enc_fused = true;
                 if (plan_only) return ASTRA_OK;
-                if (code16) gemm_nt_bf16_kernel<128, 128, 2, 2, true, true, kEpiLayer, 2><<<total + E, 512, 0, s>>>(batch);
-                else gemm_nt_bf16_kernel<128, 128, 2, 2, false, true, kEpiLayer, 2><<<total + E, 512, 0, s>>>(batch);
+                if (flat) {
+                    if (code16) gemm_nt_bf16_kernel<64, 128, 2, 2, true, true, kEpiLayer, 2><<<total + E, 512, 0, s>>>(batch);
+                    else gemm_nt_bf16_kernel<64, 128, 2, 2, false, true, kEpiLayer, 2><<<total + E, 512, 0, s>>>(batch);
+                } else if (narrow) {
+                    if (code16) gemm_nt_bf16_kernel<128, 64, 2, 2, true, true, kEpiLayer, 2><<<total + E, 512, 0, s>>>(batch);
+                    else gemm_nt_bf16_kernel<128, 64, 2, 2, false, true, kEpiLayer, 2><<<total + E, 512, 0, s>>>(batch);
+                } else {
+                    if (code16) gemm_nt_bf16_kernel<128, 128, 2, 2, true, true, kEpiLayer, 2><<<total + E, 512, 0, s>>>(batch);
+                    else gemm_nt_bf16_kernel<128, 128, 2, 2, false, true, kEpiLayer, 2><<<total + E, 512, 0, s>>>(batch);
+                }
                 return launch_status();
             }
         }
@@ -389,7 +418,7 @@ int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hi
         // tiles when those still make a single round
         bool plain = true;
         for (int i = 0; i < batch.n; ++i) plain = plain && batch.p[i].codes == nullptr;
-        if (plain && total <= kCus / 2 && g_gemm_force_cfg < 0) {
+        if (plain && g_gemm_force_cfg < 0) {
             GemmBatch sb{};
             int st = 0;
             rc = fill_batch(sb, dtype, problems, n_problems, 64, 64, &st);
@@ -398,6 +427,16 @@ int launch_gemm_batch(int dtype, const GemmProblem* problems, int n_problems, hi
                 gemm_nt_bf16_kernel<64, 64, 2, 2, false, false, kEpiLayer, 2><<<st, 512, 0, s>>>(sb);
                 return launch_status();
             }
+        }
+        if (flat) {
+            if (code16) gemm_nt_bf16_kernel<64, 128, 2, 2, true, false, kEpiLayer, 2><<<total, 512, 0, s>>>(batch);
+            else gemm_nt_bf16_kernel<64, 128, 2, 2, false, false, kEpiLayer, 2><<<total, 512, 0, s>>>(batch);
+            return launch_status();
+        }
+        if (narrow) {
+            if (code16) gemm_nt_bf16_kernel<128, 64, 2, 2, true, false, kEpiLayer, 2><<<total, 512, 0, s>>>(batch);
+            else gemm_nt_bf16_kernel<128, 64, 2, 2, false, false, kEpiLayer, 2><<<total, 512, 0, s>>>(batch);
+            return launch_status();
         }
         if (code16) gemm_nt_bf16_kernel<128, 128, 2, 2, true, false, kEpiLayer, 2><<<total, 512, 0, s>>>(batch);
         else gemm_nt_bf16_kernel<128, 128, 2, 2, false, false, kEpiLayer, 2><<<total, 512, 0, s>>>(batch);

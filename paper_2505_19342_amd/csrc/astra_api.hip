@@ -583,15 +583,21 @@ int astra_layer_forward_kv(const astra_layer_kv_desc* desc, const void* x_local,
     rc = launch_gemm_batch(dtype, pr, 3, s);
     if (rc) return rc;
 
-    // 2. what this device transmits: codes of the content rows of K and of V (the class row is not sent)
-    if (at.n_local > 0) {
-        rc = launch_vq_encode(vq, (const char*)K + (size_t)at.n_cls * pl.dkv * eb, pl.dkv, at.n_local, codebook_k, cnorm_k,
-                              codes_k_local_out, s);
-        if (rc) return rc;
-        rc = launch_vq_encode(vq, (const char*)V + (size_t)at.n_cls * pl.dkv * eb, pl.dkv, at.n_local, codebook_v, cnorm_v,
-                              codes_v_local_out, s);
-        if (rc) return rc;
+    // 2. what this device transmits: codes of the content rows of K and of V (the class row is not sent).  Nothing else in
+    //    the layer depends on them: they are offered to the attention launch, which runs them as extra workgroups on the
+    //    compute units its light query blocks leave early; if it does not take them they run as kernels of their own.
+    EncodeJob ej[2] = {};
+    const void* enc_x[2] = {(const char*)K + (size_t)at.n_cls * pl.dkv * eb, (const char*)V + (size_t)at.n_cls * pl.dkv * eb};
+    const void* enc_cb[2] = {codebook_k, codebook_v};
+    const float* enc_cn[2] = {cnorm_k, cnorm_v};
+    void* enc_out[2] = {codes_k_local_out, codes_v_local_out};
+    for (int j = 0; j < 2; ++j) {
+        ej[j].x = enc_x[j]; ej[j].codebook = enc_cb[j]; ej[j].cnorm = enc_cn[j]; ej[j].codes = enc_out[j]; ej[j].ldx = pl.dkv;
+        ej[j].n_tokens = at.n_local; ej[j].G = vq.n_groups; ej[j].K = vq.codebook_size; ej[j].dg = pl.dkv / vq.n_groups;
+        ej[j].code_bytes = code_bytes(vq.code_type);
     }
+    const bool offer = dtype == ASTRA_BF16 && at.n_local > 0;
+    bool enc_fused = false;
 
     // 3. the peers' keys and values, looked up from their codes; values go straight into the attention's layout
     if (pl.Tn_vis > 0) {
@@ -612,8 +618,14 @@ int astra_layer_forward_kv(const astra_layer_kv_desc* desc, const void* x_local,
     ap.valid_bits = (const unsigned long long*)valid_nonlocal_bits;
     ap.ldv_loc = pl.ldv_loc;
     ap.ldv_hat = pl.ldv_hat;
-    rc = launch_attention(dtype, ap, at.head_dim, s);
+    rc = launch_attention(dtype, ap, at.head_dim, s, false, offer ? ej : nullptr, offer ? 2 : 0, offer ? &enc_fused : nullptr);
     if (rc) return rc;
+    if (!enc_fused && at.n_local > 0) {
+        for (int j = 0; j < 2; ++j) {
+            rc = launch_vq_encode(vq, enc_x[j], pl.dkv, at.n_local, enc_cb[j], enc_cn[j], enc_out[j], s);
+            if (rc) return rc;
+        }
+    }
     return launch_gemm_batch(dtype, &po, 1, s);
 }
 

@@ -3,7 +3,9 @@
 // The two key/value sources are never concatenated in memory: the kernels walk the visible
 // non-local rows first and the local rows after them (softmax does not depend on key order).
 #include "common.h"
+#include "vq_encode_body.h"
 
+#include <algorithm>
 #include <type_traits>
 
 namespace astra {
@@ -58,8 +60,16 @@ __device__ __forceinline__ int swz_vt(int r) { return (r >> 1) & 7; }
 
 // LOST: the caller passed a validity bit per non-local token (an instantiation of its own, so that the code for it does
 // not disturb the register allocation and schedule of the kernel that runs without)
-template <int DH, bool VT, bool LOST = false, int NPAR = 2>
-__global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams p) {
+// ENC: the grid is the attention workgroups followed by e.n_enc_wgs workgroups that run VQ encodes nothing in this launch
+// depends on (the layer that quantises K and V after projection sends their codes to its peers): they are dispatched as
+// attention workgroups finish, i.e. into the tail that causal masking leaves on the units of the light query blocks.
+struct AttnEncode {
+    EncodeJob job[2];
+    int32_t n_jobs, n_attn_wgs, n_enc_wgs;
+};
+
+template <int DH, bool VT, bool LOST = false, int NPAR = 2, bool ENC = false>
+__global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams p, const AttnEncode e) {
     static_assert(NPAR == 2 || NPAR == 4, "two or four tile parities");
     constexpr int NQG = 8 / NPAR;              // query groups of 32 rows (wavefronts per parity)
     constexpr int kQRows = 32 * NQG;           // query rows per workgroup
@@ -73,6 +83,37 @@ __global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams
     __shared__ u32x4 lds_k[2][NPAR][PIECES];
     __shared__ u32x4 lds_v[2][NPAR][PIECES];
     static_assert(sizeof(lds_k) + sizeof(lds_v) <= 128 * 1024, "tile buffers");
+    if constexpr (ENC) {
+        static_assert(!ENC || (sizeof(lds_k) >= sizeof(u32x4) * kEncBufs * kEncCbSlots && sizeof(lds_v) >= sizeof(f32x4) * kEncBufs * kEncCnSlots),
+                      "the encode's ring of codebook tiles fits the key buffers, its norms the value buffers");
+        if ((int)blockIdx.x >= e.n_attn_wgs) {
+            u32x4* cb = &lds_k[0][0][0];
+            f32x4* cn = reinterpret_cast<f32x4*>(&lds_v[0][0][0]);
+            // the items of all jobs in one sequence, dealt in consecutive runs (consecutive items share the group)
+            const int idx = (int)blockIdx.x - e.n_attn_wgs;
+            int n_total = 0;
+            for (int j = 0; j < e.n_jobs; ++j) n_total += e.job[j].G * e.job[j].n_tb;
+            const int chunk = (n_total + e.n_enc_wgs - 1) / e.n_enc_wgs;
+            const int hi = min((idx + 1) * chunk, n_total);
+            bool zeroed = false;
+            for (int it = idx * chunk; it < hi; ++it) {
+                int j = 0, item = it;
+                while (item >= e.job[j].G * e.job[j].n_tb) {
+                    item -= e.job[j].G * e.job[j].n_tb;
+                    ++j;
+                }
+                const EncodeJob& job = e.job[j];
+                if (vq_encode_fast_needs_zero(job.dg) && !zeroed) {       // every job of a launch has the same group length
+                    vq_encode_fast_zero_lds<kAttThreads>(cb);
+                    __syncthreads();                       // zero fill done before any transfer lands
+                    zeroed = true;
+                }
+                vq_encode_fast_body<kAttThreads>(job, item / job.n_tb, item % job.n_tb, cb, cn);
+                __syncthreads();                           // all reads of this item's tiles done before the next item's transfers
+            }
+            return;
+        }
+    }
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -84,7 +125,7 @@ __global__ __launch_bounds__(kAttThreads) void attn_bf16_kernel(const AttnParams
     const int ptid = tid & (kParThreads - 1);
 
     const int n_qb = (p.Tq + kQRows - 1) / kQRows;
-    const int vt_id = xcd_remap_attn(blockIdx.x, gridDim.x);
+    const int vt_id = xcd_remap_attn(blockIdx.x, ENC ? e.n_attn_wgs : (int)gridDim.x);
     const int head = vt_id / n_qb;
     const int qb = n_qb - 1 - (vt_id % n_qb);
     const int hk = head / (p.Hq / p.Hkv);
@@ -561,9 +602,12 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnParams p, int d
     if (p.lse && lane == 0) p.lse[(int64_t)head * p.Tq + row] = M + logf(L);
 }
 
-int launch_attention(int dtype, const AttnParams& p_in, int head_dim, hipStream_t s, bool plan_only) {
+int launch_attention(int dtype, const AttnParams& p_in, int head_dim, hipStream_t s, bool plan_only, const EncodeJob* enc, int n_enc,
+                     bool* enc_fused) {
     AttnParams p = p_in;
+    if (enc_fused) *enc_fused = false;
     if (p.Tq == 0) return ASTRA_OK;
+    AttnEncode ae{};
     if (dtype == ASTRA_BF16) {
         int64_t total = (int64_t)ceil_div(p.Tq, kAttQ) * p.Hq;
         if (total > 0x7fffffff) return ASTRA_ERR_SHAPE;
@@ -578,22 +622,47 @@ int launch_attention(int dtype, const AttnParams& p_in, int head_dim, hipStream_
         // (head_dim of them, ldv tokens each) and 64 key rows of H_kv * head_dim elements
         if (vt && (int64_t)max(p.ldv_loc, p.ldv_hat) * 2 * head_dim >= (1ll << 32)) return ASTRA_ERR_UNSUPPORTED;
         if ((int64_t)p.Hkv * head_dim * 2 * kAttKV >= (1ll << 32)) return ASTRA_ERR_UNSUPPORTED;
+        // encodes offered by the caller ride in the launch's tail (128-wide heads on transposed V: the instantiations built)
+        if (enc && enc_fused && n_enc >= 1 && n_enc <= 2 && head_dim == 128 && vt && total + kAttCus <= 0x7fffffff) {
+            bool ok = true;
+            int64_t items = 0;
+            for (int j = 0; j < n_enc; ++j) {
+                ok = ok && enc[j].n_tokens > 0 && vq_encode_fast_ok(enc[j].K, enc[j].dg);
+                const int64_t n_tb = ceil_div(enc[j].n_tokens, kAttThreads / 2);
+                ok = ok && n_tb * enc[j].G <= 0x3fffffff && enc[j].dg == enc[0].dg;
+                items += n_tb * enc[j].G;
+            }
+            if (ok && items > 0) {
+                ae.n_jobs = n_enc;
+                for (int j = 0; j < n_enc; ++j) {
+                    ae.job[j] = enc[j];
+                    ae.job[j].n_tb = (int)ceil_div(enc[j].n_tokens, kAttThreads / 2);
+                }
+                ae.n_attn_wgs = (int)total;
+                ae.n_enc_wgs = (int)std::min<int64_t>(items, kAttCus);
+                for (int j = 0; j < n_enc; ++j) ae.job[j].n_wgs = ae.n_enc_wgs;
+                *enc_fused = true;
+            }
+        }
         if (plan_only) return ASTRA_OK;
-        if (head_dim == 128) {
-            if (vt && lost) attn_bf16_kernel<128, true, true><<<(int)total, kAttThreads, 0, s>>>(p);
-            else if (vt) attn_bf16_kernel<128, true><<<(int)total, kAttThreads, 0, s>>>(p);
-            else if (lost) attn_bf16_kernel<128, false, true><<<(int)total, kAttThreads, 0, s>>>(p);
-            else attn_bf16_kernel<128, false><<<(int)total, kAttThreads, 0, s>>>(p);
+        if (ae.n_enc_wgs > 0) {
+            if (lost) attn_bf16_kernel<128, true, true, 2, true><<<(int)total + ae.n_enc_wgs, kAttThreads, 0, s>>>(p, ae);
+            else attn_bf16_kernel<128, true, false, 2, true><<<(int)total + ae.n_enc_wgs, kAttThreads, 0, s>>>(p, ae);
+        } else if (head_dim == 128) {
+            if (vt && lost) attn_bf16_kernel<128, true, true><<<(int)total, kAttThreads, 0, s>>>(p, ae);
+            else if (vt) attn_bf16_kernel<128, true><<<(int)total, kAttThreads, 0, s>>>(p, ae);
+            else if (lost) attn_bf16_kernel<128, false, true><<<(int)total, kAttThreads, 0, s>>>(p, ae);
+            else attn_bf16_kernel<128, false><<<(int)total, kAttThreads, 0, s>>>(p, ae);
         } else if (four) {
-            if (vt && lost) attn_bf16_kernel<64, true, true, 4><<<(int)total, kAttThreads, 0, s>>>(p);
-            else if (vt) attn_bf16_kernel<64, true, false, 4><<<(int)total, kAttThreads, 0, s>>>(p);
-            else if (lost) attn_bf16_kernel<64, false, true, 4><<<(int)total, kAttThreads, 0, s>>>(p);
-            else attn_bf16_kernel<64, false, false, 4><<<(int)total, kAttThreads, 0, s>>>(p);
+            if (vt && lost) attn_bf16_kernel<64, true, true, 4><<<(int)total, kAttThreads, 0, s>>>(p, ae);
+            else if (vt) attn_bf16_kernel<64, true, false, 4><<<(int)total, kAttThreads, 0, s>>>(p, ae);
+            else if (lost) attn_bf16_kernel<64, false, true, 4><<<(int)total, kAttThreads, 0, s>>>(p, ae);
+            else attn_bf16_kernel<64, false, false, 4><<<(int)total, kAttThreads, 0, s>>>(p, ae);
         } else if (head_dim == 64) {
-            if (vt && lost) attn_bf16_kernel<64, true, true><<<(int)total, kAttThreads, 0, s>>>(p);
-            else if (vt) attn_bf16_kernel<64, true><<<(int)total, kAttThreads, 0, s>>>(p);
-            else if (lost) attn_bf16_kernel<64, false, true><<<(int)total, kAttThreads, 0, s>>>(p);
-            else attn_bf16_kernel<64, false><<<(int)total, kAttThreads, 0, s>>>(p);
+            if (vt && lost) attn_bf16_kernel<64, true, true><<<(int)total, kAttThreads, 0, s>>>(p, ae);
+            else if (vt) attn_bf16_kernel<64, true><<<(int)total, kAttThreads, 0, s>>>(p, ae);
+            else if (lost) attn_bf16_kernel<64, false, true><<<(int)total, kAttThreads, 0, s>>>(p, ae);
+            else attn_bf16_kernel<64, false><<<(int)total, kAttThreads, 0, s>>>(p, ae);
         } else {
             return ASTRA_ERR_UNSUPPORTED;
         }

@@ -193,7 +193,10 @@ struct AttnParams {
     const unsigned long long* valid_bits;
 };
 // plan_only: validate the launch (shape limits, kernel availability) and launch nothing
-int launch_attention(int dtype, const AttnParams& p, int head_dim, hipStream_t s, bool plan_only = false);
+// enc / n_enc / enc_fused: up to two VQ encodes that nothing in the launch depends on, offered to it; *enc_fused tells whether
+// the launch took them (extra workgroups in its tail) or the caller still has to run them
+int launch_attention(int dtype, const AttnParams& p, int head_dim, hipStream_t s, bool plan_only = false, const EncodeJob* enc = nullptr,
+                     int n_enc = 0, bool* enc_fused = nullptr);
 int launch_mfma_probe(float* out, int n_blocks, int iters, hipStream_t s);
 
 }  // namespace astra

@@ -89,6 +89,19 @@ def test_llama3_8b_shape_full_size(rank):
     run_case(wl.LLAMA3_8B, rank)
 
 
+def test_llama_width_ragged_rows_and_lost_codes():
+    """128-wide heads: the two encodes ride in the attention launch (extra workgroups behind the attention's own); here with
+    325 local rows (the last encode item is ragged) and lost codes (the instantiation with the validity bits)."""
+    cfg = dataclasses.replace(wl.LLAMA3_8B, name="kv_llama_ragged", seq_len=1300, seed=72)
+    rng = np.random.default_rng(8)
+    valid = (rng.random(cfg.n_nonlocal) > 0.1).astype(np.uint8)
+    a = run_case(cfg, 2, valid=valid)
+    b = run_case(cfg, 2)
+    assert np.abs(a["y"] - b["y"]).max() > 1e-4
+    np.testing.assert_array_equal(a["codes_k"], b["codes_k"])
+    np.testing.assert_array_equal(a["codes_v"], b["codes_v"])
+
+
 def test_results_do_not_depend_on_where_k_and_v_are_kept():
     from gpu_util import KvLayerOnGpu
     cfg = wl.GPT2_SMALL

@@ -115,6 +115,15 @@ def test_other_group_counts():
     run_case(wl.TINY_VIT, 33, 99, seed=11, n_groups_kv=16)         # the same in fp32
 
 
+def test_code_widths_of_the_one_load_per_head_path():
+    """A head's codes of a token are fetched as one aligned load when they fill 4 or 8 bytes: 16-bit codes of two groups
+    (4 bytes) and of four groups (8 bytes) per 64-wide head; 8-bit codes of four groups are the GPT-2 cases above."""
+    import dataclasses
+    cfg = dataclasses.replace(wl.GPT2_SMALL, name="gpt2_k1024", codebook_size=1024, seed=21)
+    run_case(cfg, 130, 700, seed=12, n_groups_kv=24, real_codes=False)      # dg 32: two groups per head
+    run_case(cfg, 130, 1300, seed=13, n_groups_kv=48, real_codes=False)     # dg 16: four groups per head; passes of 512 with a ragged last one
+
+
 def test_argument_errors():
     import torch
     from paper_2505_19342_amd import binding as B

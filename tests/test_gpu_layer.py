@@ -64,6 +64,14 @@ def test_biases_f32_and_bf16():
     run_case(wl.VIT_BASE, 1, biases=True)
 
 
+def test_f32_launches_of_large_and_small_tiles():
+    """The fp32 product runs on 64 x 64 tiles once a launch has 128 of them and on 32 x 32 tiles below (the tiny shape): a
+    longer sequence with ragged rows takes the large ones for the projections and, with two heads of 96, output values
+    beyond the first 64 lanes in the attention."""
+    cfg = dataclasses.replace(wl.TINY_VIT, name="f32_long", seq_len=1500, n_q_heads=2, n_kv_heads=2, head_dim=96, seed=17)
+    run_case(cfg, 1, biases=True)
+
+
 @pytest.mark.parametrize("i_dev", [0, 1, 2])
 @pytest.mark.parametrize("i_k", [0, 1, 2])
 @pytest.mark.parametrize("i_g", [0, 1, 2, 3])

@@ -600,15 +600,15 @@ int astra_layer_forward_kv(const astra_layer_kv_desc* desc, const void* x_local,
     bool enc_fused = false;
 
     // 3. the peers' keys and values, looked up from their codes; values go straight into the attention's layout
-    if (pl.Tn_vis > 0) {
+    if (pl.vt) {
+        // bf16: the three gathers are one launch
+        rc = launch_kv_pack(vq, codes_k_nonlocal, codes_v_nonlocal, codebook_k, codebook_v, V, pl.Tn_vis, pl.Tq, pl.dkv, Kh, Vh, pl.ldv_hat,
+                            Vt, pl.ldv_loc, s);
+        if (rc) return rc;
+    } else if (pl.Tn_vis > 0) {
         rc = launch_vq_decode(vq, codes_k_nonlocal, pl.Tn_vis, codebook_k, Kh, s);
         if (rc) return rc;
-        if (pl.vt) rc = launch_vt_pack(vq, nullptr, 0, codes_v_nonlocal, codebook_v, pl.Tn_vis, pl.dkv, Vh, pl.ldv_hat, s);
-        else rc = launch_vq_decode(vq, codes_v_nonlocal, pl.Tn_vis, codebook_v, Vh, s);
-        if (rc) return rc;
-    }
-    if (pl.vt) {
-        rc = launch_vt_pack(vq, V, pl.dkv, nullptr, nullptr, pl.Tq, pl.dkv, Vt, pl.ldv_loc, s);
+        rc = launch_vq_decode(vq, codes_v_nonlocal, pl.Tn_vis, codebook_v, Vh, s);
         if (rc) return rc;
     }
 

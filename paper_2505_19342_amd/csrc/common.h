@@ -123,6 +123,10 @@ int launch_vq_decode(const astra_vq_desc& d, const void* codes, int64_t n_tokens
 
 int launch_vt_pack(const astra_vq_desc& d, const void* src, int64_t ld_src, const void* codes, const void* codebook, int T, int C,
                    void* dst, int ldv, hipStream_t s);
+// K-hat rows (row-major) and V-hat (transposed layout) looked up from the peers' codes, and the local V rows into the transposed
+// layout, as one launch (bf16)
+int launch_kv_pack(const astra_vq_desc& d, const void* codes_k, const void* codes_v, const void* cb_k, const void* cb_v, const void* v_loc,
+                   int T_n, int T_q, int C, void* k_hat, void* v_hat_t, int ldv_hat, void* v_loc_t, int ldv_loc, hipStream_t s);
 
 // out[t, n] = bias[n] + sum_g P[g, codes[t, g], n] with P fp32 [G, K, N]: row-major [T, ld] in the element type, or (transposed,
 // bf16) [N, ld] in the attention kernel's V^T layout

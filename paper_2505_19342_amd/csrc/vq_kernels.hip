@@ -238,6 +238,109 @@ int launch_vt_pack(const astra_vq_desc& d, const void* src, int64_t ld_src, cons
 }
 
 // ------------------------------------------------------------------------------------------------
+// The three gathers of the layer that quantises K and V after projection, as one launch (each is a few microseconds of
+// work behind a launch's fixed cost): K-hat rows looked up from the peers' key codes (row-major), V-hat looked up from
+// their value codes and the local V rows, both into the transposed layout of vt_pack_kernel.  A workgroup moves 64
+// tokens x 64 channels; blockIdx.x walks the tiles of the three jobs one after the other.
+// ------------------------------------------------------------------------------------------------
+struct KvPackJob {
+    const void* codes_k;      // [T_n, G]
+    const void* codes_v;
+    const uint16_t* cb_k;     // [G, K, dg]
+    const uint16_t* cb_v;
+    const uint16_t* v_loc;    // [T_q, C] row-major
+    uint16_t* k_hat;          // [T_n, C] row-major
+    uint16_t* v_hat_t;        // [C, ldv_hat]
+    uint16_t* v_loc_t;        // [C, ldv_loc]
+    int32_t T_n, T_q, C, G, K, dg, ldv_hat, ldv_loc;
+    int32_t tiles_khat, tiles_vhat;     // tiles of the first two jobs
+};
+
+template <typename CodeT>
+__global__ __launch_bounds__(256) void kv_pack_kernel(const KvPackJob j) {
+    __shared__ __attribute__((aligned(16))) uint16_t tile[64 * kVtStride];
+    const int tid = threadIdx.x;
+    const int cblocks = j.C / 64;
+    int b = blockIdx.x;
+    int kind = 0;                                       // 0: K-hat rows, 1: V-hat transposed, 2: local V transposed
+    if (b >= j.tiles_khat) { b -= j.tiles_khat; kind = 1; }
+    if (kind == 1 && b >= j.tiles_vhat) { b -= j.tiles_vhat; kind = 2; }
+    const int t0 = (b / cblocks) * 64, c0 = (b % cblocks) * 64;
+    const int T = kind == 2 ? j.T_q : j.T_n;
+    const CodeT* __restrict__ codes = (const CodeT*)(kind == 0 ? j.codes_k : j.codes_v);
+    const uint16_t* __restrict__ cb = kind == 0 ? j.cb_k : j.cb_v;
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int piece = tid + 256 * it;
+        const int tl = piece >> 3, pc = piece & 7;
+        const int t = t0 + tl, c = c0 + 8 * pc;
+        const int tc = t < T ? t : T - 1;               // clamped: the load is never guarded
+        const uint16_t* from;
+        if (kind == 2) {
+            from = j.v_loc + (int64_t)tc * j.C + c;
+        } else {
+            const int g = c / j.dg, jj = c - g * j.dg;
+            int code = (int)codes[(int64_t)tc * j.G + g];
+            code = code < j.K ? code : j.K - 1;
+            from = cb + ((int64_t)g * j.K + code) * j.dg + jj;
+        }
+        u32x4 v = *reinterpret_cast<const u32x4*>(from);
+        if (t >= T) v = u32x4{0u, 0u, 0u, 0u};
+        if (kind == 0) {
+            if (t < T) *reinterpret_cast<u32x4*>(j.k_hat + (int64_t)t * j.C + c) = v;
+        } else {
+            *reinterpret_cast<u32x4*>(&tile[tl * kVtStride + 8 * pc]) = v;
+        }
+    }
+    if (kind == 0) return;                              // the same for the whole workgroup
+    __syncthreads();
+    uint16_t* __restrict__ dst = kind == 1 ? j.v_hat_t : j.v_loc_t;
+    const int ldv = kind == 1 ? j.ldv_hat : j.ldv_loc;
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int q = tid & 7;                      // which run of 8 positions of the 64 tokens
+        const int c = (tid >> 3) + 32 * it;
+        const int blk = q >> 1, half = q & 1;
+        uint16_t e[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int p = 8 * half + i;
+            const int o = (((p >> 2) & 1) << 3) | ((p >> 3) << 2) | (p & 3);
+            e[i] = tile[(16 * blk + o) * kVtStride + c];
+        }
+        u32x4 w;
+        w.x = e[0] | ((uint32_t)e[1] << 16);
+        w.y = e[2] | ((uint32_t)e[3] << 16);
+        w.z = e[4] | ((uint32_t)e[5] << 16);
+        w.w = e[6] | ((uint32_t)e[7] << 16);
+        *reinterpret_cast<u32x4*>(dst + (int64_t)(c0 + c) * ldv + t0 + 8 * q) = w;
+    }
+}
+
+// bf16 only; C = H_kv * dh a multiple of 64, dg a multiple of 8, ldv_* multiples of 64 >= the token counts.  T_n or T_q may be 0.
+int launch_kv_pack(const astra_vq_desc& d, const void* codes_k, const void* codes_v, const void* cb_k, const void* cb_v, const void* v_loc,
+                   int T_n, int T_q, int C, void* k_hat, void* v_hat_t, int ldv_hat, void* v_loc_t, int ldv_loc, hipStream_t s) {
+    const int dg = d.d_model / d.n_groups;
+    if (d.dtype != ASTRA_BF16 || d.d_model != C || C % 64 != 0 || dg % 8 != 0 || ldv_hat % 64 != 0 || ldv_loc % 64 != 0 || ldv_hat < T_n ||
+        ldv_loc < T_q || T_n < 0 || T_q < 0)
+        return ASTRA_ERR_UNSUPPORTED;
+    KvPackJob j{};
+    j.codes_k = codes_k; j.codes_v = codes_v; j.cb_k = (const uint16_t*)cb_k; j.cb_v = (const uint16_t*)cb_v; j.v_loc = (const uint16_t*)v_loc;
+    j.k_hat = (uint16_t*)k_hat; j.v_hat_t = (uint16_t*)v_hat_t; j.v_loc_t = (uint16_t*)v_loc_t;
+    j.T_n = T_n; j.T_q = T_q; j.C = C; j.G = d.n_groups; j.K = d.codebook_size; j.dg = dg; j.ldv_hat = ldv_hat; j.ldv_loc = ldv_loc;
+    const int64_t cblocks = C / 64;
+    const int64_t t_khat = ceil_div(T_n, 64) * cblocks, t_vhat = T_n > 0 ? (int64_t)(ldv_hat / 64) * cblocks : 0;
+    const int64_t t_vloc = T_q > 0 ? (int64_t)(ldv_loc / 64) * cblocks : 0;
+    const int64_t total = t_khat + t_vhat + t_vloc;
+    if (total > 0x7fffffff) return ASTRA_ERR_SHAPE;
+    if (total == 0) return ASTRA_OK;
+    j.tiles_khat = (int)t_khat; j.tiles_vhat = (int)t_vhat;
+    if (d.code_type == ASTRA_CODE_U16) kv_pack_kernel<uint16_t><<<(int)total, 256, 0, s>>>(j);
+    else kv_pack_kernel<uint8_t><<<(int)total, 256, 0, s>>>(j);
+    return launch_status();
+}
+
+// ------------------------------------------------------------------------------------------------
 // Projections of the peers' tokens from pre-projected codebooks.  A rebuilt row is a concatenation of codewords, so its
 // projection is a sum of per-group products that do not depend on the token (paper Sec. 3.2: X-hat is rebuilt from the
 // indices and projected with the same W_k, W_v as the local rows):

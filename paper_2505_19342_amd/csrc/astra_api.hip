@@ -439,10 +439,11 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
         }
         rc = launch_vq_argmin_scores(vq, scores, cnorm, at.n_local, codes_local_out, s);
         if (rc) return rc;
-    } else if (!enc_fused && at.n_local > 0) {
-        rc = launch_vq_encode(vq, ej.x, pl.D, at.n_local, codebook, cnorm, codes_local_out, s);
-        if (rc) return rc;
     }
+    // an encode the projection launch did not take is offered to the attention launch (extra workgroups in its tail); if
+    // that does not take it either, it runs as a kernel of its own
+    const bool enc_pending = !pl.wide_enc && !enc_fused && at.n_local > 0;
+    bool enc_in_attention = false;
     mark(6, s);
 
     // optional rotary positions (a block's choice, outside the paper): Q and K of the local rows (content row i at n_before + i,
@@ -455,8 +456,13 @@ static int layer_forward_impl(const astra_layer_desc* desc, const void* x_local,
     }
 
     // 3. mixed-precision attention (Eq. 1)
-    rc = launch_attention(vq.dtype, ap, at.head_dim, s);
+    rc = launch_attention(vq.dtype, ap, at.head_dim, s, false, enc_pending && offer ? &ej : nullptr, enc_pending && offer ? 1 : 0,
+                          enc_pending && offer ? &enc_in_attention : nullptr);
     if (rc) return rc;
+    if (enc_pending && !enc_in_attention) {
+        rc = launch_vq_encode(vq, ej.x, pl.D, at.n_local, codebook, cnorm, codes_local_out, s);
+        if (rc) return rc;
+    }
     mark(2, s);
 
     // 4. output projection
